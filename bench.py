@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: fused dual-number forward + adjoint x partial backward.
+
+One "step" = one forward call + one backward call over one batch of synthetic input
+already resident in HBM.  Prints ONE JSON line.  Default workload: the large HM-LSTM
+cell update (hidden 4096, batch 1024, per-element z ~ Bernoulli(0.5)).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Workloads: cfg0 cfg1 cfg2 cfg3 (p via --p-index 0|1|2) cfg4 cfg4_f64, paper_n512 /
+paper_n1024 / paper_n2048 (the paper's own experiment shape, Sec. 3.4).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a
+# copy kernel of known size); see profiles/.  Keyed by (workload, kernel).
+MEASURED_TRAFFIC = {}
+
+
+def build_workload(name, p_index):
+    import numpy as np
+    from paper_1810_08297_amd import inputs
+    dtype = np.float64 if name.endswith("_f64") else np.float32
+    base = name.replace("_f64", "")
+    if base.startswith("cfg"):
+        idx = int(base[3:])
+        op, args, adj = inputs.config_inputs(idx, dtype=dtype, p_index=p_index)
+        desc = {0: "HM-LSTM update hidden=64 batch=16", 1: "tanh(x*y+b) 4096x4096",
+                2: "HM-LSTM update hidden=1024 batch=256",
+                3: f"HM-LSTM update hidden=4096 batch=1024, per-element z ~ Bernoulli({inputs.P_SWEEP[p_index]})",
+                4: "branchy5 8192x8192"}[idx]
+    elif base.startswith("paper_n"):
+        n = int(base[len("paper_n"):])
+        args, adj = inputs.update_c_inputs(n, seed=inputs.BASE_SEED + 100 + n, dtype=dtype)
+        op, desc = "update_c", f"paper's cell update c,f,i,g {n}x{n}, z vectors of {n}"
+    else:
+        raise SystemExit(f"unknown workload {name}")
+    return op, args, adj, desc, dtype
+
+
+def algorithmic_words(n_args_full, n_ctrl_full, M, Nd, n_full_grads):
+    """Words per element the method itself must move (vectors and scalars are negligible)."""
+    fwd = n_args_full + n_ctrl_full + M + M * Nd
+    bwd = M + M * Nd + n_full_grads
+    return fwd, bwd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--p-index", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=16)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); "
+                         "no multi-GPU path exists and none is measured")
+
+    import numpy as np
+    import torch
+    import paper_1810_08297_amd as P
+
+    torch.cuda.set_device(0)
+    op, args, adj, desc, dtype = build_workload(a.workload, a.p_index)
+    es = np.dtype(dtype).itemsize
+    dev = [torch.from_numpy(x).cuda() for x in args]
+    adj_dev = [torch.from_numpy(x).cuda() for x in adj]
+    fb = P.alloc_forward(op, dev, want_branch=False)
+    didx = P.diff_arg_indices(fb.op_id)
+    shapes = [args[j].shape for j in didx]
+    bb = P.alloc_backward(adj_dev, fb.partials, shapes)
+    E = int(np.prod(fb.outs[0].shape))
+    M, Nd = len(fb.outs), len(didx)
+    n_full_args = sum(1 for x in args if x.size == E)
+    n_full_grads = sum(1 for s in shapes if int(np.prod(s)) == E)
+    fwd_words = n_full_args + M + M * Nd
+    bwd_words = M + M * Nd + n_full_grads
+    fwd_bytes, bwd_bytes = fwd_words * es * E, bwd_words * es * E
+
+    stream = torch.cuda.current_stream()
+
+    def step():
+        fb.run(dev, stream)
+        bb.run(adj_dev, fb.partials, stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(a.steps):
+        ev[k][0].record(stream)
+        fb.run(dev, stream)
+        ev[k][1].record(stream)
+        bb.run(adj_dev, fb.partials, stream)
+        ev[k][2].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
+    bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
+    ms_per_step = wall * 1e3 / a.steps
+    value = E * a.steps / wall
+
+    fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
+    dom = "forward" if fwd_avg >= bwd_avg else "backward"
+    dom_bytes = fwd_bytes if dom == "forward" else bwd_bytes
+    dom_ms = max(fwd_avg, bwd_avg)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": f"{dom} ({'fwd_tiled_kernel' if dom == 'forward' else 'bwd_tiled_kernel'})",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC.get((a.workload, dom)),
+        "algorithmic_bytes_per_launch": dom_bytes,
+        "avg_launch_ms": round(dom_ms, 5),
+    }
+    extra = {
+        "elements": E,
+        "forward": {"avg_ms": round(fwd_avg, 5), "median_ms": round(float(np.median(fwd_ms)), 5),
+                    "bytes": fwd_bytes, "GBps": round(fwd_bytes / (fwd_avg * 1e-3) / 1e9, 1)},
+        "backward": {"avg_ms": round(bwd_avg, 5), "median_ms": round(float(np.median(bwd_ms)), 5),
+                     "bytes": bwd_bytes, "GBps": round(bwd_bytes / (bwd_avg * 1e-3) / 1e9, 1)},
+        "fwd_bwd_GBps_event_time": round((fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9, 1),
+        "fwd_bwd_frac_of_hbm_peak": round((fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "elements_per_s_event_time": round(E / ((fwd_avg + bwd_avg) * 1e-3), 1),
+        "bytes_per_element": (fwd_words + bwd_words) * es,
+    }
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        import oracle
+        threads = max(1, min(a.cpu_threads, os.cpu_count() or 1))
+        # bounded sample: whole rows of the same workload, about 1M elements at most
+        rows = args[0].shape[0]
+        cols = E // rows
+        take = max(1, min(rows, (1 << 20) // max(1, cols)))
+        sub = [x[:take] if x.shape[0] == rows else x for x in args]
+        sub_adj = [x[:take] for x in adj]
+        sub_shapes = [s if s[0] != rows else (take,) + tuple(s[1:]) for s in shapes]
+        c0 = time.perf_counter()
+        o_out, o_parts, _ = oracle.forward(op, sub, threads=threads)
+        oracle.backward(sub_adj, o_parts, sub_shapes, threads=threads)
+        c1 = time.perf_counter()
+        cpu = {"value": round(take * cols / (c1 - c0), 1), "unit": "elements/s", "cores": threads,
+               "kind": "oracle", "sample": f"first {take} of {rows} rows ({take * cols} elements), "
+               f"forward + backward once, {c1 - c0:.2f} s"}
+
+    line = {
+        "metric": "fused fwd+bwd elements/s, HM-LSTM update" if op == "hmlstm_update"
+                  else f"fused fwd+bwd elements/s, {op}",
+        "value": round(value, 1), "unit": "elements/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64" if dtype == np.float64 else "f32", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {desc}", "op": op, "elements": E,
+                   "partial_planes": M * Nd, "layout": "row-major, all planes stored"},
+        "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,173 @@
+/*
+ * bcast_dual -- mixed-mode differentiation of a fused broadcast on one AMD
+ * MI355X (gfx950).  C ABI; no C++ or framework types cross this boundary.
+ *
+ * Method: "Dynamic Automatic Differentiation of GPU Broadcast Kernels"
+ * (arXiv 1810.08297).  A scalar function b : R^N -> R^M from the built-in op table
+ * is broadcast over N array arguments (Sec. 2.1.1).  The forward call evaluates b on
+ * multidimensional dual numbers, one perturbation per differentiable argument
+ * (Sec. 2.2.1, the D operator of Sec. 2.2.2), in ONE kernel, data-dependent branches
+ * included, and returns the M outputs together with the M x N_d planes
+ * d Y_i / d X_j -- the diagonal of the broadcast Jacobian (Sec. 2.2.2).  The caller
+ * keeps those planes until the reverse pass (Sec. 2.2.3); the backward call then
+ * multiplies the upstream adjoints by them and sums over the dims along which each
+ * argument was expanded (Table 1).
+ *
+ * Common rules
+ *  - Every `data` pointer is a DEVICE pointer owned by the caller.  The library
+ *    allocates no device memory, never synchronises, and enqueues work only on the
+ *    `stream` argument (a hipStream_t; NULL = the default stream).
+ *  - Views: `ndim` dims, extents `shape[d]`, strides `stride[d]` in ELEMENTS (may be
+ *    any integer >= 0 that keeps the view inside its buffer; ignored where
+ *    shape[d] == 1).  Dims an argument lacks are TRAILING size-1 dims, as in the
+ *    paper's example where an n-vector pairs with the first dim of an n x m matrix
+ *    (Sec. 2.1.1, Eq. 1).  A size-1 dim is virtually copied; it is never materialised.
+ *  - All validation happens on the host before anything is launched; on any error
+ *    nothing is written.  Return value: BCAST_OK (0) or a negative bcast_status.
+ *  - Buffers written by a call must not overlap any other buffer of that call.
+ *  - Zero-sized outputs: BCAST_OK, nothing is launched.
+ *  - Results are bitwise reproducible run to run: no atomics, fixed reduction order.
+ */
+#ifndef BCAST_DUAL_H
+#define BCAST_DUAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BCAST_MAX_DIMS 4
+#define BCAST_MAX_ARGS 20
+#define BCAST_MAX_OUTS 4
+#define BCAST_MAX_PLANES 40 /* limit on M * N_d */
+
+typedef enum { BCAST_F32 = 0, BCAST_F64 = 1 } bcast_dtype;
+
+typedef enum {
+  BCAST_OK = 0,
+  BCAST_ERR_INVALID_OP = -1,
+  BCAST_ERR_BAD_ARG_COUNT = -2,
+  BCAST_ERR_NULL_POINTER = -3,
+  BCAST_ERR_RANK_TOO_HIGH = -4,
+  BCAST_ERR_SHAPE_MISMATCH = -5,        /* an argument dim is neither the unified extent nor 1 */
+  BCAST_ERR_OUTPUT_SHAPE_MISMATCH = -6, /* an output / partial / adjoint / gradient view has the wrong shape */
+  BCAST_ERR_BAD_DTYPE = -7,
+  BCAST_ERR_WORKSPACE_TOO_SMALL = -8,
+  BCAST_ERR_LAUNCH_FAILED = -9,
+  BCAST_ERR_BAD_STRIDE = -10,           /* negative stride, or a written view that overlaps itself */
+  BCAST_ERR_MISALIGNED = -11            /* a data pointer is not aligned to its element size */
+} bcast_status;
+
+typedef struct {
+  void *data;                    /* device pointer */
+  int32_t ndim;                  /* 0 = scalar */
+  int64_t shape[BCAST_MAX_DIMS];
+  int64_t stride[BCAST_MAX_DIMS]; /* in elements */
+} bcast_tensor;
+
+/* How a call was (or would be) mapped onto the GPU; filled by the *_plan calls. */
+typedef struct {
+  int32_t path;     /* 0 nothing to do, 1 tiled 2-D kernels, 2 generic strided kernels */
+  int32_t vec;      /* elements per lane per memory instruction */
+  int32_t ndim;     /* rank after dropping size-1 dims and merging mergeable dims */
+  int64_t shape[BCAST_MAX_DIMS]; /* merged output extents, outermost first */
+  int32_t tx, ty;   /* lanes along the contiguous dim / rows per block step */
+  int32_t rows_per_block;
+  int64_t grid_x, grid_y;
+  int32_t n_launches; /* kernels this call enqueues */
+  int32_t n_second_pass; /* gradients finished by the second reduction pass */
+} bcast_plan_info;
+
+/* ---- op table --------------------------------------------------------------------
+ * Built-in scalar functions (each is already the fused composition, Sec. 2.1.2):
+ *   "hmlstm_update" N=12 (f i o g c h z z_below b_f b_i b_o b_g) -> (c', h');
+ *                   the cell update of Sec. 3.1 / 3.2.3: FLUSH if z == 1, COPY if
+ *                   z == 0 and z_below == 0, UPDATE otherwise; h' = sigma(o) tanh(c')
+ *                   except COPY (h' = h); biases add to their gate's pre-activation.
+ *                   z, z_below are control inputs (not differentiable).
+ *                   branch id: 0 UPDATE, 1 COPY, 2 FLUSH.
+ *   "update_c"      N=6 (c f i g z1 z2) -> c'; the paper's fused update (Sec. 3.2.3).
+ *   "tanh_xy_b"     N=3 -> tanh(x*y + b)
+ *   "branchy5"      N=5 (A B r s t): exp(-A)*B + r if A + s > t else log1p(A*A)*r - s;
+ *                   branch id 1 = predicate true.
+ *   "cos_x"         N=1 (the Dual example of Sec. 2.2.1), "scale_xt" N=2 (x*t),
+ *   "pair3"         N=3 -> (x1*x2 + sin x3, x1/x2 - x3*x3)  (R^3 -> R^2, Sec. 2.2.2)
+ *   "prod_tanh_K"   K = 1..18: prod_i tanh(g(x_i)), g(x) = x if x > 1/2 else -x
+ *                   (the arity study of Sec. 3.4.1); branch id = #{x_i > 1/2}.
+ * Predicates read values only, so control flow contributes no derivative. */
+int bcast_op_lookup(const char *name, int32_t *op_id);
+int bcast_op_count(void);
+const char *bcast_op_name(int32_t op_id); /* NULL if out of range */
+/* nondiff_mask bit j set = argument j is a control input: it has no partial plane and
+ * no gradient.  N_d = n_args - popcount(nondiff_mask). */
+int bcast_op_info(int32_t op_id, int32_t *n_args, int32_t *n_outputs, uint32_t *nondiff_mask,
+                  int32_t *n_branches);
+
+/* ---- forward: values + Jacobian planes in one kernel (Sec. 2.2.2, Sec. 2.2.3) -----
+ * args[n_args]      inputs (read).  Unified shape = per-dim maximum; every argument dim
+ *                   must equal it or be 1 (else BCAST_ERR_SHAPE_MISMATCH).
+ * outs[n_out]       the M outputs (written), each exactly of the unified shape.
+ * partials[M*N_d]   planes d Y_i / d X_jd (written), unified shape, index i*N_d + jd
+ *                   where jd counts differentiable arguments in argument order
+ *                   (row = output, column = argument, as in the D(b) expansion of
+ *                   Sec. 2.2.2).  A plane whose data pointer is NULL is not stored.
+ *                   `partials` itself may be NULL: values only.
+ * branch_id         optional device buffer of E bytes (E = elements of the unified
+ *                   shape), row-major over the unified shape as given (before any
+ *                   internal dim merging); receives the branch taken per element.
+ * Written views must not have zero strides on dims of extent > 1. */
+int bcast_dual_forward(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                       int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
+                       uint8_t *branch_id, void *stream);
+int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                            int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
+                            const uint8_t *branch_id, bcast_plan_info *info);
+
+/* ---- backward: adjoint x partial, summed over expanded dims (Table 1) --------------
+ * Independent of the op.
+ * adjoints[n_out]   upstream adjoints of the M outputs (read), all of one shape S.
+ * partials[M*n_grads] the planes forward produced (read), shape S, index i*n_grads + jd.
+ *                   A NULL data pointer stands for a plane of zeros.
+ * grads[n_grads]    gradient of each differentiable argument (written), in THAT
+ *                   ARGUMENT's shape: every dim equals S's or is 1 (or is a missing
+ *                   trailing dim); where it is 1 and S's extent is larger, the products
+ *                   sum_i adj_i * P_i,jd are summed over that dim.  A NULL data pointer
+ *                   skips that gradient.
+ * workspace         device scratch for the deterministic second reduction pass; at least
+ *                   bcast_dual_backward_workspace(...) bytes, 16-byte aligned; may be
+ *                   NULL when that is 0.  Contents on entry are ignored.
+ * Products are formed and summed in double (fp32 data) or in double-double (fp64 data)
+ * and rounded once; there are no atomics, so results do not depend on scheduling. */
+size_t bcast_dual_backward_workspace(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                                     const bcast_tensor *partials, int32_t n_grads,
+                                     const bcast_tensor *grads);
+int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                        const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                        void *workspace, size_t workspace_bytes, void *stream);
+int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                             const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                             bcast_plan_info *info);
+
+/* ---- misc ---------------------------------------------------------------------- */
+const char *bcast_status_string(int status);
+
+/* Launch-shape overrides for benchmarking sweeps (process-wide, not thread-safe; values
+ * outside the documented range are rejected with BCAST_ERR_BAD_ARG_COUNT).
+ *   key 0: rows per block of the tiled forward kernel (0 = automatic, else 1..64)
+ *   key 1: rows per block of the tiled backward kernel (0 = automatic, else 1..256)
+ *   key 2: 1 = non-temporal stores for outputs/partials/gradients, 0 = plain
+ *   key 3: 1 = force the generic strided kernels (testing) */
+int bcast_dual_set_tuning(int32_t key, int32_t value);
+int bcast_dual_get_tuning(int32_t key, int32_t *value);
+
+/* A plain device-to-device streaming copy of `bytes` bytes (multiple of 16, both
+ * pointers 16-byte aligned) with the same access pattern as the tiled kernels; used to
+ * measure the achievable HBM rate and to calibrate profiler byte counters. */
+int bcast_dual_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCAST_DUAL_H */

@@ -1,0 +1,13 @@
+"""bcast_dual: mixed-mode differentiation of fused broadcasts on MI355X (gfx950).
+
+The product is the C-ABI library (include/bcast_dual.h, csrc/); this package is its
+thin Python binding plus buffer-allocation helpers and the seeded workload generators.
+"""
+from .binding import (  # noqa: F401
+    BcastError, BcastTensor, PlanInfo, F32, F64, LIB_PATH, EXPORTS,
+    bcast_op_lookup, bcast_op_count, bcast_op_name, bcast_op_info, diff_arg_indices,
+    bcast_dual_forward, bcast_dual_forward_plan, bcast_dual_backward_workspace,
+    bcast_dual_backward, bcast_dual_backward_plan, bcast_dual_set_tuning,
+    bcast_dual_get_tuning, bcast_dual_copy_probe, status_string, as_view, raw_view,
+)
+from .helpers import ForwardBuffers, BackwardBuffers, alloc_forward, alloc_backward  # noqa: F401

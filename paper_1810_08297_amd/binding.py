@@ -1,0 +1,235 @@
+"""Thin ctypes binding of libbcast_dual.so -- argument marshalling only.
+
+Function names mirror the C ABI (include/bcast_dual.h).  Tensors are torch tensors
+on the GPU (PyTorch supplies device memory and streams, nothing else); every step
+of the method runs inside the library's kernels.  There is no CPU fallback: a
+missing library raises at import of the first call.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbcast_dual.so")
+
+MAX_DIMS = 4
+MAX_ARGS = 20
+MAX_OUTS = 4
+MAX_PLANES = 40
+F32, F64 = 0, 1
+
+
+class BcastTensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("ndim", ctypes.c_int32),
+                ("shape", ctypes.c_int64 * MAX_DIMS), ("stride", ctypes.c_int64 * MAX_DIMS)]
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("vec", ctypes.c_int32), ("ndim", ctypes.c_int32),
+                ("shape", ctypes.c_int64 * MAX_DIMS), ("tx", ctypes.c_int32), ("ty", ctypes.c_int32),
+                ("rows_per_block", ctypes.c_int32), ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64),
+                ("n_launches", ctypes.c_int32), ("n_second_pass", ctypes.c_int32)]
+
+    def as_dict(self):
+        d = {k: getattr(self, k) for k, _ in self._fields_ if k != "shape"}
+        d["shape"] = list(self.shape)[: self.ndim]
+        return d
+
+
+class BcastError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
+           "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
+           "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
+           "bcast_dual_get_tuning", "bcast_dual_copy_probe")
+
+
+def lib():
+    """Load the library built in-tree; building is a separate, explicit step."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_1810_08297_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.bcast_op_name.restype = ctypes.c_char_p
+        L.bcast_status_string.restype = ctypes.c_char_p
+        L.bcast_dual_backward_workspace.restype = ctypes.c_size_t
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().bcast_status_string(ctypes.c_int(status)).decode()
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise BcastError(rc, where)
+
+
+# ---- op table ------------------------------------------------------------------------------
+def bcast_op_lookup(name: str) -> int:
+    op = ctypes.c_int32()
+    _check(lib().bcast_op_lookup(name.encode(), ctypes.byref(op)), f"bcast_op_lookup({name!r})")
+    return op.value
+
+
+def bcast_op_count() -> int:
+    return lib().bcast_op_count()
+
+
+def bcast_op_name(op_id: int) -> Optional[str]:
+    s = lib().bcast_op_name(ctypes.c_int32(op_id))
+    return None if s is None else s.decode()
+
+
+def bcast_op_info(op_id: int):
+    """(n_args, n_outputs, nondiff_mask, n_branches)"""
+    a, m, nb = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    mask = ctypes.c_uint32()
+    _check(lib().bcast_op_info(ctypes.c_int32(op_id), ctypes.byref(a), ctypes.byref(m), ctypes.byref(mask),
+                               ctypes.byref(nb)), "bcast_op_info")
+    return a.value, m.value, mask.value, nb.value
+
+
+def diff_arg_indices(op_id: int):
+    n, _, mask, _ = bcast_op_info(op_id)
+    return [j for j in range(n) if not (mask >> j) & 1]
+
+
+# ---- marshalling -----------------------------------------------------------------------------
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.float64:
+        return F64
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def as_view(t) -> BcastTensor:
+    """torch tensor (or None = absent) -> bcast_tensor; strides are already in elements."""
+    v = BcastTensor()
+    if t is None:
+        v.data, v.ndim = None, 0
+        return v
+    if t.dim() > MAX_DIMS:
+        raise BcastError(-4, "as_view")
+    v.data = t.data_ptr()
+    v.ndim = t.dim()
+    for d in range(t.dim()):
+        v.shape[d] = t.shape[d]
+        v.stride[d] = t.stride(d)
+    return v
+
+
+def raw_view(ptr, shape, stride) -> BcastTensor:
+    v = BcastTensor()
+    v.data, v.ndim = ptr, len(shape)
+    for d in range(len(shape)):
+        v.shape[d], v.stride[d] = shape[d], stride[d]
+    return v
+
+
+def _views(ts: Sequence, like=None):
+    arr = (BcastTensor * max(1, len(ts)))()
+    for k, t in enumerate(ts):
+        arr[k] = t if isinstance(t, BcastTensor) else as_view(t)
+        if t is None and like is not None:  # an absent plane keeps the common shape
+            arr[k].ndim = like.ndim
+            for d in range(like.ndim):
+                arr[k].shape[d] = like.shape[d]
+    return arr
+
+
+def _stream_ptr(stream):
+    if isinstance(stream, int):  # a raw hipStream_t (0 = the default stream)
+        return ctypes.c_void_p(stream)
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+# ---- forward ----------------------------------------------------------------------------------
+def bcast_dual_forward(op_id: int, args: Sequence, outs: Sequence, partials: Optional[Sequence],
+                       branch_id=None, stream=None) -> None:
+    """Enqueue the dual-number forward kernel.  All buffers are caller-allocated."""
+    dt = _dtype_code(outs[0])
+    a = _views(args)
+    o = _views(outs)
+    p = _views(partials, o[0]) if partials is not None else None
+    _check(lib().bcast_dual_forward(
+        ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), a, ctypes.c_int32(len(outs)), o,
+        p, ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None), _stream_ptr(stream)),
+        "bcast_dual_forward")
+
+
+def bcast_dual_forward_plan(op_id: int, args, outs, partials, branch_id=None) -> dict:
+    dt = _dtype_code(outs[0])
+    a, o = _views(args), _views(outs)
+    p = _views(partials, o[0]) if partials is not None else None
+    info = PlanInfo()
+    _check(lib().bcast_dual_forward_plan(
+        ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), a, ctypes.c_int32(len(outs)), o,
+        p, ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None), ctypes.byref(info)),
+        "bcast_dual_forward_plan")
+    return info.as_dict()
+
+
+# ---- backward ---------------------------------------------------------------------------------
+def bcast_dual_backward_workspace(adjoints, partials, grads) -> int:
+    dt = _dtype_code(adjoints[0])
+    a = _views(adjoints)
+    return int(lib().bcast_dual_backward_workspace(
+        ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
+        ctypes.c_int32(len(grads)), _views(grads)))
+
+
+def bcast_dual_backward(adjoints, partials, grads, workspace=None, stream=None) -> None:
+    """Enqueue adjoint x partial with the broadcast-dim reductions.  ``workspace`` is a
+    uint8 device tensor of at least bcast_dual_backward_workspace(...) bytes (or None)."""
+    dt = _dtype_code(adjoints[0])
+    a = _views(adjoints)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().bcast_dual_backward(
+        ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
+        ctypes.c_int32(len(grads)), _views(grads), ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes),
+        _stream_ptr(stream)), "bcast_dual_backward")
+
+
+def bcast_dual_backward_plan(adjoints, partials, grads) -> dict:
+    dt = _dtype_code(adjoints[0])
+    a = _views(adjoints)
+    info = PlanInfo()
+    _check(lib().bcast_dual_backward_plan(
+        ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
+        ctypes.c_int32(len(grads)), _views(grads), ctypes.byref(info)), "bcast_dual_backward_plan")
+    return info.as_dict()
+
+
+# ---- misc -------------------------------------------------------------------------------------
+def bcast_dual_set_tuning(key: int, value: int) -> None:
+    _check(lib().bcast_dual_set_tuning(ctypes.c_int32(key), ctypes.c_int32(value)), "bcast_dual_set_tuning")
+
+
+def bcast_dual_get_tuning(key: int) -> int:
+    v = ctypes.c_int32()
+    _check(lib().bcast_dual_get_tuning(ctypes.c_int32(key), ctypes.byref(v)), "bcast_dual_get_tuning")
+    return v.value
+
+
+def bcast_dual_copy_probe(dst, src, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().bcast_dual_copy_probe(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
+                                       ctypes.c_size_t(nbytes), _stream_ptr(stream)), "bcast_dual_copy_probe")

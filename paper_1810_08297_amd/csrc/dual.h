@@ -1,0 +1,218 @@
+// Multidimensional dual numbers for device code (Sec. 2.2.1 of arXiv 1810.08297).
+//
+// x + sum_k y_k eps_k with eps_i eps_j = 0.  A Dual carries its value and one partial
+// per perturbation it can depend on.  WHICH perturbations those are is part of the
+// type (MASK, one bit per differentiable argument of the broadcast): the sum of two
+// duals has the union of their masks, a seed has one bit.  Partials that are
+// structurally zero therefore never occupy a register and are never multiplied --
+// the dead-partial elimination does not depend on floating-point folding rules.
+// Comparisons read the value part only, so control flow adds no derivative.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+#include <utility>
+
+namespace bd {
+
+#define BD_DEV __device__ __forceinline__
+
+constexpr int BD_MAX_BITS = 20;
+
+constexpr int popc(uint32_t m) { return __builtin_popcount(m); }
+constexpr int slot_of(uint32_t mask, int bit) { return popc(mask & ((1u << bit) - 1u)); }
+
+template <int I, int N, class F>
+BD_DEV void static_for(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// ---- scalar math in the working precision ------------------------------------------
+template <class T> struct smath;
+template <> struct smath<float> {
+  static BD_DEV float exp(float x) { return ::expf(x); }
+  static BD_DEV float log1p(float x) { return ::log1pf(x); }
+  static BD_DEV float sin(float x) { return ::sinf(x); }
+  static BD_DEV float cos(float x) { return ::cosf(x); }
+  static BD_DEV float abs(float x) { return ::fabsf(x); }
+  static BD_DEV float copysign(float m, float s) { return ::copysignf(m, s); }
+  // hardware reciprocal (1 ulp) refined by one Newton step
+  static BD_DEV float rcp(float d) {
+    float r = __builtin_amdgcn_rcpf(d);
+    return ::fmaf(::fmaf(-d, r, 1.0f), r, r);
+  }
+};
+template <> struct smath<double> {
+  static BD_DEV double exp(double x) { return ::exp(x); }
+  static BD_DEV double log1p(double x) { return ::log1p(x); }
+  static BD_DEV double sin(double x) { return ::sin(x); }
+  static BD_DEV double cos(double x) { return ::cos(x); }
+  static BD_DEV double abs(double x) { return ::fabs(x); }
+  static BD_DEV double copysign(double m, double s) { return ::copysign(m, s); }
+  static BD_DEV double rcp(double d) { return 1.0 / d; }
+};
+
+// sigma(x) and sigma'(x) from e = exp(-|x|): no overflow, no cancellation
+template <class T>
+BD_DEV void sigmoid_vd(T x, T &s, T &ds) {
+  T e = smath<T>::exp(-smath<T>::abs(x));
+  T r = smath<T>::rcp(T(1) + e);
+  T er = e * r;
+  s = x >= T(0) ? r : er;
+  ds = er * r;
+}
+// tanh(x) and 1 - tanh^2(x) from q = exp(-2|x|): the derivative keeps full relative
+// accuracy where tanh saturates
+template <class T>
+BD_DEV void tanh_vd(T x, T &t, T &dt) {
+  T q = smath<T>::exp(T(-2) * smath<T>::abs(x));
+  T r = smath<T>::rcp(T(1) + q);
+  t = smath<T>::copysign((T(1) - q) * r, x);
+  dt = T(4) * q * r * r;
+}
+
+// ---- the dual type -------------------------------------------------------------------
+template <class T, uint32_t MASK>
+struct Dual {
+  using value_type = T;
+  static constexpr uint32_t mask = MASK;
+  static constexpr int K = popc(MASK);
+  T v;
+  T d[K > 0 ? K : 1];
+
+  BD_DEV Dual() {}
+  BD_DEV explicit Dual(T value) : v(value) {
+    for (int k = 0; k < (K > 0 ? K : 1); ++k) d[k] = T(0);
+  }
+  // widening: a dual that depends on fewer perturbations, zero elsewhere
+  template <uint32_t SUB, class = std::enable_if_t<(SUB & ~MASK) == 0 && SUB != MASK>>
+  BD_DEV Dual(const Dual<T, SUB> &o) : v(o.v) {
+    static_for<0, BD_MAX_BITS>([&](auto B) {
+      constexpr int bit = decltype(B)::value;
+      if constexpr ((MASK >> bit) & 1u) d[slot_of(MASK, bit)] = o.template partial<bit>();
+    });
+  }
+  // tangent extraction (the tg operator of Sec. 2.2.1) for one perturbation
+  template <int BIT>
+  BD_DEV T partial() const {
+    if constexpr ((MASK >> BIT) & 1u)
+      return d[slot_of(MASK, BIT)];
+    else
+      return T(0);
+  }
+};
+
+template <class X> struct is_dual : std::false_type {};
+template <class T, uint32_t M> struct is_dual<Dual<T, M>> : std::true_type {};
+
+// seed x + eps_bit
+template <class T, int BIT>
+BD_DEV Dual<T, (1u << BIT)> seed(T x) {
+  Dual<T, (1u << BIT)> r;
+  r.v = x;
+  r.d[0] = T(1);
+  return r;
+}
+
+// r = value v with partials fa(a') + fb(b') over the union of the masks
+template <class T, uint32_t MA, uint32_t MB, class FA, class FB>
+BD_DEV Dual<T, (MA | MB)> zip(T v, const Dual<T, MA> &a, const Dual<T, MB> &b, FA fa, FB fb) {
+  constexpr uint32_t MR = MA | MB;
+  Dual<T, MR> r;
+  r.v = v;
+  static_for<0, BD_MAX_BITS>([&](auto B) {
+    constexpr int bit = decltype(B)::value;
+    if constexpr ((MR >> bit) & 1u) {
+      constexpr bool ina = (MA >> bit) & 1u, inb = (MB >> bit) & 1u;
+      if constexpr (ina && inb)
+        r.d[slot_of(MR, bit)] = fa(a.template partial<bit>()) + fb(b.template partial<bit>());
+      else if constexpr (ina)
+        r.d[slot_of(MR, bit)] = fa(a.template partial<bit>());
+      else
+        r.d[slot_of(MR, bit)] = fb(b.template partial<bit>());
+    }
+  });
+  return r;
+}
+// unary chain rule: f(x + y eps) = f(x) + f'(x) y eps
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> chain(T v, T dv, const Dual<T, MA> &a) {
+  Dual<T, MA> r;
+  r.v = v;
+  for (int k = 0; k < Dual<T, MA>::K; ++k) r.d[k] = dv * a.d[k];
+  return r;
+}
+
+// ---- arithmetic ---------------------------------------------------------------------
+template <class T, uint32_t MA, uint32_t MB>
+BD_DEV auto operator+(const Dual<T, MA> &a, const Dual<T, MB> &b) {
+  return zip(a.v + b.v, a, b, [](T x) { return x; }, [](T x) { return x; });
+}
+template <class T, uint32_t MA, uint32_t MB>
+BD_DEV auto operator-(const Dual<T, MA> &a, const Dual<T, MB> &b) {
+  return zip(a.v - b.v, a, b, [](T x) { return x; }, [](T x) { return -x; });
+}
+template <class T, uint32_t MA, uint32_t MB>
+BD_DEV auto operator*(const Dual<T, MA> &a, const Dual<T, MB> &b) {
+  const T av = a.v, bv = b.v;
+  return zip(av * bv, a, b, [bv](T x) { return x * bv; }, [av](T x) { return x * av; });
+}
+template <class T, uint32_t MA, uint32_t MB>
+BD_DEV auto operator/(const Dual<T, MA> &a, const Dual<T, MB> &b) {
+  const T inv = smath<T>::rcp(b.v);
+  const T q = a.v * inv;
+  const T mq = -q * inv;
+  return zip(q, a, b, [inv](T x) { return x * inv; }, [mq](T x) { return x * mq; });
+}
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator-(const Dual<T, MA> &a) { return chain(-a.v, T(-1), a); }
+
+// dual (op) plain scalar
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator+(const Dual<T, MA> &a, T s) { Dual<T, MA> r = a; r.v = a.v + s; return r; }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator+(T s, const Dual<T, MA> &a) { return a + s; }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator-(const Dual<T, MA> &a, T s) { Dual<T, MA> r = a; r.v = a.v - s; return r; }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator-(T s, const Dual<T, MA> &a) { return chain(s - a.v, T(-1), a); }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator*(const Dual<T, MA> &a, T s) { return chain(a.v * s, s, a); }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> operator*(T s, const Dual<T, MA> &a) { return chain(a.v * s, s, a); }
+
+// ---- comparisons: value part only -----------------------------------------------------
+template <class X> BD_DEV auto val(const X &x) {
+  if constexpr (is_dual<X>::value) return x.v; else return x;
+}
+#define BD_CMP(OP)                                                                              \
+  template <class A, class B, class = std::enable_if_t<is_dual<A>::value || is_dual<B>::value>> \
+  BD_DEV bool operator OP(const A &a, const B &b) { return val(a) OP val(b); }
+BD_CMP(>)
+BD_CMP(<)
+BD_CMP(>=)
+BD_CMP(<=)
+BD_CMP(==)
+BD_CMP(!=)
+#undef BD_CMP
+
+// ---- elementary functions -------------------------------------------------------------
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> exp(const Dual<T, MA> &a) { T e = smath<T>::exp(a.v); return chain(e, e, a); }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> log1p(const Dual<T, MA> &a) {
+  return chain(smath<T>::log1p(a.v), smath<T>::rcp(T(1) + a.v), a);
+}
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> sin(const Dual<T, MA> &a) { return chain(smath<T>::sin(a.v), smath<T>::cos(a.v), a); }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> cos(const Dual<T, MA> &a) { return chain(smath<T>::cos(a.v), -smath<T>::sin(a.v), a); }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> sigmoid(const Dual<T, MA> &a) { T s, ds; sigmoid_vd(a.v, s, ds); return chain(s, ds, a); }
+template <class T, uint32_t MA>
+BD_DEV Dual<T, MA> tanh(const Dual<T, MA> &a) { T t, dt; tanh_vd(a.v, t, dt); return chain(t, dt, a); }
+
+}  // namespace bd

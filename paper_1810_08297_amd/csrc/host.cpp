@@ -1,0 +1,737 @@
+// Host side of the library: the op table, argument validation, the broadcast plan
+// (shape unification, stride-0 expansion, dim merging -- Sec. 2.1.1 of arXiv 1810.08297:
+// size-1 dims are virtually copied and arguments are indexed directly, never materialised),
+// launch geometry, and the extern "C" entry points.  Nothing here touches device memory;
+// everything is validated before the first launch.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <array>
+#include <cstring>
+#include <vector>
+
+#include "bcast_dual.h"
+#include "kparams.h"
+
+using namespace bd;
+
+// ---- launchers defined in the kernel translation units ----------------------------------
+#define BD_DECLARE_OP(IDENT)                                                                        \
+  hipError_t bd_fwd_tiled_##IDENT(int, int, const FwdTiledParams &, dim3, hipStream_t);             \
+  hipError_t bd_fwd_generic_##IDENT(int, const FwdGenericParams &, dim3, hipStream_t);
+#define BD_ARITY_LIST(X) \
+  X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18)
+BD_DECLARE_OP(hmlstm_update)
+BD_DECLARE_OP(update_c)
+BD_DECLARE_OP(tanh_xy_b)
+BD_DECLARE_OP(branchy5)
+BD_DECLARE_OP(cos_x)
+BD_DECLARE_OP(scale_xt)
+BD_DECLARE_OP(pair3)
+#define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K)
+BD_ARITY_LIST(BD_DECL_ARITY)
+
+hipError_t bd_bwd_tiled(int dt, int vec, const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
+hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
+hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
+hipError_t bd_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t s);
+
+namespace {
+
+struct OpDesc {
+  const char *name;
+  int n_args, n_out;
+  uint32_t nondiff;
+  int n_branches;
+  hipError_t (*tiled)(int, int, const FwdTiledParams &, dim3, hipStream_t);
+  hipError_t (*generic)(int, const FwdGenericParams &, dim3, hipStream_t);
+};
+
+#define BD_OP_ROW(NAME, N, M, NONDIFF, NBR) {#NAME, N, M, NONDIFF, NBR, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME},
+#define BD_ARITY_ROW(K) BD_OP_ROW(prod_tanh_##K, K, 1, 0u, K + 1)
+const OpDesc kOps[] = {
+    BD_OP_ROW(hmlstm_update, 12, 2, (1u << 6) | (1u << 7), 3)
+    BD_OP_ROW(tanh_xy_b, 3, 1, 0u, 1)
+    BD_OP_ROW(branchy5, 5, 1, 0u, 2)
+    BD_OP_ROW(update_c, 6, 1, (1u << 4) | (1u << 5), 3)
+    BD_OP_ROW(cos_x, 1, 1, 0u, 1)
+    BD_OP_ROW(scale_xt, 2, 1, 0u, 1)
+    BD_OP_ROW(pair3, 3, 2, 0u, 1)
+    BD_ARITY_LIST(BD_ARITY_ROW)};
+constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
+
+// ---- tuning overrides ------------------------------------------------------------------------
+int g_tune[4] = {0, 0, 1, 0};
+
+// ---- small helpers ---------------------------------------------------------------------------
+inline size_t elem_size(int dt) { return dt == BCAST_F32 ? 4 : 8; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int ilog2_ceil(int64_t x) {
+  int l = 0;
+  while (((int64_t)1 << l) < x) ++l;
+  return l;
+}
+inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+using Dims = std::array<int64_t, BCAST_MAX_DIMS>;
+
+// A view padded to the common rank D with trailing size-1 dims.
+struct PView {
+  void *p = nullptr;
+  Dims shape{{1, 1, 1, 1}};
+  Dims stride{{0, 0, 0, 0}};
+};
+
+int check_view(const bcast_tensor &t, size_t esize, bool allow_null, bool written, PView &out) {
+  if (t.ndim < 0 || t.ndim > BCAST_MAX_DIMS) return BCAST_ERR_RANK_TOO_HIGH;
+  bool empty = false;
+  for (int d = 0; d < t.ndim; ++d) empty |= (t.shape[d] == 0);
+  if (t.data == nullptr && !allow_null && !empty) return BCAST_ERR_NULL_POINTER;
+  if (reinterpret_cast<uintptr_t>(t.data) % esize != 0) return BCAST_ERR_MISALIGNED;
+  out.p = t.data;
+  for (int d = 0; d < t.ndim; ++d) {
+    if (t.shape[d] < 0) return BCAST_ERR_SHAPE_MISMATCH;
+    out.shape[d] = t.shape[d];
+    out.stride[d] = t.shape[d] == 1 ? 0 : t.stride[d];
+    if (out.stride[d] < 0) return BCAST_ERR_BAD_STRIDE;
+  }
+  if (written && t.data != nullptr) {
+    // every written element must have its own address
+    std::vector<std::pair<int64_t, int64_t>> se;
+    for (int d = 0; d < t.ndim; ++d)
+      if (t.shape[d] > 1) se.emplace_back(t.stride[d], t.shape[d]);
+    std::sort(se.begin(), se.end());
+    int64_t reach = 0;
+    for (auto &q : se) {
+      if (q.first <= reach) return BCAST_ERR_BAD_STRIDE;
+      reach += (q.second - 1) * q.first;
+    }
+  }
+  return BCAST_OK;
+}
+
+// The merged problem: dims of extent 1 dropped, the rest ordered by the key tensor's
+// stride (largest first) and adjacent dims fused wherever every tensor allows it.
+struct Canon {
+  int nd = 0;
+  Dims shape{{1, 1, 1, 1}};
+  int64_t E = 1;
+  std::vector<Dims> strides;  // per tensor, merged dims, outermost first
+};
+
+void canonicalize(int D, const Dims &U, const std::vector<Dims> &eff, int key, Canon &c) {
+  std::vector<int> order;
+  for (int d = 0; d < D; ++d)
+    if (U[d] > 1) order.push_back(d);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return eff[key][a] > eff[key][b]; });
+  std::vector<int64_t> shp;
+  std::vector<Dims> st(eff.size());
+  std::vector<std::vector<int64_t>> cur(eff.size());
+  for (int d : order) {
+    bool merge = !shp.empty();
+    if (merge)
+      for (size_t t = 0; t < eff.size() && merge; ++t) merge = (cur[t].back() == eff[t][d] * U[d]);
+    if (merge) {
+      shp.back() *= U[d];
+      for (size_t t = 0; t < eff.size(); ++t) cur[t].back() = eff[t][d];
+    } else {
+      shp.push_back(U[d]);
+      for (size_t t = 0; t < eff.size(); ++t) cur[t].push_back(eff[t][d]);
+    }
+  }
+  c.nd = (int)shp.size();
+  c.E = 1;
+  for (int d = 0; d < c.nd; ++d) {
+    c.shape[d] = shp[d];
+    c.E *= shp[d];
+  }
+  c.strides.assign(eff.size(), Dims{{0, 0, 0, 0}});
+  for (size_t t = 0; t < eff.size(); ++t)
+    for (int d = 0; d < c.nd; ++d) c.strides[t][d] = cur[t][d];
+}
+
+// rows / columns of a merged problem of rank <= 2, and one tensor's strides in it
+struct Shape2 {
+  int64_t R = 1, C = 1;
+};
+inline Shape2 shape2(const Canon &c) {
+  Shape2 s;
+  if (c.nd == 1) s.C = c.shape[0];
+  if (c.nd == 2) { s.R = c.shape[0]; s.C = c.shape[1]; }
+  return s;
+}
+inline TView tview(const Canon &c, size_t t, void *p) {
+  TView v{p, 0, 0};
+  if (c.nd == 1) v.sc = c.strides[t][0];
+  if (c.nd == 2) { v.sr = c.strides[t][0]; v.sc = c.strides[t][1]; }
+  return v;
+}
+inline GView gview(const Canon &c, size_t t, void *p) {
+  GView v{p, {0, 0, 0, 0}};
+  for (int d = 0; d < c.nd; ++d) v.s[d] = c.strides[t][d];
+  return v;
+}
+
+struct Geometry {
+  int vec = 1, log2_tx = 0, steps = 1;
+  int64_t n_ct = 1, n_rt = 1;
+};
+
+// lanes along the columns: the smallest power of two covering the row, at most a block
+void tile_columns(int64_t C, int vec, Geometry &g) {
+  const int64_t units = ceil_div(C, vec);
+  g.log2_tx = std::min(8, ilog2_ceil(units));
+  g.n_ct = ceil_div(units, (int64_t)1 << g.log2_tx);
+}
+// false if the problem needs more blocks than one launch can have
+bool tile_rows(int64_t R, int steps, Geometry &g) {
+  const int TY = kBlock >> g.log2_tx;
+  const int64_t row_steps = ceil_div(R, TY);
+  steps = (int)std::max<int64_t>(1, std::min<int64_t>(steps, row_steps));
+  g.steps = steps;
+  g.n_rt = ceil_div(row_steps, steps);
+  return g.n_ct <= 0x7fffffffLL && g.n_rt <= 0x7fffffffLL / g.n_ct;
+}
+// enough blocks to fill 256 CUs several times over, a few rows per block to amortise
+// the per-block set-up
+int auto_steps(int64_t R, const Geometry &g, int max_steps) {
+  const int TY = kBlock >> g.log2_tx;
+  const int64_t row_steps = ceil_div(R, TY);
+  const int64_t want_blocks = 256 * 16;
+  int64_t s = (row_steps * g.n_ct) / want_blocks;
+  return (int)std::max<int64_t>(1, std::min<int64_t>(s, max_steps));
+}
+
+// ---- forward planning ----------------------------------------------------------------------------
+struct FwdPlan {
+  bcast_plan_info info{};
+  bool tiled = false;
+  FwdTiledParams tp{};
+  FwdGenericParams gp{};
+  dim3 grid{1, 1, 1};
+};
+
+int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args, int32_t n_out,
+                 const bcast_tensor *outs, const bcast_tensor *partials, const uint8_t *branch_id,
+                 FwdPlan &plan) {
+  if (op_id < 0 || op_id >= kNumOps) return BCAST_ERR_INVALID_OP;
+  if (dt != BCAST_F32 && dt != BCAST_F64) return BCAST_ERR_BAD_DTYPE;
+  const OpDesc &op = kOps[op_id];
+  if (n_args != op.n_args || n_out != op.n_out) return BCAST_ERR_BAD_ARG_COUNT;
+  if (args == nullptr || outs == nullptr) return BCAST_ERR_NULL_POINTER;
+  const size_t es = elem_size(dt);
+  const int N = op.n_args, M = op.n_out;
+  const int ND = N - __builtin_popcount(op.nondiff);
+  const int n_planes = partials ? M * ND : 0;
+
+  std::vector<PView> v(N + M + n_planes);
+  int D = 0;
+  for (int j = 0; j < N; ++j) {
+    if (int rc = check_view(args[j], es, false, false, v[j])) return rc;
+    D = std::max(D, args[j].ndim);
+  }
+  for (int i = 0; i < M; ++i) {
+    if (int rc = check_view(outs[i], es, false, true, v[N + i])) return rc;
+    D = std::max(D, outs[i].ndim);
+  }
+  for (int k = 0; k < n_planes; ++k) {
+    if (int rc = check_view(partials[k], es, true, true, v[N + M + k])) return rc;
+    D = std::max(D, partials[k].ndim);
+  }
+  // unified shape: per dim the extent that is not 1 (all such must agree)
+  Dims U{{1, 1, 1, 1}};
+  for (int d = 0; d < D; ++d)
+    for (int j = 0; j < N; ++j) {
+      const int64_t s = v[j].shape[d];
+      if (s == 1) continue;
+      if (U[d] == 1) U[d] = s;
+      else if (U[d] != s) return BCAST_ERR_SHAPE_MISMATCH;
+    }
+  bool E0 = false;
+  for (int d = 0; d < D; ++d) E0 |= (U[d] == 0);
+  for (size_t t = N; t < v.size(); ++t)
+    if ((v[t].p || (E0 && t < (size_t)(N + M))) && v[t].shape != U) return BCAST_ERR_OUTPUT_SHAPE_MISMATCH;
+
+  int64_t E = 1;
+  for (int d = 0; d < D; ++d) E *= U[d];
+  plan.info = bcast_plan_info{};
+  if (E == 0) return BCAST_OK;
+
+  // effective strides: stride 0 wherever an argument's dim is 1 (virtual copy)
+  std::vector<Dims> eff;
+  for (auto &pv : v) eff.push_back(pv.p ? pv.stride : v[N].stride);  // absent planes never block a merge
+  const bool want_branch = branch_id != nullptr;
+  if (want_branch) {  // row-major over the unified shape as given
+    Dims bs{{0, 0, 0, 0}};
+    int64_t acc = 1;
+    for (int d = D - 1; d >= 0; --d) {
+      bs[d] = U[d] > 1 ? acc : 0;
+      acc *= U[d];
+    }
+    eff.push_back(bs);
+  }
+  Canon c;
+  canonicalize(D, U, eff, N /* key: the first output */, c);
+  plan.info.ndim = c.nd;
+  for (int d = 0; d < c.nd; ++d) plan.info.shape[d] = c.shape[d];
+
+  bool tiled = (c.nd <= 2) && !g_tune[3];
+  const Shape2 s2 = shape2(c);
+  if (tiled && s2.C > 1) {
+    for (int j = 0; j < N && tiled; ++j) {
+      const int64_t sc = tview(c, j, nullptr).sc;
+      tiled = (sc == 0 || sc == 1);
+    }
+    for (size_t t = N; t < v.size() && tiled; ++t)
+      if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
+  }
+  plan.tiled = tiled;
+  if (tiled) {
+    FwdTiledParams &p = plan.tp;
+    p.R = s2.R;
+    p.C = s2.C;
+    const int vw = (int)(16 / es);
+    bool vec_ok = (s2.C % vw == 0);
+    for (size_t t = 0; t < v.size() && vec_ok; ++t) {
+      if (!v[t].p) continue;
+      const TView tv = tview(c, t, v[t].p);
+      if (tv.sc == 0 && s2.C > 1) continue;  // a broadcast load: one element
+      vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % 16 == 0) && (s2.R == 1 || tv.sr % vw == 0);
+    }
+    Geometry g;
+    g.vec = vec_ok ? vw : 1;
+    tile_columns(s2.C, g.vec, g);
+    if (!tile_rows(s2.R, g_tune[0] > 0 ? g_tune[0] : auto_steps(s2.R, g, 4), g)) return BCAST_ERR_LAUNCH_FAILED;
+    p.n_ct = g.n_ct;
+    p.log2_tx = g.log2_tx;
+    p.steps = g.steps;
+    p.nt_store = g_tune[2];
+    p.has_partials = n_planes > 0;
+    for (int j = 0; j < N; ++j) p.arg[j] = tview(c, j, v[j].p);
+    for (int i = 0; i < M; ++i) p.out[i] = tview(c, N + i, v[N + i].p);
+    for (int k = 0; k < n_planes; ++k) p.part[k] = tview(c, N + M + k, v[N + M + k].p);
+    p.branch = want_branch ? tview(c, v.size(), const_cast<uint8_t *>(branch_id)) : TView{nullptr, 0, 0};
+    plan.grid = dim3((unsigned)(g.n_ct * g.n_rt), 1, 1);
+    plan.info.path = 1;
+    plan.info.vec = g.vec;
+    plan.info.tx = 1 << g.log2_tx;
+    plan.info.ty = kBlock >> g.log2_tx;
+    plan.info.rows_per_block = plan.info.ty * g.steps;
+    plan.info.grid_x = g.n_ct;
+    plan.info.grid_y = g.n_rt;
+  } else {
+    FwdGenericParams &p = plan.gp;
+    p.nd = c.nd;
+    for (int d = 0; d < BCAST_MAX_DIMS; ++d) p.shape[d] = d < c.nd ? c.shape[d] : 1;
+    p.E = c.E;
+    for (int j = 0; j < N; ++j) p.arg[j] = gview(c, j, v[j].p);
+    for (int i = 0; i < M; ++i) p.out[i] = gview(c, N + i, v[N + i].p);
+    for (int k = 0; k < M * ND; ++k)
+      p.part[k] = k < n_planes ? gview(c, N + M + k, v[N + M + k].p) : GView{nullptr, {0, 0, 0, 0}};
+    p.branch = want_branch ? gview(c, v.size(), const_cast<uint8_t *>(branch_id)) : GView{nullptr, {0, 0, 0, 0}};
+    const int64_t blocks = ceil_div(c.E, kBlock);
+    if (blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
+    plan.grid = dim3((unsigned)blocks, 1, 1);
+    plan.info.path = 2;
+    plan.info.vec = 1;
+    plan.info.tx = kBlock;
+    plan.info.ty = 1;
+    plan.info.rows_per_block = 1;
+    plan.info.grid_x = blocks;
+    plan.info.grid_y = 1;
+  }
+  plan.info.n_launches = 1;
+  return BCAST_OK;
+}
+
+// ---- backward planning ---------------------------------------------------------------------------
+constexpr size_t kLdsBudget = 48 * 1024;
+
+struct BwdPlan {
+  bcast_plan_info info{};
+  bool tiled = false;
+  int vec = 1;
+  std::vector<BwdTiledParams> main;  // usually one launch
+  std::vector<size_t> main_lds;
+  dim3 grid{1, 1, 1};
+  Pass2Params p2{};
+  int64_t p2_blocks = 0;
+  std::vector<std::pair<bool, BwdGenericParams>> generic;  // (is reduction, params)
+  std::vector<int64_t> generic_blocks;
+  size_t ws_bytes = 0;
+};
+
+int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bcast_tensor *partials,
+                  int32_t n_grads, const bcast_tensor *grads, BwdPlan &plan) {
+  if (dt != BCAST_F32 && dt != BCAST_F64) return BCAST_ERR_BAD_DTYPE;
+  if (n_out < 1 || n_out > BCAST_MAX_OUTS || n_grads < 1 || n_grads > BCAST_MAX_ARGS ||
+      n_out * n_grads > BCAST_MAX_PLANES)
+    return BCAST_ERR_BAD_ARG_COUNT;
+  if (adjoints == nullptr || partials == nullptr || grads == nullptr) return BCAST_ERR_NULL_POINTER;
+  const size_t es = elem_size(dt);
+  const size_t as = dt == BCAST_F32 ? 8 : 16;  // accumulator bytes
+  const int M = n_out, ND = n_grads;
+  std::vector<PView> v(M + M * ND + ND);
+  int D = 0;
+  for (int i = 0; i < M; ++i) {
+    if (int rc = check_view(adjoints[i], es, false, false, v[i])) return rc;
+    D = std::max(D, adjoints[i].ndim);
+  }
+  for (int k = 0; k < M * ND; ++k) {
+    if (int rc = check_view(partials[k], es, true, false, v[M + k])) return rc;
+    D = std::max(D, partials[k].ndim);
+  }
+  for (int j = 0; j < ND; ++j) {
+    if (int rc = check_view(grads[j], es, true, true, v[M + M * ND + j])) return rc;
+    D = std::max(D, grads[j].ndim);
+  }
+  const Dims U = v[0].shape;
+  for (int t = 0; t < M + M * ND; ++t)
+    if (v[t].p && v[t].shape != U) return BCAST_ERR_OUTPUT_SHAPE_MISMATCH;
+  for (int j = 0; j < ND; ++j)
+    for (int d = 0; d < BCAST_MAX_DIMS && v[M + M * ND + j].p; ++d) {
+      const int64_t s = v[M + M * ND + j].shape[d];
+      if (s != U[d] && s != 1) return BCAST_ERR_OUTPUT_SHAPE_MISMATCH;
+    }
+  int64_t E = 1;
+  for (int d = 0; d < BCAST_MAX_DIMS; ++d) E *= U[d];
+  plan.info = bcast_plan_info{};
+  if (E == 0) return BCAST_OK;
+
+  std::vector<Dims> eff;
+  for (auto &pv : v) eff.push_back(pv.stride);
+  for (int k = 0; k < M * ND; ++k)
+    if (!v[M + k].p) eff[M + k] = eff[0];  // absent planes never block a merge
+  for (int j = 0; j < ND; ++j)
+    if (!v[M + M * ND + j].p) eff[M + M * ND + j] = eff[0];
+  Canon c;
+  (void)D;
+  canonicalize(BCAST_MAX_DIMS, U, eff, 0 /* key: the first adjoint */, c);
+  plan.info.ndim = c.nd;
+  for (int d = 0; d < c.nd; ++d) plan.info.shape[d] = c.shape[d];
+  const size_t g0 = M + M * ND;
+
+  const Shape2 s2 = shape2(c);
+  bool tiled = (c.nd <= 2) && !g_tune[3];
+  // class of each gradient in the 2-D picture
+  std::vector<int> cls(ND, kGradSkip);
+  if (tiled) {
+    for (int j = 0; j < ND; ++j) {
+      if (!v[g0 + j].p) continue;
+      const TView tv = tview(c, g0 + j, nullptr);
+      const bool rows_red = s2.R > 1 && tv.sr == 0;
+      const bool cols_red = s2.C > 1 && tv.sc == 0;
+      cls[j] = rows_red ? (cols_red ? kGradAllSum : kGradColSum) : (cols_red ? kGradRowSum : kGradFull);
+    }
+    if (s2.C > 1) {
+      for (int t = 0; t < M + M * ND && tiled; ++t)
+        if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
+      for (int j = 0; j < ND && tiled; ++j)
+        if (cls[j] == kGradFull) tiled = (tview(c, g0 + j, nullptr).sc == 1);
+    }
+  }
+  plan.tiled = tiled;
+  if (tiled) {
+    const int vw = (int)(16 / es);
+    bool vec_ok = (s2.C % vw == 0);
+    for (size_t t = 0; t < v.size() && vec_ok; ++t) {
+      if (!v[t].p) continue;
+      if (t >= g0 && cls[t - g0] != kGradFull) continue;  // reduced gradients are stored by element
+      const TView tv = tview(c, t, v[t].p);
+      vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % 16 == 0) && (s2.R == 1 || tv.sr % vw == 0);
+    }
+    Geometry g;
+    g.vec = vec_ok ? vw : 1;
+    plan.vec = g.vec;
+    tile_columns(s2.C, g.vec, g);
+    bool any_rowwise = false;  // sums over rows: worth many rows per block
+    int n_rowsum = 0;
+    for (int j = 0; j < ND; ++j) {
+      any_rowwise |= (cls[j] == kGradColSum || cls[j] == kGradAllSum);
+      n_rowsum += (cls[j] == kGradRowSum);
+    }
+    const int TY = kBlock >> g.log2_tx;
+    int steps = g_tune[1] > 0 ? g_tune[1] : (any_rowwise ? (int)ceil_div(32, TY) : auto_steps(s2.R, g, 4));
+    // rows wider than a wavefront park one accumulator per wavefront and row in LDS
+    const int wpr = g.log2_tx > 6 ? (1 << (g.log2_tx - 6)) : 1;
+    if (g.log2_tx > 6 && n_rowsum > 0) {
+      const int64_t max_rows = (int64_t)(kLdsBudget / 2) / ((int64_t)n_rowsum * wpr * as);
+      steps = (int)std::max<int64_t>(1, std::min<int64_t>(steps, max_rows / TY));
+    }
+    if (!tile_rows(s2.R, steps, g)) return BCAST_ERR_LAUNCH_FAILED;
+    plan.grid = dim3((unsigned)(g.n_ct * g.n_rt), 1, 1);
+    const int rows_pb = TY * g.steps;
+
+    // split the gradients over launches so that each launch's LDS accumulators fit
+    size_t ws = 0;
+    plan.p2.n_jobs = 0;
+    int64_t p2_blocks = 0;
+    BwdTiledParams cur{};
+    auto reset = [&](BwdTiledParams &p) {
+      p = BwdTiledParams{};
+      p.R = s2.R;
+      p.C = s2.C;
+      p.log2_tx = g.log2_tx;
+      p.steps = g.steps;
+      p.nt_store = g_tune[2];
+      p.M = M;
+      p.n_ct = g.n_ct;
+      p.n_rt = g.n_rt;
+      for (int i = 0; i < M; ++i) p.adj[i] = tview(c, i, v[i].p);
+    };
+    auto lds_need = [&](const BwdTiledParams &p, size_t &row_off, size_t &col_off, size_t &all_off) {
+      size_t o = 0;
+      row_off = o;
+      if (g.log2_tx > 6) o += align16((size_t)p.n_row_slots * rows_pb * wpr * as);
+      col_off = o;
+      o += align16((size_t)p.n_col_slots * kBlock * g.vec * as);
+      all_off = o;
+      o += align16((size_t)p.n_all_slots * kBlock * as);
+      return o;
+    };
+    auto flush = [&]() {
+      if (cur.n_entries == 0) return;
+      size_t ro, co, ao;
+      const size_t total = lds_need(cur, ro, co, ao);
+      cur.lds_row_off = (uint32_t)ro;
+      cur.lds_col_off = (uint32_t)co;
+      cur.lds_all_off = (uint32_t)ao;
+      plan.main.push_back(cur);
+      plan.main_lds.push_back(total);
+    };
+    reset(cur);
+    for (int j = 0; j < ND; ++j) {
+      if (cls[j] == kGradSkip) continue;
+      BwdTiledParams trial = cur;
+      trial.n_row_slots += (cls[j] == kGradRowSum);
+      trial.n_col_slots += (cls[j] == kGradColSum);
+      trial.n_all_slots += (cls[j] == kGradAllSum);
+      size_t ro, co, ao;
+      if (cur.n_entries > 0 && lds_need(trial, ro, co, ao) > kLdsBudget) {
+        flush();
+        reset(cur);
+      }
+      BwdEntry &en = cur.e[cur.n_entries++];
+      for (int i = 0; i < M; ++i) en.P[i] = tview(c, M + i * ND + j, v[M + i * ND + j].p);
+      en.g = tview(c, g0 + j, v[g0 + j].p);
+      en.cls = cls[j];
+      en.ws_off = 0;
+      en.direct = 1;
+      Pass2Job job{};
+      job.g = en.g.p;
+      if (cls[j] == kGradRowSum) {
+        en.slot = cur.n_row_slots++;
+        en.direct = g.n_ct == 1;
+        job = Pass2Job{en.g.p, en.g.sr, s2.R, g.n_ct, 1, g.n_ct, 0, 0, 0, g.n_ct <= 256 ? 0 : 1, 0};
+        job.n_blocks = job.kind == 0 ? ceil_div(s2.R, kBlock / 64) : s2.R;
+      } else if (cls[j] == kGradColSum) {
+        en.slot = cur.n_col_slots++;
+        en.direct = g.n_rt == 1;
+        job = Pass2Job{en.g.p, en.g.sc, s2.C, g.n_rt, s2.C, 1, 0, 0, ceil_div(s2.C, 64), 2, 0};
+      } else if (cls[j] == kGradAllSum) {
+        en.slot = cur.n_all_slots++;
+        en.direct = g.n_ct * g.n_rt == 1;
+        job = Pass2Job{en.g.p, 0, 1, g.n_ct * g.n_rt, 1, 0, 0, 0, 1, 1, 0};
+      }
+      if (!en.direct) {
+        en.ws_off = (int64_t)ws;
+        job.ws_off = (int64_t)ws;
+        job.first_block = p2_blocks;
+        p2_blocks += job.n_blocks;
+        ws += align16((size_t)job.n_out * job.n_part * as);
+        plan.p2.job[plan.p2.n_jobs++] = job;
+      }
+    }
+    flush();
+    if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
+    plan.p2_blocks = p2_blocks;
+    plan.ws_bytes = ws;
+    plan.info.path = 1;
+    plan.info.vec = g.vec;
+    plan.info.tx = 1 << g.log2_tx;
+    plan.info.ty = TY;
+    plan.info.rows_per_block = rows_pb;
+    plan.info.grid_x = g.n_ct;
+    plan.info.grid_y = g.n_rt;
+    plan.info.n_launches = (int)plan.main.size() + (p2_blocks > 0 ? 1 : 0);
+    plan.info.n_second_pass = plan.p2.n_jobs;
+  } else {
+    for (int j = 0; j < ND; ++j) {
+      if (!v[g0 + j].p) continue;
+      BwdGenericParams p{};
+      p.nd = c.nd;
+      p.M = M;
+      p.E = c.E;
+      for (int d = 0; d < BCAST_MAX_DIMS; ++d) p.shape[d] = d < c.nd ? c.shape[d] : 1;
+      for (int i = 0; i < M; ++i) {
+        p.adj[i] = gview(c, i, v[i].p);
+        p.P[i] = gview(c, M + i * ND + j, v[M + i * ND + j].p);
+      }
+      p.g = gview(c, g0 + j, v[g0 + j].p);
+      p.n_kept = 1;
+      p.n_fibre = 1;
+      bool reduce = false;
+      for (int d = 0; d < c.nd; ++d) {
+        p.reduced[d] = (p.g.s[d] == 0);
+        reduce |= p.reduced[d] != 0;
+        (p.reduced[d] ? p.n_fibre : p.n_kept) *= c.shape[d];
+      }
+      const int64_t blocks = reduce ? p.n_kept : ceil_div(c.E, kBlock);
+      if (blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
+      plan.generic.emplace_back(reduce, p);
+      plan.generic_blocks.push_back(blocks);
+    }
+    plan.info.path = 2;
+    plan.info.vec = 1;
+    plan.info.tx = kBlock;
+    plan.info.ty = 1;
+    plan.info.rows_per_block = 1;
+    plan.info.grid_x = plan.generic_blocks.empty() ? 0 : plan.generic_blocks[0];
+    plan.info.grid_y = 1;
+    plan.info.n_launches = (int)plan.generic.size();
+  }
+  return BCAST_OK;
+}
+
+}  // namespace
+
+// ---- the C ABI ---------------------------------------------------------------------------------------
+extern "C" {
+
+int bcast_op_count(void) { return kNumOps; }
+
+const char *bcast_op_name(int32_t op_id) { return (op_id >= 0 && op_id < kNumOps) ? kOps[op_id].name : nullptr; }
+
+int bcast_op_lookup(const char *name, int32_t *op_id) {
+  if (name == nullptr || op_id == nullptr) return BCAST_ERR_NULL_POINTER;
+  for (int k = 0; k < kNumOps; ++k)
+    if (std::strcmp(kOps[k].name, name) == 0) {
+      *op_id = k;
+      return BCAST_OK;
+    }
+  return BCAST_ERR_INVALID_OP;
+}
+
+int bcast_op_info(int32_t op_id, int32_t *n_args, int32_t *n_outputs, uint32_t *nondiff_mask,
+                  int32_t *n_branches) {
+  if (op_id < 0 || op_id >= kNumOps) return BCAST_ERR_INVALID_OP;
+  if (n_args) *n_args = kOps[op_id].n_args;
+  if (n_outputs) *n_outputs = kOps[op_id].n_out;
+  if (nondiff_mask) *nondiff_mask = kOps[op_id].nondiff;
+  if (n_branches) *n_branches = kOps[op_id].n_branches;
+  return BCAST_OK;
+}
+
+int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                            int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
+                            const uint8_t *branch_id, bcast_plan_info *info) {
+  if (info == nullptr) return BCAST_ERR_NULL_POINTER;
+  FwdPlan plan;
+  const int rc = plan_forward(op_id, (int)dt, n_args, args, n_out, outs, partials, branch_id, plan);
+  if (rc == BCAST_OK) *info = plan.info;
+  return rc;
+}
+
+int bcast_dual_forward(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                       int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
+                       uint8_t *branch_id, void *stream) {
+  FwdPlan plan;
+  const int rc = plan_forward(op_id, (int)dt, n_args, args, n_out, outs, partials, branch_id, plan);
+  if (rc != BCAST_OK) return rc;
+  if (plan.info.path == 0) return BCAST_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t err = plan.tiled ? kOps[op_id].tiled((int)dt, plan.info.vec, plan.tp, plan.grid, s)
+                              : kOps[op_id].generic((int)dt, plan.gp, plan.grid, s);
+  return err == hipSuccess ? BCAST_OK : BCAST_ERR_LAUNCH_FAILED;
+}
+
+size_t bcast_dual_backward_workspace(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                                     const bcast_tensor *partials, int32_t n_grads,
+                                     const bcast_tensor *grads) {
+  BwdPlan plan;
+  if (plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, plan) != BCAST_OK) return 0;
+  return plan.ws_bytes;
+}
+
+int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                             const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                             bcast_plan_info *info) {
+  if (info == nullptr) return BCAST_ERR_NULL_POINTER;
+  BwdPlan plan;
+  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, plan);
+  if (rc == BCAST_OK) *info = plan.info;
+  return rc;
+}
+
+int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                        const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                        void *workspace, size_t workspace_bytes, void *stream) {
+  BwdPlan plan;
+  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, plan);
+  if (rc != BCAST_OK) return rc;
+  if (plan.info.path == 0) return BCAST_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (plan.tiled) {
+    if (plan.ws_bytes > 0) {
+      if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
+      if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
+      if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
+    }
+    for (size_t k = 0; k < plan.main.size(); ++k) {
+      plan.main[k].ws = static_cast<unsigned char *>(workspace);
+      if (bd_bwd_tiled((int)dt, plan.vec, plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
+        return BCAST_ERR_LAUNCH_FAILED;
+    }
+    if (plan.p2_blocks > 0) {
+      plan.p2.ws = static_cast<unsigned char *>(workspace);
+      if (bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s) != hipSuccess) return BCAST_ERR_LAUNCH_FAILED;
+    }
+  } else {
+    for (size_t k = 0; k < plan.generic.size(); ++k)
+      if (bd_bwd_generic((int)dt, plan.generic[k].first, plan.generic[k].second, plan.generic_blocks[k], s) !=
+          hipSuccess)
+        return BCAST_ERR_LAUNCH_FAILED;
+  }
+  return BCAST_OK;
+}
+
+const char *bcast_status_string(int status) {
+  switch (status) {
+    case BCAST_OK: return "ok";
+    case BCAST_ERR_INVALID_OP: return "invalid op";
+    case BCAST_ERR_BAD_ARG_COUNT: return "wrong number of arguments, outputs or gradients";
+    case BCAST_ERR_NULL_POINTER: return "null pointer";
+    case BCAST_ERR_RANK_TOO_HIGH: return "rank exceeds BCAST_MAX_DIMS";
+    case BCAST_ERR_SHAPE_MISMATCH: return "argument shapes do not broadcast";
+    case BCAST_ERR_OUTPUT_SHAPE_MISMATCH: return "output, partial, adjoint or gradient view has the wrong shape";
+    case BCAST_ERR_BAD_DTYPE: return "unknown dtype";
+    case BCAST_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case BCAST_ERR_LAUNCH_FAILED: return "kernel launch failed";
+    case BCAST_ERR_BAD_STRIDE: return "negative stride or self-overlapping written view";
+    case BCAST_ERR_MISALIGNED: return "pointer not aligned";
+    default: return "unknown status";
+  }
+}
+
+int bcast_dual_set_tuning(int32_t key, int32_t value) {
+  static const int lo[4] = {0, 0, 0, 0}, hi[4] = {64, 256, 1, 1};
+  if (key < 0 || key > 3 || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
+  g_tune[key] = value;
+  return BCAST_OK;
+}
+int bcast_dual_get_tuning(int32_t key, int32_t *value) {
+  if (key < 0 || key > 3 || value == nullptr) return BCAST_ERR_BAD_ARG_COUNT;
+  *value = g_tune[key];
+  return BCAST_OK;
+}
+
+int bcast_dual_copy_probe(void *dst, const void *src, size_t bytes, void *stream) {
+  if (dst == nullptr || src == nullptr) return BCAST_ERR_NULL_POINTER;
+  if (bytes % 16 != 0 || reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
+    return BCAST_ERR_MISALIGNED;
+  if (bytes / 16 / kBlock > 0x7fffffffULL) return BCAST_ERR_LAUNCH_FAILED;
+  return bd_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? BCAST_OK
+                                                                                         : BCAST_ERR_LAUNCH_FAILED;
+}
+
+}  // extern "C"

@@ -1,0 +1,114 @@
+// Kernel argument blocks shared by the host planner and the HIP kernels.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bcast_dual.h"
+
+namespace bd {
+
+constexpr int kBlock = 256;  // threads per block of every tiled kernel (4 wavefronts)
+
+// A 2-D view used by the tiled kernels: element (r, c) lives at p + r*sr + c*sc.
+// For tensors read or written with vector instructions sc is 0 or 1.
+struct TView {
+  void *p;
+  int64_t sr;
+  int64_t sc;
+};
+
+struct FwdTiledParams {
+  int64_t R, C;        // rows, columns of the merged 2-D problem
+  int32_t log2_tx;     // lanes along the columns = 1 << log2_tx; rows per step = 256 >> log2_tx
+  int32_t steps;       // row steps per block
+  int32_t nt_store;    // non-temporal stores
+  int32_t has_partials;
+  int64_t n_ct;        // column tiles; block b serves column tile b % n_ct of row tile b / n_ct
+  TView arg[BCAST_MAX_ARGS];
+  TView out[BCAST_MAX_OUTS];
+  TView part[BCAST_MAX_PLANES];
+  TView branch;        // uint8 elements; p == nullptr: not requested
+};
+
+// A strided view of up to BCAST_MAX_DIMS merged dims for the generic kernels.
+struct GView {
+  void *p;
+  int64_t s[BCAST_MAX_DIMS];
+};
+
+struct FwdGenericParams {
+  int32_t nd;
+  int64_t shape[BCAST_MAX_DIMS];
+  int64_t E;
+  GView arg[BCAST_MAX_ARGS];
+  GView out[BCAST_MAX_OUTS];
+  GView part[BCAST_MAX_PLANES];
+  GView branch;
+};
+
+// ---- backward ------------------------------------------------------------------------
+enum GradClass : int32_t {
+  kGradSkip = -1,
+  kGradFull = 0,    // gradient has the output's shape: elementwise product (Table 1)
+  kGradRowSum = 1,  // argument varied along rows only: sum over columns
+  kGradColSum = 2,  // argument varied along columns only: sum over rows
+  kGradAllSum = 3,  // scalar argument: sum over everything
+};
+
+struct BwdEntry {
+  TView P[BCAST_MAX_OUTS];  // planes d Y_i / d X_j for this j; p == nullptr: zeros
+  TView g;                  // gradient view (sr/sc are 0 on reduced dims)
+  int32_t cls;
+  int32_t slot;             // index among the entries of the same class in this launch
+  int64_t ws_off;           // byte offset of this entry's partial sums in the workspace
+  int32_t direct;           // 1: this launch writes the final gradient (no second pass)
+  int32_t pad;
+};
+
+struct BwdTiledParams {
+  int64_t R, C;
+  int32_t log2_tx, steps, nt_store, M;
+  int32_t n_entries;
+  int32_t n_row_slots, n_col_slots, n_all_slots;
+  uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS
+  uint32_t pad;
+  int64_t n_ct, n_rt;  // column tiles, row tiles; block b = rt * n_ct + ct
+  unsigned char *ws;
+  TView adj[BCAST_MAX_OUTS];
+  BwdEntry e[BCAST_MAX_ARGS];
+};
+
+// second pass: one job per gradient that needs it
+struct Pass2Job {
+  void *g;              // final gradient
+  int64_t g_stride;     // elements between consecutive outputs
+  int64_t n_out;        // outputs of this job
+  int64_t n_part;       // partial sums per output
+  int64_t part_stride;  // in accumulator elements: between partials of one output
+  int64_t out_stride;   // in accumulator elements: between outputs
+  int64_t ws_off;       // bytes
+  int64_t first_block;  // blocks [first_block, first_block + n_blocks) serve this job
+  int64_t n_blocks;
+  int32_t kind;         // 0: one wavefront per output, 1: one block per output, 2: 64 outputs x 4 groups per block
+  int32_t pad;
+};
+struct Pass2Params {
+  int32_t n_jobs;
+  int32_t pad;
+  unsigned char *ws;
+  Pass2Job job[BCAST_MAX_ARGS];
+};
+
+struct BwdGenericParams {
+  int32_t nd, M;
+  int64_t shape[BCAST_MAX_DIMS];
+  int64_t E;
+  GView adj[BCAST_MAX_OUTS];
+  GView P[BCAST_MAX_OUTS];
+  GView g;
+  // reduction geometry: kept dims enumerate gradient elements, reduced dims the fibre
+  int32_t reduced[BCAST_MAX_DIMS];
+  int64_t n_kept, n_fibre;
+};
+
+}  // namespace bd

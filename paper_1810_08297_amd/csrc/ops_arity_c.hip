@@ -1,0 +1,5 @@
+// Forward kernels of the arity-study family, arities 16..18.
+#include "fwd_kernels.h"
+BD_DEFINE_OP(bd::OpProdTanh<16>, prod_tanh_16)
+BD_DEFINE_OP(bd::OpProdTanh<17>, prod_tanh_17)
+BD_DEFINE_OP(bd::OpProdTanh<18>, prod_tanh_18)

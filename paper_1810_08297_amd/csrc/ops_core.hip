@@ -1,0 +1,4 @@
+// Forward kernels of the HM-LSTM cell-update ops.
+#include "fwd_kernels.h"
+BD_DEFINE_OP(bd::OpHmLstmUpdate, hmlstm_update)
+BD_DEFINE_OP(bd::OpUpdateC, update_c)

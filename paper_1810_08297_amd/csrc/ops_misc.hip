@@ -1,0 +1,7 @@
+// Forward kernels of the generic broadcast ops.
+#include "fwd_kernels.h"
+BD_DEFINE_OP(bd::OpTanhXyB, tanh_xy_b)
+BD_DEFINE_OP(bd::OpBranchy5, branchy5)
+BD_DEFINE_OP(bd::OpCosX, cos_x)
+BD_DEFINE_OP(bd::OpScaleXt, scale_xt)
+BD_DEFINE_OP(bd::OpPair3, pair3)

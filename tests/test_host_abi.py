@@ -1,0 +1,207 @@
+"""CPU-only tests of the library's host side: exported symbols, op table, argument
+validation (every error is reported before anything is launched) and the plan."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_1810_08297_amd as P
+from paper_1810_08297_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bcast_dual.h")).read()
+    body = header[header.index('extern "C"'):]
+    declared = set(re.findall(r"\b(bcast_[a-z0-9_]+)\s*\(", body))
+    assert declared == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_op_table():
+    names = [P.bcast_op_name(k) for k in range(P.bcast_op_count())]
+    for n in ("hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3",
+              "prod_tanh_1", "prod_tanh_18"):
+        assert n in names
+    assert P.bcast_op_name(-1) is None and P.bcast_op_name(10 ** 6) is None
+    op = P.bcast_op_lookup("hmlstm_update")
+    assert P.bcast_op_info(op) == (12, 2, (1 << 6) | (1 << 7), 3)
+    assert P.diff_arg_indices(op) == [0, 1, 2, 3, 4, 5, 8, 9, 10, 11]
+    assert P.bcast_op_info(P.bcast_op_lookup("branchy5")) == (5, 1, 0, 2)
+    with pytest.raises(P.BcastError) as e:
+        P.bcast_op_lookup("no_such_op")
+    assert e.value.status == -1
+    assert P.status_string(0) == "ok" and "workspace" in P.status_string(-8)
+
+
+def _t(*shape, dtype=torch.float32):
+    return torch.zeros(shape, dtype=dtype)
+
+
+def _fwd_status(op, args, outs, parts, branch=None):
+    try:
+        P.bcast_dual_forward_plan(P.bcast_op_lookup(op), args, outs, parts, branch)
+        return 0
+    except P.BcastError as e:
+        return e.status
+
+
+def test_forward_validation_errors():
+    x, y, b = _t(4, 6), _t(4, 6), _t(4, 1)
+    out, parts = [_t(4, 6)], [_t(4, 6) for _ in range(3)]
+    assert _fwd_status("tanh_xy_b", [x, y, b], out, parts) == 0
+    assert _fwd_status("tanh_xy_b", [x, y], out, parts) == -2                      # argument count
+    assert _fwd_status("tanh_xy_b", [x, _t(4, 5), b], out, parts) == -5           # not broadcastable
+    assert _fwd_status("tanh_xy_b", [x, y, b], [_t(4, 1)], parts) == -6           # output shape
+    assert _fwd_status("tanh_xy_b", [x, y, b], out, [_t(4, 6), _t(6, 4), _t(4, 6)]) == -6
+    assert _fwd_status("tanh_xy_b", [x, y, b], [_t(4, 6).expand(4, 6)[:, :1].expand(4, 6)], parts) == -10
+    v = B.as_view(x)
+    v.ndim = 5
+    assert _fwd_status("tanh_xy_b", [v, y, b], out, parts) == -4
+    v = B.as_view(x)
+    v.data = None
+    assert _fwd_status("tanh_xy_b", [v, y, b], out, parts) == -3
+    v = B.as_view(x)
+    v.data = x.data_ptr() + 2
+    assert _fwd_status("tanh_xy_b", [v, y, b], out, parts) == -11
+    v = B.as_view(x)
+    v.stride[0] = -6
+    assert _fwd_status("tanh_xy_b", [v, y, b], out, parts) == -10
+    # the real entry point reports the same errors and launches nothing (no GPU here)
+    with pytest.raises(P.BcastError) as e:
+        P.bcast_dual_forward(P.bcast_op_lookup("tanh_xy_b"), [x, y], out, parts, stream=0)
+    assert e.value.status == -2
+    with pytest.raises(P.BcastError) as e:
+        P.bcast_dual_forward(999, [x, y, b], out, parts, stream=0)
+    assert e.value.status == -1
+    rc = B.lib().bcast_dual_forward(ctypes.c_int32(1), ctypes.c_int(7), ctypes.c_int32(3), B._views([x, y, b]),
+                                    ctypes.c_int32(1), B._views(out), B._views(parts), None, None)
+    assert rc == -7
+
+
+def test_zero_sized_problem_is_ok_and_launches_nothing():
+    x, y, b = _t(0, 6), _t(0, 6), _t(0, 1)
+    info = P.bcast_dual_forward_plan(P.bcast_op_lookup("tanh_xy_b"), [x, y, b], [_t(0, 6)],
+                                     [_t(0, 6) for _ in range(3)])
+    assert info["path"] == 0 and info["n_launches"] == 0
+    P.bcast_dual_forward(P.bcast_op_lookup("tanh_xy_b"), [x, y, b], [_t(0, 6)],
+                         [_t(0, 6) for _ in range(3)], stream=0)
+    P.bcast_dual_backward([_t(0, 6)], [_t(0, 6)] * 3, [_t(0, 6), _t(0, 6), _t(0, 1)], None, stream=0)
+
+
+def test_forward_plan_geometry():
+    op = P.bcast_op_lookup("hmlstm_update")
+
+    def hm(H, Bt, z_full=False, dtype=torch.float32):
+        full = lambda: _t(H, Bt, dtype=dtype)
+        args = [full() for _ in range(6)] + [full() if z_full else _t(1, Bt, dtype=dtype), _t(1, Bt, dtype=dtype)] + \
+               [_t(H, 1, dtype=dtype) for _ in range(4)]
+        return args, [full(), full()], [full() for _ in range(20)]
+
+    a, o, p = hm(4096, 1024)
+    info = P.bcast_dual_forward_plan(op, a, o, p)
+    assert info["path"] == 1 and info["vec"] == 4 and info["shape"] == [4096, 1024]
+    assert info["tx"] == 256 and info["ty"] == 1 and info["n_launches"] == 1
+    assert info["grid_x"] * info["grid_y"] * info["rows_per_block"] >= 4096
+    a, o, p = hm(64, 16)
+    info = P.bcast_dual_forward_plan(op, a, o, p)
+    assert info["tx"] == 4 and info["ty"] == 64 and info["grid_x"] * info["grid_y"] == 1
+    a, o, p = hm(64, 15)  # odd row length: scalar accesses
+    assert P.bcast_dual_forward_plan(op, a, o, p)["vec"] == 1
+    a, o, p = hm(64, 16, dtype=torch.float64)
+    assert P.bcast_dual_forward_plan(op, a, o, p)["vec"] == 2
+    # everything contiguous and full-shape: the two dims merge into one
+    op1 = P.bcast_op_lookup("cos_x")
+    info = P.bcast_dual_forward_plan(op1, [_t(8, 32)], [_t(8, 32)], [_t(8, 32)])
+    assert info["ndim"] == 1 and info["shape"] == [256]
+    # column-major data is the same problem with the dims swapped
+    xt = _t(32, 8).t()
+    info = P.bcast_dual_forward_plan(op1, [xt], [_t(32, 8).t()], [_t(32, 8).t()])
+    assert info["path"] == 1 and info["shape"] == [256]
+    # a transposed input against row-major outputs needs the generic kernel
+    info = P.bcast_dual_forward_plan(op1, [xt], [_t(8, 32)], [_t(8, 32)])
+    assert info["path"] == 2
+    # rank 4 that cannot merge
+    x4 = _t(3, 5, 7, 9)[:, :4, :6, :8]
+    info = P.bcast_dual_forward_plan(op1, [x4], [torch.zeros_like(x4)], [torch.zeros_like(x4)])
+    assert info["path"] == 2 and info["ndim"] == 4
+    # missing dims are trailing (the n-vector pairs with the first dim, Sec. 2.1.1 Eq. 1)
+    op3 = P.bcast_op_lookup("pair3")
+    A, alpha, a = _t(2, 3), _t(1), _t(2)
+    outs, parts = [_t(2, 3), _t(2, 3)], [_t(2, 3) for _ in range(6)]
+    assert P.bcast_dual_forward_plan(op3, [A, alpha, a], outs, parts)["path"] == 1
+    with pytest.raises(P.BcastError):
+        P.bcast_dual_forward_plan(op3, [A, alpha, _t(3)], outs, parts)
+
+
+def test_backward_plan_and_workspace():
+    R, C = 8192, 8192
+    big = torch.empty(0)
+
+    def fake(shape):  # shapes only: a view over no real memory, never dereferenced by the planner
+        st, acc = [], 1
+        for s in reversed(shape):
+            st.append(acc)
+            acc *= s
+        return B.raw_view(4096, shape, list(reversed(st)))
+
+    adj = [fake((R, C))]
+    parts = [fake((R, C)) for _ in range(5)]
+    grads = [fake((R, C)), fake((R, C)), fake((1, C)), fake((R, 1)), fake((1, 1))]
+    L = B.lib()
+    info = B.PlanInfo()
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
+    assert rc == 0
+    d = info.as_dict()
+    assert d["path"] == 1 and d["vec"] == 4 and d["n_second_pass"] == 3 and d["n_launches"] == 2
+    n_ct, n_rt = d["grid_x"], d["grid_y"]
+    assert n_ct == 8 and d["rows_per_block"] >= 32
+    ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                         ctypes.c_int32(5), B._views(grads))
+    assert ws == 8 * (n_rt * C + R * n_ct + n_rt * n_ct)
+    ws64 = L.bcast_dual_backward_workspace(ctypes.c_int(1), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                           ctypes.c_int32(5), B._views(grads))
+    assert ws64 > ws
+    # too small a workspace is refused before any launch
+    rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                               ctypes.c_int32(5), B._views(grads), ctypes.c_void_p(4096), ctypes.c_size_t(64), None)
+    assert rc == -8
+    rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                               ctypes.c_int32(5), B._views(grads), None, ctypes.c_size_t(0), None)
+    assert rc == -3
+    # HM-LSTM at batch <= 1024: bias row sums finish inside the main pass
+    H, Bt = 4096, 1024
+    adj = [fake((H, Bt))] * 2
+    parts = [fake((H, Bt))] * 20
+    grads = [fake((H, Bt))] * 6 + [fake((H, 1))] * 4
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
+                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
+    assert rc == 0 and info.n_launches == 1 and info.n_second_pass == 0
+    assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
+                                           ctypes.c_int32(10), B._views(grads)) == 0
+    # gradient shape that is neither the adjoint's nor 1
+    bad = grads[:9] + [fake((H, 2))]
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
+                                    ctypes.c_int32(10), B._views(bad), ctypes.byref(info))
+    assert rc == -6
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(5), B._views(adj * 3), B._views(parts),
+                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
+    assert rc == -2
+
+
+def test_tuning_keys():
+    assert P.bcast_dual_get_tuning(2) == 1
+    P.bcast_dual_set_tuning(0, 3)
+    assert P.bcast_dual_get_tuning(0) == 3
+    P.bcast_dual_set_tuning(0, 0)
+    with pytest.raises(P.BcastError):
+        P.bcast_dual_set_tuning(0, 1000)
+    with pytest.raises(P.BcastError):
+        P.bcast_dual_set_tuning(9, 0)
