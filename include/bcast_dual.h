@@ -94,6 +94,9 @@ typedef struct {
  *                   branch id 1 = predicate true.
  *   "cos_x"         N=1 (the Dual example of Sec. 2.2.1), "scale_xt" N=2 (x*t),
  *   "pair3"         N=3 -> (x1*x2 + sin x3, x1/x2 - x3*x3)  (R^3 -> R^2, Sec. 2.2.2)
+ *   "linear12"      N=12, the HM-LSTM argument list with trivial arithmetic:
+ *                   (sum of the ten differentiable arguments + z*z_below,
+ *                    f*c + i*h + o*g + b_f*b_i + b_o*b_g); for profiling memory behaviour.
  *   "prod_tanh_K"   K = 1..18: prod_i tanh(g(x_i)), g(x) = x if x > 1/2 else -x
  *                   (the arity study of Sec. 3.4.1); branch id = #{x_i > 1/2}.
  * Predicates read values only, so control flow contributes no derivative. */
@@ -155,17 +158,40 @@ const char *bcast_status_string(int status);
 
 /* Launch-shape overrides for benchmarking sweeps (process-wide, not thread-safe; values
  * outside the documented range are rejected with BCAST_ERR_BAD_ARG_COUNT).
- *   key 0: rows per block of the tiled forward kernel (0 = automatic, else 1..64)
+ *   key 0: unused (kept so that the other keys keep their numbers)
  *   key 1: rows per block of the tiled backward kernel (0 = automatic, else 1..256)
  *   key 2: 1 = non-temporal stores for outputs/partials/gradients, 0 = plain
- *   key 3: 1 = force the generic strided kernels (testing) */
+ *   key 3: 1 = force the generic strided kernels (testing)
+ *   key 4: widest vector access per lane in bytes: 16 (default), 8 or 4
+ *   key 5: 1 = always use the generic tiled backward kernel, never a kernel compiled for
+ *          the call's mix of gradient classes (testing)
+ *   key 6: 1 (default) = the tiled backward kernel walks its tiles last to first, so that it
+ *          starts with the planes the forward kernel wrote last, which the memory-side
+ *          cache may still hold; 0 = first to last */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 
-/* A plain device-to-device streaming copy of `bytes` bytes (multiple of 16, both
- * pointers 16-byte aligned) with the same access pattern as the tiled kernels; used to
- * measure the achievable HBM rate and to calibrate profiler byte counters. */
-int bcast_dual_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+/* Partial-storage layout.  The planes of one call (outputs, the M x N_d partials, the
+ * gradients, and ideally the arguments too) are streamed side by side, every wavefront
+ * touching the same offset of each.  If the planes start a large power of two apart, those
+ * accesses land on the same HBM channel; measured on MI355X, 7 read + 22 written planes of
+ * 16 MiB move at 5.2 TB/s back to back and at 6.4 TB/s when each plane is shifted by one
+ * more 4 KiB page than its predecessor.  This helper lays n_planes of plane_bytes each out
+ * in one slab that way: offsets[k] (bytes, 256-byte aligned) is where plane k starts;
+ * returns the slab size in bytes (offsets may be NULL to query only the size).  Using it is
+ * optional: any non-overlapping views are accepted by forward and backward. */
+size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offsets);
+
+/* Streaming probe for roofline calibration: fp32 planes are cut into chunks of 1024 floats
+ * (4 KiB); one 256-lane block reads chunk b of each of the n_in input planes with 16-byte
+ * loads, adds them, and writes chunk b of each of the n_out output planes -- the access
+ * pattern of the tiled kernels with no arithmetic to speak of.  Chunk b of plane k starts at
+ * plane[k] + b * chunk_stride[k] floats (1024 = a dense plane; larger = planes interleaved in
+ * one buffer).  in/out and the stride arrays are HOST arrays (at most 32 entries each) of
+ * DEVICE pointers (16-byte aligned) and strides (multiples of 4; output strides >= 1024).
+ * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters. */
+int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
+                            void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream);
 
 #ifdef __cplusplus
 }

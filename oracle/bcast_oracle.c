@@ -216,6 +216,20 @@ static void op_pair3(int n, const real *x, const void *xw, int f64, real *y, rea
   J[5] = -2.0L * x[2];
   *br = 0;
 }
+/* the HM-LSTM argument list with trivial arithmetic (a profiling aid of the library) */
+static void op_linear12(int n, const real *x, const void *xw, int f64, real *y, real *J, int *br) {
+  (void)n; (void)xw; (void)f64;
+  for (int k = 0; k < 24; ++k) J[k] = 0.0L;
+  y[0] = x[A_Z] * x[A_ZB];
+  for (int k = 0; k < HM_N; ++k)
+    if (k != A_Z && k != A_ZB) { y[0] += x[k]; J[k] = 1.0L; }
+  y[1] = x[A_F] * x[A_C] + x[A_I] * x[A_H] + x[A_O] * x[A_G] + x[A_BF] * x[A_BI] + x[A_BO] * x[A_BG];
+  real *Jh = J + HM_N;
+  Jh[A_F] = x[A_C]; Jh[A_C] = x[A_F]; Jh[A_I] = x[A_H]; Jh[A_H] = x[A_I]; Jh[A_O] = x[A_G]; Jh[A_G] = x[A_O];
+  Jh[A_BF] = x[A_BI]; Jh[A_BI] = x[A_BF]; Jh[A_BO] = x[A_BG]; Jh[A_BG] = x[A_BO];
+  *br = 0;
+}
+
 /* arity study (Sec. 3.4.1): f = prod_i tanh(g(x_i)), g(x) = x if x > 1/2 else -x.
  * branch id = number of arguments with x_i > 1/2. */
 static void op_prod_tanh(int n, const real *x, const void *xw, int f64, real *y, real *J, int *br) {
@@ -247,6 +261,7 @@ static const op_desc OPS[] = {
     {"cos_x", 1, 1, 0u, op_cos_x},
     {"scale_xt", 2, 1, 0u, op_scale_xt},
     {"pair3", 3, 2, 0u, op_pair3},
+    {"linear12", HM_N, 2, (1u << A_Z) | (1u << A_ZB), op_linear12},
     {"prod_tanh", 0, 1, 0u, op_prod_tanh},
 };
 

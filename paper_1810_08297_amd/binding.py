@@ -49,7 +49,7 @@ _lib = None
 EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
            "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
-           "bcast_dual_get_tuning", "bcast_dual_copy_probe")
+           "bcast_dual_get_tuning", "bcast_dual_stream_probe", "bcast_dual_slab_layout")
 
 
 def lib():
@@ -63,6 +63,7 @@ def lib():
         L.bcast_op_name.restype = ctypes.c_char_p
         L.bcast_status_string.restype = ctypes.c_char_p
         L.bcast_dual_backward_workspace.restype = ctypes.c_size_t
+        L.bcast_dual_slab_layout.restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -152,6 +153,8 @@ def _views(ts: Sequence, like=None):
 
 
 def _stream_ptr(stream):
+    if isinstance(stream, ctypes.c_void_p):
+        return stream
     if isinstance(stream, int):  # a raw hipStream_t (0 = the default stream)
         return ctypes.c_void_p(stream)
     import torch
@@ -229,7 +232,55 @@ def bcast_dual_get_tuning(key: int) -> int:
     return v.value
 
 
-def bcast_dual_copy_probe(dst, src, stream=None) -> None:
-    nbytes = src.numel() * src.element_size()
-    _check(lib().bcast_dual_copy_probe(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
-                                       ctypes.c_size_t(nbytes), _stream_ptr(stream)), "bcast_dual_copy_probe")
+def bcast_dual_stream_probe(in_ptrs, in_strides, out_ptrs, out_strides, n_chunks, stream=None) -> None:
+    """in_ptrs/out_ptrs: device addresses (ints); strides in floats per 4 KiB chunk."""
+    def arr(ctype, vals):
+        return (ctype * max(1, len(vals)))(*vals)
+    _check(lib().bcast_dual_stream_probe(
+        ctypes.c_int32(len(in_ptrs)), arr(ctypes.c_void_p, in_ptrs), arr(ctypes.c_int64, in_strides),
+        ctypes.c_int32(len(out_ptrs)), arr(ctypes.c_void_p, out_ptrs), arr(ctypes.c_int64, out_strides),
+        ctypes.c_int64(n_chunks), _stream_ptr(stream)), "bcast_dual_stream_probe")
+
+
+def bcast_dual_slab_layout(plane_bytes: int, n_planes: int):
+    """(total_bytes, [offset of plane k]) of the staggered slab layout."""
+    offs = (ctypes.c_size_t * max(1, n_planes))()
+    total = lib().bcast_dual_slab_layout(ctypes.c_size_t(plane_bytes), ctypes.c_int32(n_planes), offs)
+    return int(total), [int(offs[k]) for k in range(n_planes)]
+
+
+class PreparedForward:
+    """A forward call whose argument block is marshalled once; ``launch`` only enqueues.
+    The tensors must stay alive and keep their addresses between launches."""
+
+    def __init__(self, op_id, args, outs, partials, branch_id=None):
+        self._keep = (args, outs, partials, branch_id)
+        self._op = ctypes.c_int32(op_id)
+        self._dt = ctypes.c_int(_dtype_code(outs[0]))
+        self._na, self._a = ctypes.c_int32(len(args)), _views(args)
+        self._no, self._o = ctypes.c_int32(len(outs)), _views(outs)
+        self._p = _views(partials, self._o[0]) if partials is not None else None
+        self._b = ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None)
+        self._fn = lib().bcast_dual_forward
+
+    def launch(self, stream=None):
+        _check(self._fn(self._op, self._dt, self._na, self._a, self._no, self._o, self._p, self._b,
+                        _stream_ptr(stream)), "bcast_dual_forward")
+
+
+class PreparedBackward:
+    """A backward call whose argument block is marshalled once (see PreparedForward)."""
+
+    def __init__(self, adjoints, partials, grads, workspace=None):
+        self._keep = (adjoints, partials, grads, workspace)
+        self._dt = ctypes.c_int(_dtype_code(adjoints[0]))
+        self._no, self._a = ctypes.c_int32(len(adjoints)), _views(adjoints)
+        self._p = _views(partials, self._a[0])
+        self._ng, self._g = ctypes.c_int32(len(grads)), _views(grads)
+        self._ws = ctypes.c_void_p(workspace.data_ptr() if workspace is not None else None)
+        self._wsb = ctypes.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0)
+        self._fn = lib().bcast_dual_backward
+
+    def launch(self, stream=None):
+        _check(self._fn(self._dt, self._no, self._a, self._p, self._ng, self._g, self._ws, self._wsb,
+                        _stream_ptr(stream)), "bcast_dual_backward")

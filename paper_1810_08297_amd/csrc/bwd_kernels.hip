@@ -97,162 +97,291 @@ BD_DEV A seg_reduce(A v, int log2w) {
   return v;
 }
 
+// Sum over one whole wavefront (all 64 lanes active); every lane returns the total.  Four
+// DPP butterfly steps give each 16-lane row its sum, the four row sums are then read through
+// scalar registers and added in lane order.
+BD_DEV double read_lane(double x, int lane) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), lane),
+                          __builtin_amdgcn_readlane(__double2loint(x), lane));
+}
+BD_DEV dd read_lane(dd x, int lane) { return dd{read_lane(x.hi, lane), read_lane(x.lo, lane)}; }
+template <class T, class A>
+BD_DEV A wave_total(A v) {
+  using AT = acc_traits<T>;
+  v = seg_reduce<T, A>(v, 4);
+  A t = read_lane(v, 0);
+  AT::add(t, read_lane(v, 16));
+  AT::add(t, read_lane(v, 32));
+  AT::add(t, read_lane(v, 48));
+  return t;
+}
+
 // ---- tiled main pass -------------------------------------------------------------------------
-// Same TY x TX lane arrangement as the forward kernel.  Per row step a lane loads the M
-// adjoint vectors once and then, gradient by gradient, the M plane vectors; what happens to
-// t_j = sum_i adj_i * P_ij depends on the gradient's class:
+// Same TY x TX lane arrangement as the forward kernel, walking `steps` rows per block.  Per
+// row step a lane loads the M adjoint vectors and the M plane vectors of every gradient;
+// what happens to t_j = sum_i adj_i * P_ij depends on the gradient's class:
 //   full     : stored at once
-//   row sum  : summed over the lane's columns, butterfly over the row's lanes in the
+//   row sum  : summed over the lane's columns, reduced over the row's lanes in the
 //              wavefront, then (rows wider than a wavefront) one LDS cell per wavefront
 //   col sum  : added to the lane's own LDS accumulators, combined over the block's rows at the end
 //   all sum  : added to the lane's own LDS accumulator, block tree at the end
 // A block writes a final gradient directly when it alone covers the reduced extent,
 // otherwise its partial sum goes to the workspace for the second pass.
-template <class T, int VEC, int MCT>
-__global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams p) {
+//
+// Two kernels share this scheme.  The signature kernel is compiled for a fixed number of
+// outputs and of gradients of each class (the host sorts the gradient table by class), so
+// every table access is a constant, all loads of a row step are issued before the first
+// use and nothing is decided at run time but the ragged edge.  The generic kernel reads
+// the class of each gradient from the table and takes any mix, one gradient at a time.
+template <class T, int VEC>
+struct BwdGeom {
   using AT = acc_traits<T>;
   using A = typename AT::type;
+  int tid, ltx, TX, tx, ty, TY, wpr, rows_pb;
+  uint32_t bid, rt, ct;
+  int64_t c0, r0;
+  bool colvalid, interior;
+  uint32_t off0, off_step;
+  A *lds_row, *lds_col, *lds_all;
+
+  BD_DEV BwdGeom(const BwdTiledParams &p, unsigned char *smem) {
+    tid = threadIdx.x;
+    ltx = p.log2_tx;
+    TX = 1 << ltx;
+    tx = tid & (TX - 1);
+    ty = tid >> ltx;
+    TY = kBlock >> ltx;
+    wpr = ltx > 6 ? (1 << (ltx - 6)) : 1;
+    rows_pb = TY * p.steps;
+    const uint32_t nct = (uint32_t)p.n_ct;
+    // In reverse mode the grid is walked from the last tile to the first: the planes that
+    // the forward kernel wrote last are the ones still held by the memory-side cache.
+    bid = p.reverse ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    rt = bid / nct;
+    ct = bid - rt * nct;
+    c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
+    colvalid = c0 < p.C;
+    r0 = (int64_t)rt * rows_pb;
+    interior = r0 + rows_pb <= p.R && ((((int64_t)ct + 1) << ltx) * VEC) <= p.C;
+    // one byte offset per lane and row serves the adjoints, every plane and every full gradient
+    off0 = (uint32_t)((r0 + ty) * p.row_stride + c0) * (uint32_t)sizeof(T);
+    off_step = (uint32_t)(TY * p.row_stride) * (uint32_t)sizeof(T);
+    lds_row = reinterpret_cast<A *>(smem + p.lds_row_off);
+    lds_col = reinterpret_cast<A *>(smem + p.lds_col_off);
+    lds_all = reinterpret_cast<A *>(smem + p.lds_all_off);
+    for (int s = 0; s < p.n_col_slots; ++s)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) lds_col[(s * kBlock + tid) * VEC + v] = AT::zero();
+    for (int s = 0; s < p.n_all_slots; ++s) lds_all[s * kBlock + tid] = AT::zero();
+  }
+};
+
+// one vector of a plane; lanes outside the problem read offset 0 and get zeros
+template <class T, int VEC, bool EDGE>
+BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) {
+  if (EDGE) {
+    load_vec<T, VEC>(at<const T>(base, valid ? off : 0u), x);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) x[v] = valid ? x[v] : T(0);
+  } else {
+    load_vec<T, VEC>(at<const T>(base, off), x);
+  }
+}
+
+// the per-class treatment of one gradient at one row step
+template <class T, int VEC, int MAXM, bool EDGE>
+BD_DEV void apply_full(const BwdEntry &en, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], uint32_t off,
+                       bool valid, bool nt) {
+  T o[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
+  if (!EDGE || valid) store_vec<T, VEC>(at<T>(en.g.p, off), o, nt);
+}
+template <class T, int VEC, int MAXM>
+BD_DEV void apply_rowsum(const BwdTiledParams &p, const BwdGeom<T, VEC> &g, const BwdEntry &en,
+                         const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], int64_t r, int ri) {
+  using AT = acc_traits<T>;
+  using A = typename AT::type;
+  A rs = AT::zero();
+#pragma unroll
+  for (int v = 0; v < VEC; ++v)
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) AT::add_prod(rs, adj[i][v], P[i][v]);
+  if (g.ltx >= 6) {  // the wavefront lies inside one row
+    rs = wave_total<T, A>(rs);
+    if ((g.tid & 63) == 0 && r < p.R) {
+      if (g.ltx > 6)
+        g.lds_row[(en.slot * g.rows_pb + ri) * g.wpr + (g.tx >> 6)] = rs;
+      else if (en.direct)
+        static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(rs);
+      else
+        reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = rs;
+    }
+  } else {  // several rows per wavefront: segmented butterfly
+    rs = seg_reduce<T, A>(rs, g.ltx);
+    if (g.tx == 0 && r < p.R) {
+      if (en.direct)
+        static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(rs);
+      else
+        reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = rs;
+    }
+  }
+}
+template <class T, int VEC, int MAXM>
+BD_DEV void apply_colsum(const BwdGeom<T, VEC> &g, const BwdEntry &en, const T (&adj)[MAXM][VEC],
+                         const T (&P)[MAXM][VEC]) {
+  using AT = acc_traits<T>;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    auto c = g.lds_col[(en.slot * kBlock + g.tid) * VEC + v];
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) AT::add_prod(c, adj[i][v], P[i][v]);
+    g.lds_col[(en.slot * kBlock + g.tid) * VEC + v] = c;
+  }
+}
+template <class T, int VEC, int MAXM>
+BD_DEV void apply_allsum(const BwdGeom<T, VEC> &g, const BwdEntry &en, const T (&adj)[MAXM][VEC],
+                         const T (&P)[MAXM][VEC]) {
+  using AT = acc_traits<T>;
+  auto c = g.lds_all[en.slot * kBlock + g.tid];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v)
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) AT::add_prod(c, adj[i][v], P[i][v]);
+  g.lds_all[en.slot * kBlock + g.tid] = c;
+}
+
+// after the row walk: combine what the block's lanes parked in LDS
+template <class T, int VEC>
+BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
+  using AT = acc_traits<T>;
+  using A = typename AT::type;
+  if (p.n_row_slots + p.n_col_slots + p.n_all_slots == 0) return;
+  __syncthreads();
+  for (int e = 0; e < p.n_entries; ++e) {
+    const BwdEntry &en = p.e[e];
+    if (en.cls == kGradRowSum && g.ltx > 6) {
+      for (int q = g.tid; q < g.rows_pb; q += kBlock) {
+        const int64_t r = g.r0 + q;
+        if (r < p.R) {
+          A s = g.lds_row[(en.slot * g.rows_pb + q) * g.wpr];
+          for (int w = 1; w < g.wpr; ++w) AT::add(s, g.lds_row[(en.slot * g.rows_pb + q) * g.wpr + w]);
+          if (en.direct)
+            static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(s);
+          else
+            reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = s;
+        }
+      }
+    } else if (en.cls == kGradColSum) {
+      if (g.ty == 0 && g.colvalid) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          A s = g.lds_col[(en.slot * kBlock + g.tx) * VEC + v];
+          for (int y = 1; y < g.TY; ++y) AT::add(s, g.lds_col[(en.slot * kBlock + y * g.TX + g.tx) * VEC + v]);
+          if (en.direct)
+            static_cast<T *>(en.g.p)[(g.c0 + v) * en.g.sc] = AT::fin(s);
+          else
+            reinterpret_cast<A *>(p.ws + en.ws_off)[(int64_t)g.rt * p.C + g.c0 + v] = s;
+        }
+      }
+    } else if (en.cls == kGradAllSum) {
+      A s = g.lds_all[en.slot * kBlock + g.tid];
+      s = wave_total<T, A>(s);
+      __syncthreads();
+      if ((g.tid & 63) == 0) g.lds_all[en.slot * kBlock + (g.tid >> 6)] = s;
+      __syncthreads();
+      if (g.tid == 0) {
+        A t = g.lds_all[en.slot * kBlock];
+        for (int w = 1; w < kBlock / 64; ++w) AT::add(t, g.lds_all[en.slot * kBlock + w]);
+        if (en.direct)
+          static_cast<T *>(en.g.p)[0] = AT::fin(t);
+        else
+          reinterpret_cast<A *>(p.ws + en.ws_off)[g.bid] = t;
+      }
+    }
+  }
+}
+
+// Signature kernel: M outputs; the gradient table holds NF full, then NR row-sum, then NC
+// col-sum, then NA all-sum gradients, every plane present.
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA>
+__global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
+  constexpr int NE = NF + NR + NC + NA;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const BwdGeom<T, VEC> g(p, smem);
+  const bool nt = p.nt_store != 0;
+  auto walk = [&](auto edge_tag) {
+    constexpr bool EDGE = decltype(edge_tag)::value;
+    uint32_t off = g.off0;
+    for (int k = 0; k < p.steps; ++k, off += g.off_step) {
+      const int ri = k * g.TY + g.ty;
+      const int64_t r = g.r0 + ri;
+      const bool valid = g.colvalid && r < p.R;
+      T adj[M][VEC], P[NE][M][VEC];
+#pragma unroll
+      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.adj[i].p, off, valid, adj[i]);
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+#pragma unroll
+        for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.e[e].P[i].p, off, valid, P[e][i]);
+#pragma unroll
+      for (int e = 0; e < NF; ++e) apply_full<T, VEC, M, EDGE>(p.e[e], adj, P[e], off, valid, nt);
+#pragma unroll
+      for (int e = NF; e < NF + NR; ++e) apply_rowsum<T, VEC, M>(p, g, p.e[e], adj, P[e], r, ri);
+#pragma unroll
+      for (int e = NF + NR; e < NF + NR + NC; ++e) apply_colsum<T, VEC, M>(g, p.e[e], adj, P[e]);
+#pragma unroll
+      for (int e = NF + NR + NC; e < NE; ++e) apply_allsum<T, VEC, M>(g, p.e[e], adj, P[e]);
+    }
+  };
+  if (g.interior)
+    walk(std::false_type{});
+  else
+    walk(std::true_type{});
+  bwd_finalize<T, VEC>(p, g);
+}
+
+// Generic kernel: any number of outputs up to BCAST_MAX_OUTS (MCT = 0) and any mix of
+// gradient classes and absent planes, one gradient at a time.
+template <class T, int VEC, int MCT>
+__global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams p) {
   constexpr int MAXM = MCT > 0 ? MCT : BCAST_MAX_OUTS;
   extern __shared__ __align__(16) unsigned char smem[];
-  A *lds_row = reinterpret_cast<A *>(smem + p.lds_row_off);
-  A *lds_col = reinterpret_cast<A *>(smem + p.lds_col_off);
-  A *lds_all = reinterpret_cast<A *>(smem + p.lds_all_off);
-
+  const BwdGeom<T, VEC> g(p, smem);
   const int M = MCT > 0 ? MCT : p.M;
-  const int tid = threadIdx.x;
-  const int ltx = p.log2_tx;
-  const int TX = 1 << ltx;
-  const int tx = tid & (TX - 1);
-  const int ty = tid >> ltx;
-  const int TY = kBlock >> ltx;
-  const int txw = ltx < 6 ? ltx : 6;
-  const int wpr = ltx > 6 ? (1 << (ltx - 6)) : 1;
-  const int rows_pb = TY * p.steps;
-  const uint32_t nct = (uint32_t)p.n_ct;
-  const uint32_t rt = blockIdx.x / nct, ct = blockIdx.x - rt * nct;
-  const int64_t c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
-  const bool colvalid = c0 < p.C;
-  const int64_t r0 = (int64_t)rt * rows_pb;
   const bool nt = p.nt_store != 0;
-
-  for (int s = 0; s < p.n_col_slots; ++s)
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) lds_col[(s * kBlock + tid) * VEC + v] = AT::zero();
-  for (int s = 0; s < p.n_all_slots; ++s) lds_all[s * kBlock + tid] = AT::zero();
-
-  for (int k = 0; k < p.steps; ++k) {
-    const int ri = k * TY + ty;
-    const int64_t r = r0 + ri;
-    const bool valid = colvalid && r < p.R;
+  uint32_t off = g.off0;
+  for (int k = 0; k < p.steps; ++k, off += g.off_step) {
+    const int ri = k * g.TY + g.ty;
+    const int64_t r = g.r0 + ri;
+    const bool valid = g.colvalid && r < p.R;
     T adj[MAXM][VEC];
 #pragma unroll
     for (int i = 0; i < MAXM; ++i) {
-      if (i < M && valid) {
-        load_vec<T, VEC>(static_cast<const T *>(p.adj[i].p) + r * p.adj[i].sr + c0, adj[i]);
-      } else {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) adj[i][v] = T(0);
-      }
+      for (int v = 0; v < VEC; ++v) adj[i][v] = T(0);
+      if (i < M) load_plane<T, VEC, true>(p.adj[i].p, off, valid, adj[i]);
     }
     for (int e = 0; e < p.n_entries; ++e) {
       const BwdEntry &en = p.e[e];
       T P[MAXM][VEC];
 #pragma unroll
       for (int i = 0; i < MAXM; ++i) {
-        if (i < M && valid && en.P[i].p != nullptr) {
-          load_vec<T, VEC>(static_cast<const T *>(en.P[i].p) + r * en.P[i].sr + c0, P[i]);
-        } else {
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) P[i][v] = T(0);
-        }
+        for (int v = 0; v < VEC; ++v) P[i][v] = T(0);
+        if (i < M && en.P[i].p != nullptr) load_plane<T, VEC, true>(en.P[i].p, off, valid, P[i]);
       }
-      if (en.cls == kGradFull) {
-        if (valid) {
-          T o[VEC];
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
-          store_vec<T, VEC>(static_cast<T *>(en.g.p) + r * en.g.sr + c0, o, nt);
-        }
-      } else if (en.cls == kGradRowSum) {
-        A rs = AT::zero();
-#pragma unroll
-        for (int v = 0; v < VEC; ++v)
-#pragma unroll
-          for (int i = 0; i < MAXM; ++i) AT::add_prod(rs, adj[i][v], P[i][v]);
-        rs = seg_reduce<T, A>(rs, txw);
-        if (ltx <= 6) {
-          if (tx == 0 && r < p.R) {
-            if (en.direct)
-              static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(rs);
-            else
-              reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + ct] = rs;
-          }
-        } else if ((tid & 63) == 0) {
-          lds_row[(en.slot * rows_pb + ri) * wpr + (tx >> 6)] = rs;
-        }
-      } else if (en.cls == kGradColSum) {
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-          A c = lds_col[(en.slot * kBlock + tid) * VEC + v];
-#pragma unroll
-          for (int i = 0; i < MAXM; ++i) AT::add_prod(c, adj[i][v], P[i][v]);
-          lds_col[(en.slot * kBlock + tid) * VEC + v] = c;
-        }
-      } else if (en.cls == kGradAllSum) {
-        A c = lds_all[en.slot * kBlock + tid];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v)
-#pragma unroll
-          for (int i = 0; i < MAXM; ++i) AT::add_prod(c, adj[i][v], P[i][v]);
-        lds_all[en.slot * kBlock + tid] = c;
-      }
+      if (en.cls == kGradFull)
+        apply_full<T, VEC, MAXM, true>(en, adj, P, off, valid, nt);
+      else if (en.cls == kGradRowSum)
+        apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
+      else if (en.cls == kGradColSum)
+        apply_colsum<T, VEC, MAXM>(g, en, adj, P);
+      else if (en.cls == kGradAllSum)
+        apply_allsum<T, VEC, MAXM>(g, en, adj, P);
     }
   }
-  if (p.n_row_slots + p.n_col_slots + p.n_all_slots == 0) return;
-  __syncthreads();
-
-  for (int e = 0; e < p.n_entries; ++e) {
-    const BwdEntry &en = p.e[e];
-    if (en.cls == kGradRowSum && ltx > 6) {
-      for (int q = tid; q < rows_pb; q += kBlock) {
-        const int64_t r = r0 + q;
-        if (r < p.R) {
-          A s = lds_row[(en.slot * rows_pb + q) * wpr];
-          for (int w = 1; w < wpr; ++w) AT::add(s, lds_row[(en.slot * rows_pb + q) * wpr + w]);
-          if (en.direct)
-            static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(s);
-          else
-            reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + ct] = s;
-        }
-      }
-    } else if (en.cls == kGradColSum) {
-      if (ty == 0 && colvalid) {
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-          A s = lds_col[(en.slot * kBlock + tx) * VEC + v];
-          for (int y = 1; y < TY; ++y) AT::add(s, lds_col[(en.slot * kBlock + y * TX + tx) * VEC + v]);
-          if (en.direct)
-            static_cast<T *>(en.g.p)[(c0 + v) * en.g.sc] = AT::fin(s);
-          else
-            reinterpret_cast<A *>(p.ws + en.ws_off)[(int64_t)rt * p.C + c0 + v] = s;
-        }
-      }
-    } else if (en.cls == kGradAllSum) {
-      A s = lds_all[en.slot * kBlock + tid];
-      s = seg_reduce<T, A>(s, 6);
-      __syncthreads();
-      if ((tid & 63) == 0) lds_all[en.slot * kBlock + (tid >> 6)] = s;
-      __syncthreads();
-      if (tid == 0) {
-        A t = lds_all[en.slot * kBlock];
-        for (int w = 1; w < kBlock / 64; ++w) AT::add(t, lds_all[en.slot * kBlock + w]);
-        if (en.direct)
-          static_cast<T *>(en.g.p)[0] = AT::fin(t);
-        else
-          reinterpret_cast<A *>(p.ws + en.ws_off)[blockIdx.x] = t;
-      }
-    }
-  }
+  bwd_finalize<T, VEC>(p, g);
 }
 
 // ---- second pass: add the per-block partial sums in a fixed order ------------------------------
@@ -377,12 +506,37 @@ __global__ __launch_bounds__(kBlock) void bwd_generic_reduce_kernel(const BwdGen
   }
 }
 
-// ---- streaming copy with the tiled kernels' access pattern ------------------------------------------
+// ---- streaming probe with the tiled kernels' access pattern --------------------------------------------
+// Block b moves the b-th 4 KiB chunk of every plane: it reads n_in planes, adds them up and
+// writes n_out planes.  Chunk b of plane k lives at base_k + b * stride_k (in floats), so the
+// same kernel measures separate planes (stride 1024) and planes interleaved in one buffer.
+struct ProbeParams {
+  int32_t n_in, n_out;
+  int64_t n_chunks;
+  const float *in[32];
+  int64_t in_stride[32];
+  float *out[32];
+  int64_t out_stride[32];
+  float *sink;
+};
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(kBlock) void copy_probe_kernel(f32x4 *__restrict__ dst,
-                                                           const f32x4 *__restrict__ src, int64_t n16) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n16) __builtin_nontemporal_store(src[i], &dst[i]);
+__global__ __launch_bounds__(kBlock) void stream_probe_kernel(const ProbeParams p) {
+  const int64_t b = blockIdx.x;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  int k = 0;
+  for (; k + 8 <= p.n_in; k += 8) {  // eight loads in flight per lane
+    f32x4 t[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      t[q] = *reinterpret_cast<const f32x4 *>(p.in[k + q] + b * p.in_stride[k + q] + threadIdx.x * 4);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc += t[q];
+  }
+  for (; k < p.n_in; ++k)
+    acc += *reinterpret_cast<const f32x4 *>(p.in[k] + b * p.in_stride[k] + threadIdx.x * 4);
+  for (int k = 0; k < p.n_out; ++k)
+    __builtin_nontemporal_store(acc + (float)k, reinterpret_cast<f32x4 *>(p.out[k] + b * p.out_stride[k] + threadIdx.x * 4));
+  if (p.n_out == 0 && acc[0] == 12345.678f) p.sink[0] = acc[1];  // keeps the loads alive
 }
 
 }  // namespace bd
@@ -390,22 +544,54 @@ __global__ __launch_bounds__(kBlock) void copy_probe_kernel(f32x4 *__restrict__ 
 // ---- launch wrappers --------------------------------------------------------------------------------
 using namespace bd;
 
-hipError_t bd_bwd_tiled(int dt, int vec, const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
-#define BD_LAUNCH(T, V)                                                                          \
-  do {                                                                                           \
-    if (p.M == 1)                                                                                \
-      hipLaunchKernelGGL((bwd_tiled_kernel<T, V, 1>), grid, dim3(kBlock), lds, s, p);            \
-    else if (p.M == 2)                                                                           \
-      hipLaunchKernelGGL((bwd_tiled_kernel<T, V, 2>), grid, dim3(kBlock), lds, s, p);            \
-    else                                                                                         \
-      hipLaunchKernelGGL((bwd_tiled_kernel<T, V, 0>), grid, dim3(kBlock), lds, s, p);            \
+// Gradient-class signatures with a compiled kernel: {M, full, row-sum, col-sum, all-sum}.
+#define BD_SIGNATURES(X) \
+  X(2, 6, 4, 0, 0) /* HM-LSTM update with per-row biases */ \
+  X(1, 2, 1, 0, 0) /* tanh(x*y + b) */                      \
+  X(1, 2, 1, 1, 1) /* branchy5 */                           \
+  X(1, 4, 0, 0, 0) /* six-argument cell update */           \
+  X(1, 1, 0, 0, 0) X(1, 2, 0, 0, 0) X(1, 3, 0, 0, 0) X(1, 5, 0, 0, 0) X(1, 8, 0, 0, 0)
+
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na) {
+#define BD_SIG_TEST(m, f, r, c, a) \
+  if (M == m && nf == f && nr == r && nc == c && na == a) return true;
+  BD_SIGNATURES(BD_SIG_TEST)
+#undef BD_SIG_TEST
+  return false;
+}
+
+hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, const BwdTiledParams &p,
+                        dim3 grid, size_t lds, hipStream_t s) {
+  const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
+  if (signature && widest) {
+#define BD_SIG_GO(m, f, r, c, a)                                                                        \
+  if (p.M == m && nf == f && nr == r && nc == c && na == a) {                                           \
+    if (dt == BCAST_F32)                                                                                \
+      hipLaunchKernelGGL((bwd_sig_kernel<float, 4, m, f, r, c, a>), grid, dim3(kBlock), lds, s, p);     \
+    else                                                                                                \
+      hipLaunchKernelGGL((bwd_sig_kernel<double, 2, m, f, r, c, a>), grid, dim3(kBlock), lds, s, p);    \
+    return hipGetLastError();                                                                           \
+  }
+    BD_SIGNATURES(BD_SIG_GO)
+#undef BD_SIG_GO
+  }
+#define BD_GO(T, V, MM) hipLaunchKernelGGL((bwd_tiled_kernel<T, V, MM>), grid, dim3(kBlock), lds, s, p)
+#define BD_LAUNCH(T, V)                \
+  do {                                 \
+    if (p.M == 1) BD_GO(T, V, 1);      \
+    else if (p.M == 2) BD_GO(T, V, 2); \
+    else BD_GO(T, V, 0);               \
   } while (0)
   if (dt == BCAST_F32) {
-    if (vec > 1) BD_LAUNCH(float, 4); else BD_LAUNCH(float, 1);
+    if (vec == 4) BD_LAUNCH(float, 4);
+    else if (vec == 2) BD_LAUNCH(float, 2);
+    else BD_LAUNCH(float, 1);
   } else {
-    if (vec > 1) BD_LAUNCH(double, 2); else BD_LAUNCH(double, 1);
+    if (vec == 2) BD_LAUNCH(double, 2);
+    else BD_LAUNCH(double, 1);
   }
 #undef BD_LAUNCH
+#undef BD_GO
   return hipGetLastError();
 }
 
@@ -429,11 +615,24 @@ hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_
   return hipGetLastError();
 }
 
-hipError_t bd_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t s) {
-  const int64_t n16 = (int64_t)(bytes / 16);
-  if (n16 == 0) return hipSuccess;
-  const int64_t blocks = (n16 + kBlock - 1) / kBlock;
-  hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                     static_cast<f32x4 *>(dst), static_cast<const f32x4 *>(src), n16);
+hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
+                           const int64_t *out_stride, int64_t n_chunks, hipStream_t s) {
+  ProbeParams p{};
+  p.n_in = n_in;
+  p.n_out = n_out;
+  p.n_chunks = n_chunks;
+  for (int k = 0; k < n_in; ++k) {
+    p.in[k] = static_cast<const float *>(in[k]);
+    p.in_stride[k] = in_stride[k];
+  }
+  for (int k = 0; k < n_out; ++k) {
+    p.out[k] = static_cast<float *>(out[k]);
+    p.out_stride[k] = out_stride[k];
+  }
+  p.sink = n_out > 0 ? p.out[0] : const_cast<float *>(p.in[0]);
+#ifndef BD_PROBE_LDS
+#define BD_PROBE_LDS 0
+#endif
+  hipLaunchKernelGGL(stream_probe_kernel, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
   return hipGetLastError();
 }

@@ -12,6 +12,7 @@ namespace bd {
 
 template <class T, int VEC> struct vec_of;
 template <> struct vec_of<float, 4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct vec_of<float, 2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct vec_of<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
 
 template <class T, int VEC>
@@ -38,18 +39,20 @@ BD_DEV void store_vec(T *p, const T (&x)[VEC], bool nt) {
   }
 }
 
-// one argument for VEC consecutive columns of row r: a vector load where the argument
-// varies along the columns, one element replicated where it is stride-0 there
-template <class T, int VEC>
-BD_DEV void load_arg(const TView &a, int64_t r, int64_t c0, T (&x)[VEC]) {
-  const T *base = static_cast<const T *>(a.p) + r * a.sr;
-  if (a.sc != 0) {
-    load_vec<T, VEC>(base + c0, x);
-  } else {
-    T s = *base;
-#pragma unroll
-    for (int k = 0; k < VEC; ++k) x[k] = s;
-  }
+// base + byte offset; with a uniform base and a 32-bit lane offset this is the
+// scalar-base + vector-offset addressing mode: no per-plane address arithmetic
+template <class T>
+BD_DEV T *at(const void *base, uint32_t byte_off) {
+  // The empty asm pins the zero-extension of the offset to the basic block of the access;
+  // instruction selection only folds base + zext(offset) into one instruction when it sees
+  // both there (accesses sit behind uniform null-pointer and bounds branches).
+  asm("" : "+v"(byte_off));
+  return reinterpret_cast<T *>(const_cast<char *>(static_cast<const char *>(base)) + byte_off);
+}
+
+BD_DEV float or_bits(float a, float b) { return __uint_as_float(__float_as_uint(a) | __float_as_uint(b)); }
+BD_DEV double or_bits(double a, double b) {
+  return __longlong_as_double(__double_as_longlong(a) | __double_as_longlong(b));
 }
 
 template <class Op, class T, int J>
@@ -64,12 +67,19 @@ BD_DEV int eval_op(const T (&a)[Op::N][VEC], int v, Y *y, std::index_sequence<J.
   return Op::apply(y, make_arg<Op, T, (int)J>(a[J][v])...);
 }
 
-// Tiled 2-D kernel.  Block = 256 lanes arranged TY x TX; a lane owns VEC consecutive
-// columns and walks `steps` rows spaced TY apart.  Arguments that do not vary along the
-// rows (row vectors, scalars) are loaded once and stay in registers for the whole walk;
-// arguments that do not vary along the columns are one broadcast load per row.
+// Tiled 2-D kernel.  Block = 256 lanes arranged TY x TX over TY rows; a lane owns VEC
+// consecutive columns of one row.  Stride-0 arguments are served from registers: a column
+// vector or scalar is one broadcast load per lane, a row vector one vector load from its
+// only row.  There is deliberately no row loop: with ~30 plane pointers live across a loop
+// the scalar register file overflows, and one short-lived block per row tile measured as
+// fast as longer-lived ones.
+#ifndef BD_FWD_WAVES
+#define BD_FWD_ATTR
+#else
+#define BD_FWD_ATTR __attribute__((amdgpu_waves_per_eu(BD_FWD_WAVES, BD_FWD_WAVES)))
+#endif
 template <class Op, class T, int VEC>
-__global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams p) {
+__global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const FwdTiledParams p) {
   constexpr int N = Op::N, M = Op::M;
   constexpr int ND = N - popc(Op::NONDIFF);
   using Y = Dual<T, (ND >= 32 ? 0xffffffffu : ((1u << ND) - 1u))>;
@@ -81,19 +91,41 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   const uint32_t rt = blockIdx.x / nct, ct = blockIdx.x - rt * nct;
   const int64_t c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
   if (c0 >= p.C) return;
-  int64_t r = (int64_t)rt * ((int64_t)TY * p.steps) + ty;
+  const int64_t r = (int64_t)rt * TY + ty;
+  if (r >= p.R) return;
   const bool nt = p.nt_store != 0;
+  const uint32_t col_off = (uint32_t)c0 * (uint32_t)sizeof(T);
+  const uint32_t off = (uint32_t)(r * p.row_stride + c0) * (uint32_t)sizeof(T);
 
+  // Every argument is fetched in whichever of two forms applies -- a vector for arguments
+  // that vary along the columns, one broadcast element otherwise -- into registers of its
+  // own; the form that does not apply is skipped by a uniform branch and reads as zero
+  // bits, and the two are OR-ed together afterwards.  Keeping the forms apart (the second
+  // test goes through a copy of the mask the compiler cannot see through, or it would fold
+  // the two forms into one register again) lets all loads be in flight together instead of
+  // each waiting for the one before.
+  uint32_t colinv_again = p.col_invariant;
+  asm volatile("" : "+s"(colinv_again));
+  T avec[N][VEC], asc[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
+    if (!((p.col_invariant >> j) & 1u))  // from this row, or (row vectors) from the only row
+      load_vec<T, VEC>(at<const T>(p.arg_p[j], ((p.row_invariant >> j) & 1u) ? col_off : off), avec[j]);
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    asc[j] = T(0);
+    if ((colinv_again >> j) & 1u)  // one value for the row (column vectors) or for everything (scalars)
+      asc[j] = static_cast<const T *>(p.arg_p[j])[((p.row_invariant >> j) & 1u) ? 0 : r * p.arg_sr[j]];
+  }
   T a[N][VEC];
 #pragma unroll
   for (int j = 0; j < N; ++j)
-    if (p.arg[j].sr == 0) load_arg<T, VEC>(p.arg[j], 0, c0, a[j]);
-
-  for (int k = 0; k < p.steps && r < p.R; ++k, r += TY) {
 #pragma unroll
-    for (int j = 0; j < N; ++j)
-      if (p.arg[j].sr != 0) load_arg<T, VEC>(p.arg[j], r, c0, a[j]);
-
+    for (int v = 0; v < VEC; ++v) a[j][v] = or_bits(avec[j][v], asc[j]);
+  {
     Y y[VEC][M];
     int br[VEC];
 #pragma unroll
@@ -104,32 +136,32 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      store_vec<T, VEC>(static_cast<T *>(p.out[i].p) + r * p.out[i].sr + c0, o, nt);
+      store_vec<T, VEC>(at<T>(p.out_p[i], off), o, nt);
     }
     if (p.has_partials) {
 #pragma unroll
       for (int i = 0; i < M; ++i) {
         static_for<0, ND>([&](auto JD) {
           constexpr int jd = decltype(JD)::value;
-          const TView &pl = p.part[i * ND + jd];
-          if (pl.p != nullptr) {
+          void *pl = p.part_p[i * ND + jd];
+          if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-            store_vec<T, VEC>(static_cast<T *>(pl.p) + r * pl.sr + c0, o, nt);
+            store_vec<T, VEC>(at<T>(pl, off), o, nt);
           }
         });
       }
     }
-    if (p.branch.p != nullptr) {
-      uint8_t *bp = static_cast<uint8_t *>(p.branch.p) + r * p.branch.sr + c0 * p.branch.sc;
-      if (VEC == 4 && p.branch.sc == 1 && (reinterpret_cast<uintptr_t>(bp) & 3u) == 0) {
+    if (p.branch_p != nullptr) {
+      uint8_t *bp = p.branch_p + r * p.branch_sr + c0 * p.branch_sc;
+      if (VEC == 4 && p.branch_sc == 1 && (reinterpret_cast<uintptr_t>(bp) & 3u) == 0) {  // four ids in one store
         uint32_t w = 0;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) w |= (uint32_t)(br[v] & 0xff) << (8 * v);
         *reinterpret_cast<uint32_t *>(bp) = w;
       } else {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) bp[v * p.branch.sc] = (uint8_t)br[v];
+        for (int v = 0; v < VEC; ++v) bp[v * p.branch_sc] = (uint8_t)br[v];
       }
     }
   }
@@ -180,8 +212,10 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
 template <class Op>
 hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
   if (dt == BCAST_F32) {
-    if (vec > 1)
+    if (vec == 4)
       hipLaunchKernelGGL((fwd_tiled_kernel<Op, float, 4>), grid, dim3(kBlock), 0, s, p);
+    else if (vec == 2)
+      hipLaunchKernelGGL((fwd_tiled_kernel<Op, float, 2>), grid, dim3(kBlock), 0, s, p);
     else
       hipLaunchKernelGGL((fwd_tiled_kernel<Op, float, 1>), grid, dim3(kBlock), 0, s, p);
   } else {

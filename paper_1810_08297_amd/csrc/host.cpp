@@ -28,13 +28,19 @@ BD_DECLARE_OP(branchy5)
 BD_DECLARE_OP(cos_x)
 BD_DECLARE_OP(scale_xt)
 BD_DECLARE_OP(pair3)
+BD_DECLARE_OP(linear12)
+#ifndef BD_NO_ARITY
 #define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K)
 BD_ARITY_LIST(BD_DECL_ARITY)
+#endif
 
-hipError_t bd_bwd_tiled(int dt, int vec, const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na);
+hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, const BwdTiledParams &p,
+                        dim3 grid, size_t lds, hipStream_t s);
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
-hipError_t bd_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t s);
+hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
+                           const int64_t *out_stride, int64_t n_chunks, hipStream_t s);
 
 namespace {
 
@@ -57,11 +63,16 @@ const OpDesc kOps[] = {
     BD_OP_ROW(cos_x, 1, 1, 0u, 1)
     BD_OP_ROW(scale_xt, 2, 1, 0u, 1)
     BD_OP_ROW(pair3, 3, 2, 0u, 1)
-    BD_ARITY_LIST(BD_ARITY_ROW)};
+    BD_OP_ROW(linear12, 12, 2, (1u << 6) | (1u << 7), 1)
+#ifndef BD_NO_ARITY
+    BD_ARITY_LIST(BD_ARITY_ROW)
+#endif
+};
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-int g_tune[4] = {0, 0, 1, 0};
+constexpr int kNumTune = 7;
+int g_tune[kNumTune] = {0, 0, 1, 0, 16, 0, 1};
 
 // ---- small helpers ---------------------------------------------------------------------------
 inline size_t elem_size(int dt) { return dt == BCAST_F32 ? 4 : 8; }
@@ -170,6 +181,23 @@ inline GView gview(const Canon &c, size_t t, void *p) {
   GView v{p, {0, 0, 0, 0}};
   for (int d = 0; d < c.nd; ++d) v.s[d] = c.strides[t][d];
   return v;
+}
+
+// Row stride shared by every view that varies along rows and columns, or -1 if they differ
+// or if some element would sit beyond a 32-bit byte offset.
+int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es) {
+  if (s2.R == 1) return 0;
+  int64_t sr = -1;
+  for (size_t t = 0; t < v.size(); ++t) {
+    if (!v[t].p) continue;
+    const TView tv = tview(c, t, nullptr);
+    if (tv.sr == 0 || tv.sc == 0) continue;
+    if (sr < 0) sr = tv.sr;
+    else if (sr != tv.sr) return -1;
+  }
+  if (sr < 0) return 0;  // no such view: the offset is never used
+  const unsigned __int128 last = ((unsigned __int128)(s2.R - 1) * sr + s2.C) * es;
+  return last <= 0xffffffffULL ? sr : -1;
 }
 
 struct Geometry {
@@ -285,32 +313,50 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (size_t t = N; t < v.size() && tiled; ++t)
       if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
   }
+  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es) : -1;
+  tiled = tiled && fwd_sr >= 0;
   plan.tiled = tiled;
   if (tiled) {
     FwdTiledParams &p = plan.tp;
+    p.row_stride = fwd_sr;
     p.R = s2.R;
     p.C = s2.C;
-    const int vw = (int)(16 / es);
-    bool vec_ok = (s2.C % vw == 0);
-    for (size_t t = 0; t < v.size() && vec_ok; ++t) {
-      if (!v[t].p) continue;
-      const TView tv = tview(c, t, v[t].p);
-      if (tv.sc == 0 && s2.C > 1) continue;  // a broadcast load: one element
-      vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % 16 == 0) && (s2.R == 1 || tv.sr % vw == 0);
+    // widest vector (16 bytes per lane at most) that every vector-accessed view allows
+    int vw = (int)(std::max<int>(g_tune[4], (int)es) / es);
+    for (; vw > 1; vw /= 2) {
+      bool vec_ok = (s2.C % vw == 0);
+      for (size_t t = 0; t < v.size() && vec_ok; ++t) {
+        if (!v[t].p) continue;
+        const TView tv = tview(c, t, v[t].p);
+        if (tv.sc == 0 && s2.C > 1) continue;  // a broadcast load: one element
+        vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0);
+      }
+      if (vec_ok) break;
     }
     Geometry g;
-    g.vec = vec_ok ? vw : 1;
+    g.vec = vw;
     tile_columns(s2.C, g.vec, g);
-    if (!tile_rows(s2.R, g_tune[0] > 0 ? g_tune[0] : auto_steps(s2.R, g, 4), g)) return BCAST_ERR_LAUNCH_FAILED;
+    if (!tile_rows(s2.R, 1, g)) return BCAST_ERR_LAUNCH_FAILED;  // the forward kernel has no row loop
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
     p.steps = g.steps;
     p.nt_store = g_tune[2];
     p.has_partials = n_planes > 0;
-    for (int j = 0; j < N; ++j) p.arg[j] = tview(c, j, v[j].p);
-    for (int i = 0; i < M; ++i) p.out[i] = tview(c, N + i, v[N + i].p);
-    for (int k = 0; k < n_planes; ++k) p.part[k] = tview(c, N + M + k, v[N + M + k].p);
-    p.branch = want_branch ? tview(c, v.size(), const_cast<uint8_t *>(branch_id)) : TView{nullptr, 0, 0};
+    for (int j = 0; j < N; ++j) {
+      const TView tv = tview(c, j, v[j].p);
+      p.arg_p[j] = tv.p;
+      p.arg_sr[j] = tv.sr;
+      if (tv.sr == 0) p.row_invariant |= 1u << j;
+      if (tv.sc == 0) p.col_invariant |= 1u << j;
+    }
+    for (int i = 0; i < M; ++i) p.out_p[i] = v[N + i].p;
+    for (int k = 0; k < n_planes; ++k) p.part_p[k] = v[N + M + k].p;
+    if (want_branch) {
+      const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
+      p.branch_p = static_cast<uint8_t *>(tv.p);
+      p.branch_sr = tv.sr;
+      p.branch_sc = tv.sc;
+    }
     plan.grid = dim3((unsigned)(g.n_ct * g.n_rt), 1, 1);
     plan.info.path = 1;
     plan.info.vec = g.vec;
@@ -351,6 +397,8 @@ struct BwdPlan {
   bcast_plan_info info{};
   bool tiled = false;
   int vec = 1;
+  bool signature = false;          // a kernel compiled for exactly this mix of gradient classes exists
+  int n_cls[4] = {0, 0, 0, 0};     // gradients per class: full, row-sum, col-sum, all-sum
   std::vector<BwdTiledParams> main;  // usually one launch
   std::vector<size_t> main_lds;
   dim3 grid{1, 1, 1};
@@ -430,18 +478,30 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (cls[j] == kGradFull) tiled = (tview(c, g0 + j, nullptr).sc == 1);
     }
   }
+  int64_t bwd_sr = -1;
+  if (tiled) {
+    // reduced gradients are addressed on their own; only full-shape views share the offset
+    std::vector<PView> fullv = v;
+    for (int j = 0; j < ND; ++j)
+      if (cls[j] != kGradFull) fullv[g0 + j].p = nullptr;
+    bwd_sr = common_row_stride(c, fullv, s2, es);
+    tiled = bwd_sr >= 0;
+  }
   plan.tiled = tiled;
   if (tiled) {
-    const int vw = (int)(16 / es);
-    bool vec_ok = (s2.C % vw == 0);
-    for (size_t t = 0; t < v.size() && vec_ok; ++t) {
-      if (!v[t].p) continue;
-      if (t >= g0 && cls[t - g0] != kGradFull) continue;  // reduced gradients are stored by element
-      const TView tv = tview(c, t, v[t].p);
-      vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % 16 == 0) && (s2.R == 1 || tv.sr % vw == 0);
+    int vw = (int)(std::max<int>(g_tune[4], (int)es) / es);
+    for (; vw > 1; vw /= 2) {
+      bool vec_ok = (s2.C % vw == 0);
+      for (size_t t = 0; t < v.size() && vec_ok; ++t) {
+        if (!v[t].p) continue;
+        if (t >= g0 && cls[t - g0] != kGradFull) continue;  // reduced gradients are stored by element
+        const TView tv = tview(c, t, v[t].p);
+        vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0);
+      }
+      if (vec_ok) break;
     }
     Geometry g;
-    g.vec = vec_ok ? vw : 1;
+    g.vec = vw;
     plan.vec = g.vec;
     tile_columns(s2.C, g.vec, g);
     bool any_rowwise = false;  // sums over rows: worth many rows per block
@@ -474,9 +534,11 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.log2_tx = g.log2_tx;
       p.steps = g.steps;
       p.nt_store = g_tune[2];
+      p.reverse = g_tune[6];
       p.M = M;
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
+      p.row_stride = bwd_sr;
       for (int i = 0; i < M; ++i) p.adj[i] = tview(c, i, v[i].p);
     };
     auto lds_need = [&](const BwdTiledParams &p, size_t &row_off, size_t &col_off, size_t &all_off) {
@@ -500,8 +562,18 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       plan.main_lds.push_back(total);
     };
     reset(cur);
-    for (int j = 0; j < ND; ++j) {
-      if (cls[j] == kGradSkip) continue;
+    // the gradient table is ordered by class (full, row-sum, col-sum, all-sum), which is
+    // what the signature kernels expect; within a class the argument order is kept
+    std::vector<int> order;
+    bool all_planes = true;
+    for (int want = kGradFull; want <= kGradAllSum; ++want)
+      for (int j = 0; j < ND; ++j)
+        if (cls[j] == want) {
+          order.push_back(j);
+          plan.n_cls[want]++;
+          for (int i = 0; i < M; ++i) all_planes = all_planes && v[M + i * ND + j].p != nullptr;
+        }
+    for (int j : order) {
       BwdTiledParams trial = cur;
       trial.n_row_slots += (cls[j] == kGradRowSum);
       trial.n_col_slots += (cls[j] == kGradColSum);
@@ -543,6 +615,8 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
     }
     flush();
+    plan.signature = all_planes && plan.main.size() == 1 && g_tune[5] == 0 &&
+                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3]);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
     plan.ws_bytes = ws;
@@ -679,7 +753,8 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
     }
     for (size_t k = 0; k < plan.main.size(); ++k) {
       plan.main[k].ws = static_cast<unsigned char *>(workspace);
-      if (bd_bwd_tiled((int)dt, plan.vec, plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
+      if (bd_bwd_tiled((int)dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
+                       plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
         return BCAST_ERR_LAUNCH_FAILED;
     }
     if (plan.p2_blocks > 0) {
@@ -714,24 +789,47 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[4] = {0, 0, 0, 0}, hi[4] = {64, 256, 1, 1};
-  if (key < 0 || key > 3 || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0}, hi[kNumTune] = {64, 256, 1, 1, 16, 16, 1};
+  if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
+  if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;
   return BCAST_OK;
 }
 int bcast_dual_get_tuning(int32_t key, int32_t *value) {
-  if (key < 0 || key > 3 || value == nullptr) return BCAST_ERR_BAD_ARG_COUNT;
+  if (key < 0 || key >= kNumTune || value == nullptr) return BCAST_ERR_BAD_ARG_COUNT;
   *value = g_tune[key];
   return BCAST_OK;
 }
 
-int bcast_dual_copy_probe(void *dst, const void *src, size_t bytes, void *stream) {
-  if (dst == nullptr || src == nullptr) return BCAST_ERR_NULL_POINTER;
-  if (bytes % 16 != 0 || reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
-    return BCAST_ERR_MISALIGNED;
-  if (bytes / 16 / kBlock > 0x7fffffffULL) return BCAST_ERR_LAUNCH_FAILED;
-  return bd_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? BCAST_OK
-                                                                                         : BCAST_ERR_LAUNCH_FAILED;
+size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offsets) {
+  if (n_planes <= 0) return 0;
+  // HBM channels interleave at 4 KiB: planes whose starts differ by a multiple of a large
+  // power of two put the same element of every plane on the same channel.  One extra 4 KiB
+  // page per plane staggers them.  Small planes are only aligned.
+  const size_t page = 4096;
+  const size_t rounded = (plane_bytes + page - 1) / page * page;
+  const size_t stride = plane_bytes >= (size_t)1 << 20 ? rounded + page : (plane_bytes + 255) / 256 * 256;
+  if (offsets)
+    for (int32_t k = 0; k < n_planes; ++k) offsets[k] = (size_t)k * stride;
+  return (size_t)n_planes * stride;
+}
+
+int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
+                            void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream) {
+  if (n_in < 0 || n_in > 32 || n_out < 0 || n_out > 32 || n_in + n_out == 0) return BCAST_ERR_BAD_ARG_COUNT;
+  if ((n_in && (!in || !in_chunk_stride)) || (n_out && (!out || !out_chunk_stride))) return BCAST_ERR_NULL_POINTER;
+  if (n_chunks < 0 || n_chunks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
+  for (int k = 0; k < n_in; ++k) {
+    if (!in[k]) return BCAST_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(in[k]) % 16 || in_chunk_stride[k] % 4 || in_chunk_stride[k] < 0) return BCAST_ERR_MISALIGNED;
+  }
+  for (int k = 0; k < n_out; ++k) {
+    if (!out[k]) return BCAST_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(out[k]) % 16 || out_chunk_stride[k] % 4 || out_chunk_stride[k] < 1024) return BCAST_ERR_MISALIGNED;
+  }
+  if (n_chunks == 0) return BCAST_OK;
+  return bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks,
+                         static_cast<hipStream_t>(stream)) == hipSuccess ? BCAST_OK : BCAST_ERR_LAUNCH_FAILED;
 }
 
 }  // extern "C"

@@ -10,7 +10,10 @@ namespace bd {
 constexpr int kBlock = 256;  // threads per block of every tiled kernel (4 wavefronts)
 
 // A 2-D view used by the tiled kernels: element (r, c) lives at p + r*sr + c*sc.
-// For tensors read or written with vector instructions sc is 0 or 1.
+// For tensors read or written with vector instructions sc is 0 or 1.  Every view that
+// varies along both rows and columns shares ONE row stride (row_stride of the parameter
+// block) and fits 32-bit byte offsets, so a lane computes a single offset per row and
+// every plane is addressed as (uniform base pointer) + (that offset).
 struct TView {
   void *p;
   int64_t sr;
@@ -24,10 +27,17 @@ struct FwdTiledParams {
   int32_t nt_store;    // non-temporal stores
   int32_t has_partials;
   int64_t n_ct;        // column tiles; block b serves column tile b % n_ct of row tile b / n_ct
-  TView arg[BCAST_MAX_ARGS];
-  TView out[BCAST_MAX_OUTS];
-  TView part[BCAST_MAX_PLANES];
-  TView branch;        // uint8 elements; p == nullptr: not requested
+  int64_t row_stride;  // elements between rows of every full-shape view (0 when R == 1)
+  uint32_t row_invariant;  // bit j: argument j does not vary along the rows
+  uint32_t col_invariant;  // bit j: argument j does not vary along the columns
+  // pointers are kept apart from the rarely used strides so that a few wide scalar loads
+  // fetch them and nothing else occupies scalar registers
+  const void *arg_p[BCAST_MAX_ARGS];
+  void *out_p[BCAST_MAX_OUTS];
+  void *part_p[BCAST_MAX_PLANES];  // nullptr: plane not stored
+  uint8_t *branch_p;               // nullptr: not requested
+  int64_t branch_sr, branch_sc;
+  int64_t arg_sr[BCAST_MAX_ARGS];  // row stride of the column-invariant arguments
 };
 
 // A strided view of up to BCAST_MAX_DIMS merged dims for the generic kernels.
@@ -69,10 +79,11 @@ struct BwdTiledParams {
   int64_t R, C;
   int32_t log2_tx, steps, nt_store, M;
   int32_t n_entries;
+  int32_t reverse;  // 1: blocks walk the tiles from the last to the first
   int32_t n_row_slots, n_col_slots, n_all_slots;
   uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS
-  uint32_t pad;
   int64_t n_ct, n_rt;  // column tiles, row tiles; block b = rt * n_ct + ct
+  int64_t row_stride;  // elements between rows of every full-shape view (0 when R == 1)
   unsigned char *ws;
   TView adj[BCAST_MAX_OUTS];
   BwdEntry e[BCAST_MAX_ARGS];

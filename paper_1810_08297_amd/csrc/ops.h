@@ -123,6 +123,21 @@ struct OpPair3 {
   }
 };
 
+// An arithmetic-light op with the argument list of the HM-LSTM update (same planes, same
+// traffic, almost no math): separates memory behaviour from arithmetic when profiling.
+struct OpLinear12 {
+  static constexpr int N = 12, M = 2, NBR = 1;
+  static constexpr uint32_t NONDIFF = (1u << 6) | (1u << 7);
+  template <class Y, class F, class I, class O, class G, class C, class H, class Z, class BF, class BI,
+            class BO, class BG>
+  static BD_DEV int apply(Y *y, const F &f, const I &i, const O &o, const G &g, const C &c, const H &h,
+                          const Z &z, const Z &zb, const BF &bf, const BI &bi, const BO &bo, const BG &bg) {
+    y[0] = f + i + o + g + c + h + bf + bi + bo + bg + z * zb;
+    y[1] = f * c + i * h + o * g + bf * bi + bo * bg;
+    return 0;
+  }
+};
+
 // Arity study (Sec. 3.4.1): prod_i tanh(g(x_i)), g(x) = x if x > 1/2 else -x.
 template <int ARITY>
 struct OpProdTanh {

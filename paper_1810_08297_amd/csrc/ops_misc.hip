@@ -5,3 +5,4 @@ BD_DEFINE_OP(bd::OpBranchy5, branchy5)
 BD_DEFINE_OP(bd::OpCosX, cos_x)
 BD_DEFINE_OP(bd::OpScaleXt, scale_xt)
 BD_DEFINE_OP(bd::OpPair3, pair3)
+BD_DEFINE_OP(bd::OpLinear12, linear12)

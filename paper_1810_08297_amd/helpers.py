@@ -13,20 +13,29 @@ class ForwardBuffers:
     outs: List = field(default_factory=list)       # M tensors of the unified shape
     partials: List = field(default_factory=list)   # M*N_d planes, index i*N_d + jd
     branch: Optional[object] = None                # uint8, unified shape
+    slab: Optional[object] = None                  # keeps the memory of outs/partials alive
 
     def run(self, args, stream=None):
         B.bcast_dual_forward(self.op_id, args, self.outs, self.partials, self.branch, stream)
         return self
+
+    def prepare(self, args):
+        """Marshal the call once; the returned object's launch() only enqueues the kernel."""
+        return B.PreparedForward(self.op_id, args, self.outs, self.partials, self.branch)
 
 
 @dataclass
 class BackwardBuffers:
     grads: List = field(default_factory=list)      # N_d tensors in their argument's shape
     workspace: Optional[object] = None
+    slab: Optional[object] = None
 
     def run(self, adjoints, partials, stream=None):
         B.bcast_dual_backward(adjoints, partials, self.grads, self.workspace, stream)
         return self
+
+    def prepare(self, adjoints, partials):
+        return B.PreparedBackward(adjoints, partials, self.grads, self.workspace)
 
 
 def unified_shape(args):
@@ -39,23 +48,59 @@ def unified_shape(args):
     return tuple(shape)
 
 
-def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: bool = True) -> ForwardBuffers:
+def _numel(shape):
+    n = 1
+    for s in shape:
+        n *= int(s)
+    return n
+
+
+def alloc_planes(shapes, dtype, device, staggered: bool = True):
+    """Contiguous tensors of the given shapes.  With ``staggered`` the ones that share the
+    largest size are carved out of one slab in the library's staggered layout
+    (bcast_dual_slab_layout); the rest are ordinary allocations.  Returns (tensors, slab)."""
+    import torch
+    es = torch.empty((), dtype=dtype).element_size()
+    shapes = [tuple(int(x) for x in s) for s in shapes]
+    big = max((_numel(s) for s in shapes), default=0)
+    idx = [k for k, s in enumerate(shapes) if _numel(s) == big] if staggered and big > 0 else []
+    out = [None] * len(shapes)
+    slab = None
+    if idx:
+        total, offs = B.bcast_dual_slab_layout(big * es, len(idx))
+        slab = torch.empty(total, dtype=torch.uint8, device=device)
+        for n, k in enumerate(idx):
+            out[k] = slab[offs[n]: offs[n] + big * es].view(dtype).view(shapes[k])
+    for k, s in enumerate(shapes):
+        if out[k] is None:
+            out[k] = torch.empty(s, dtype=dtype, device=device)
+    return out, slab
+
+
+def to_slab(tensors, staggered: bool = True):
+    """Copy tensors (same dtype and device) into freshly allocated staggered planes."""
+    out, slab = alloc_planes([t.shape for t in tensors], tensors[0].dtype, tensors[0].device, staggered)
+    for o, t in zip(out, tensors):
+        o.copy_(t)
+    return out, slab
+
+
+def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: bool = True,
+                  staggered: bool = True) -> ForwardBuffers:
     import torch
     op_id = B.bcast_op_lookup(op_name)
     n, m, mask, _ = B.bcast_op_info(op_id)
     nd = n - bin(mask).count("1")
     shape = unified_shape(args)
-    kw = dict(dtype=args[0].dtype, device=args[0].device)
-    outs = [torch.empty(shape, **kw) for _ in range(m)]
-    parts = [torch.empty(shape, **kw) for _ in range(m * nd)] if want_partials else None
+    n_planes = m + (m * nd if want_partials else 0)
+    planes, slab = alloc_planes([shape] * n_planes, args[0].dtype, args[0].device, staggered)
     br = torch.empty(shape, dtype=torch.uint8, device=args[0].device) if want_branch else None
-    return ForwardBuffers(op_id, outs, parts, br)
+    return ForwardBuffers(op_id, planes[:m], planes[m:] if want_partials else None, br, slab)
 
 
-def alloc_backward(adjoints, partials, grad_shapes) -> BackwardBuffers:
+def alloc_backward(adjoints, partials, grad_shapes, staggered: bool = True) -> BackwardBuffers:
     import torch
-    kw = dict(dtype=adjoints[0].dtype, device=adjoints[0].device)
-    grads = [torch.empty(tuple(s), **kw) for s in grad_shapes]
+    grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered)
     nbytes = B.bcast_dual_backward_workspace(adjoints, partials, grads)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
-    return BackwardBuffers(grads, ws)
+    return BackwardBuffers(grads, ws, slab)

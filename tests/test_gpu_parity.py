@@ -20,6 +20,7 @@ def small_args(op, R, C, dtype, seed=0):
     full, row, col, sc = (R, C), (1, C), (R, 1), (1, 1)
     shp = {
         "hmlstm_update": [full] * 6 + [row, row] + [col] * 4,
+        "linear12": [full] * 6 + [row, row] + [col] * 4,
         "tanh_xy_b": [full, full, col],
         "branchy5": [full, full, row, col, sc],
         "update_c": [full] * 4 + [row, row],
@@ -28,7 +29,7 @@ def small_args(op, R, C, dtype, seed=0):
         "pair3": [full, sc, col],
     }[op]
     args = [rng.standard_normal(s).astype(dtype) for s in shp]
-    if op == "hmlstm_update":
+    if op in ("hmlstm_update", "linear12"):
         args[6] = (rng.random(shp[6]) < 0.4).astype(dtype)
         args[7] = (rng.random(shp[7]) < 0.5).astype(dtype)
     if op == "update_c":
@@ -41,7 +42,7 @@ def small_args(op, R, C, dtype, seed=0):
     return args, adj
 
 
-OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3"]
+OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12"]
 # several tiles, ragged tails, one row / one column / one element, rows wider than a block
 SHAPES = [(1, 1), (1, 7), (5, 1), (3, 5), (64, 16), (7, 33), (129, 260), (2, 4100), (300, 1028), (1, 5000)]
 

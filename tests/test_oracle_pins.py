@@ -24,6 +24,7 @@ def shapes_for(op, R, C):
     full, row, col, sc = (R, C), (1, C), (R, 1), (1, 1)
     return {
         "hmlstm_update": [full] * 6 + [row, row] + [col] * 4,
+        "linear12": [full] * 6 + [row, row] + [col] * 4,
         "tanh_xy_b": [full, full, col],
         "branchy5": [full, full, row, col, sc],
         "update_c": [full] * 4 + [row, row],
@@ -36,7 +37,7 @@ def shapes_for(op, R, C):
 def random_args(op, R, C, dtype=np.float64, rng=RNG):
     shp = shapes_for(op, R, C)
     args = [rng.standard_normal(s).astype(dtype) for s in shp]
-    if op == "hmlstm_update":
+    if op in ("hmlstm_update", "linear12"):
         args[6] = (rng.random(shp[6]) < 0.5).astype(dtype)
         args[7] = (rng.random(shp[7]) < 0.5).astype(dtype)
     if op == "update_c":
@@ -64,6 +65,10 @@ def tape_program(op, x):
         else:
             cn = T.sigmoid(f + bf) * c + T.sigmoid(i + bi) * T.tanh(g + bg)
         return [cn, T.sigmoid(o + bo) * T.tanh(cn)]
+    if op == "linear12":
+        f, i, o, g, c, h, z, zb, bf, bi, bo, bg = x
+        return [f + i + o + g + c + h + bf + bi + bo + bg + z.v * zb.v,
+                f * c + i * h + o * g + bf * bi + bo * bg]
     if op == "update_c":
         c, f, i, g, z1, z2 = x
         if z1.v == 1.0:
@@ -91,7 +96,7 @@ def tape_program(op, x):
     raise KeyError(op)
 
 
-OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3"]
+OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12"]
 
 
 def assert_close(a, b, rtol, atol, what=""):
