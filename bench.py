@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--p-index", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=16)
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run the library's 1-in 1-out stream probe on a buffer of this many MiB "
+                         "(a copy of known size, for scaling profiler byte counters)")
     ap.add_argument("--tune", type=lambda t: tuple(int(x) for x in t.split("=")), action="append", default=[],
                     help="KEY=VALUE launch-shape override (see bcast_dual_set_tuning), repeatable")
     a = ap.parse_args()
@@ -109,6 +112,13 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
+    if a.copy_probe_mib > 0:
+        n = a.copy_probe_mib * (1 << 20) // 4
+        src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr)
+        torch.cuda.synchronize()
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
     torch.cuda.synchronize()
