@@ -24,8 +24,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a
-# copy kernel of known size); see profiles/.  Keyed by (workload, kernel).
-MEASURED_TRAFFIC = {}
+# copy kernel of known size); see profiles/hbm_traffic_cfg3_pmc.md.  Keyed by (workload, kernel).
+MEASURED_TRAFFIC = {("cfg3", "forward"): 487.1e6, ("cfg3", "backward"): 470.5e6}
 
 
 def build_workload(name, p_index):
