@@ -108,6 +108,12 @@ const char *bcast_op_name(int32_t op_id); /* NULL if out of range */
 int bcast_op_info(int32_t op_id, int32_t *n_args, int32_t *n_outputs, uint32_t *nondiff_mask,
                   int32_t *n_branches);
 
+/* What the op table knows about the M * N_d planes of an op, for callers that want a leaner
+ * partial store: alias[k] == k: plane k has content of its own; alias[k] == j < k: plane k is
+ * identical to plane j on every branch (e.g. a bias and the gate it is added to); alias[k] == -1:
+ * plane k is zero on every branch.  `alias` receives M * N_d entries. */
+int bcast_op_plane_alias(int32_t op_id, int32_t *alias);
+
 /* ---- forward: values + Jacobian planes in one kernel (Sec. 2.2.2, Sec. 2.2.3) -----
  * args[n_args]      inputs (read).  Unified shape = per-dim maximum; every argument dim
  *                   must equal it or be 1 (else BCAST_ERR_SHAPE_MISMATCH).
@@ -116,6 +122,9 @@ int bcast_op_info(int32_t op_id, int32_t *n_args, int32_t *n_outputs, uint32_t *
  *                   where jd counts differentiable arguments in argument order
  *                   (row = output, column = argument, as in the D(b) expansion of
  *                   Sec. 2.2.2).  A plane whose data pointer is NULL is not stored.
+ *                   Two slots may be given the very same view where bcast_op_plane_alias
+ *                   declares the planes identical (it is then written once); any other
+ *                   sharing of a view is refused with BCAST_ERR_BAD_STRIDE.
  *                   `partials` itself may be NULL: values only.
  * branch_id         optional device buffer of E bytes (E = elements of the unified
  *                   shape), row-major over the unified shape as given (before any

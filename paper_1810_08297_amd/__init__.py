@@ -5,7 +5,7 @@ thin Python binding plus buffer-allocation helpers and the seeded workload gener
 """
 from .binding import (  # noqa: F401
     BcastError, BcastTensor, PlanInfo, F32, F64, LIB_PATH, EXPORTS,
-    bcast_op_lookup, bcast_op_count, bcast_op_name, bcast_op_info, diff_arg_indices,
+    bcast_op_lookup, bcast_op_count, bcast_op_name, bcast_op_info, bcast_op_plane_alias, diff_arg_indices,
     bcast_dual_forward, bcast_dual_forward_plan, bcast_dual_backward_workspace,
     bcast_dual_backward, bcast_dual_backward_plan, bcast_dual_set_tuning,
     bcast_dual_get_tuning, bcast_dual_stream_probe, bcast_dual_slab_layout, status_string, as_view, raw_view, PreparedForward, PreparedBackward,

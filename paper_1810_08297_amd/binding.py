@@ -49,7 +49,7 @@ _lib = None
 EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
            "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
-           "bcast_dual_get_tuning", "bcast_dual_stream_probe", "bcast_dual_slab_layout")
+           "bcast_dual_get_tuning", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias")
 
 
 def lib():
@@ -100,6 +100,15 @@ def bcast_op_info(op_id: int):
     _check(lib().bcast_op_info(ctypes.c_int32(op_id), ctypes.byref(a), ctypes.byref(m), ctypes.byref(mask),
                                ctypes.byref(nb)), "bcast_op_info")
     return a.value, m.value, mask.value, nb.value
+
+
+def bcast_op_plane_alias(op_id: int):
+    """alias[k] per plane: k = own content, j < k = identical to plane j, -1 = always zero."""
+    n, m, mask, _ = bcast_op_info(op_id)
+    cnt = m * (n - bin(mask).count("1"))
+    arr = (ctypes.c_int32 * cnt)()
+    _check(lib().bcast_op_plane_alias(ctypes.c_int32(op_id), arr), "bcast_op_plane_alias")
+    return [int(x) for x in arr]
 
 
 def diff_arg_indices(op_id: int):

@@ -303,8 +303,10 @@ BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
 }
 
 // Signature kernel: M outputs; the gradient table holds NF full, then NR row-sum, then NC
-// col-sum, then NA all-sum gradients, every plane present.
-template <class T, int VEC, int M, int NF, int NR, int NC, int NA>
+// col-sum, then NA all-sum gradients.  Bit e*M + i of ABSENT says that plane i of gradient e
+// is absent (a structurally zero partial the caller chose not to store): it is neither
+// loaded nor multiplied.
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT>
 __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
   constexpr int NE = NF + NR + NC + NA;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -323,7 +325,14 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
-        for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.e[e].P[i].p, off, valid, P[e][i]);
+        for (int i = 0; i < M; ++i) {
+          if ((ABSENT >> (e * M + i)) & 1u) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) P[e][i][v] = T(0);
+          } else {
+            load_plane<T, VEC, EDGE>(p.e[e].P[i].p, off, valid, P[e][i]);
+          }
+        }
 #pragma unroll
       for (int e = 0; e < NF; ++e) apply_full<T, VEC, M, EDGE>(p.e[e], adj, P[e], off, valid, nt);
 #pragma unroll
@@ -544,33 +553,39 @@ __global__ __launch_bounds__(kBlock) void stream_probe_kernel(const ProbeParams 
 // ---- launch wrappers --------------------------------------------------------------------------------
 using namespace bd;
 
-// Gradient-class signatures with a compiled kernel: {M, full, row-sum, col-sum, all-sum}.
-#define BD_SIGNATURES(X) \
-  X(2, 6, 4, 0, 0) /* HM-LSTM update with per-row biases */ \
-  X(1, 2, 1, 0, 0) /* tanh(x*y + b) */                      \
-  X(1, 2, 1, 1, 1) /* branchy5 */                           \
-  X(1, 4, 0, 0, 0) /* six-argument cell update */           \
-  X(1, 1, 0, 0, 0) X(1, 2, 0, 0, 0) X(1, 3, 0, 0, 0) X(1, 5, 0, 0, 0) X(1, 8, 0, 0, 0)
+// Gradient-class signatures with a compiled kernel: {M, full, row-sum, col-sum, all-sum,
+// absent-plane mask}.  The HM-LSTM update appears twice: with all 20 planes, and with the
+// planes of c' with respect to o and h (and the bias b_o) left out -- they are zero on
+// every branch.  Table order there: f i o g c h | b_f b_i b_o b_g, planes (c', h') per gradient.
+#define BD_HM_LEAN ((1ull << (2 * 2 + 0)) | (1ull << (5 * 2 + 0)) | (1ull << (8 * 2 + 0)))
+#define BD_SIGNATURES(X)                                          \
+  X(2, 6, 4, 0, 0, 0ull) /* HM-LSTM update, per-row biases */     \
+  X(2, 6, 4, 0, 0, BD_HM_LEAN)                                    \
+  X(1, 2, 1, 0, 0, 0ull) /* tanh(x*y + b) */                      \
+  X(1, 2, 1, 1, 1, 0ull) /* branchy5 */                           \
+  X(1, 2, 1, 1, 1, 1ull << 4) /* branchy5 without the always-zero plane of t */ \
+  X(1, 4, 0, 0, 0, 0ull) /* six-argument cell update */           \
+  X(1, 1, 0, 0, 0, 0ull) X(1, 2, 0, 0, 0, 0ull) X(1, 3, 0, 0, 0, 0ull) X(1, 5, 0, 0, 0, 0ull) X(1, 8, 0, 0, 0, 0ull)
 
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na) {
-#define BD_SIG_TEST(m, f, r, c, a) \
-  if (M == m && nf == f && nr == r && nc == c && na == a) return true;
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent) {
+#define BD_SIG_TEST(m, f, r, c, a, ab) \
+  if (M == m && nf == f && nr == r && nc == c && na == a && absent == (ab)) return true;
   BD_SIGNATURES(BD_SIG_TEST)
 #undef BD_SIG_TEST
   return false;
 }
 
-hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, const BwdTiledParams &p,
-                        dim3 grid, size_t lds, hipStream_t s) {
+hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent,
+                        const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
   if (signature && widest) {
-#define BD_SIG_GO(m, f, r, c, a)                                                                        \
-  if (p.M == m && nf == f && nr == r && nc == c && na == a) {                                           \
-    if (dt == BCAST_F32)                                                                                \
-      hipLaunchKernelGGL((bwd_sig_kernel<float, 4, m, f, r, c, a>), grid, dim3(kBlock), lds, s, p);     \
-    else                                                                                                \
-      hipLaunchKernelGGL((bwd_sig_kernel<double, 2, m, f, r, c, a>), grid, dim3(kBlock), lds, s, p);    \
-    return hipGetLastError();                                                                           \
+#define BD_SIG_GO(m, f, r, c, a, ab)                                                                        \
+  if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab)) {                             \
+    if (dt == BCAST_F32)                                                                                    \
+      hipLaunchKernelGGL((bwd_sig_kernel<float, 4, m, f, r, c, a, (ab)>), grid, dim3(kBlock), lds, s, p);   \
+    else                                                                                                    \
+      hipLaunchKernelGGL((bwd_sig_kernel<double, 2, m, f, r, c, a, (ab)>), grid, dim3(kBlock), lds, s, p);  \
+    return hipGetLastError();                                                                               \
   }
     BD_SIGNATURES(BD_SIG_GO)
 #undef BD_SIG_GO

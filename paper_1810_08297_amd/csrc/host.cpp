@@ -34,9 +34,9 @@ BD_DECLARE_OP(linear12)
 BD_ARITY_LIST(BD_DECL_ARITY)
 #endif
 
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na);
-hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, const BwdTiledParams &p,
-                        dim3 grid, size_t lds, hipStream_t s);
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent);
+hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent,
+                        const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
@@ -49,16 +49,24 @@ struct OpDesc {
   int n_args, n_out;
   uint32_t nondiff;
   int n_branches;
+  const int8_t *alias;  // per plane: own index, index of an identical earlier plane, or -1 (always zero); nullptr: all distinct
   hipError_t (*tiled)(int, int, const FwdTiledParams &, dim3, hipStream_t);
   hipError_t (*generic)(int, const FwdGenericParams &, dim3, hipStream_t);
 };
 
-#define BD_OP_ROW(NAME, N, M, NONDIFF, NBR) {#NAME, N, M, NONDIFF, NBR, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME},
+// HM-LSTM update, planes (c' then h') x (f i o g c h b_f b_i b_o b_g): a bias enters only through
+// its gate's pre-activation, so its plane equals the gate's; c' never depends on o, h, b_o.
+const int8_t kAliasHmLstm[20] = {0, 1, -1, 3, 4, -1, 0, 1, -1, 3, 10, 11, 12, 13, 14, 15, 10, 11, 12, 13};
+// branchy5 (A B r s t): the threshold t only appears in the predicate
+const int8_t kAliasBranchy5[5] = {0, 1, 2, 3, -1};
+
+#define BD_OP_ROW(NAME, N, M, NONDIFF, NBR) {#NAME, N, M, NONDIFF, NBR, nullptr, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME},
+#define BD_OP_ROW_A(NAME, N, M, NONDIFF, NBR, ALIAS) {#NAME, N, M, NONDIFF, NBR, ALIAS, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME},
 #define BD_ARITY_ROW(K) BD_OP_ROW(prod_tanh_##K, K, 1, 0u, K + 1)
 const OpDesc kOps[] = {
-    BD_OP_ROW(hmlstm_update, 12, 2, (1u << 6) | (1u << 7), 3)
+    BD_OP_ROW_A(hmlstm_update, 12, 2, (1u << 6) | (1u << 7), 3, kAliasHmLstm)
     BD_OP_ROW(tanh_xy_b, 3, 1, 0u, 1)
-    BD_OP_ROW(branchy5, 5, 1, 0u, 2)
+    BD_OP_ROW_A(branchy5, 5, 1, 0u, 2, kAliasBranchy5)
     BD_OP_ROW(update_c, 6, 1, (1u << 4) | (1u << 5), 3)
     BD_OP_ROW(cos_x, 1, 1, 0u, 1)
     BD_OP_ROW(scale_xt, 2, 1, 0u, 1)
@@ -285,6 +293,20 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
   plan.info = bcast_plan_info{};
   if (E == 0) return BCAST_OK;
 
+  // Two plane slots may share one view only where the op declares the planes identical;
+  // the later slot is then not written a second time.
+  std::vector<char> dup(n_planes, 0);
+  for (int k = 1; k < n_planes; ++k) {
+    if (!v[N + M + k].p) continue;
+    for (int j = 0; j < k; ++j) {
+      if (v[N + M + j].p != v[N + M + k].p) continue;
+      const bool same_view = v[N + M + j].stride == v[N + M + k].stride;
+      if (!same_view || !op.alias || op.alias[k] < 0 || op.alias[k] != op.alias[j]) return BCAST_ERR_BAD_STRIDE;
+      dup[k] = 1;
+      break;
+    }
+  }
+
   // effective strides: stride 0 wherever an argument's dim is 1 (virtual copy)
   std::vector<Dims> eff;
   for (auto &pv : v) eff.push_back(pv.p ? pv.stride : v[N].stride);  // absent planes never block a merge
@@ -350,7 +372,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       if (tv.sc == 0) p.col_invariant |= 1u << j;
     }
     for (int i = 0; i < M; ++i) p.out_p[i] = v[N + i].p;
-    for (int k = 0; k < n_planes; ++k) p.part_p[k] = v[N + M + k].p;
+    for (int k = 0; k < n_planes; ++k) p.part_p[k] = dup[k] ? nullptr : v[N + M + k].p;
     if (want_branch) {
       const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
       p.branch_p = static_cast<uint8_t *>(tv.p);
@@ -373,7 +395,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (int j = 0; j < N; ++j) p.arg[j] = gview(c, j, v[j].p);
     for (int i = 0; i < M; ++i) p.out[i] = gview(c, N + i, v[N + i].p);
     for (int k = 0; k < M * ND; ++k)
-      p.part[k] = k < n_planes ? gview(c, N + M + k, v[N + M + k].p) : GView{nullptr, {0, 0, 0, 0}};
+      p.part[k] = (k < n_planes && !dup[k]) ? gview(c, N + M + k, v[N + M + k].p) : GView{nullptr, {0, 0, 0, 0}};
     p.branch = want_branch ? gview(c, v.size(), const_cast<uint8_t *>(branch_id)) : GView{nullptr, {0, 0, 0, 0}};
     const int64_t blocks = ceil_div(c.E, kBlock);
     if (blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
@@ -399,6 +421,7 @@ struct BwdPlan {
   int vec = 1;
   bool signature = false;          // a kernel compiled for exactly this mix of gradient classes exists
   int n_cls[4] = {0, 0, 0, 0};     // gradients per class: full, row-sum, col-sum, all-sum
+  uint64_t absent = 0;             // bit e*M + i: plane i of table entry e is absent
   std::vector<BwdTiledParams> main;  // usually one launch
   std::vector<size_t> main_lds;
   dim3 grid{1, 1, 1};
@@ -565,13 +588,13 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // the gradient table is ordered by class (full, row-sum, col-sum, all-sum), which is
     // what the signature kernels expect; within a class the argument order is kept
     std::vector<int> order;
-    bool all_planes = true;
     for (int want = kGradFull; want <= kGradAllSum; ++want)
       for (int j = 0; j < ND; ++j)
         if (cls[j] == want) {
+          for (int i = 0; i < M; ++i)
+            if (v[M + i * ND + j].p == nullptr && order.size() * M + i < 64) plan.absent |= 1ull << (order.size() * M + i);
           order.push_back(j);
           plan.n_cls[want]++;
-          for (int i = 0; i < M; ++i) all_planes = all_planes && v[M + i * ND + j].p != nullptr;
         }
     for (int j : order) {
       BwdTiledParams trial = cur;
@@ -615,8 +638,8 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
     }
     flush();
-    plan.signature = all_planes && plan.main.size() == 1 && g_tune[5] == 0 &&
-                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3]);
+    plan.signature = plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
+                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
     plan.ws_bytes = ws;
@@ -696,6 +719,15 @@ int bcast_op_info(int32_t op_id, int32_t *n_args, int32_t *n_outputs, uint32_t *
   return BCAST_OK;
 }
 
+int bcast_op_plane_alias(int32_t op_id, int32_t *alias) {
+  if (op_id < 0 || op_id >= kNumOps) return BCAST_ERR_INVALID_OP;
+  if (alias == nullptr) return BCAST_ERR_NULL_POINTER;
+  const OpDesc &op = kOps[op_id];
+  const int n = op.n_out * (op.n_args - __builtin_popcount(op.nondiff));
+  for (int k = 0; k < n; ++k) alias[k] = op.alias ? op.alias[k] : k;
+  return BCAST_OK;
+}
+
 int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                             int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
                             const uint8_t *branch_id, bcast_plan_info *info) {
@@ -754,7 +786,7 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
     for (size_t k = 0; k < plan.main.size(); ++k) {
       plan.main[k].ws = static_cast<unsigned char *>(workspace);
       if (bd_bwd_tiled((int)dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
-                       plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
+                       plan.absent, plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
         return BCAST_ERR_LAUNCH_FAILED;
     }
     if (plan.p2_blocks > 0) {

@@ -86,16 +86,24 @@ def to_slab(tensors, staggered: bool = True):
 
 
 def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: bool = True,
-                  staggered: bool = True) -> ForwardBuffers:
+                  staggered: bool = True, lean: bool = False) -> ForwardBuffers:
+    """``lean``: planes the op table declares identical share one buffer and planes it declares
+    zero are left out (None); forward and backward give the same results with fewer bytes moved."""
     import torch
     op_id = B.bcast_op_lookup(op_name)
     n, m, mask, _ = B.bcast_op_info(op_id)
     nd = n - bin(mask).count("1")
     shape = unified_shape(args)
-    n_planes = m + (m * nd if want_partials else 0)
-    planes, slab = alloc_planes([shape] * n_planes, args[0].dtype, args[0].device, staggered)
     br = torch.empty(shape, dtype=torch.uint8, device=args[0].device) if want_branch else None
-    return ForwardBuffers(op_id, planes[:m], planes[m:] if want_partials else None, br, slab)
+    if not want_partials:
+        outs, slab = alloc_planes([shape] * m, args[0].dtype, args[0].device, staggered)
+        return ForwardBuffers(op_id, outs, None, br, slab)
+    alias = B.bcast_op_plane_alias(op_id) if lean else list(range(m * nd))
+    own = [k for k in range(m * nd) if alias[k] == k]
+    planes, slab = alloc_planes([shape] * (m + len(own)), args[0].dtype, args[0].device, staggered)
+    store = dict(zip(own, planes[m:]))
+    parts = [None if alias[k] < 0 else store[alias[k]] for k in range(m * nd)]
+    return ForwardBuffers(op_id, planes[:m], parts, br, slab)
 
 
 def alloc_backward(adjoints, partials, grad_shapes, staggered: bool = True) -> BackwardBuffers:

@@ -363,3 +363,47 @@ def test_end_to_end_against_wide_oracle_reports_cancellation():
         scale = oracle.backward(absA, absP, [args[j].shape for j in didx], threads=16)[k]
         err = np.abs(bb.grads[k].cpu().numpy().astype(np.float64) - want[k])
         assert np.all(err <= 1e-6 * scale + 1e-6)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_lean_plane_layout_gives_identical_results(dtype):
+    """Identical planes stored once and always-zero planes left out: same outputs, same
+    gradients, bit for bit, and the gradients still match the oracle."""
+    op, args, adj = inputs.config_inputs(2, dtype=dtype)
+    dev = [to_dev(a) for a in args]
+    adj_dev = [to_dev(a) for a in adj]
+    didx = oracle.diff_arg_indices(op, 12)
+    shapes = [args[j].shape for j in didx]
+    full = P.alloc_forward(op, dev).run(dev)
+    lean = P.alloc_forward(op, dev, lean=True).run(dev)
+    alias = P.bcast_op_plane_alias(lean.op_id)
+    assert sum(p is None for p in lean.partials) == 3
+    assert len({p.data_ptr() for p in lean.partials if p is not None}) == 10
+    gf = P.alloc_backward(adj_dev, full.partials, shapes).run(adj_dev, full.partials)
+    gl = P.alloc_backward(adj_dev, lean.partials, shapes).run(adj_dev, lean.partials)
+    info = P.bcast_dual_backward_plan(adj_dev, lean.partials, gl.grads)
+    assert info["path"] == 1
+    torch.cuda.synchronize()
+    for a, b in zip(full.outs, lean.outs):
+        assert torch.equal(a, b)
+    for k, a in enumerate(alias):
+        if a >= 0:
+            assert torch.equal(full.partials[k], lean.partials[k])
+        else:
+            assert bool((full.partials[k] == 0).all())
+    for a, b in zip(gf.grads, gl.grads):
+        assert torch.equal(a, b)
+    want = oracle.backward(adj, [None if p is None else p.cpu().numpy() for p in lean.partials], shapes, threads=16)
+    for k in range(10):
+        check_close(gl.grads[k].cpu().numpy(), want[k], f"lean grad {k}")
+    # branchy5: the plane of the threshold t is always zero
+    op, args, adj = inputs.config_inputs(4, dtype=dtype, scale=1 / 16)
+    dev = [to_dev(a) for a in args]
+    lean = P.alloc_forward(op, dev, lean=True).run(dev)
+    assert lean.partials[4] is None
+    gl = P.alloc_backward([to_dev(adj[0])], lean.partials, [a.shape for a in args]).run([to_dev(adj[0])], lean.partials)
+    torch.cuda.synchronize()
+    want = oracle.backward(adj, [None if p is None else p.cpu().numpy() for p in lean.partials],
+                           [a.shape for a in args], threads=16)
+    for k in range(5):
+        check_close(gl.grads[k].cpu().numpy(), want[k], f"branchy5 lean grad {k}")

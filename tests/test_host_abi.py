@@ -205,3 +205,54 @@ def test_tuning_keys():
         P.bcast_dual_set_tuning(0, 1000)
     with pytest.raises(P.BcastError):
         P.bcast_dual_set_tuning(9, 0)
+
+
+def test_plane_alias_table_agrees_with_the_oracle():
+    """Planes the op table calls identical or zero are so in the oracle, on inputs that reach
+    every branch; everything else has content of its own."""
+    import oracle
+    rng = np.random.default_rng(3)
+    R, C = 12, 16
+    full, row, col, sc = (R, C), (1, C), (R, 1), (1, 1)
+    cases = {
+        "hmlstm_update": [full] * 6 + [row, row] + [col] * 4,
+        "branchy5": [full, full, row, col, sc],
+        "tanh_xy_b": [full, full, col],
+        "update_c": [full] * 4 + [row, row],
+    }
+    for op, shp in cases.items():
+        args = [rng.standard_normal(s) for s in shp]
+        if op == "hmlstm_update":
+            args[6] = np.array([[1, 0, 0, 1] * 4], float)
+            args[7] = np.array([[0, 0, 1, 1] * 4], float)
+        if op == "update_c":
+            args[4] = np.array([[1, 0, 0, 1] * 4], float)
+            args[5] = np.array([[0, 0, 1, 1] * 4], float)
+        _, planes, br = oracle.forward(op, args)
+        assert len(np.unique(br)) == {"hmlstm_update": 3, "update_c": 3, "branchy5": 2, "tanh_xy_b": 1}[op]
+        alias = P.bcast_op_plane_alias(P.bcast_op_lookup(op))
+        assert len(alias) == len(planes)
+        for k, a in enumerate(alias):
+            if a < 0:
+                assert np.all(planes[k] == 0), (op, k)
+            elif a != k:
+                assert a < k and alias[a] == a and np.array_equal(planes[k], planes[a]), (op, k)
+            else:
+                assert np.any(planes[k] != 0), (op, k)
+                assert all(not np.array_equal(planes[k], planes[j]) for j in range(k) if alias[j] == j), (op, k)
+    assert P.bcast_op_plane_alias(P.bcast_op_lookup("hmlstm_update")).count(-1) == 3
+
+
+def test_shared_plane_views_only_where_declared_identical():
+    op = P.bcast_op_lookup("hmlstm_update")
+    H, Bt = 8, 16
+    full = lambda: _t(H, Bt)
+    args = [full() for _ in range(6)] + [_t(1, Bt), _t(1, Bt)] + [_t(H, 1) for _ in range(4)]
+    outs = [full(), full()]
+    parts = [full() for _ in range(20)]
+    parts[6] = parts[0]          # d c'/d b_f shares d c'/d f: declared identical
+    P.bcast_dual_forward_plan(op, args, outs, parts)
+    parts[1] = parts[0]          # d c'/d i is not
+    with pytest.raises(P.BcastError) as e:
+        P.bcast_dual_forward_plan(op, args, outs, parts)
+    assert e.value.status == -10
