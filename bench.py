@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC = {("cfg3", "forward"): 487.1e6, ("cfg3", "backward"): 470.5e6}
 
 
-def build_workload(name, p_index):
+def build_workload(name, p_index, uniform_run=0):
     import numpy as np
     from paper_1810_08297_amd import inputs
     dtype = np.float64 if name.endswith("_f64") else np.float32
@@ -42,8 +42,10 @@ def build_workload(name, p_index):
                 4: "branchy5 8192x8192"}[idx]
     elif base.startswith("paper_n"):
         n = int(base[len("paper_n"):])
-        args, adj = inputs.update_c_inputs(n, seed=inputs.BASE_SEED + 100 + n, dtype=dtype)
-        op, desc = "update_c", f"paper's cell update c,f,i,g {n}x{n}, z vectors of {n}"
+        args, adj = inputs.update_c_inputs(n, seed=inputs.BASE_SEED + 100 + n, dtype=dtype, uniform_run=uniform_run)
+        op, desc = "update_c", (f"paper's cell update c,f,i,g {n}x{n}, z vectors of {n}, " +
+                                (f"control inputs constant over runs of {uniform_run}" if uniform_run else
+                                 "random control inputs"))
     else:
         raise SystemExit(f"unknown workload {name}")
     return op, args, adj, desc, dtype
@@ -65,6 +67,8 @@ def main():
     ap.add_argument("--p-index", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=16)
+    ap.add_argument("--uniform-run", type=int, default=0,
+                    help="paper_n* workloads: make z1, z2 constant over aligned runs of this many elements")
     ap.add_argument("--lean", action="store_true",
                     help="store planes the op table declares identical once and leave always-zero planes out")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -82,7 +86,7 @@ def main():
     import paper_1810_08297_amd as P
 
     torch.cuda.set_device(0)
-    op, args, adj, desc, dtype = build_workload(a.workload, a.p_index)
+    op, args, adj, desc, dtype = build_workload(a.workload, a.p_index, a.uniform_run)
     es = np.dtype(dtype).itemsize
     # every full-shape buffer of the step lives in the library's staggered slab layout
     dev, _slab_a = P.to_slab([torch.from_numpy(x).cuda() for x in args])

@@ -1,0 +1,58 @@
+"""Arity study (Sec. 3.4.1 of arXiv 1810.08297) on one MI355X.
+
+  python -m paper_1810_08297_amd.arity_study [--n 1024] [--max-arity 18]
+
+D(f).(x_1 .. x_N) with f = prod_i tanh(g(x_i)), g(x) = x if x > 1/2 else -x, every x_j an
+n x n fp32 matrix: the dual-number forward kernel reads N planes and writes 1 + N, and its
+register use grows with N.  Prints per arity the forward and backward times (HIP events on
+the launch stream, median of 50) and the achieved fraction of the HBM peak.
+"""
+from __future__ import annotations
+
+import argparse
+
+import numpy as np
+
+
+def main():
+    import torch
+    import paper_1810_08297_amd as P
+    from paper_1810_08297_amd import inputs
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--n", type=int, default=1024)
+    ap.add_argument("--max-arity", type=int, default=18)
+    a = ap.parse_args()
+    E = a.n * a.n
+    stream = torch.cuda.current_stream()
+
+    def median_us(call, reps=50):
+        ev = []
+        for _ in range(reps + 5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            call()
+            e1.record(stream)
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        return float(np.median([x.elapsed_time(y) for x, y in ev[5:]])) * 1e3
+
+    print(f"{'N':>3s} {'fwd us':>9s} {'fwd GB/s':>9s} {'% peak':>7s} {'bwd us':>9s} {'bwd GB/s':>9s} {'% peak':>7s}")
+    for k in range(1, a.max_arity + 1):
+        xs, adj = inputs.prod_tanh_inputs(k, a.n, a.n, seed=inputs.BASE_SEED + 200 + k)
+        dev, _s1 = P.to_slab([torch.from_numpy(x).cuda() for x in xs])
+        adj_dev = [torch.from_numpy(adj[0]).cuda()]
+        fb = P.alloc_forward(f"prod_tanh_{k}", dev)
+        bb = P.alloc_backward(adj_dev, fb.partials, [x.shape for x in xs])
+        f, b = fb.prepare(dev), bb.prepare(adj_dev, fb.partials)
+        tf = median_us(lambda: f.launch())
+        tb = median_us(lambda: b.launch())
+        fbytes, bbytes = (2 * k + 1) * E * 4, (2 * k + 1) * E * 4
+        print(f"{k:3d} {tf:9.2f} {fbytes / tf / 1e3:9.1f} {fbytes / tf / 1e3 / 80:7.1f} {tb:9.2f} "
+              f"{bbytes / tb / 1e3:9.1f} {bbytes / tb / 1e3 / 80:7.1f}", flush=True)
+        del dev, _s1, fb, bb, f, b
+        torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    main()
