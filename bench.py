@@ -69,6 +69,7 @@ def main():
     ap.add_argument("--cpu-threads", type=int, default=16)
     ap.add_argument("--uniform-run", type=int, default=0,
                     help="paper_n* workloads: make z1, z2 constant over aligned runs of this many elements")
+    ap.add_argument("--no-lean-extra", action="store_true", help="skip the additional lean-layout measurement")
     ap.add_argument("--lean", action="store_true",
                     help="store planes the op table declares identical once and leave always-zero planes out")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -93,81 +94,92 @@ def main():
     adj_dev, _slab_b = P.to_slab([torch.from_numpy(x).cuda() for x in adj])
     for key, val in a.tune:
         P.bcast_dual_set_tuning(key, val)
-    fb = P.alloc_forward(op, dev, want_branch=False, lean=a.lean)
-    didx = P.diff_arg_indices(fb.op_id)
-    shapes = [args[j].shape for j in didx]
-    bb = P.alloc_backward(adj_dev, fb.partials, shapes)
-    E = int(np.prod(fb.outs[0].shape))
-    M, Nd = len(fb.outs), len(didx)
-    n_full_args = sum(1 for x in args if x.size == E)
-    n_full_grads = sum(1 for s in shapes if int(np.prod(s)) == E)
-    n_stored = len({t.data_ptr() for t in fb.partials if t is not None})  # planes that cross the HBM interface
-    fwd_words = n_full_args + M + n_stored
-    bwd_words = M + n_stored + n_full_grads
-    fwd_bytes, bwd_bytes = fwd_words * es * E, bwd_words * es * E
-
     import ctypes
     stream = torch.cuda.current_stream()
     sptr = ctypes.c_void_p(stream.cuda_stream)
-    fwd_call = fb.prepare(dev)                    # argument blocks marshalled once;
-    bwd_call = bb.prepare(adj_dev, fb.partials)   # each launch() is one C-ABI call
 
-    def step():
-        fwd_call.launch(sptr)
-        bwd_call.launch(sptr)
-
-    for _ in range(a.warmup):
-        step()
-    torch.cuda.synchronize()
-    if a.copy_probe_mib > 0:
-        n = a.copy_probe_mib * (1 << 20) // 4
-        src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr)
+    def measure(lean):
+        """warm-up + timed steps for one partial-storage layout; returns the numbers of the run"""
+        fb = P.alloc_forward(op, dev, want_branch=False, lean=lean)
+        didx = P.diff_arg_indices(fb.op_id)
+        shapes = [args[j].shape for j in didx]
+        bb = P.alloc_backward(adj_dev, fb.partials, shapes)
+        E = int(np.prod(fb.outs[0].shape))
+        M, Nd = len(fb.outs), len(didx)
+        n_full_args = sum(1 for x in args if x.size == E)
+        n_full_grads = sum(1 for s_ in shapes if int(np.prod(s_)) == E)
+        n_stored = len({t.data_ptr() for t in fb.partials if t is not None})  # planes that cross the HBM interface
+        fwd_words = n_full_args + M + n_stored
+        bwd_words = M + n_stored + n_full_grads
+        fwd_bytes, bwd_bytes = fwd_words * es * E, bwd_words * es * E
+        fwd_call = fb.prepare(dev)                    # argument blocks marshalled once;
+        bwd_call = bb.prepare(adj_dev, fb.partials)   # each launch() is one C-ABI call
+        for _ in range(a.warmup):
+            fwd_call.launch(sptr)
+            bwd_call.launch(sptr)
         torch.cuda.synchronize()
+        if a.copy_probe_mib > 0 and not lean:
+            n = a.copy_probe_mib * (1 << 20) // 4
+            src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr)
+            torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(a.steps):
+            ev[k][0].record(stream)
+            fwd_call.launch(sptr)
+            ev[k][1].record(stream)
+            bwd_call.launch(sptr)
+            ev[k][2].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
+        bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
+        fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
+        both = (fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
+        return {
+            "E": E, "M": M, "Nd": Nd, "n_stored": n_stored, "shapes": shapes, "wall": wall,
+            "value": E * a.steps / wall, "ms_per_step": wall * 1e3 / a.steps,
+            "fwd_avg": fwd_avg, "bwd_avg": bwd_avg, "fwd_bytes": fwd_bytes, "bwd_bytes": bwd_bytes,
+            "detail": {
+                "elements": E,
+                "forward": {"avg_ms": round(fwd_avg, 5), "median_ms": round(float(np.median(fwd_ms)), 5),
+                            "bytes": fwd_bytes, "GBps": round(fwd_bytes / (fwd_avg * 1e-3) / 1e9, 1)},
+                "backward": {"avg_ms": round(bwd_avg, 5), "median_ms": round(float(np.median(bwd_ms)), 5),
+                             "bytes": bwd_bytes, "GBps": round(bwd_bytes / (bwd_avg * 1e-3) / 1e9, 1)},
+                "fwd_bwd_GBps_event_time": round(both, 1),
+                "fwd_bwd_frac_of_hbm_peak": round(both / HBM_PEAK_GBS, 4),
+                "elements_per_s_event_time": round(E / ((fwd_avg + bwd_avg) * 1e-3), 1),
+                "bytes_per_element": (fwd_words + bwd_words) * es,
+            },
+        }
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(a.steps):
-        ev[k][0].record(stream)
-        fwd_call.launch(sptr)
-        ev[k][1].record(stream)
-        bwd_call.launch(sptr)
-        ev[k][2].record(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall = t1 - t0
-    fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
-    bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
-    ms_per_step = wall * 1e3 / a.steps
-    value = E * a.steps / wall
-
-    fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
+    run = measure(a.lean)
+    E, M, Nd, n_stored, shapes = run["E"], run["M"], run["Nd"], run["n_stored"], run["shapes"]
+    value, ms_per_step, extra = run["value"], run["ms_per_step"], run["detail"]
+    fwd_avg, bwd_avg = run["fwd_avg"], run["bwd_avg"]
     dom = "forward" if fwd_avg >= bwd_avg else "backward"
-    dom_bytes = fwd_bytes if dom == "forward" else bwd_bytes
+    dom_bytes = run["fwd_bytes"] if dom == "forward" else run["bwd_bytes"]
     dom_ms = max(fwd_avg, bwd_avg)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": f"{dom} ({'fwd_tiled_kernel' if dom == 'forward' else 'bwd_tiled_kernel'})",
+        "bound": "hbm", "kernel": f"{dom} ({'fwd_tiled_kernel' if dom == 'forward' else 'bwd_sig_kernel'})",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": None if a.lean else MEASURED_TRAFFIC.get((a.workload, dom)),
         "algorithmic_bytes_per_launch": dom_bytes,
         "avg_launch_ms": round(dom_ms, 5),
     }
-    extra = {
-        "elements": E,
-        "forward": {"avg_ms": round(fwd_avg, 5), "median_ms": round(float(np.median(fwd_ms)), 5),
-                    "bytes": fwd_bytes, "GBps": round(fwd_bytes / (fwd_avg * 1e-3) / 1e9, 1)},
-        "backward": {"avg_ms": round(bwd_avg, 5), "median_ms": round(float(np.median(bwd_ms)), 5),
-                     "bytes": bwd_bytes, "GBps": round(bwd_bytes / (bwd_avg * 1e-3) / 1e9, 1)},
-        "fwd_bwd_GBps_event_time": round((fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9, 1),
-        "fwd_bwd_frac_of_hbm_peak": round((fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        "elements_per_s_event_time": round(E / ((fwd_avg + bwd_avg) * 1e-3), 1),
-        "bytes_per_element": (fwd_words + bwd_words) * es,
-    }
+    # the same step with the leaner partial store (same outputs and gradients, fewer bytes), for reference
+    lean_extra = None
+    if not a.lean and not a.no_lean_extra:
+        lr = measure(True)
+        if lr["n_stored"] < n_stored:
+            lean_extra = {"value": round(lr["value"], 1), "unit": "elements/s", "ms_per_step": round(lr["ms_per_step"], 5),
+                          "planes_stored": lr["n_stored"], **lr["detail"]}
 
     cpu = None
     if not a.no_cpu_baseline:
@@ -203,7 +215,7 @@ def main():
                    "partial_planes": M * Nd, "planes_stored": n_stored,
                    "layout": "row-major, staggered slab, " + ("identical planes stored once, zero planes left out"
                                                               if a.lean else "all planes stored")},
-        "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
+        "roofline": roofline, "cpu_baseline": cpu, "detail": extra, "lean_layout": lean_extra,
     }
     print(json.dumps(line))
 
