@@ -57,7 +57,8 @@ typedef enum {
   BCAST_ERR_WORKSPACE_TOO_SMALL = -8,
   BCAST_ERR_LAUNCH_FAILED = -9,
   BCAST_ERR_BAD_STRIDE = -10,           /* negative stride, or a written view that overlaps itself */
-  BCAST_ERR_MISALIGNED = -11            /* a data pointer is not aligned to its element size */
+  BCAST_ERR_MISALIGNED = -11,           /* a data pointer is not aligned to its element size */
+  BCAST_ERR_UNSUPPORTED = -12           /* this entry point has no kernel for the op or the layout */
 } bcast_status;
 
 typedef struct {
@@ -161,6 +162,22 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
 int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                              const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
                              bcast_plan_info *info);
+
+/* ---- backward without cached planes: D applied in the reverse pass (Sec. 2.2.3, last paragraph) ----
+ * The other side of the paper's memory/compute trade-off: nothing is kept between the passes
+ * (the forward pass is then called with partials == NULL).  One kernel reads the op's arguments
+ * and the adjoints, evaluates b on dual numbers again and reduces sum_i adj_i * dY_i/dX_jd into
+ * each gradient exactly as bcast_dual_backward does.
+ * args[n_args] as in forward; adjoints[n_out] of the unified shape; grads[n_grads = N_d] in their
+ * argument's shape (NULL data: skipped).  Available for problems that merge to at most two dims
+ * with unit inner stride (the tiled kernels) and for every op except the prod_tanh_K family;
+ * otherwise BCAST_ERR_UNSUPPORTED.  Workspace rules as for bcast_dual_backward. */
+size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                                               int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
+                                               const bcast_tensor *grads);
+int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                                  int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
+                                  const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- misc ---------------------------------------------------------------------- */
 const char *bcast_status_string(int status);

@@ -49,7 +49,8 @@ _lib = None
 EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
            "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
-           "bcast_dual_get_tuning", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias")
+           "bcast_dual_get_tuning", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
+           "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace")
 
 
 def lib():
@@ -64,6 +65,7 @@ def lib():
         L.bcast_status_string.restype = ctypes.c_char_p
         L.bcast_dual_backward_workspace.restype = ctypes.c_size_t
         L.bcast_dual_slab_layout.restype = ctypes.c_size_t
+        L.bcast_dual_backward_recompute_workspace.restype = ctypes.c_size_t
         _lib = L
     return _lib
 
@@ -293,3 +295,40 @@ class PreparedBackward:
     def launch(self, stream=None):
         _check(self._fn(self._dt, self._no, self._a, self._p, self._ng, self._g, self._ws, self._wsb,
                         _stream_ptr(stream)), "bcast_dual_backward")
+
+
+def bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads) -> int:
+    dt = _dtype_code(adjoints[0])
+    return int(lib().bcast_dual_backward_recompute_workspace(
+        ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
+        ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads)))
+
+
+def bcast_dual_backward_recompute(op_id, args, adjoints, grads, workspace=None, stream=None) -> None:
+    """Gradients straight from arguments and adjoints: the dual numbers are evaluated again."""
+    dt = _dtype_code(adjoints[0])
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().bcast_dual_backward_recompute(
+        ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
+        ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads),
+        ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), _stream_ptr(stream)), "bcast_dual_backward_recompute")
+
+
+class PreparedRecompute:
+    """A recompute-backward call marshalled once (see PreparedForward)."""
+
+    def __init__(self, op_id, args, adjoints, grads, workspace=None):
+        self._keep = (args, adjoints, grads, workspace)
+        self._op = ctypes.c_int32(op_id)
+        self._dt = ctypes.c_int(_dtype_code(adjoints[0]))
+        self._na, self._a = ctypes.c_int32(len(args)), _views(args)
+        self._no, self._o = ctypes.c_int32(len(adjoints)), _views(adjoints)
+        self._ng, self._g = ctypes.c_int32(len(grads)), _views(grads)
+        self._ws = ctypes.c_void_p(workspace.data_ptr() if workspace is not None else None)
+        self._wsb = ctypes.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0)
+        self._fn = lib().bcast_dual_backward_recompute
+
+    def launch(self, stream=None):
+        _check(self._fn(self._op, self._dt, self._na, self._a, self._no, self._o, self._ng, self._g, self._ws,
+                        self._wsb, _stream_ptr(stream)), "bcast_dual_backward_recompute")

@@ -19,6 +19,10 @@ using namespace bd;
 #define BD_DECLARE_OP(IDENT)                                                                        \
   hipError_t bd_fwd_tiled_##IDENT(int, int, const FwdTiledParams &, dim3, hipStream_t);             \
   hipError_t bd_fwd_generic_##IDENT(int, const FwdGenericParams &, dim3, hipStream_t);
+#define BD_DECLARE_RECOMPUTE(IDENT)                                                                            \
+  hipError_t bd_bwdr_tiled_##IDENT(int, int, bool, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, \
+                                   hipStream_t);                                                               \
+  uint64_t bd_bwdr_pattern_##IDENT();
 #define BD_ARITY_LIST(X) \
   X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18)
 BD_DECLARE_OP(hmlstm_update)
@@ -29,6 +33,14 @@ BD_DECLARE_OP(cos_x)
 BD_DECLARE_OP(scale_xt)
 BD_DECLARE_OP(pair3)
 BD_DECLARE_OP(linear12)
+BD_DECLARE_RECOMPUTE(hmlstm_update)
+BD_DECLARE_RECOMPUTE(update_c)
+BD_DECLARE_RECOMPUTE(tanh_xy_b)
+BD_DECLARE_RECOMPUTE(branchy5)
+BD_DECLARE_RECOMPUTE(cos_x)
+BD_DECLARE_RECOMPUTE(scale_xt)
+BD_DECLARE_RECOMPUTE(pair3)
+BD_DECLARE_RECOMPUTE(linear12)
 #ifndef BD_NO_ARITY
 #define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K)
 BD_ARITY_LIST(BD_DECL_ARITY)
@@ -52,6 +64,8 @@ struct OpDesc {
   const int8_t *alias;  // per plane: own index, index of an identical earlier plane, or -1 (always zero); nullptr: all distinct
   hipError_t (*tiled)(int, int, const FwdTiledParams &, dim3, hipStream_t);
   hipError_t (*generic)(int, const FwdGenericParams &, dim3, hipStream_t);
+  hipError_t (*recompute)(int, int, bool, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, hipStream_t);  // may be null
+  uint64_t (*recompute_pattern)();
 };
 
 // HM-LSTM update, planes (c' then h') x (f i o g c h b_f b_i b_o b_g): a bias enters only through
@@ -60,9 +74,12 @@ const int8_t kAliasHmLstm[20] = {0, 1, -1, 3, 4, -1, 0, 1, -1, 3, 10, 11, 12, 13
 // branchy5 (A B r s t): the threshold t only appears in the predicate
 const int8_t kAliasBranchy5[5] = {0, 1, 2, 3, -1};
 
-#define BD_OP_ROW(NAME, N, M, NONDIFF, NBR) {#NAME, N, M, NONDIFF, NBR, nullptr, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME},
-#define BD_OP_ROW_A(NAME, N, M, NONDIFF, NBR, ALIAS) {#NAME, N, M, NONDIFF, NBR, ALIAS, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME},
-#define BD_ARITY_ROW(K) BD_OP_ROW(prod_tanh_##K, K, 1, 0u, K + 1)
+#define BD_OP_ROW(NAME, N, M, NONDIFF, NBR) \
+  {#NAME, N, M, NONDIFF, NBR, nullptr, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME},
+#define BD_OP_ROW_A(NAME, N, M, NONDIFF, NBR, ALIAS) \
+  {#NAME, N, M, NONDIFF, NBR, ALIAS, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME},
+#define BD_ARITY_ROW(K) \
+  {"prod_tanh_" #K, K, 1, 0u, K + 1, nullptr, bd_fwd_tiled_prod_tanh_##K, bd_fwd_generic_prod_tanh_##K, nullptr, nullptr},
 const OpDesc kOps[] = {
     BD_OP_ROW_A(hmlstm_update, 12, 2, (1u << 6) | (1u << 7), 3, kAliasHmLstm)
     BD_OP_ROW(tanh_xy_b, 3, 1, 0u, 1)
@@ -422,6 +439,8 @@ struct BwdPlan {
   bool signature = false;          // a kernel compiled for exactly this mix of gradient classes exists
   int n_cls[4] = {0, 0, 0, 0};     // gradients per class: full, row-sum, col-sum, all-sum
   uint64_t absent = 0;             // bit e*M + i: plane i of table entry e is absent
+  RecomputeArgs ra{};              // recompute mode only
+  bool fixed_pattern = false;      // recompute mode: the call has the op's compiled-in broadcast pattern
   std::vector<BwdTiledParams> main;  // usually one launch
   std::vector<size_t> main_lds;
   dim3 grid{1, 1, 1};
@@ -432,25 +451,36 @@ struct BwdPlan {
   size_t ws_bytes = 0;
 };
 
+// With `rop` set this plans the recompute-in-reverse call instead: there are no planes, the
+// op's n_args arguments are read (and must broadcast to the adjoints' shape), and only the
+// tiled kernels are available.
 int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bcast_tensor *partials,
-                  int32_t n_grads, const bcast_tensor *grads, BwdPlan &plan) {
+                  int32_t n_grads, const bcast_tensor *grads, BwdPlan &plan, const OpDesc *rop = nullptr,
+                  const bcast_tensor *args = nullptr) {
   if (dt != BCAST_F32 && dt != BCAST_F64) return BCAST_ERR_BAD_DTYPE;
   if (n_out < 1 || n_out > BCAST_MAX_OUTS || n_grads < 1 || n_grads > BCAST_MAX_ARGS ||
       n_out * n_grads > BCAST_MAX_PLANES)
     return BCAST_ERR_BAD_ARG_COUNT;
-  if (adjoints == nullptr || partials == nullptr || grads == nullptr) return BCAST_ERR_NULL_POINTER;
+  if (adjoints == nullptr || (partials == nullptr && !rop) || grads == nullptr || (rop && !args))
+    return BCAST_ERR_NULL_POINTER;
+  const int NA = rop ? rop->n_args : 0;
   const size_t es = elem_size(dt);
   const size_t as = dt == BCAST_F32 ? 8 : 16;  // accumulator bytes
   const int M = n_out, ND = n_grads;
-  std::vector<PView> v(M + M * ND + ND);
+  std::vector<PView> v(M + M * ND + ND + NA);
+  const size_t a0 = M + M * ND + ND;  // first argument view (recompute mode)
   int D = 0;
   for (int i = 0; i < M; ++i) {
     if (int rc = check_view(adjoints[i], es, false, false, v[i])) return rc;
     D = std::max(D, adjoints[i].ndim);
   }
-  for (int k = 0; k < M * ND; ++k) {
+  for (int k = 0; k < M * ND && !rop; ++k) {
     if (int rc = check_view(partials[k], es, true, false, v[M + k])) return rc;
     D = std::max(D, partials[k].ndim);
+  }
+  for (int j = 0; j < NA; ++j) {
+    if (int rc = check_view(args[j], es, false, false, v[a0 + j])) return rc;
+    D = std::max(D, args[j].ndim);
   }
   for (int j = 0; j < ND; ++j) {
     if (int rc = check_view(grads[j], es, true, true, v[M + M * ND + j])) return rc;
@@ -463,6 +493,11 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     for (int d = 0; d < BCAST_MAX_DIMS && v[M + M * ND + j].p; ++d) {
       const int64_t s = v[M + M * ND + j].shape[d];
       if (s != U[d] && s != 1) return BCAST_ERR_OUTPUT_SHAPE_MISMATCH;
+    }
+  for (int j = 0; j < NA; ++j)
+    for (int d = 0; d < BCAST_MAX_DIMS; ++d) {
+      const int64_t sdim = v[a0 + j].shape[d];
+      if (sdim != U[d] && sdim != 1) return BCAST_ERR_SHAPE_MISMATCH;
     }
   int64_t E = 1;
   for (int d = 0; d < BCAST_MAX_DIMS; ++d) E *= U[d];
@@ -499,6 +534,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
       for (int j = 0; j < ND && tiled; ++j)
         if (cls[j] == kGradFull) tiled = (tview(c, g0 + j, nullptr).sc == 1);
+      for (int j = 0; j < NA && tiled; ++j) {
+        const int64_t sc = tview(c, a0 + j, nullptr).sc;
+        tiled = (sc == 0 || sc == 1);
+      }
     }
   }
   int64_t bwd_sr = -1;
@@ -511,18 +550,21 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     tiled = bwd_sr >= 0;
   }
   plan.tiled = tiled;
+  if (rop && !tiled) return BCAST_ERR_UNSUPPORTED;
   if (tiled) {
     int vw = (int)(std::max<int>(g_tune[4], (int)es) / es);
     for (; vw > 1; vw /= 2) {
       bool vec_ok = (s2.C % vw == 0);
       for (size_t t = 0; t < v.size() && vec_ok; ++t) {
         if (!v[t].p) continue;
-        if (t >= g0 && cls[t - g0] != kGradFull) continue;  // reduced gradients are stored by element
+        if (t >= g0 && t < a0 && cls[t - g0] != kGradFull) continue;  // reduced gradients are stored by element
         const TView tv = tview(c, t, v[t].p);
+        if (t >= a0 && tv.sc == 0 && s2.C > 1) continue;              // a broadcast load: one element
         vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0);
       }
       if (vec_ok) break;
     }
+    if (rop && vw != (int)(16 / es)) vw = 1;  // the recompute kernels exist for the widest vector and for 1
     Geometry g;
     g.vec = vw;
     plan.vec = g.vec;
@@ -535,6 +577,12 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     }
     const int TY = kBlock >> g.log2_tx;
     int steps = g_tune[1] > 0 ? g_tune[1] : (any_rowwise ? (int)ceil_div(32, TY) : auto_steps(s2.R, g, 4));
+    if (rop) {
+      uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
+      for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
+      plan.fixed_pattern = g_tune[5] == 0 && pattern == rop->recompute_pattern();
+      if (plan.fixed_pattern && !any_rowwise) steps = 1;  // that kernel has no row loop
+    }
     // rows wider than a wavefront park one accumulator per wavefront and row in LDS
     const int wpr = g.log2_tx > 6 ? (1 << (g.log2_tx - 6)) : 1;
     if (g.log2_tx > 6 && n_rowsum > 0) {
@@ -638,7 +686,20 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
     }
     flush();
-    plan.signature = plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
+    if (rop) {
+      if (plan.main.size() > 1) return BCAST_ERR_UNSUPPORTED;
+      RecomputeArgs &ra = plan.ra;
+      for (int jd = 0; jd < BCAST_MAX_ARGS; ++jd) ra.entry_of[jd] = -1;
+      for (size_t e = 0; e < order.size(); ++e) ra.entry_of[order[e]] = (int8_t)e;
+      for (int j = 0; j < NA; ++j) {
+        const TView tv = tview(c, a0 + j, v[a0 + j].p);
+        ra.arg_p[j] = tv.p;
+        ra.arg_sr[j] = tv.sr;
+        if (tv.sr == 0) ra.row_invariant |= 1u << j;
+        if (tv.sc == 0) ra.col_invariant |= 1u << j;
+      }
+    }
+    plan.signature = !rop && plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
@@ -802,6 +863,48 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
   return BCAST_OK;
 }
 
+static int recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args, int32_t n_out,
+                          const bcast_tensor *adjoints, int32_t n_grads, const bcast_tensor *grads, BwdPlan &plan) {
+  if (op_id < 0 || op_id >= kNumOps) return BCAST_ERR_INVALID_OP;
+  const OpDesc &op = kOps[op_id];
+  if (n_args != op.n_args || n_out != op.n_out || n_grads != op.n_args - __builtin_popcount(op.nondiff))
+    return BCAST_ERR_BAD_ARG_COUNT;
+  if (op.recompute == nullptr) return BCAST_ERR_UNSUPPORTED;
+  return plan_backward((int)dt, n_out, adjoints, nullptr, n_grads, grads, plan, &op, args);
+}
+
+size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                                               int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
+                                               const bcast_tensor *grads) {
+  BwdPlan plan;
+  if (recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, plan) != BCAST_OK) return 0;
+  return plan.ws_bytes;
+}
+
+int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                                  int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
+                                  const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream) {
+  BwdPlan plan;
+  const int rc = recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, plan);
+  if (rc != BCAST_OK) return rc;
+  if (plan.info.path == 0 || plan.main.empty()) return BCAST_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (plan.ws_bytes > 0) {
+    if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
+    if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
+  }
+  plan.main[0].ws = static_cast<unsigned char *>(workspace);
+  if (kOps[op_id].recompute((int)dt, plan.vec, plan.fixed_pattern, plan.main[0], plan.ra, plan.grid, plan.main_lds[0],
+                            s) != hipSuccess)
+    return BCAST_ERR_LAUNCH_FAILED;
+  if (plan.p2_blocks > 0) {
+    plan.p2.ws = static_cast<unsigned char *>(workspace);
+    if (bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s) != hipSuccess) return BCAST_ERR_LAUNCH_FAILED;
+  }
+  return BCAST_OK;
+}
+
 const char *bcast_status_string(int status) {
   switch (status) {
     case BCAST_OK: return "ok";
@@ -816,6 +919,7 @@ const char *bcast_status_string(int status) {
     case BCAST_ERR_LAUNCH_FAILED: return "kernel launch failed";
     case BCAST_ERR_BAD_STRIDE: return "negative stride or self-overlapping written view";
     case BCAST_ERR_MISALIGNED: return "pointer not aligned";
+    case BCAST_ERR_UNSUPPORTED: return "layout or op not supported by this entry point";
     default: return "unknown status";
   }
 }

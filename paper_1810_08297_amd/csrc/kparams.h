@@ -89,6 +89,15 @@ struct BwdTiledParams {
   BwdEntry e[BCAST_MAX_ARGS];
 };
 
+// The arguments of the broadcast, for the kernel that evaluates the dual numbers again in
+// the reverse pass instead of reading cached planes.
+struct RecomputeArgs {
+  uint32_t row_invariant, col_invariant;   // as in FwdTiledParams
+  const void *arg_p[BCAST_MAX_ARGS];
+  int64_t arg_sr[BCAST_MAX_ARGS];
+  int8_t entry_of[BCAST_MAX_ARGS];         // differentiable argument jd -> row of the gradient table, -1: skipped
+};
+
 // second pass: one job per gradient that needs it
 struct Pass2Job {
   void *g;              // final gradient

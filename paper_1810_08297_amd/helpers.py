@@ -112,3 +112,12 @@ def alloc_backward(adjoints, partials, grad_shapes, staggered: bool = True) -> B
     nbytes = B.bcast_dual_backward_workspace(adjoints, partials, grads)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
     return BackwardBuffers(grads, ws, slab)
+
+
+def alloc_recompute(op_id: int, args, adjoints, grad_shapes, staggered: bool = True) -> BackwardBuffers:
+    """Gradient buffers and workspace for bcast_dual_backward_recompute."""
+    import torch
+    grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered)
+    nbytes = B.bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
+    return BackwardBuffers(grads, ws, slab)

@@ -52,7 +52,7 @@ def full_rank(a, nd):
     return a.reshape(a.shape + (1,) * (nd - a.ndim))
 
 
-def check_op(op, args_np, adj_np, *, threads=8, view=None, what=""):
+def check_op(op, args_np, adj_np, *, threads=8, view=None, what="", recompute=True):
     """Forward + backward parity of one op on one set of host arrays.
 
     `view(dev_tensor, k)` may re-lay out argument k on the device (strides, transposes)
@@ -82,4 +82,16 @@ def check_op(op, args_np, adj_np, *, threads=8, view=None, what=""):
     want = oracle.backward(adj_np, gpu_planes, [full_rank(args_np[j], nd).shape for j in didx], threads=threads)
     for k, (g, w) in enumerate(zip(bb.grads, want)):
         check_close(g.cpu().numpy().reshape(w.shape), w, f"{what}{op} gradient of argument {didx[k]}")
+    # the recompute-in-reverse entry point must give the same gradients without any planes
+    if recompute:
+        try:
+            rb = P.alloc_recompute(fb.op_id, args_dev, adj_dev, gshapes)
+            P.bcast_dual_backward_recompute(fb.op_id, args_dev, adj_dev, rb.grads, rb.workspace)
+        except P.BcastError as e:
+            assert e.status == -12, e  # only "unsupported layout/op" is an acceptable refusal
+            assert recompute != "required", f"{what}{op}: recompute refused"
+        else:
+            torch.cuda.synchronize()
+            for k, (g, w) in enumerate(zip(rb.grads, want)):
+                check_close(g.cpu().numpy().reshape(w.shape), w, f"{what}{op} recomputed gradient of argument {didx[k]}")
     return fb, bb

@@ -52,7 +52,7 @@ SHAPES = [(1, 1), (1, 7), (5, 1), (3, 5), (64, 16), (7, 33), (129, 260), (2, 410
 def test_ops_all_shapes(op, dtype):
     for k, (R, C) in enumerate(SHAPES):
         args, adj = small_args(op, R, C, dtype, seed=k)
-        check_op(op, args, adj, what=f"[{R}x{C}] ")
+        check_op(op, args, adj, what=f"[{R}x{C}] ", recompute="required")
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
@@ -407,3 +407,61 @@ def test_lean_plane_layout_gives_identical_results(dtype):
                            [a.shape for a in args], threads=16)
     for k in range(5):
         check_close(gl.grads[k].cpu().numpy(), want[k], f"branchy5 lean grad {k}")
+
+
+def test_recompute_refuses_what_it_cannot_do_and_skips_null_gradients():
+    # rank 3 that does not merge to two dims: only the plane-reading path has generic kernels
+    rng = np.random.default_rng(4)
+    x = to_dev(rng.standard_normal((3, 1, 5)).astype(np.float32))
+    t = to_dev(rng.standard_normal((1, 4, 1)).astype(np.float32))
+    adj = to_dev(rng.standard_normal((3, 4, 5)).astype(np.float32))
+    op = P.bcast_op_lookup("scale_xt")
+    with pytest.raises(P.BcastError) as e:
+        P.bcast_dual_backward_recompute(op, [x, t], [adj], [torch.empty_like(x), torch.empty_like(t)])
+    assert e.value.status == -12
+    with pytest.raises(P.BcastError) as e:
+        xs = [to_dev(rng.standard_normal((4, 8)).astype(np.float32)) for _ in range(3)]
+        P.bcast_dual_backward_recompute(P.bcast_op_lookup("prod_tanh_3"), xs, [xs[0]], [torch.empty_like(a) for a in xs])
+    assert e.value.status == -12
+    # a NULL gradient is skipped, the others are unaffected
+    args, adjn = small_args("branchy5", 33, 260, np.float32, seed=9)
+    dev = [to_dev(a) for a in args]
+    adj_dev = [to_dev(adjn[0])]
+    op = P.bcast_op_lookup("branchy5")
+    full = P.alloc_recompute(op, dev, adj_dev, [a.shape for a in args])
+    P.bcast_dual_backward_recompute(op, dev, adj_dev, full.grads, full.workspace)
+    part = P.alloc_recompute(op, dev, adj_dev, [a.shape for a in args])
+    sentinel = part.grads[1]
+    sentinel.fill_(7.0)
+    grads = list(part.grads)
+    grads[1] = None
+    P.bcast_dual_backward_recompute(op, dev, adj_dev, grads, part.workspace)
+    torch.cuda.synchronize()
+    assert bool((sentinel == 7.0).all())
+    for k in (0, 2, 3, 4):
+        assert torch.equal(grads[k], full.grads[k])
+
+
+def test_recompute_fixed_and_runtime_patterns_agree():
+    """The recompute kernel compiled for the op's usual broadcast pattern and the one that
+    reads the gradient classes at run time give the same bits."""
+    for op, idx in (("hmlstm_update", 2), ("branchy5", 4)):
+        _, args, adj = inputs.config_inputs(idx, scale=1 / 4 if idx == 4 else 1.0)
+        dev = [to_dev(a) for a in args]
+        adj_dev = [to_dev(a) for a in adj]
+        op_id = P.bcast_op_lookup(op)
+        shapes = [args[j].shape for j in P.diff_arg_indices(op_id)]
+        a = P.alloc_recompute(op_id, dev, adj_dev, shapes)
+        P.bcast_dual_backward_recompute(op_id, dev, adj_dev, a.grads, a.workspace)
+        P.bcast_dual_set_tuning(5, 1)
+        try:
+            b = P.alloc_recompute(op_id, dev, adj_dev, shapes)
+            P.bcast_dual_backward_recompute(op_id, dev, adj_dev, b.grads, b.workspace)
+        finally:
+            P.bcast_dual_set_tuning(5, 0)
+        torch.cuda.synchronize()
+        for x, y in zip(a.grads, b.grads):
+            if x.numel() == args[0].size or op == "hmlstm_update":
+                assert torch.equal(x, y)
+            else:  # sums taken with a different number of rows per block may round differently
+                check_close(x.cpu().numpy(), y.cpu().numpy(), f"{op} reduced gradient")
