@@ -181,6 +181,46 @@ def main():
             lean_extra = {"value": round(lr["value"], 1), "unit": "elements/s", "ms_per_step": round(lr["ms_per_step"], 5),
                           "planes_stored": lr["n_stored"], **lr["detail"]}
 
+    # the other side of the paper's trade-off (end of Sec. 2.2.3): no planes at all, the dual
+    # numbers are evaluated again in the reverse pass -- values-only forward + recompute backward
+    recompute_extra = None
+    if not a.lean and not a.no_lean_extra:
+        try:
+            fbv = P.alloc_forward(op, dev, want_branch=False, want_partials=False)
+            rb = P.alloc_recompute(fbv.op_id, dev, adj_dev, shapes)
+            fcall = fbv.prepare(dev)
+            rcall = P.PreparedRecompute(fbv.op_id, dev, adj_dev, rb.grads, rb.workspace)
+        except P.BcastError:
+            fcall = None
+        if fcall is not None:
+            for _ in range(a.warmup):
+                fcall.launch(sptr)
+                rcall.launch(sptr)
+            torch.cuda.synchronize()
+            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+            t0 = time.perf_counter()
+            for k in range(a.steps):
+                ev[k][0].record(stream)
+                fcall.launch(sptr)
+                ev[k][1].record(stream)
+                rcall.launch(sptr)
+                ev[k][2].record(stream)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            f_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+            r_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+            n_full_args = sum(1 for x in args if x.size == E)
+            n_full_grads = sum(1 for s_ in shapes if int(np.prod(s_)) == E)
+            f_bytes, r_bytes = (n_full_args + M) * es * E, (n_full_args + M + n_full_grads) * es * E
+            recompute_extra = {
+                "value": round(E * a.steps / wall, 1), "unit": "elements/s", "ms_per_step": round(wall * 1e3 / a.steps, 5),
+                "forward_values_only": {"avg_ms": round(f_ms, 5), "bytes": f_bytes,
+                                        "GBps": round(f_bytes / (f_ms * 1e-3) / 1e9, 1)},
+                "backward_recompute": {"avg_ms": round(r_ms, 5), "bytes": r_bytes,
+                                       "GBps": round(r_bytes / (r_ms * 1e-3) / 1e9, 1)},
+                "bytes_per_element": (f_bytes + r_bytes) // E,
+            }
+
     cpu = None
     if not a.no_cpu_baseline:
         import oracle
@@ -216,6 +256,7 @@ def main():
                    "layout": "row-major, staggered slab, " + ("identical planes stored once, zero planes left out"
                                                               if a.lean else "all planes stored")},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra, "lean_layout": lean_extra,
+        "recompute_in_reverse": recompute_extra,
     }
     print(json.dumps(line))
 
