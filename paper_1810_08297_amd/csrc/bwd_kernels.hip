@@ -17,13 +17,16 @@ namespace bd {
 template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT>
 __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
   constexpr int NE = NF + NR + NC + NA;
+  // Without sums over rows a block takes one row step and needs no loop (the host plans it so):
+  // table entries are then read where they are used instead of being held across iterations.
+  constexpr bool LOOP = NC + NA > 0;
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
   const bool nt = p.nt_store != 0;
   auto walk = [&](auto edge_tag) {
     constexpr bool EDGE = decltype(edge_tag)::value;
     uint32_t off = g.off0;
-    for (int k = 0; k < p.steps; ++k, off += g.off_step) {
+    for (int k = 0; k < (LOOP ? p.steps : 1); ++k, off += g.off_step) {
       const int ri = k * g.TY + g.ty;
       const int64_t r = g.r0 + ri;
       const bool valid = g.colvalid && r < p.R;

@@ -576,12 +576,19 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       n_rowsum += (cls[j] == kGradRowSum);
     }
     const int TY = kBlock >> g.log2_tx;
-    int steps = g_tune[1] > 0 ? g_tune[1] : (any_rowwise ? (int)ceil_div(32, TY) : auto_steps(s2.R, g, 4));
+    // Sums over rows want many rows per block (fewer per-block partials for the second pass,
+    // the LDS combine amortised): about two blocks per CU, between 8 and 128 rows each.
+    const int64_t rows_rowwise = std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
+    int steps = g_tune[1] > 0 ? g_tune[1] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
+    if (!rop && !any_rowwise && g_tune[1] == 0 && g_tune[5] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
       for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
       plan.fixed_pattern = g_tune[5] == 0 && pattern == rop->recompute_pattern();
-      if (plan.fixed_pattern && !any_rowwise) steps = 1;  // that kernel has no row loop
+      if (plan.fixed_pattern && !any_rowwise) {
+        if (g_tune[1] > 1) plan.fixed_pattern = false;  // an explicit rows-per-block override needs the looping kernel
+        else steps = 1;                                  // that kernel has no row loop
+      }
     }
     // rows wider than a wavefront park one accumulator per wavefront and row in LDS
     const int wpr = g.log2_tx > 6 ? (1 << (g.log2_tx - 6)) : 1;
@@ -700,6 +707,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
     }
     plan.signature = !rop && plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
+                     (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
