@@ -70,6 +70,10 @@ def main():
     ap.add_argument("--uniform-run", type=int, default=0,
                     help="paper_n* workloads: make z1, z2 constant over aligned runs of this many elements")
     ap.add_argument("--no-lean-extra", action="store_true", help="skip the additional lean-layout measurement")
+    ap.add_argument("--unfused-baseline", action="store_true",
+                    help="also time the same function as per-primitive library kernels with reverse-mode autograd")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from a captured HIP graph and report its rate")
     ap.add_argument("--lean", action="store_true",
                     help="store planes the op table declares identical once and leave always-zero planes out")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -221,6 +225,76 @@ def main():
                 "bytes_per_element": (f_bytes + r_bytes) // E,
             }
 
+    # the same step replayed from a HIP graph (one launch of the graph = forward + backward):
+    # separates the host's per-call cost from the kernels' for the small, launch-bound configs
+    graph_extra = None
+    if a.graph:
+        fb = P.alloc_forward(op, dev, want_branch=False, lean=a.lean)
+        bb = P.alloc_backward(adj_dev, fb.partials, shapes)
+        fcall, bcall = fb.prepare(dev), bb.prepare(adj_dev, fb.partials)
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                fcall.launch()
+                bcall.launch()
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fcall.launch()
+            bcall.launch()
+        for _ in range(a.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        graph_extra = {"value": round(E * a.steps / wall, 1), "unit": "elements/s",
+                       "ms_per_step": round(wall * 1e3 / a.steps, 5)}
+
+    # unfused comparison: one library kernel per primitive, both branches + select, reverse mode
+    unfused_extra = None
+    if a.unfused_baseline:
+        from paper_1810_08297_amd.unfused_baseline import UnfusedStep
+        ust = UnfusedStep(op, dev, adj_dev)
+        for _ in range(max(3, a.warmup // 4)):
+            ust.run()
+        torch.cuda.synchronize()
+        n_un = max(5, a.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(n_un):
+            ust.run()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        unfused_extra = {"value": round(E * n_un / wall, 1), "unit": "elements/s", "steps": n_un,
+                         "ms_per_step": round(wall * 1e3 / n_un, 5), "kind": "torch elementwise kernels + autograd"}
+        # the same kernels replayed from a HIP graph: takes the framework's host time out of the comparison
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            with torch.cuda.stream(side):
+                for _ in range(3):
+                    ust.run()
+            stream.wait_stream(side)
+            torch.cuda.synchronize()
+            ug = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(ug):
+                ust.run()
+            for _ in range(3):
+                ug.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n_un):
+                ug.replay()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            unfused_extra["graph_replay"] = {"value": round(E * n_un / wall, 1), "ms_per_step": round(wall * 1e3 / n_un, 5)}
+        except Exception as e:  # capture of library kernels is best effort; the eager number stands
+            unfused_extra["graph_replay"] = {"error": str(e)[:200]}
+
     cpu = None
     if not a.no_cpu_baseline:
         import oracle
@@ -256,7 +330,8 @@ def main():
                    "layout": "row-major, staggered slab, " + ("identical planes stored once, zero planes left out"
                                                               if a.lean else "all planes stored")},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra, "lean_layout": lean_extra,
-        "recompute_in_reverse": recompute_extra,
+        "recompute_in_reverse": recompute_extra, "graph_replay": graph_extra,
+        "unfused_baseline": unfused_extra,
     }
     print(json.dumps(line))
 

@@ -186,7 +186,8 @@ const char *bcast_status_string(int status);
  * outside the documented range are rejected with BCAST_ERR_BAD_ARG_COUNT).
  *   key 0: unused (kept so that the other keys keep their numbers)
  *   key 1: rows per block of the tiled backward kernel (0 = automatic, else 1..256)
- *   key 2: 1 = non-temporal stores for outputs/partials/gradients, 0 = plain
+ *   key 2: non-temporal stores: bit 0 = the forward kernel's outputs and partials, bit 1 = the
+ *          backward kernels' gradients (default 3 = both, 0 = plain stores)
  *   key 3: 1 = force the generic strided kernels (testing)
  *   key 4: widest vector access per lane in bytes: 16 (default), 8 or 4
  *   key 5: 1 = always use the generic tiled backward kernel, never a kernel compiled for

@@ -179,11 +179,11 @@ struct BwdGeom {
 template <class T, int VEC, bool EDGE>
 BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) {
   if (EDGE) {
-    load_vec<T, VEC>(at<const T>(base, valid ? off : 0u), x);
+    load_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(base, valid ? off : 0u), x);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) x[v] = valid ? x[v] : T(0);
   } else {
-    load_vec<T, VEC>(at<const T>(base, off), x);
+    load_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(base, off), x);
   }
 }
 

@@ -48,7 +48,21 @@ template <> struct smath<float> {
     return ::fmaf(p, e * 0.6931471805599453f, p);
 #endif
   }
-  static BD_DEV float log1p(float x) { return ::log1pf(x); }
+  // log(u) + (x - (u - 1)) / u with u = fl(1 + x): the second term gives back what the
+  // rounding of 1 + x dropped, so tiny x return x and nothing cancels.  log(u) is the hardware
+  // log2 (1 ulp) times ln 2, the constant's own rounding error folded in.  About 2 ulp.
+  static BD_DEV float log1p(float x) {
+#ifdef BD_LIBM_LOG1P
+    return ::log1pf(x);
+#else
+    const float u = 1.0f + x;
+    const float l2 = __builtin_amdgcn_logf(u);
+    float l = l2 * 0.693147182464599609375f;  // ln 2 rounded to float ...
+    l = ::fmaf(l2, -1.904654323148236e-9f, l);  // ... and the remainder of ln 2
+    const float lost = x - (u - 1.0f);
+    return (x > 3.0e38f || u == 0.0f) ? l : ::fmaf(lost, __builtin_amdgcn_rcpf(u), l);  // inf and -1 pass through
+#endif
+  }
   static BD_DEV float sin(float x) { return ::sinf(x); }
   static BD_DEV float cos(float x) { return ::cosf(x); }
   static BD_DEV float abs(float x) { return ::fabsf(x); }

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
 #pragma unroll
       for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
       if (!((ra.col_invariant >> j) & 1u))
-        load_vec<T, VEC>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : off_ld), avec[j]);
+        load_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : off_ld), avec[j]);
     }
 #pragma unroll
     for (int j = 0; j < N; ++j) {

@@ -465,3 +465,73 @@ def test_recompute_fixed_and_runtime_patterns_agree():
                 assert torch.equal(x, y)
             else:  # sums taken with a different number of rows per block may round differently
                 check_close(x.cpu().numpy(), y.cpu().numpy(), f"{op} reduced gradient")
+
+
+@pytest.mark.parametrize("op,R,C", [("hmlstm_update", 64, 16), ("branchy5", 300, 1100), ("tanh_xy_b", 257, 515)])
+def test_graph_replays_match_eager(op, R, C):
+    """Forward + backward (+ the fixed-order second pass where one runs) captured into one HIP
+    graph: the library allocates nothing, clears nothing with memset nodes and never
+    synchronises, so every replay -- with new data in the same buffers and eager work in
+    between -- must give the bits the eager calls give."""
+    args0, adj0 = small_args(op, R, C, np.float32, seed=11)
+    dev = [to_dev(a) for a in args0]
+    adj_dev = [to_dev(a) for a in adj0]
+    fb = P.alloc_forward(op, dev, want_branch=True)
+    didx = oracle.diff_arg_indices(op, len(args0))
+    gshapes = [args0[j].shape for j in didx]
+    bb = P.alloc_backward(adj_dev, fb.partials, gshapes)
+    fcall, bcall = fb.prepare(dev), bb.prepare(adj_dev, fb.partials)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fcall.launch()
+        bcall.launch()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fcall.launch()
+        bcall.launch()
+    for rep in range(3):
+        args_r, adj_r = small_args(op, R, C, np.float32, seed=20 + rep)
+        for d, a in zip(dev, args_r):
+            d.copy_(torch.from_numpy(a))
+        for d, a in zip(adj_dev, adj_r):
+            d.copy_(torch.from_numpy(a))
+        # eager result first, kept aside; then poison the outputs and replay
+        fcall.launch()
+        bcall.launch()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in fb.outs + fb.partials + bb.grads] + [fb.branch.clone()]
+        for t in fb.outs + fb.partials + bb.grads:
+            t.fill_(float("nan"))
+        fb.branch.fill_(255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        now = fb.outs + fb.partials + bb.grads + [fb.branch]
+        for k, (e, n) in enumerate(zip(eager, now)):
+            assert torch.equal(e, n), f"{op} replay {rep}: buffer {k} differs from the eager call"
+        # and the replayed gradients are the oracle's
+        want = oracle.backward(adj_r, [p.cpu().numpy() for p in fb.partials],
+                               [full_rank(args_r[j], 2).shape for j in didx], threads=8)
+        for k, (g, w) in enumerate(zip(bb.grads, want)):
+            check_close(g.cpu().numpy().reshape(w.shape), w, f"{op} replay {rep} gradient {didx[k]}")
+
+
+@pytest.mark.parametrize("op", ["hmlstm_update", "update_c", "tanh_xy_b", "branchy5"])
+def test_unfused_baseline_computes_the_same_function(op):
+    """The per-primitive comparison point timed by the benchmark is the same mathematical
+    function: its outputs and reverse-mode gradients agree with the oracle's (looser line:
+    library fp32 kernels, fp32 sums)."""
+    from paper_1810_08297_amd.unfused_baseline import UnfusedStep
+    args, adj = small_args(op, 130, 200, np.float32, seed=5)
+    o_out, o_parts, _ = oracle.forward(op, args, threads=8)
+    didx = oracle.diff_arg_indices(op, len(args))
+    want = oracle.backward(adj, o_parts, [args[j].shape for j in didx], threads=8)
+    outs, grads = UnfusedStep(op, [to_dev(a) for a in args], [to_dev(a) for a in adj]).run()
+    for k, (g, w) in enumerate(zip(outs, o_out)):
+        check_close(g.detach().cpu().numpy(), w, f"{op} unfused output {k}", rtol=1e-4, atol=1e-5)
+    for k, (g, w) in enumerate(zip(grads, want)):
+        scale = float(np.abs(w).max()) + 1.0
+        check_close(g.cpu().numpy().reshape(w.shape), w, f"{op} unfused gradient {didx[k]}", rtol=1e-4, atol=1e-5 * scale)

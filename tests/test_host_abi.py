@@ -197,7 +197,7 @@ def test_backward_plan_and_workspace():
 
 
 def test_tuning_keys():
-    assert P.bcast_dual_get_tuning(2) == 1 and P.bcast_dual_get_tuning(6) == 1
+    assert P.bcast_dual_get_tuning(2) == 3 and P.bcast_dual_get_tuning(6) == 1
     P.bcast_dual_set_tuning(0, 3)
     assert P.bcast_dual_get_tuning(0) == 3
     P.bcast_dual_set_tuning(0, 0)
