@@ -194,7 +194,12 @@ const char *bcast_status_string(int status);
  *          the call's mix of gradient classes (testing)
  *   key 6: 1 (default) = the tiled backward kernel walks its tiles last to first, so that it
  *          starts with the planes the forward kernel wrote last, which the memory-side
- *          cache may still hold; 0 = first to last */
+ *          cache may still hold; 0 = first to last
+ *   key 7: loads of the streaming probe: 1 (default) = nontemporal, as the kernels load their
+ *          once-read operands; 0 = plain
+ *   key 8: rows of a backward block that takes several row steps: 1 (default) = every n-th
+ *          row step of the problem (the resident blocks sweep one contiguous band of each
+ *          plane together), 0 = one contiguous run of rows per block */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 
@@ -216,7 +221,8 @@ size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offs
  * plane[k] + b * chunk_stride[k] floats (1024 = a dense plane; larger = planes interleaved in
  * one buffer).  in/out and the stride arrays are HOST arrays (at most 32 entries each) of
  * DEVICE pointers (16-byte aligned) and strides (multiples of 4; output strides >= 1024).
- * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters. */
+ * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters.  Tuning key 6
+ * (chunk order) and key 7 (load policy) apply. */
 int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
                             void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream);
 

@@ -138,7 +138,8 @@ struct BwdGeom {
   using A = typename AT::type;
   int tid, ltx, TX, tx, ty, TY, wpr, rows_pb;
   uint32_t bid, rt, ct;
-  int64_t c0, r0;
+  int64_t c0, r_first;  // r_first: row of the block's first row step at ty = 0
+  int64_t r_step;       // rows from one row step of the block to its next
   bool colvalid, interior;
   uint32_t off0, off_step;
   A *lds_row, *lds_col, *lds_all;
@@ -160,11 +161,21 @@ struct BwdGeom {
     ct = bid - rt * nct;
     c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
     colvalid = c0 < p.C;
-    r0 = (int64_t)rt * rows_pb;
-    interior = r0 + rows_pb <= p.R && ((((int64_t)ct + 1) << ltx) * VEC) <= p.C;
+    // Which rows a block takes.  Contiguous: steps * TY consecutive rows.  Interleaved: its
+    // k-th row step is step k * n_rt + rt of the whole problem, so that the blocks resident at
+    // one time sweep one contiguous band of every plane together (a contiguous run per block
+    // puts the blocks a large power of two apart, on the same memory channels).
+    if (p.interleave) {
+      r_first = (int64_t)rt * TY;
+      r_step = (int64_t)p.n_rt * TY;
+    } else {
+      r_first = (int64_t)rt * rows_pb;
+      r_step = TY;
+    }
+    interior = r_first + (p.steps - 1) * r_step + TY <= p.R && ((((int64_t)ct + 1) << ltx) * VEC) <= p.C;
     // one byte offset per lane and row serves the adjoints, every plane and every full gradient
-    off0 = (uint32_t)((r0 + ty) * p.row_stride + c0) * (uint32_t)sizeof(T);
-    off_step = (uint32_t)(TY * p.row_stride) * (uint32_t)sizeof(T);
+    off0 = (uint32_t)((r_first + ty) * p.row_stride + c0) * (uint32_t)sizeof(T);
+    off_step = (uint32_t)(r_step * p.row_stride) * (uint32_t)sizeof(T);
     lds_row = reinterpret_cast<A *>(smem + p.lds_row_off);
     lds_col = reinterpret_cast<A *>(smem + p.lds_col_off);
     lds_all = reinterpret_cast<A *>(smem + p.lds_all_off);
@@ -172,6 +183,13 @@ struct BwdGeom {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) lds_col[(s * kBlock + tid) * VEC + v] = AT::zero();
     for (int s = 0; s < p.n_all_slots; ++s) lds_all[s * kBlock + tid] = AT::zero();
+  }
+  // row of this lane at row step k of the block
+  BD_DEV int64_t row(int k) const { return r_first + ty + k * r_step; }
+  // row behind the block-local row index q = k * TY + ty
+  BD_DEV int64_t row_of_local(int q) const {
+    const int lty = 8 - ltx;  // kBlock = 256 lanes = TY * TX
+    return r_first + (q >> lty) * r_step + (q & (TY - 1));
   }
 };
 
@@ -261,7 +279,7 @@ BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
     const BwdEntry &en = p.e[e];
     if (en.cls == kGradRowSum && g.ltx > 6) {
       for (int q = g.tid; q < g.rows_pb; q += kBlock) {
-        const int64_t r = g.r0 + q;
+        const int64_t r = g.row_of_local(q);
         if (r < p.R) {
           A s = g.lds_row[(en.slot * g.rows_pb + q) * g.wpr];
           for (int w = 1; w < g.wpr; ++w) AT::add(s, g.lds_row[(en.slot * g.rows_pb + q) * g.wpr + w]);

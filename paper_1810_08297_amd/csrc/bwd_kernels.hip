@@ -14,50 +14,97 @@ namespace bd {
 // col-sum, then NA all-sum gradients.  Bit e*M + i of ABSENT says that plane i of gradient e
 // is absent (a structurally zero partial the caller chose not to store): it is neither
 // loaded nor multiplied.
+// Row steps per loop iteration of the looping kernels (all loads of an iteration issued before
+// the first use).  Measured on 8192 x 8192: 1 -> 381 us, 2 -> 389 us, 4 -> 395 us; 1 it is.
+#ifndef BD_BWD_UNROLL
+#define BD_BWD_UNROLL 1
+#endif
 template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT>
 __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
+  using AT = acc_traits<T>;
+  using A = typename AT::type;
   constexpr int NE = NF + NR + NC + NA;
   // Without sums over rows a block takes one row step and needs no loop (the host plans it so):
   // table entries are then read where they are used instead of being held across iterations.
   constexpr bool LOOP = NC + NA > 0;
+  constexpr int U = LOOP && (NE + 1) * M <= 8 ? BD_BWD_UNROLL : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
   const bool nt = p.nt_store != 0;
-  auto walk = [&](auto edge_tag) {
-    constexpr bool EDGE = decltype(edge_tag)::value;
-    uint32_t off = g.off0;
-    for (int k = 0; k < (LOOP ? p.steps : 1); ++k, off += g.off_step) {
-      const int ri = k * g.TY + g.ty;
-      const int64_t r = g.r0 + ri;
-      const bool valid = g.colvalid && r < p.R;
-      T adj[M][VEC], P[NE][M][VEC];
+  // sums over rows accumulate in registers during the walk and are parked in LDS afterwards
+  A colacc[NC > 0 ? NC : 1][VEC], allacc[NA > 0 ? NA : 1];
 #pragma unroll
-      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.adj[i].p, off, valid, adj[i]);
+  for (int e = 0; e < (NC > 0 ? NC : 1); ++e)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) colacc[e][v] = AT::zero();
+#pragma unroll
+  for (int e = 0; e < (NA > 0 ? NA : 1); ++e) allacc[e] = AT::zero();
+
+  auto rows = [&](auto edge_tag, auto count_tag, int k, uint32_t off) {
+    constexpr bool EDGE = decltype(edge_tag)::value;
+    constexpr int CNT = decltype(count_tag)::value;
+    T adj[CNT][M][VEC], P[CNT][NE][M][VEC];
+    bool valid[CNT];
+#pragma unroll
+    for (int u = 0; u < CNT; ++u) {
+      const uint32_t o = off + (uint32_t)u * g.off_step;
+      valid[u] = g.colvalid && g.row(k + u) < p.R;
+#pragma unroll
+      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.adj[i].p, o, valid[u], adj[u][i]);
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
         for (int i = 0; i < M; ++i) {
           if ((ABSENT >> (e * M + i)) & 1u) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) P[e][i][v] = T(0);
+            for (int v = 0; v < VEC; ++v) P[u][e][i][v] = T(0);
           } else {
-            load_plane<T, VEC, EDGE>(p.e[e].P[i].p, off, valid, P[e][i]);
+            load_plane<T, VEC, EDGE>(p.e[e].P[i].p, o, valid[u], P[u][e][i]);
           }
         }
+    }
 #pragma unroll
-      for (int e = 0; e < NF; ++e) apply_full<T, VEC, M, EDGE>(p.e[e], adj, P[e], off, valid, nt);
+    for (int u = 0; u < CNT; ++u) {
+      const uint32_t o = off + (uint32_t)u * g.off_step;
+      const int ri = (k + u) * g.TY + g.ty;
+      const int64_t r = g.row(k + u);
 #pragma unroll
-      for (int e = NF; e < NF + NR; ++e) apply_rowsum<T, VEC, M>(p, g, p.e[e], adj, P[e], r, ri);
+      for (int e = 0; e < NF; ++e) apply_full<T, VEC, M, EDGE>(p.e[e], adj[u], P[u][e], o, valid[u], nt);
 #pragma unroll
-      for (int e = NF + NR; e < NF + NR + NC; ++e) apply_colsum<T, VEC, M>(g, p.e[e], adj, P[e]);
+      for (int e = NF; e < NF + NR; ++e) apply_rowsum<T, VEC, M>(p, g, p.e[e], adj[u], P[u][e], r, ri);
 #pragma unroll
-      for (int e = NF + NR + NC; e < NE; ++e) apply_allsum<T, VEC, M>(g, p.e[e], adj, P[e]);
+      for (int e = 0; e < NC; ++e)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+#pragma unroll
+          for (int i = 0; i < M; ++i) AT::add_prod(colacc[e][v], adj[u][i][v], P[u][NF + NR + e][i][v]);
+#pragma unroll
+      for (int e = 0; e < NA; ++e)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+#pragma unroll
+          for (int i = 0; i < M; ++i) AT::add_prod(allacc[e], adj[u][i][v], P[u][NF + NR + NC + e][i][v]);
     }
   };
-  if (g.interior)
-    walk(std::false_type{});
-  else
-    walk(std::true_type{});
+  const int steps = LOOP ? p.steps : 1;
+  uint32_t off = g.off0;
+  int k = 0;
+  if (g.interior) {
+    if constexpr (U > 1)
+      for (; k + U <= steps; k += U, off += (uint32_t)U * g.off_step)
+        rows(std::false_type{}, std::integral_constant<int, U>{}, k, off);
+    for (; k < steps; ++k, off += g.off_step) rows(std::false_type{}, std::integral_constant<int, 1>{}, k, off);
+  } else {
+    for (; k < steps; ++k, off += g.off_step) rows(std::true_type{}, std::integral_constant<int, 1>{}, k, off);
+  }
+  if constexpr (LOOP) {  // slots were handed out in table order within each class
+#pragma unroll
+    for (int e = 0; e < NC; ++e)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) g.lds_col[(p.e[NF + NR + e].slot * kBlock + g.tid) * VEC + v] = colacc[e][v];
+#pragma unroll
+    for (int e = 0; e < NA; ++e) g.lds_all[p.e[NF + NR + NC + e].slot * kBlock + g.tid] = allacc[e];
+  }
   bwd_finalize<T, VEC>(p, g);
 }
 
@@ -73,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
   uint32_t off = g.off0;
   for (int k = 0; k < p.steps; ++k, off += g.off_step) {
     const int ri = k * g.TY + g.ty;
-    const int64_t r = g.r0 + ri;
+    const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
     T adj[MAXM][VEC];
 #pragma unroll
@@ -238,22 +285,28 @@ struct ProbeParams {
   float *out[32];
   int64_t out_stride[32];
   float *sink;
+  int reverse;
 };
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <bool NT>
+BD_DEV f32x4 probe_load(const float *q) {
+  return NT ? __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(q)) : *reinterpret_cast<const f32x4 *>(q);
+}
+template <bool NT>
 __global__ __launch_bounds__(kBlock) void stream_probe_kernel(const ProbeParams p) {
-  const int64_t b = blockIdx.x;
+  const int64_t b = p.reverse ? p.n_chunks - 1 - (int64_t)blockIdx.x : (int64_t)blockIdx.x;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   int k = 0;
   for (; k + 8 <= p.n_in; k += 8) {  // eight loads in flight per lane
     f32x4 t[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q)
-      t[q] = *reinterpret_cast<const f32x4 *>(p.in[k + q] + b * p.in_stride[k + q] + threadIdx.x * 4);
+      t[q] = probe_load<NT>(p.in[k + q] + b * p.in_stride[k + q] + threadIdx.x * 4);
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc += t[q];
   }
   for (; k < p.n_in; ++k)
-    acc += *reinterpret_cast<const f32x4 *>(p.in[k] + b * p.in_stride[k] + threadIdx.x * 4);
+    acc += probe_load<NT>(p.in[k] + b * p.in_stride[k] + threadIdx.x * 4);
   for (int k = 0; k < p.n_out; ++k)
     __builtin_nontemporal_store(acc + (float)k, reinterpret_cast<f32x4 *>(p.out[k] + b * p.out_stride[k] + threadIdx.x * 4));
   if (p.n_out == 0 && acc[0] == 12345.678f) p.sink[0] = acc[1];  // keeps the loads alive
@@ -342,8 +395,9 @@ hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_
 }
 
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
-                           const int64_t *out_stride, int64_t n_chunks, hipStream_t s) {
+                           const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, hipStream_t s) {
   ProbeParams p{};
+  p.reverse = reverse;
   p.n_in = n_in;
   p.n_out = n_out;
   p.n_chunks = n_chunks;
@@ -359,6 +413,9 @@ hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_st
 #ifndef BD_PROBE_LDS
 #define BD_PROBE_LDS 0
 #endif
-  hipLaunchKernelGGL(stream_probe_kernel, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
+  if (nt_loads)
+    hipLaunchKernelGGL(stream_probe_kernel<true>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
+  else
+    hipLaunchKernelGGL(stream_probe_kernel<false>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
   return hipGetLastError();
 }

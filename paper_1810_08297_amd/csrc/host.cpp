@@ -52,7 +52,7 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
-                           const int64_t *out_stride, int64_t n_chunks, hipStream_t s);
+                           const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, hipStream_t s);
 
 namespace {
 
@@ -96,8 +96,8 @@ const OpDesc kOps[] = {
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-constexpr int kNumTune = 7;
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1};
+constexpr int kNumTune = 9;
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1};
 
 // ---- small helpers ---------------------------------------------------------------------------
 inline size_t elem_size(int dt) { return dt == BCAST_F32 ? 4 : 8; }
@@ -577,8 +577,12 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     }
     const int TY = kBlock >> g.log2_tx;
     // Sums over rows want many rows per block (fewer per-block partials for the second pass,
-    // the LDS combine amortised): about two blocks per CU, between 8 and 128 rows each.
-    const int64_t rows_rowwise = std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
+    // the LDS combine amortised), and measured best is a grid of one block per CU (256 on
+    // MI355X): 8192 x 8192 runs 381 us at 256 rows per block, 399 us at 128, 434 us at 32.
+    // The recompute kernels carry the op's arithmetic and want two blocks per CU to hide it
+    // (same problem: 314 us at 128 rows per block, 478 us at 256).
+    const int64_t rows_rowwise = rop != nullptr ? std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512))
+                                                : std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256));
     int steps = g_tune[1] > 0 ? g_tune[1] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
     if (!rop && !any_rowwise && g_tune[1] == 0 && g_tune[5] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
@@ -613,6 +617,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.steps = g.steps;
       p.nt_store = (g_tune[2] >> 1) & 1;
       p.reverse = g_tune[6];
+      p.interleave = g_tune[8];
       p.M = M;
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
@@ -933,7 +938,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;
@@ -972,7 +977,7 @@ int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *
     if (reinterpret_cast<uintptr_t>(out[k]) % 16 || out_chunk_stride[k] % 4 || out_chunk_stride[k] < 1024) return BCAST_ERR_MISALIGNED;
   }
   if (n_chunks == 0) return BCAST_OK;
-  return bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks,
+  return bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[7] != 0, g_tune[6] != 0,
                          static_cast<hipStream_t>(stream)) == hipSuccess ? BCAST_OK : BCAST_ERR_LAUNCH_FAILED;
 }
 

@@ -80,6 +80,7 @@ struct BwdTiledParams {
   int32_t log2_tx, steps, nt_store, M;
   int32_t n_entries;
   int32_t reverse;  // 1: blocks walk the tiles from the last to the first
+  int32_t interleave;  // 1: row tile rt takes row steps rt, rt + n_rt, rt + 2 n_rt, ... instead of a contiguous run
   int32_t n_row_slots, n_col_slots, n_all_slots;
   uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS
   int64_t n_ct, n_rt;  // column tiles, row tiles; block b = rt * n_ct + ct

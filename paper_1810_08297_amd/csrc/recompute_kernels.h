@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
   uint32_t off = g.off0;
   for (int k = 0; k < (LOOP ? p.steps : 1); ++k, off += g.off_step) {
     const int ri = k * g.TY + g.ty;
-    const int64_t r = g.r0 + ri;
+    const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
     const uint32_t off_ld = valid ? off : 0u;       // lanes outside the problem read element 0
     const int64_t r_ld = r < p.R ? r : 0;

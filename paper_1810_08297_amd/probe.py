@@ -24,7 +24,11 @@ def main():
     ap.add_argument("--rows", type=int, default=4096)
     ap.add_argument("--cols", type=int, default=1024)
     ap.add_argument("--staggered", type=int, default=1)
+    ap.add_argument("--mix", action="append", default=[], help="R,W: a mix of R read and W written planes (repeatable)")
+    ap.add_argument("--nt-loads", type=int, default=1, help="1 = nontemporal loads (what the kernels use), 0 = plain")
     a = ap.parse_args()
+    P.bcast_dual_set_tuning(7, a.nt_loads)
+    P.bcast_dual_set_tuning(6, 0)
     E = a.rows * a.cols
     assert E % 1024 == 0
     chunks = E // 1024
@@ -54,9 +58,11 @@ def main():
         torch.cuda.synchronize()
         return float(np.median([x.elapsed_time(y) for x, y in ts[3:]])) * 1e3
 
-    print(f"planes of {a.rows} x {a.cols} fp32 ({E * 4 / 2**20:.0f} MiB), staggered layout: {bool(a.staggered)}")
+    print(f"planes of {a.rows} x {a.cols} fp32 ({E * 4 / 2**20:.0f} MiB), staggered layout: {bool(a.staggered)}, "
+          f"nontemporal loads: {bool(a.nt_loads)}")
     print(f"{'mix':>12s} {'back to back':>24s} {'after a 1 GiB copy':>24s}")
-    for nin, nout in ((1, 1), (2, 4), (4, 2), (7, 22), (22, 6), (8, 8), (16, 16), (29, 0), (0, 29)):
+    mixes = [tuple(int(x) for x in m.split(",")) for m in a.mix]
+    for nin, nout in mixes or ((1, 1), (2, 4), (4, 2), (7, 22), (22, 6), (8, 8), (16, 16), (29, 0), (0, 29)):
         ip, k1 = planes(nin)
         op, k2 = planes(nout)
         fn = lambda: P.bcast_dual_stream_probe(ip, [1024] * nin, op, [1024] * nout, chunks)
@@ -66,26 +72,33 @@ def main():
         print(f"{nin:4d}r + {nout:2d}w {t1:10.1f} us {byt / t1 / 1e3:8.1f} GB/s {t2:10.1f} us {byt / t2 / 1e3:8.1f} GB/s",
               flush=True)
         del k1, k2
+    if mixes:
+        return
     # a training step: 7 arguments -> 2 outputs + 20 planes, then 2 adjoints + 20 planes -> 6 gradients
     args, k1 = planes(7)
     outs, k2 = planes(22)
     adj, k3 = planes(2)
     grads, k4 = planes(6)
-    tf, tb = [], []
-    for it in range(40):
-        e0, e1, e2 = ev(), ev(), ev()
-        e0.record()
-        P.bcast_dual_stream_probe(args, [1024] * 7, outs, [1024] * 22, chunks)
-        e1.record()
-        P.bcast_dual_stream_probe(adj + outs[2:], [1024] * 22, grads, [1024] * 6, chunks)
-        e2.record()
-        tf.append((e0, e1))
-        tb.append((e1, e2))
-    torch.cuda.synchronize()
-    f = float(np.median([x.elapsed_time(y) for x, y in tf[5:]])) * 1e3
-    b = float(np.median([x.elapsed_time(y) for x, y in tb[5:]])) * 1e3
-    print(f"alternating: forward-like 7r+22w {f:.1f} us {29 * E * 4 / f / 1e3:.1f} GB/s | backward-like 22r+6w "
-          f"{b:.1f} us {28 * E * 4 / b / 1e3:.1f} GB/s | step {f + b:.1f} us {57 * E * 4 / (f + b) / 1e3:.1f} GB/s")
+    for reverse in (0, 1):  # the backward-like launch walks its chunks first to last / last to first
+        tf, tb = [], []
+        for it in range(40):
+            e0, e1, e2 = ev(), ev(), ev()
+            e0.record()
+            P.bcast_dual_set_tuning(6, 0)
+            P.bcast_dual_stream_probe(args, [1024] * 7, outs, [1024] * 22, chunks)
+            e1.record()
+            P.bcast_dual_set_tuning(6, reverse)
+            P.bcast_dual_stream_probe(adj + outs[2:], [1024] * 22, grads, [1024] * 6, chunks)
+            e2.record()
+            tf.append((e0, e1))
+            tb.append((e1, e2))
+        torch.cuda.synchronize()
+        f = float(np.median([x.elapsed_time(y) for x, y in tf[5:]])) * 1e3
+        b = float(np.median([x.elapsed_time(y) for x, y in tb[5:]])) * 1e3
+        print(f"alternating, backward-like {'last to first' if reverse else 'first to last'}: forward-like 7r+22w {f:.1f} us "
+              f"{29 * E * 4 / f / 1e3:.1f} GB/s | backward-like 22r+6w {b:.1f} us {28 * E * 4 / b / 1e3:.1f} GB/s | "
+              f"step {f + b:.1f} us {57 * E * 4 / (f + b) / 1e3:.1f} GB/s")
+    P.bcast_dual_set_tuning(6, 1)
 
 
 if __name__ == "__main__":

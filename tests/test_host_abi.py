@@ -162,7 +162,7 @@ def test_backward_plan_and_workspace():
     d = info.as_dict()
     assert d["path"] == 1 and d["vec"] == 4 and d["n_second_pass"] == 3 and d["n_launches"] == 2
     n_ct, n_rt = d["grid_x"], d["grid_y"]
-    assert n_ct == 8 and d["rows_per_block"] == 128
+    assert n_ct == 8 and d["rows_per_block"] == 256
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
                                          ctypes.c_int32(5), B._views(grads))
     assert ws == 8 * (n_rt * C + R * n_ct + n_rt * n_ct)
@@ -204,7 +204,7 @@ def test_tuning_keys():
     with pytest.raises(P.BcastError):
         P.bcast_dual_set_tuning(0, 1000)
     with pytest.raises(P.BcastError):
-        P.bcast_dual_set_tuning(9, 0)
+        P.bcast_dual_set_tuning(11, 0)
 
 
 def test_plane_alias_table_agrees_with_the_oracle():
