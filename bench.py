@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a
-# copy kernel of known size); see profiles/hbm_traffic_cfg3_pmc.md.  Keyed by (workload, kernel).
-MEASURED_TRAFFIC = {("cfg3", "forward"): 487.1e6, ("cfg3", "backward"): 470.5e6}
+# copy kernel of known size); see profiles/hbm_traffic_pmc.md.  Keyed by (workload, kernel).
+MEASURED_TRAFFIC = {("cfg3", "forward"): 487.1e6, ("cfg3", "backward"): 470.4e6,
+                    ("cfg4", "forward"): 2146.2e6, ("cfg4", "backward"): 2154.0e6}
 
 
 def build_workload(name, p_index, uniform_run=0):
@@ -72,6 +73,8 @@ def main():
     ap.add_argument("--no-lean-extra", action="store_true", help="skip the additional lean-layout measurement")
     ap.add_argument("--unfused-baseline", action="store_true",
                     help="also time the same function as per-primitive library kernels with reverse-mode autograd")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="per-kernel HIP events on every n-th timed step (1 = every step)")
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from a captured HIP graph and report its rate")
     ap.add_argument("--lean", action="store_true",
@@ -129,17 +132,25 @@ def main():
             for _ in range(3):
                 P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr)
             torch.cuda.synchronize()
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+        # HIP events bracket the two launches of every `event_every`-th timed step (each event
+        # costs the stream a microsecond or two, so not every step carries them)
+        ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, a.steps, a.event_every)}
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(a.steps):
-            ev[k][0].record(stream)
-            fwd_call.launch(sptr)
-            ev[k][1].record(stream)
-            bwd_call.launch(sptr)
-            ev[k][2].record(stream)
+            e = ev.get(k)
+            if e is None:
+                fwd_call.launch(sptr)
+                bwd_call.launch(sptr)
+            else:
+                e[0].record(stream)
+                fwd_call.launch(sptr)
+                e[1].record(stream)
+                bwd_call.launch(sptr)
+                e[2].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        ev = list(ev.values())
         fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
         bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
         fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
@@ -154,6 +165,7 @@ def main():
                             "bytes": fwd_bytes, "GBps": round(fwd_bytes / (fwd_avg * 1e-3) / 1e9, 1)},
                 "backward": {"avg_ms": round(bwd_avg, 5), "median_ms": round(float(np.median(bwd_ms)), 5),
                              "bytes": bwd_bytes, "GBps": round(bwd_bytes / (bwd_avg * 1e-3) / 1e9, 1)},
+                "event_samples": len(ev),
                 "fwd_bwd_GBps_event_time": round(both, 1),
                 "fwd_bwd_frac_of_hbm_peak": round(both / HBM_PEAK_GBS, 4),
                 "elements_per_s_event_time": round(E / ((fwd_avg + bwd_avg) * 1e-3), 1),
@@ -201,16 +213,22 @@ def main():
                 fcall.launch(sptr)
                 rcall.launch(sptr)
             torch.cuda.synchronize()
-            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+            ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, a.steps, a.event_every)}
             t0 = time.perf_counter()
             for k in range(a.steps):
-                ev[k][0].record(stream)
-                fcall.launch(sptr)
-                ev[k][1].record(stream)
-                rcall.launch(sptr)
-                ev[k][2].record(stream)
+                e = ev.get(k)
+                if e is None:
+                    fcall.launch(sptr)
+                    rcall.launch(sptr)
+                else:
+                    e[0].record(stream)
+                    fcall.launch(sptr)
+                    e[1].record(stream)
+                    rcall.launch(sptr)
+                    e[2].record(stream)
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
+            ev = list(ev.values())
             f_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
             r_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
             n_full_args = sum(1 for x in args if x.size == E)

@@ -25,7 +25,8 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
   using A = typename AT::type;
   constexpr int NE = NF + NR + NC + NA;
   // Without sums over rows a block takes one row step and needs no loop (the host plans it so):
-  // table entries are then read where they are used instead of being held across iterations.
+  // table entries are then read where they are used instead of being held across iterations
+  // (measured with the loop forced on: 2 to 16 rows per block cost 3 to 12 % on the HM-LSTM update).
   constexpr bool LOOP = NC + NA > 0;
   constexpr int U = LOOP && (NE + 1) * M <= 8 ? BD_BWD_UNROLL : 1;
   extern __shared__ __align__(16) unsigned char smem[];
