@@ -46,8 +46,8 @@ BD_DECLARE_RECOMPUTE(linear12)
 BD_ARITY_LIST(BD_DECL_ARITY)
 #endif
 
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent);
-hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent,
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share);
+hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
@@ -439,6 +439,7 @@ struct BwdPlan {
   bool signature = false;          // a kernel compiled for exactly this mix of gradient classes exists
   int n_cls[4] = {0, 0, 0, 0};     // gradients per class: full, row-sum, col-sum, all-sum
   uint64_t absent = 0;             // bit e*M + i: plane i of table entry e is absent
+  uint64_t share = 0;              // 4 bits per table entry e: s + 1 if e has the very planes of an earlier entry s
   RecomputeArgs ra{};              // recompute mode only
   bool fixed_pattern = false;      // recompute mode: the call has the op's compiled-in broadcast pattern
   std::vector<BwdTiledParams> main;  // usually one launch
@@ -656,6 +657,21 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
           order.push_back(j);
           plan.n_cls[want]++;
         }
+    // entries whose planes are the very views of an earlier entry (a caller that stores
+    // identical planes once): the signature kernels load such planes once
+    for (size_t e = 1; rop == nullptr && e < order.size() && e < 16; ++e)
+      for (size_t src = 0; src < e; ++src) {
+        bool same = true, any = false;
+        for (int i = 0; i < M; ++i) {
+          const PView &a = v[M + i * ND + order[e]], &b = v[M + i * ND + order[src]];
+          same = same && a.p == b.p;
+          any = any || a.p != nullptr;
+        }
+        if (same && any) {
+          plan.share |= (uint64_t)(src + 1) << (4 * e);
+          break;
+        }
+      }
     for (int j : order) {
       BwdTiledParams trial = cur;
       trial.n_row_slots += (cls[j] == kGradRowSum);
@@ -713,7 +729,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     }
     plan.signature = !rop && plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
-                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent);
+                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
     plan.ws_bytes = ws;
@@ -860,7 +876,7 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
     for (size_t k = 0; k < plan.main.size(); ++k) {
       plan.main[k].ws = static_cast<unsigned char *>(workspace);
       if (bd_bwd_tiled((int)dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
-                       plan.absent, plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
+                       plan.absent, plan.share, plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
         return BCAST_ERR_LAUNCH_FAILED;
     }
     if (plan.p2_blocks > 0) {

@@ -227,19 +227,26 @@ def test_second_pass_geometries(dtype):
 
 
 def test_tuned_launch_shapes_agree():
-    """Any rows-per-block choice gives results within tolerance of the oracle."""
+    """Any rows-per-block choice, either assignment of rows to blocks and either tile order
+    give results within tolerance of the oracle."""
     args, adj = small_args("branchy5", 333, 1100, np.float32, seed=6)
     try:
         for fwd_steps, bwd_steps in ((1, 1), (3, 7), (64, 256)):
-            P.bcast_dual_set_tuning(0, fwd_steps)
-            P.bcast_dual_set_tuning(1, bwd_steps)
-            check_op("branchy5", args, adj, what=f"[steps {fwd_steps}/{bwd_steps}] ")
+            for interleave, reverse in ((1, 1), (0, 0)):
+                P.bcast_dual_set_tuning(0, fwd_steps)
+                P.bcast_dual_set_tuning(1, bwd_steps)
+                P.bcast_dual_set_tuning(8, interleave)
+                P.bcast_dual_set_tuning(6, reverse)
+                check_op("branchy5", args, adj, what=f"[steps {fwd_steps}/{bwd_steps} interleave {interleave} reverse {reverse}] ")
+        P.bcast_dual_set_tuning(1, 0)
+        for op, R, C in (("hmlstm_update", 300, 1028), ("tanh_xy_b", 129, 260)):
+            a2, j2 = small_args(op, R, C, np.float64, seed=8)
+            check_op(op, a2, j2, what="[contiguous rows, first to last] ")
         P.bcast_dual_set_tuning(2, 0)  # plain stores
         check_op("branchy5", args, adj, what="[plain stores] ")
     finally:
-        P.bcast_dual_set_tuning(0, 0)
-        P.bcast_dual_set_tuning(1, 0)
-        P.bcast_dual_set_tuning(2, 1)
+        for key, default in ((0, 0), (1, 0), (2, 3), (6, 1), (8, 1)):
+            P.bcast_dual_set_tuning(key, default)
 
 
 def test_run_to_run_bitwise_determinism():
