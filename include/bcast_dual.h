@@ -169,7 +169,7 @@ int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *
  * and the adjoints, evaluates b on dual numbers again and reduces sum_i adj_i * dY_i/dX_jd into
  * each gradient exactly as bcast_dual_backward does.
  * args[n_args] as in forward; adjoints[n_out] of the unified shape; grads[n_grads = N_d] in their
- * argument's shape (NULL data: skipped).  Available for problems that merge to at most two dims
+ * argument's shape (NULL data: skipped; any other shape: BCAST_ERR_OUTPUT_SHAPE_MISMATCH).  Available for problems that merge to at most two dims
  * with unit inner stride (the tiled kernels) and for every op except the prod_tanh_K family;
  * otherwise BCAST_ERR_UNSUPPORTED.  Workspace rules as for bcast_dual_backward. */
 size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,

@@ -500,6 +500,14 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       const int64_t sdim = v[a0 + j].shape[d];
       if (sdim != U[d] && sdim != 1) return BCAST_ERR_SHAPE_MISMATCH;
     }
+  if (rop) {  // the arguments are known here: each gradient must have its own argument's shape
+    int jd = 0;
+    for (int j = 0; j < NA; ++j) {
+      if ((rop->nondiff >> j) & 1u) continue;
+      if (v[M + M * ND + jd].p && v[M + M * ND + jd].shape != v[a0 + j].shape) return BCAST_ERR_OUTPUT_SHAPE_MISMATCH;
+      ++jd;
+    }
+  }
   int64_t E = 1;
   for (int d = 0; d < BCAST_MAX_DIMS; ++d) E *= U[d];
   plan.info = bcast_plan_info{};

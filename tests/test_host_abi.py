@@ -256,3 +256,87 @@ def test_shared_plane_views_only_where_declared_identical():
     with pytest.raises(P.BcastError) as e:
         P.bcast_dual_forward_plan(op, args, outs, parts)
     assert e.value.status == -10
+
+
+def _rowmajor(ptr, shape):
+    st, acc = [], 1
+    for s in reversed(shape):
+        st.append(acc if s > 1 else 0)
+        acc *= s
+    return B.raw_view(ptr, shape, list(reversed(st)))
+
+
+def _fwd_plan(op_name, dt, args, outs, parts):
+    info = B.PlanInfo()
+    rc = B.lib().bcast_dual_forward_plan(ctypes.c_int32(P.bcast_op_lookup(op_name)), ctypes.c_int(dt),
+                                         ctypes.c_int32(len(args)), B._views(args), ctypes.c_int32(len(outs)),
+                                         B._views(outs), B._views(parts), None, ctypes.byref(info))
+    return rc, info.as_dict()
+
+
+def test_alignment_and_offset_range_pick_the_access_width_and_the_kernel():
+    """The planner (no memory is touched: the views point at addresses that are never
+    dereferenced) narrows the vector width to what every pointer is aligned to, refuses
+    pointers not aligned to the element, and leaves the tiled kernels -- which address with
+    32-bit byte offsets -- for planes of 4 GiB and more."""
+    R, C = 512, 1024
+    slot = 1 << 34  # written views must not overlap: every view gets an address range of its own
+
+    def call(dt, shape, shifts=(0, 0), col=None, stride=None):
+        mk = (lambda k, sh=0: B.raw_view((k + 1) * slot + sh, shape, stride)) if stride else \
+             (lambda k, sh=0: _rowmajor((k + 1) * slot + sh, shape))
+        args = [mk(0, shifts[0]), mk(1, shifts[1]), _rowmajor(9 * slot, col or (shape[0], 1))]
+        return _fwd_plan("tanh_xy_b", dt, args, [mk(2)], [mk(3), mk(4), mk(5)])
+
+    for shift, vec in ((0, 4), (8, 2), (4, 1), (12, 1)):
+        rc, d = call(0, (R, C), (0, shift))
+        assert rc == 0 and d["path"] == 1 and d["vec"] == vec, (shift, d)
+    rc, d = call(1, (R, C), (0, 8))
+    assert rc == 0 and d["vec"] == 1  # fp64: 8-byte alignment allows one element per access
+    assert call(0, (R, C), (2, 0))[0] == -11
+    assert call(1, (R, C), (4, 0))[0] == -11
+    # a row stride that is not a multiple of the vector width narrows it too
+    rc, d = call(0, (R, C), stride=(C + 2, 1))
+    assert rc == 0 and d["path"] == 1 and d["vec"] == 2
+    # 40000 x 30000 fp32 = 4.8 GB per plane: byte offsets no longer fit 32 bits
+    rc, d = call(0, (40000, 30000))
+    assert rc == 0 and d["path"] == 2
+    rc, d = call(0, (32768, 32764))  # 4 294 443 008 bytes < 2^32
+    assert rc == 0 and d["path"] == 1
+
+
+def test_recompute_validation_on_the_host():
+    L = B.lib()
+    R, C = 64, 256
+    base = 1 << 20
+    count = [0]
+
+    def full(shape=(R, C)):  # every view at an address range of its own
+        count[0] += 1
+        return _rowmajor(base + count[0] * (1 << 30), shape)
+
+    op = P.bcast_op_lookup("tanh_xy_b")
+    args = [full(), full(), full((R, 1))]
+    grads = [full(), full(), full((R, 1))]
+
+    def ws(op_id, a, adj, g, dt=0):
+        return L.bcast_dual_backward_recompute_workspace(ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(a)),
+                                                         B._views(a), ctypes.c_int32(len(adj)), B._views(adj),
+                                                         ctypes.c_int32(len(g)), B._views(g))
+
+    def run(op_id, a, adj, g, dt=0):
+        return L.bcast_dual_backward_recompute(ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(a)), B._views(a),
+                                               ctypes.c_int32(len(adj)), B._views(adj), ctypes.c_int32(len(g)),
+                                               B._views(g), None, ctypes.c_size_t(0), None)
+
+    assert ws(op, args, [full()], grads) == 0  # row sums of 256 columns finish inside the main pass
+    assert run(999, args, [full()], grads) == -1
+    assert run(op, args[:2], [full()], grads) == -2
+    assert run(op, args, [full(), full()], grads) == -2
+    assert run(op, args, [full()], grads[:2]) == -2
+    assert run(op, args, [full()], grads, dt=7) == -7
+    assert run(op, args, [full((R, C + 1))], grads) == -6
+    assert run(op, args, [full()], [full(), full(), full((1, C))]) == -6  # b is [R x 1]: its gradient too
+    assert run(P.bcast_op_lookup("prod_tanh_3"), [full(), full(), full()], [full()], [full(), full(), full()]) == -12  # no recompute kernel
+    # a transposed argument has no tiled layout: refused, the cached-plane path still serves it
+    assert run(op, [B.raw_view(base, (R, C), (1, R)), full(), args[2]], [full()], grads) == -12
