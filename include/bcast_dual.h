@@ -199,7 +199,11 @@ const char *bcast_status_string(int status);
  *          once-read operands; 0 = plain
  *   key 8: rows of a backward block that takes several row steps: 1 (default) = every n-th
  *          row step of the problem (the resident blocks sweep one contiguous band of each
- *          plane together), 0 = one contiguous run of rows per block */
+ *          plane together), 0 = one contiguous run of rows per block
+ *   key 9: 1 = XCD-aware tile order in the tiled kernels: the hardware deals consecutive blocks
+ *          round-robin to the 8 XCDs, and block b then serves tile (b % 8) * (blocks / 8) + b / 8,
+ *          i.e. every XCD gets one contiguous eighth of the tiles; 0 (default) = tile b.  Measured
+ *          slower (the eight bands sit a power of two apart in every plane) */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 

@@ -156,7 +156,9 @@ struct BwdGeom {
     const uint32_t nct = (uint32_t)p.n_ct;
     // In reverse mode the grid is walked from the last tile to the first: the planes that
     // the forward kernel wrote last are the ones still held by the memory-side cache.
-    bid = p.reverse ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    bid = blockIdx.x;
+    if (p.xcd_remap) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);
+    if (p.reverse) bid = gridDim.x - 1 - bid;
     rt = bid / nct;
     ct = bid - rt * nct;
     c0 = ((((int64_t)ct) << ltx) + tx) * VEC;

@@ -108,7 +108,9 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   const int ty = threadIdx.x >> ltx;
   const int TY = kBlock >> ltx;
   const uint32_t nct = (uint32_t)p.n_ct;
-  const uint32_t rt = blockIdx.x / nct, ct = blockIdx.x - rt * nct;
+  uint32_t bid = blockIdx.x;
+  if (p.xcd_remap) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);  // the host sets this only for grids of 8 n blocks
+  const uint32_t rt = bid / nct, ct = bid - rt * nct;
   const int64_t c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
   if (c0 >= p.C) return;
   const int64_t r = (int64_t)rt * TY + ty;

@@ -96,8 +96,8 @@ const OpDesc kOps[] = {
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-constexpr int kNumTune = 9;
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1};
+constexpr int kNumTune = 10;
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0};
 
 // ---- small helpers ---------------------------------------------------------------------------
 inline size_t elem_size(int dt) { return dt == BCAST_F32 ? 4 : 8; }
@@ -380,6 +380,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     p.log2_tx = g.log2_tx;
     p.steps = g.steps;
     p.nt_store = g_tune[2] & 1;
+    p.xcd_remap = g_tune[9] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
     p.has_partials = n_planes > 0;
     for (int j = 0; j < N; ++j) {
       const TView tv = tview(c, j, v[j].p);
@@ -627,6 +628,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.nt_store = (g_tune[2] >> 1) & 1;
       p.reverse = g_tune[6];
       p.interleave = g_tune[8];
+      p.xcd_remap = g_tune[9] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
       p.M = M;
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
@@ -962,7 +964,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;

@@ -26,6 +26,7 @@ struct FwdTiledParams {
   int32_t steps;       // row steps per block
   int32_t nt_store;    // non-temporal stores
   int32_t has_partials;
+  int32_t xcd_remap;   // 1: consecutive tiles go to one XCD (block b of a grid of 8 n serves tile (b % 8) n + b / 8)
   int64_t n_ct;        // column tiles; block b serves column tile b % n_ct of row tile b / n_ct
   int64_t row_stride;  // elements between rows of every full-shape view (0 when R == 1)
   uint32_t row_invariant;  // bit j: argument j does not vary along the rows
@@ -80,6 +81,7 @@ struct BwdTiledParams {
   int32_t log2_tx, steps, nt_store, M;
   int32_t n_entries;
   int32_t reverse;  // 1: blocks walk the tiles from the last to the first
+  int32_t xcd_remap;   // as in FwdTiledParams
   int32_t interleave;  // 1: row tile rt takes row steps rt, rt + n_rt, rt + 2 n_rt, ... instead of a contiguous run
   int32_t n_row_slots, n_col_slots, n_all_slots;
   uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS
