@@ -79,6 +79,9 @@ typedef struct {
   int64_t grid_x, grid_y;
   int32_t n_launches; /* kernels this call enqueues */
   int32_t n_second_pass; /* gradients finished by the second reduction pass */
+  int32_t specialized; /* backward: 1 if the main pass is a kernel compiled for this call's mix of
+                          gradient classes, absent and shared planes; 0 = the kernels that read the
+                          gradient table at run time.  forward: 0 */
 } bcast_plan_info;
 
 /* ---- op table --------------------------------------------------------------------

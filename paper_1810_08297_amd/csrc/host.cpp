@@ -752,6 +752,8 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     plan.info.grid_y = g.n_rt;
     plan.info.n_launches = (int)plan.main.size() + (p2_blocks > 0 ? 1 : 0);
     plan.info.n_second_pass = plan.p2.n_jobs;
+    // the class-specialised kernels exist for the widest vector only
+    plan.info.specialized = plan.signature && ((dt == BCAST_F32 && g.vec == 4) || (dt == BCAST_F64 && g.vec == 2));
   } else {
     for (int j = 0; j < ND; ++j) {
       if (!v[g0 + j].p) continue;

@@ -389,7 +389,8 @@ def test_lean_plane_layout_gives_identical_results(dtype):
     gf = P.alloc_backward(adj_dev, full.partials, shapes).run(adj_dev, full.partials)
     gl = P.alloc_backward(adj_dev, lean.partials, shapes).run(adj_dev, lean.partials)
     info = P.bcast_dual_backward_plan(adj_dev, lean.partials, gl.grads)
-    assert info["path"] == 1
+    assert info["path"] == 1 and info["specialized"] == 1  # shared planes loaded once, zero planes skipped
+    assert P.bcast_dual_backward_plan(adj_dev, full.partials, gf.grads)["specialized"] == 1
     torch.cuda.synchronize()
     for a, b in zip(full.outs, lean.outs):
         assert torch.equal(a, b)

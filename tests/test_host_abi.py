@@ -163,6 +163,11 @@ def test_backward_plan_and_workspace():
     assert d["path"] == 1 and d["vec"] == 4 and d["n_second_pass"] == 3 and d["n_launches"] == 2
     n_ct, n_rt = d["grid_x"], d["grid_y"]
     assert n_ct == 8 and d["rows_per_block"] == 256
+    assert d["specialized"] == 0  # every plane at one address: not a layout a class-specialised kernel was built for
+    distinct = [B.raw_view(4096 + (k + 1) * (1 << 30), (R, C), (C, 1)) for k in range(5)]
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(distinct),
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
+    assert rc == 0 and info.specialized == 1  # config 4 runs the kernel compiled for full, full, col-sum, row-sum, all-sum
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
                                          ctypes.c_int32(5), B._views(grads))
     assert ws == 8 * (n_rt * C + R * n_ct + n_rt * n_ct)
@@ -184,6 +189,10 @@ def test_backward_plan_and_workspace():
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
                                     ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
     assert rc == 0 and info.n_launches == 1 and info.n_second_pass == 0
+    parts_distinct = [B.raw_view(4096 + (k + 1) * (1 << 30), (H, Bt), (Bt, 1)) for k in range(20)]
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts_distinct),
+                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
+    assert rc == 0 and info.specialized == 1 and info.rows_per_block == 1  # config 3: class-specialised, no row loop
     assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
                                            ctypes.c_int32(10), B._views(grads)) == 0
     # gradient shape that is neither the adjoint's nor 1
