@@ -543,3 +543,52 @@ def test_unfused_baseline_computes_the_same_function(op):
     for k, (g, w) in enumerate(zip(grads, want)):
         scale = float(np.abs(w).max()) + 1.0
         check_close(g.cpu().numpy().reshape(w.shape), w, f"{op} unfused gradient {didx[k]}", rtol=1e-4, atol=1e-5 * scale)
+
+
+def _random_case(seed, dtype):
+    """One random problem: an op with no control inputs, a random rank <= 4 output shape, every
+    argument independently broadcast along a random subset of dims, and every device view
+    randomly re-laid out (permuted storage order, padded rows, or every second element)."""
+    rng = np.random.default_rng(9000 + seed)
+    op = ["tanh_xy_b", "branchy5", "pair3", "scale_xt", "cos_x"][seed % 5]
+    n_args = oracle.op_info(op)[0]
+    nd = int(rng.integers(1, 5))
+    shape = tuple(int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64])) for _ in range(nd))
+    args = []
+    for j in range(n_args):
+        keep = rng.random(nd) < 0.6
+        if j == 0:
+            keep[:] = True  # one argument spans the whole output, so the unified shape is `shape`
+        s = tuple(n if k else 1 for n, k in zip(shape, keep))
+        a = rng.standard_normal(s).astype(dtype)
+        if op == "pair3" and j == 1:
+            a = (np.abs(a) + 0.5).astype(dtype)
+        if op == "branchy5" and j == 1:
+            a = rng.uniform(0.1, 2, s).astype(dtype)
+        args.append(a)
+    adj = [rng.standard_normal(shape).astype(dtype) for _ in range(oracle.op_info(op)[1])]
+    styles = rng.integers(0, 4, n_args)
+
+    def view(t, k):
+        style = styles[k]
+        if style == 1 and t.dim() >= 2:  # storage order reversed: the first dim is the contiguous one
+            perm = list(range(t.dim()))[::-1]
+            return t.permute(perm).contiguous().permute(perm)
+        if style == 2 and t.dim() >= 1 and t.shape[-1] > 1:  # rows padded by three elements
+            wide = torch.empty(*t.shape[:-1], t.shape[-1] + 3, dtype=t.dtype, device=t.device)
+            wide[..., :t.shape[-1]] = t
+            return wide[..., :t.shape[-1]]
+        if style == 3 and t.dim() >= 1 and t.shape[-1] > 1:  # every second element of a wider buffer
+            wide = torch.empty(*t.shape[:-1], 2 * t.shape[-1], dtype=t.dtype, device=t.device)
+            wide[..., ::2] = t
+            return wide[..., ::2]
+        return t
+
+    return op, args, adj, view, shape, styles
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_random_shapes_broadcast_patterns_and_layouts(dtype):
+    for seed in range(60):
+        op, args, adj, view, shape, styles = _random_case(seed, dtype)
+        check_op(op, args, adj, view=view, what=f"[case {seed}: {op} {shape} layouts {list(styles)}] ")
