@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--unfused-baseline", action="store_true",
                     help="also time the same function as per-primitive library kernels with reverse-mode autograd")
     ap.add_argument("--event-every", type=int, default=4,
-                    help="per-kernel HIP events on every n-th timed step (1 = every step)")
+                    help="per-kernel HIP event pairs on every n-th timed step (1 = every step)")
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from a captured HIP graph and report its rate")
     ap.add_argument("--lean", action="store_true",
@@ -132,27 +132,28 @@ def main():
             for _ in range(3):
                 P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr)
             torch.cuda.synchronize()
-        # HIP events bracket the two launches of every `event_every`-th timed step (each event
-        # costs the stream a microsecond or two, so not every step carries them)
-        ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, a.steps, a.event_every)}
+        # Per-kernel durations: on every `event_every`-th timed step each of the two launches
+        # stamps a pair of HIP events with the kernel's own begin and end (the library arms them
+        # through hipExtLaunchKernelGGL).  Stream markers around the launches would also hold
+        # their own cost and the gap to the next launch, and slow the step they sit in.
+        timers = {k: (P.LaunchTimer(), P.LaunchTimer()) for k in range(0, a.steps, a.event_every)}
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(a.steps):
-            e = ev.get(k)
-            if e is None:
+            t = timers.get(k)
+            if t is None:
                 fwd_call.launch(sptr)
                 bwd_call.launch(sptr)
             else:
-                e[0].record(stream)
+                t[0].arm()
                 fwd_call.launch(sptr)
-                e[1].record(stream)
+                t[1].arm()
                 bwd_call.launch(sptr)
-                e[2].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        ev = list(ev.values())
-        fwd_ms = np.array([e[0].elapsed_time(e[1]) for e in ev])
-        bwd_ms = np.array([e[1].elapsed_time(e[2]) for e in ev])
+        ev = list(timers.values())
+        fwd_ms = np.array([t[0].ms() for t in ev])
+        bwd_ms = np.array([t[1].ms() for t in ev])  # the main backward kernel (a second reduction pass is not in it)
         fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
         both = (fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
         return {
@@ -213,24 +214,23 @@ def main():
                 fcall.launch(sptr)
                 rcall.launch(sptr)
             torch.cuda.synchronize()
-            ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, a.steps, a.event_every)}
+            timers = {k: (P.LaunchTimer(), P.LaunchTimer()) for k in range(0, a.steps, a.event_every)}
             t0 = time.perf_counter()
             for k in range(a.steps):
-                e = ev.get(k)
-                if e is None:
+                t = timers.get(k)
+                if t is None:
                     fcall.launch(sptr)
                     rcall.launch(sptr)
                 else:
-                    e[0].record(stream)
+                    t[0].arm()
                     fcall.launch(sptr)
-                    e[1].record(stream)
+                    t[1].arm()
                     rcall.launch(sptr)
-                    e[2].record(stream)
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
-            ev = list(ev.values())
-            f_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-            r_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+            ev = list(timers.values())
+            f_ms = float(np.mean([t[0].ms() for t in ev]))
+            r_ms = float(np.mean([t[1].ms() for t in ev]))
             n_full_args = sum(1 for x in args if x.size == E)
             n_full_grads = sum(1 for s_ in shapes if int(np.prod(s_)) == E)
             f_bytes, r_bytes = (n_full_args + M) * es * E, (n_full_args + M + n_full_grads) * es * E

@@ -210,6 +210,15 @@ const char *bcast_status_string(int status);
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 
+/* Timing of one launch by the runtime itself.  start_event and stop_event are two hipEvent_t
+ * the caller created (with timing enabled).  The NEXT main-pass kernel this library launches --
+ * the forward kernel, the main backward or recompute kernel (not the second reduction pass), or
+ * the stream probe -- stamps them with that kernel's own begin and end, so that
+ * hipEventElapsedTime(start, stop) is the kernel's duration with no launch gap in it; the pair is
+ * then disarmed.  NULL, NULL disarms without a launch; one NULL is BCAST_ERR_NULL_POINTER.
+ * Process-wide and not thread-safe, like the tuning keys. */
+int bcast_dual_set_launch_events(void *start_event, void *stop_event);
+
 /* Partial-storage layout.  The planes of one call (outputs, the M x N_d partials, the
  * gradients, and ideally the arguments too) are streamed side by side, every wavefront
  * touching the same offset of each.  If the planes start a large power of two apart, those

@@ -49,7 +49,7 @@ _lib = None
 EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
            "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
-           "bcast_dual_get_tuning", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
+           "bcast_dual_get_tuning", "bcast_dual_set_launch_events", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
            "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace")
 
 
@@ -241,6 +241,12 @@ def bcast_dual_get_tuning(key: int) -> int:
     v = ctypes.c_int32()
     _check(lib().bcast_dual_get_tuning(ctypes.c_int32(key), ctypes.byref(v)), "bcast_dual_get_tuning")
     return v.value
+
+
+def bcast_dual_set_launch_events(start_event, stop_event) -> None:
+    """start_event/stop_event: hipEvent_t handles (ints or c_void_p), or None, None to disarm."""
+    _check(lib().bcast_dual_set_launch_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event)),
+           "bcast_dual_set_launch_events")
 
 
 def bcast_dual_stream_probe(in_ptrs, in_strides, out_ptrs, out_strides, n_chunks, stream=None) -> None:

@@ -357,15 +357,15 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
 #define BD_SIG_GO(m, f, r, c, a, ab, sh)                                                                          \
   if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {                  \
     if (dt == BCAST_F32)                                                                                          \
-      hipLaunchKernelGGL((bwd_sig_kernel<float, 4, m, f, r, c, a, (ab), (sh)>), grid, dim3(kBlock), lds, s, p);   \
+      launch((bwd_sig_kernel<float, 4, m, f, r, c, a, (ab), (sh)>), grid, dim3(kBlock), lds, s, p);   \
     else                                                                                                          \
-      hipLaunchKernelGGL((bwd_sig_kernel<double, 2, m, f, r, c, a, (ab), (sh)>), grid, dim3(kBlock), lds, s, p);  \
+      launch((bwd_sig_kernel<double, 2, m, f, r, c, a, (ab), (sh)>), grid, dim3(kBlock), lds, s, p);  \
     return hipGetLastError();                                                                                     \
   }
     BD_SIGNATURES(BD_SIG_GO)
 #undef BD_SIG_GO
   }
-#define BD_GO(T, V, MM) hipLaunchKernelGGL((bwd_tiled_kernel<T, V, MM>), grid, dim3(kBlock), lds, s, p)
+#define BD_GO(T, V, MM) launch((bwd_tiled_kernel<T, V, MM>), grid, dim3(kBlock), lds, s, p)
 #define BD_LAUNCH(T, V)                \
   do {                                 \
     if (p.M == 1) BD_GO(T, V, 1);      \
@@ -396,11 +396,11 @@ hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStrea
 hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s) {
   dim3 grid((unsigned)n_blocks);
   if (dt == BCAST_F32) {
-    if (reduce) hipLaunchKernelGGL((bwd_generic_reduce_kernel<float>), grid, dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL((bwd_generic_full_kernel<float>), grid, dim3(kBlock), 0, s, p);
+    if (reduce) launch((bwd_generic_reduce_kernel<float>), grid, dim3(kBlock), 0, s, p);
+    else launch((bwd_generic_full_kernel<float>), grid, dim3(kBlock), 0, s, p);
   } else {
-    if (reduce) hipLaunchKernelGGL((bwd_generic_reduce_kernel<double>), grid, dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL((bwd_generic_full_kernel<double>), grid, dim3(kBlock), 0, s, p);
+    if (reduce) launch((bwd_generic_reduce_kernel<double>), grid, dim3(kBlock), 0, s, p);
+    else launch((bwd_generic_full_kernel<double>), grid, dim3(kBlock), 0, s, p);
   }
   return hipGetLastError();
 }
@@ -425,8 +425,8 @@ hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_st
 #define BD_PROBE_LDS 0
 #endif
   if (nt_loads)
-    hipLaunchKernelGGL(stream_probe_kernel<true>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
+    launch(stream_probe_kernel<true>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
   else
-    hipLaunchKernelGGL(stream_probe_kernel<false>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
+    launch(stream_probe_kernel<false>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
   return hipGetLastError();
 }

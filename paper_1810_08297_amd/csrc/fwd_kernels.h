@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "kparams.h"
+#include "launch.h"
 #include "ops.h"
 
 namespace bd {
@@ -239,16 +240,16 @@ template <class Op, bool PARTIALS>
 void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
   if (dt == BCAST_F32) {
     if (vec == 4)
-      hipLaunchKernelGGL((fwd_tiled_kernel<Op, float, 4, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, float, 4, PARTIALS>), grid, dim3(kBlock), 0, s, p);
     else if (vec == 2)
-      hipLaunchKernelGGL((fwd_tiled_kernel<Op, float, 2, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, float, 2, PARTIALS>), grid, dim3(kBlock), 0, s, p);
     else
-      hipLaunchKernelGGL((fwd_tiled_kernel<Op, float, 1, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, float, 1, PARTIALS>), grid, dim3(kBlock), 0, s, p);
   } else {
     if (vec > 1)
-      hipLaunchKernelGGL((fwd_tiled_kernel<Op, double, 2, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, double, 2, PARTIALS>), grid, dim3(kBlock), 0, s, p);
     else
-      hipLaunchKernelGGL((fwd_tiled_kernel<Op, double, 1, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, double, 1, PARTIALS>), grid, dim3(kBlock), 0, s, p);
   }
 }
 template <class Op>
@@ -262,9 +263,9 @@ hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid,
 template <class Op>
 hipError_t launch_fwd_generic(int dt, const FwdGenericParams &p, dim3 grid, hipStream_t s) {
   if (dt == BCAST_F32)
-    hipLaunchKernelGGL((fwd_generic_kernel<Op, float>), grid, dim3(kBlock), 0, s, p);
+    launch((fwd_generic_kernel<Op, float>), grid, dim3(kBlock), 0, s, p);
   else
-    hipLaunchKernelGGL((fwd_generic_kernel<Op, double>), grid, dim3(kBlock), 0, s, p);
+    launch((fwd_generic_kernel<Op, double>), grid, dim3(kBlock), 0, s, p);
   return hipGetLastError();
 }
 

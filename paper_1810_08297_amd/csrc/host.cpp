@@ -54,6 +54,10 @@ hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
                            const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, hipStream_t s);
 
+namespace bd {
+hipEvent_t g_launch_events[2] = {nullptr, nullptr};  // see launch.h
+}
+
 namespace {
 
 struct OpDesc {
@@ -972,6 +976,13 @@ int bcast_dual_set_tuning(int32_t key, int32_t value) {
   g_tune[key] = value;
   return BCAST_OK;
 }
+int bcast_dual_set_launch_events(void *start_event, void *stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return BCAST_ERR_NULL_POINTER;
+  bd::g_launch_events[0] = static_cast<hipEvent_t>(start_event);
+  bd::g_launch_events[1] = static_cast<hipEvent_t>(stop_event);
+  return BCAST_OK;
+}
+
 int bcast_dual_get_tuning(int32_t key, int32_t *value) {
   if (key < 0 || key >= kNumTune || value == nullptr) return BCAST_ERR_BAD_ARG_COUNT;
   *value = g_tune[key];

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
 template <class Op>
 hipError_t launch_bwdr_tiled(int dt, int vec, bool fixed_pattern, const BwdTiledParams &p, const RecomputeArgs &ra,
                              dim3 grid, size_t lds, hipStream_t s) {
-#define BD_GO(T, V, PAT) hipLaunchKernelGGL((bwdr_tiled_kernel<Op, T, V, PAT>), grid, dim3(kBlock), lds, s, p, ra)
+#define BD_GO(T, V, PAT) launch((bwdr_tiled_kernel<Op, T, V, PAT>), grid, dim3(kBlock), lds, s, p, ra)
   if (dt == BCAST_F32) {
     if (vec == 4) {
       if (fixed_pattern) BD_GO(float, 4, Op::RECOMPUTE_PATTERN); else BD_GO(float, 4, 0ull);

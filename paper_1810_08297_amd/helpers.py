@@ -121,3 +121,38 @@ def alloc_recompute(op_id: int, args, adjoints, grad_shapes, staggered: bool = T
     nbytes = B.bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
     return BackwardBuffers(grads, ws, slab)
+
+
+class LaunchTimer:
+    """A pair of HIP events for `bcast_dual_set_launch_events`: `arm()` before the call whose
+    main kernel is to be timed, `ms()` after the stream has been synchronised."""
+
+    _hip = None
+
+    def __init__(self):
+        import ctypes
+        if LaunchTimer._hip is None:
+            LaunchTimer._hip = ctypes.CDLL("libamdhip64.so")
+        self._start, self._stop = ctypes.c_void_p(), ctypes.c_void_p()
+        for ev in (self._start, self._stop):
+            if LaunchTimer._hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+
+    def arm(self):
+        from . import binding
+        binding.bcast_dual_set_launch_events(self._start.value, self._stop.value)
+
+    def ms(self) -> float:
+        import ctypes
+        out = ctypes.c_float()
+        rc = LaunchTimer._hip.hipEventElapsedTime(ctypes.byref(out), self._start, self._stop)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(out.value)
+
+    def __del__(self):
+        try:
+            for ev in (self._start, self._stop):
+                LaunchTimer._hip.hipEventDestroy(ev)
+        except Exception:
+            pass

@@ -592,3 +592,41 @@ def test_random_shapes_broadcast_patterns_and_layouts(dtype):
     for seed in range(60):
         op, args, adj, view, shape, styles = _random_case(seed, dtype)
         check_op(op, args, adj, view=view, what=f"[case {seed}: {op} {shape} layouts {list(styles)}] ")
+
+
+def test_launch_events_time_one_kernel_and_disarm():
+    """An armed event pair is stamped by the next main-pass launch only, and that launch
+    computes what an ordinary launch computes."""
+    op, args, adj = inputs.config_inputs(2)
+    dev = [to_dev(a) for a in args]
+    fb = P.alloc_forward(op, dev)
+    fb.run(dev)
+    torch.cuda.synchronize()
+    plain = [t.clone() for t in fb.outs + fb.partials]
+    for t in fb.outs + fb.partials:
+        t.fill_(float("nan"))
+    timer = P.LaunchTimer()
+    timer.arm()
+    fb.run(dev)
+    torch.cuda.synchronize()
+    first = timer.ms()
+    assert 1e-3 < first < 5.0, first  # config 2 forward: some 10 us
+    for a, b in zip(plain, fb.outs + fb.partials):
+        assert torch.equal(a, b)
+    fb.run(dev)  # not armed any more: the events keep the stamps of the first launch
+    torch.cuda.synchronize()
+    assert timer.ms() == first
+    # backward: the main kernel takes the pair, the second reduction pass does not
+    a4, j4 = small_args("branchy5", 300, 1100, np.float32, seed=2)
+    d4, dj = [to_dev(a) for a in a4], [to_dev(a) for a in j4]
+    f4 = P.alloc_forward("branchy5", d4).run(d4)
+    bb = P.alloc_backward(dj, f4.partials, [a.shape for a in a4])
+    bb.run(dj, f4.partials)
+    torch.cuda.synchronize()
+    ref = [g.clone() for g in bb.grads]
+    timer.arm()
+    bb.run(dj, f4.partials)
+    torch.cuda.synchronize()
+    assert 1e-3 < timer.ms() < 5.0
+    for a, b in zip(ref, bb.grads):
+        assert torch.equal(a, b)

@@ -349,3 +349,11 @@ def test_recompute_validation_on_the_host():
     assert run(P.bcast_op_lookup("prod_tanh_3"), [full(), full(), full()], [full()], [full(), full(), full()]) == -12  # no recompute kernel
     # a transposed argument has no tiled layout: refused, the cached-plane path still serves it
     assert run(op, [B.raw_view(base, (R, C), (1, R)), full(), args[2]], [full()], grads) == -12
+
+
+def test_launch_events_argument_check():
+    L = B.lib()
+    assert L.bcast_dual_set_launch_events(None, None) == 0
+    assert L.bcast_dual_set_launch_events(ctypes.c_void_p(4096), None) == -3
+    assert L.bcast_dual_set_launch_events(None, ctypes.c_void_p(4096)) == -3
+    assert L.bcast_dual_set_launch_events(None, None) == 0  # nothing stays armed
