@@ -41,6 +41,20 @@ BD_DEV void load_vec(const T *p, T (&x)[VEC]) {
     for (int k = 0; k < VEC; ++k) x[k] = v[k];
   }
 }
+// A lane's VEC consecutive elements held as ONE value (a register tuple), for code that must
+// keep a conditionally loaded vector whole until all loads have been issued.
+template <class T, int VEC> struct lane_vec { using type = typename vec_of<T, VEC>::type; };
+template <class T> struct lane_vec<T, 1> { using type = T; };
+template <class T, int VEC, bool NT = false>
+BD_DEV typename lane_vec<T, VEC>::type load_lane_vec(const T *p) {
+  using V = typename lane_vec<T, VEC>::type;
+  return NT ? __builtin_nontemporal_load(reinterpret_cast<const V *>(p)) : *reinterpret_cast<const V *>(p);
+}
+template <class T, int VEC>
+BD_DEV T lane_elem(const typename lane_vec<T, VEC>::type &x, int k) {
+  if constexpr (VEC == 1) return x; else return x[k];
+}
+
 template <class T, int VEC>
 BD_DEV void store_vec(T *p, const T (&x)[VEC], bool nt) {
   if constexpr (VEC == 1) {

@@ -603,6 +603,16 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
       for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
       plan.fixed_pattern = g_tune[5] == 0 && pattern == rop->recompute_pattern();
+      // the fixed-pattern kernels take each argument's broadcast form from its gradient's class:
+      // the argument's own strides must say the same (an expanded stride-0 view would not)
+      for (int j = 0, jd = 0; j < NA && plan.fixed_pattern; ++j) {
+        if ((rop->nondiff >> j) & 1u) continue;
+        const TView tv = tview(c, a0 + j, v[a0 + j].p);
+        const bool rows_fixed = cls[jd] == kGradColSum || cls[jd] == kGradAllSum;
+        const bool cols_fixed = cls[jd] == kGradRowSum || cls[jd] == kGradAllSum;
+        if ((tv.sr == 0) != rows_fixed || (tv.sc == 0) != cols_fixed) plan.fixed_pattern = false;
+        ++jd;
+      }
       if (plan.fixed_pattern && !any_rowwise) {
         if (g_tune[1] > 1) plan.fixed_pattern = false;  // an explicit rows-per-block override needs the looping kernel
         else steps = 1;                                  // that kernel has no row loop

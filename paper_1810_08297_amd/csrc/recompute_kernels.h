@@ -18,6 +18,17 @@ constexpr bool pattern_sums_rows(uint64_t pattern) {
   }
   return false;
 }
+// How argument j reaches the lanes when the pattern is fixed at compile time: the class of its
+// gradient says along which dims it varies.  Control inputs have no gradient; their form, and
+// every form under the run-time pattern, is read from the invariance masks.
+enum { kFormRuntime = 0, kFormFull, kFormRowVector, kFormColVector, kFormScalar };
+template <class Op, uint64_t PATTERN>
+constexpr int arg_form(int j) {
+  if (PATTERN == 0 || ((Op::NONDIFF >> j) & 1u)) return kFormRuntime;
+  const int jd = popc(~Op::NONDIFF & ((1u << j) - 1u));
+  const int cls = (int)((PATTERN >> (3 * jd)) & 7u) - 1;
+  return cls == kGradFull ? kFormFull : cls == kGradColSum ? kFormRowVector : cls == kGradRowSum ? kFormColVector : kFormScalar;
+}
 template <class Op, class T, int VEC, uint64_t PATTERN>
 __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams p, const RecomputeArgs ra) {
   constexpr bool LOOP = PATTERN == 0 || pattern_sums_rows(PATTERN);
@@ -37,29 +48,79 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
     const bool valid = g.colvalid && r < p.R;
     const uint32_t off_ld = valid ? off : 0u;       // lanes outside the problem read element 0
     const int64_t r_ld = r < p.R ? r : 0;
-    // arguments: both forms into registers of their own, all loads in flight together
-    T avec[N][VEC], asc[N];
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
-      if (!((ra.col_invariant >> j) & 1u))
-        load_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : off_ld), avec[j]);
-    }
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
+    // Arguments.  Where the pattern fixes an argument's broadcast form the matching load is
+    // issued unconditionally.  Otherwise (control inputs, run-time pattern) both forms go into
+    // registers of their own, the one that does not apply skipped by a uniform branch and left
+    // as zero bits, and the two are OR-ed together afterwards; a lane's vector stays one value
+    // (one register tuple) and passes through an opaque point after the last load, or the
+    // compiler consumes single elements inside the conditional blocks and waits there for the
+    // load it has just issued.
+    using LV = typename lane_vec<T, VEC>::type;
+    LV avec[N];
+    T asc[N];
+    static_for<0, N>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      constexpr int form = arg_form<Op, PATTERN>(j);
+      avec[j] = LV(T(0));
+      if constexpr (form == kFormFull)
+        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], off_ld));
+      else if constexpr (form == kFormRowVector)
+        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], col_off));
+      else if constexpr (form == kFormRuntime) {
+        const bool colinv = (ra.col_invariant >> j) & 1u;
+        if constexpr (PATTERN != 0) {
+          // a control input beside unconditional loads: no branch either -- where the vector
+          // form does not apply the lane reads the first adjoint's vector instead (valid
+          // memory that is loaded anyway) and the result is replaced by zero bits
+          const LV x = load_lane_vec<T, VEC>(at<const T>(colinv ? p.adj[0].p : ra.arg_p[j],
+                                                         (colinv || !((ra.row_invariant >> j) & 1u)) ? off_ld : col_off));
+          avec[j] = colinv ? LV(T(0)) : x;
+        } else if (!colinv) {
+          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : off_ld));
+        }
+      }
+    });
+    static_for<0, N>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      constexpr int form = arg_form<Op, PATTERN>(j);
       asc[j] = T(0);
-      if ((colinv_again >> j) & 1u)
-        asc[j] = static_cast<const T *>(ra.arg_p[j])[((ra.row_invariant >> j) & 1u) ? 0 : r_ld * ra.arg_sr[j]];
-    }
+      if constexpr (form == kFormColVector)
+        asc[j] = static_cast<const T *>(ra.arg_p[j])[r_ld * ra.arg_sr[j]];
+      else if constexpr (form == kFormScalar)
+        asc[j] = static_cast<const T *>(ra.arg_p[j])[0];
+      else if constexpr (form == kFormRuntime) {
+        const bool colinv = (colinv_again >> j) & 1u;
+        if constexpr (PATTERN != 0) {  // element 0 exists for every argument
+          const T x = static_cast<const T *>(ra.arg_p[j])[(colinv && !((ra.row_invariant >> j) & 1u)) ? r_ld * ra.arg_sr[j] : 0];
+          asc[j] = colinv ? x : T(0);
+        } else if (colinv) {
+          asc[j] = static_cast<const T *>(ra.arg_p[j])[((ra.row_invariant >> j) & 1u) ? 0 : r_ld * ra.arg_sr[j]];
+        }
+      }
+    });
     T adj[M][VEC];
 #pragma unroll
     for (int i = 0; i < M; ++i) load_plane<T, VEC, true>(p.adj[i].p, off, valid, adj[i]);
+#pragma unroll
+    for (int j = 0; j < N; ++j)  // the opaque point after the last load
+      if (arg_form<Op, PATTERN>(j) == kFormRuntime) {
+        asm volatile("" : "+v"(asc[j]));
+        asm volatile("" : "+v"(avec[j]));
+      }
     T a[N][VEC];
+    static_for<0, N>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      constexpr int form = arg_form<Op, PATTERN>(j);
 #pragma unroll
-    for (int j = 0; j < N; ++j)
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) a[j][v] = or_bits(avec[j][v], asc[j]);
+      for (int v = 0; v < VEC; ++v) {
+        if constexpr (form == kFormFull || form == kFormRowVector)
+          a[j][v] = lane_elem<T, VEC>(avec[j], v);
+        else if constexpr (form == kFormColVector || form == kFormScalar)
+          a[j][v] = asc[j];
+        else
+          a[j][v] = or_bits(lane_elem<T, VEC>(avec[j], v), asc[j]);
+      }
+    });
     Y y[VEC][M];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) (void)eval_op<Op, T, VEC>(a, v, y[v], std::make_index_sequence<N>{});

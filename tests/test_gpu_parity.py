@@ -475,6 +475,39 @@ def test_recompute_fixed_and_runtime_patterns_agree():
                 check_close(x.cpu().numpy(), y.cpu().numpy(), f"{op} reduced gradient")
 
 
+def test_recompute_with_expanded_and_control_input_forms():
+    """The fixed-pattern recompute kernels take an argument's broadcast form from its
+    gradient's class; an argument that is a stride-0 expansion of a smaller array has a
+    full-shape gradient but not a full-shape layout and must still be read correctly.  Control
+    inputs (no gradient) are read in whatever form they come: row vector, column vector,
+    scalar, full shape."""
+    rng = np.random.default_rng(31)
+    R, C = 96, 516
+    x_row = rng.standard_normal((1, C)).astype(np.float32)
+    y = rng.standard_normal((R, C)).astype(np.float32)
+    b = rng.standard_normal((R, 1)).astype(np.float32)
+    adj = [rng.standard_normal((R, C)).astype(np.float32)]
+    x_full = np.ascontiguousarray(np.broadcast_to(x_row, (R, C)))
+    o_out, o_parts, _ = oracle.forward("tanh_xy_b", [x_full, y, b], threads=8)
+    want = oracle.backward(adj, o_parts, [(R, C), (R, C), (R, 1)], threads=8)
+    dev = [to_dev(x_row).expand(R, C), to_dev(y), to_dev(b)]
+    adj_dev = [to_dev(adj[0])]
+    op_id = P.bcast_op_lookup("tanh_xy_b")
+    rb = P.alloc_recompute(op_id, dev, adj_dev, [(R, C), (R, C), (R, 1)])
+    P.bcast_dual_backward_recompute(op_id, dev, adj_dev, rb.grads, rb.workspace)
+    torch.cuda.synchronize()
+    for k, (g, w) in enumerate(zip(rb.grads, want)):
+        check_close(g.cpu().numpy().reshape(w.shape), w, f"expanded x: recomputed gradient {k}")
+    # HM-LSTM update with the two control inputs in every form
+    op_id = P.bcast_op_lookup("hmlstm_update")
+    forms = {"row": (1, C), "col": (R, 1), "scalar": (1, 1), "full": (R, C)}
+    for zf, zbf in (("row", "row"), ("full", "row"), ("col", "scalar"), ("scalar", "col"), ("row", "full")):
+        args, adj2 = small_args("hmlstm_update", R, C, np.float32, seed=40)
+        args[6] = (rng.random(forms[zf]) < 0.4).astype(np.float32)
+        args[7] = (rng.random(forms[zbf]) < 0.5).astype(np.float32)
+        check_op("hmlstm_update", args, adj2, what=f"[z {zf}, z_below {zbf}] ", recompute="required")
+
+
 @pytest.mark.parametrize("op,R,C", [("hmlstm_update", 64, 16), ("branchy5", 300, 1100), ("tanh_xy_b", 257, 515)])
 def test_graph_replays_match_eager(op, R, C):
     """Forward + backward (+ the fixed-order second pass where one runs) captured into one HIP
