@@ -216,7 +216,8 @@ int bcast_dual_get_tuning(int32_t key, int32_t *value);
  * the stream probe -- stamps them with that kernel's own begin and end, so that
  * hipEventElapsedTime(start, stop) is the kernel's duration with no launch gap in it; the pair is
  * then disarmed.  NULL, NULL disarms without a launch; one NULL is BCAST_ERR_NULL_POINTER.
- * Process-wide and not thread-safe, like the tuning keys. */
+ * Process-wide and not thread-safe, like the tuning keys; not to be armed while the stream is
+ * being captured into a graph. */
 int bcast_dual_set_launch_events(void *start_event, void *stop_event);
 
 /* Partial-storage layout.  The planes of one call (outputs, the M x N_d partials, the
