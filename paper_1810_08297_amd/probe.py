@@ -24,6 +24,8 @@ def main():
     ap.add_argument("--rows", type=int, default=4096)
     ap.add_argument("--cols", type=int, default=1024)
     ap.add_argument("--staggered", type=int, default=1)
+    ap.add_argument("--stagger-bytes", type=int, default=-1,
+                    help="place plane k at k * (plane bytes + this) in one buffer instead of using the library's slab layout")
     ap.add_argument("--mix", action="append", default=[], help="R,W: a mix of R read and W written planes (repeatable)")
     ap.add_argument("--nt-loads", type=int, default=1, help="1 = nontemporal loads (what the kernels use), 0 = plain")
     a = ap.parse_args()
@@ -34,6 +36,11 @@ def main():
     chunks = E // 1024
 
     def planes(n):
+        if a.stagger_bytes >= 0 and n > 0:
+            stride = E * 4 + a.stagger_bytes
+            slab = torch.empty((n * stride + 4096) // 4, dtype=torch.float32, device="cuda").normal_()
+            base = (slab.data_ptr() + 4095) // 4096 * 4096
+            return [base + k * stride for k in range(n)], slab
         t, slab = P.alloc_planes([(a.rows, a.cols)] * n, torch.float32, "cuda", bool(a.staggered))
         for x in t:
             x.normal_()
