@@ -223,9 +223,9 @@ int bcast_dual_set_launch_events(void *start_event, void *stop_event);
 /* Partial-storage layout.  The planes of one call (outputs, the M x N_d partials, the
  * gradients, and ideally the arguments too) are streamed side by side, every wavefront
  * touching the same offset of each.  If the planes start a large power of two apart, those
- * accesses land on the same HBM channel; measured on MI355X, 7 read + 22 written planes of
- * 16 MiB move at 5.2 TB/s back to back and at 6.4 TB/s when each plane is shifted by one
- * more 4 KiB page than its predecessor.  This helper lays n_planes of plane_bytes each out
+ * accesses land on the same HBM channel; measured on MI355X, 29 written planes of 16 MiB move
+ * at 4.0 TB/s when they start 16 MiB apart and at 5.7 TB/s when each plane is shifted by one
+ * more 4 KiB page than its predecessor (7 read + 22 written planes: 4.7 against 5.2 TB/s).  This helper lays n_planes of plane_bytes each out
  * in one slab that way: offsets[k] (bytes, 256-byte aligned) is where plane k starts;
  * returns the slab size in bytes (offsets may be NULL to query only the size).  Using it is
  * optional: any non-overlapping views are accepted by forward and backward. */
