@@ -206,7 +206,11 @@ const char *bcast_status_string(int status);
  *   key 9: 1 = XCD-aware tile order in the tiled kernels: the hardware deals consecutive blocks
  *          round-robin to the 8 XCDs, and block b then serves tile (b % 8) * (blocks / 8) + b / 8,
  *          i.e. every XCD gets one contiguous eighth of the tiles; 0 (default) = tile b.  Measured
- *          slower (the eight bands sit a power of two apart in every plane) */
+ *          slower (the eight bands sit a power of two apart in every plane)
+ *   key 10: 1 (default) = where a kernel was built for it, a backward block takes all 2 or 4
+ *          column chunks of a row, so that row sums of rows up to 4 x 1024 (fp64: 4 x 512)
+ *          elements finish in the main pass; 0 = one chunk per block, wide rows through the
+ *          second pass */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 

@@ -142,6 +142,8 @@ struct BwdGeom {
   int64_t r_step;       // rows from one row step of the block to its next
   bool colvalid, interior;
   uint32_t off0, off_step;
+  int chunk_cols;        // columns one lane arrangement covers: TX * VEC
+  uint32_t chunk_bytes;  // ... in bytes
   A *lds_row, *lds_col, *lds_all;
 
   BD_DEV BwdGeom(const BwdTiledParams &p, unsigned char *smem) {
@@ -161,7 +163,12 @@ struct BwdGeom {
     if (p.reverse) bid = gridDim.x - 1 - bid;
     rt = bid / nct;
     ct = bid - rt * nct;
-    c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
+    // a block covers p.col_chunks consecutive column chunks of TX * VEC columns (1 unless the
+    // kernel was compiled to take several per row step); c0 is the lane's column in the first
+    const int cc = p.col_chunks > 0 ? p.col_chunks : 1;
+    chunk_cols = TX * VEC;
+    chunk_bytes = (uint32_t)chunk_cols * (uint32_t)sizeof(T);
+    c0 = (((int64_t)ct * cc) << ltx) * VEC + (int64_t)tx * VEC;
     colvalid = c0 < p.C;
     // Which rows a block takes.  Contiguous: steps * TY consecutive rows.  Interleaved: its
     // k-th row step is step k * n_rt + rt of the whole problem, so that the blocks resident at
@@ -174,7 +181,7 @@ struct BwdGeom {
       r_first = (int64_t)rt * rows_pb;
       r_step = TY;
     }
-    interior = r_first + (p.steps - 1) * r_step + TY <= p.R && ((((int64_t)ct + 1) << ltx) * VEC) <= p.C;
+    interior = r_first + (p.steps - 1) * r_step + TY <= p.R && (((((int64_t)ct + 1) * cc) << ltx) * VEC) <= p.C;
     // one byte offset per lane and row serves the adjoints, every plane and every full gradient
     off0 = (uint32_t)((r_first + ty) * p.row_stride + c0) * (uint32_t)sizeof(T);
     off_step = (uint32_t)(r_step * p.row_stride) * (uint32_t)sizeof(T);
@@ -216,16 +223,21 @@ BD_DEV void apply_full(const BwdEntry &en, const T (&adj)[MAXM][VEC], const T (&
   for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
   if (!EDGE || valid) store_vec<T, VEC>(at<T>(en.g.p, off), o, nt);
 }
+// row sums in two halves: a lane's own columns first (over as many column chunks as the kernel
+// holds), then once per row step the reduction over the row's lanes and the store
 template <class T, int VEC, int MAXM>
-BD_DEV void apply_rowsum(const BwdTiledParams &p, const BwdGeom<T, VEC> &g, const BwdEntry &en,
-                         const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], int64_t r, int ri) {
+BD_DEV void rowsum_lane(typename acc_traits<T>::type &rs, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC]) {
   using AT = acc_traits<T>;
-  using A = typename AT::type;
-  A rs = AT::zero();
 #pragma unroll
   for (int v = 0; v < VEC; ++v)
 #pragma unroll
     for (int i = 0; i < MAXM; ++i) AT::add_prod(rs, adj[i][v], P[i][v]);
+}
+template <class T, int VEC>
+BD_DEV void rowsum_finish(const BwdTiledParams &p, const BwdGeom<T, VEC> &g, const BwdEntry &en,
+                          typename acc_traits<T>::type rs, int64_t r, int ri) {
+  using AT = acc_traits<T>;
+  using A = typename AT::type;
   if (g.ltx >= 6) {  // the wavefront lies inside one row
     rs = wave_total<T, A>(rs);
     if ((g.tid & 63) == 0 && r < p.R) {
@@ -245,6 +257,13 @@ BD_DEV void apply_rowsum(const BwdTiledParams &p, const BwdGeom<T, VEC> &g, cons
         reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = rs;
     }
   }
+}
+template <class T, int VEC, int MAXM>
+BD_DEV void apply_rowsum(const BwdTiledParams &p, const BwdGeom<T, VEC> &g, const BwdEntry &en,
+                         const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], int64_t r, int ri) {
+  typename acc_traits<T>::type rs = acc_traits<T>::zero();
+  rowsum_lane<T, VEC, MAXM>(rs, adj, P);
+  rowsum_finish<T, VEC>(p, g, en, rs, r, ri);
 }
 template <class T, int VEC, int MAXM>
 BD_DEV void apply_colsum(const BwdGeom<T, VEC> &g, const BwdEntry &en, const T (&adj)[MAXM][VEC],

@@ -15,25 +15,25 @@ namespace bd {
 // is absent (a structurally zero partial the caller chose not to store): it is neither
 // loaded nor multiplied.  SHARE holds 4 bits per gradient e: s + 1 when e's planes are the very
 // views of an earlier gradient s (identical planes stored once), which are then loaded once.
-// Row steps per loop iteration of the looping kernels (all loads of an iteration issued before
-// the first use).  Measured on 8192 x 8192: 1 -> 381 us, 2 -> 389 us, 4 -> 395 us; 1 it is.
-#ifndef BD_BWD_UNROLL
-#define BD_BWD_UNROLL 1
-#endif
+// CU: column chunks of TX * VEC columns a block takes per row step.  Kernels without sums over
+// rows are also built for 2 and 4 chunks where few planes are read: a row of up to 4 x 1024
+// elements then lies inside one block and its row sums finish there, with no partial sums and
+// no second pass (tanh(x*y + b) at 4096 x 4096: one launch instead of two).
 constexpr int share_src(uint64_t share, int e) {
   const int s = (int)((share >> (4 * e)) & 15u);
   return s ? s - 1 : e;
 }
-template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE>
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, int CU>
 __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
   using AT = acc_traits<T>;
   using A = typename AT::type;
   constexpr int NE = NF + NR + NC + NA;
   // Without sums over rows a block takes one row step and needs no loop (the host plans it so):
   // table entries are then read where they are used instead of being held across iterations
-  // (measured with the loop forced on: 2 to 16 rows per block cost 3 to 12 % on the HM-LSTM update).
+  // (measured with the loop forced on: 2 to 16 rows per block cost 3 to 12 % on the HM-LSTM
+  // update; taking two or four row steps per iteration of the looping kernels gained nothing).
   constexpr bool LOOP = NC + NA > 0;
-  constexpr int U = LOOP && (NE + 1) * M <= 8 ? BD_BWD_UNROLL : 1;
+  static_assert(!LOOP || CU == 1, "several column chunks only in the kernels without a row loop");
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
   const bool nt = p.nt_store != 0;
@@ -46,17 +46,18 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
   for (int e = 0; e < (NA > 0 ? NA : 1); ++e) allacc[e] = AT::zero();
 
-  auto rows = [&](auto edge_tag, auto count_tag, int k, uint32_t off) {
+  auto row_step = [&](auto edge_tag, int k, uint32_t off) {
     constexpr bool EDGE = decltype(edge_tag)::value;
-    constexpr int CNT = decltype(count_tag)::value;
-    T adj[CNT][M][VEC], P[CNT][NE][M][VEC];
-    bool valid[CNT];
+    const int ri = k * g.TY + g.ty;
+    const int64_t r = g.row(k);
+    T adj[CU][M][VEC], P[CU][NE][M][VEC];
+    bool valid[CU];
 #pragma unroll
-    for (int u = 0; u < CNT; ++u) {
-      const uint32_t o = off + (uint32_t)u * g.off_step;
-      valid[u] = g.colvalid && g.row(k + u) < p.R;
+    for (int q = 0; q < CU; ++q) {  // every load of the row step is issued before the first use
+      const uint32_t o = off + (uint32_t)q * g.chunk_bytes;
+      valid[q] = r < p.R && g.c0 + (int64_t)q * g.chunk_cols < p.C;
 #pragma unroll
-      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.adj[i].p, o, valid[u], adj[u][i]);
+      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.adj[i].p, o, valid[q], adj[q][i]);
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
@@ -65,46 +66,43 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
             // loaded under the gradient it is shared with
           } else if ((ABSENT >> (e * M + i)) & 1u) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) P[u][e][i][v] = T(0);
+            for (int v = 0; v < VEC; ++v) P[q][e][i][v] = T(0);
           } else {
-            load_plane<T, VEC, EDGE>(p.e[e].P[i].p, o, valid[u], P[u][e][i]);
+            load_plane<T, VEC, EDGE>(p.e[e].P[i].p, o, valid[q], P[q][e][i]);
           }
         }
     }
 #pragma unroll
-    for (int u = 0; u < CNT; ++u) {
-      const uint32_t o = off + (uint32_t)u * g.off_step;
-      const int ri = (k + u) * g.TY + g.ty;
-      const int64_t r = g.row(k + u);
+    for (int q = 0; q < CU; ++q)
 #pragma unroll
-      for (int e = 0; e < NF; ++e) apply_full<T, VEC, M, EDGE>(p.e[e], adj[u], P[u][share_src(SHARE, e)], o, valid[u], nt);
+      for (int e = 0; e < NF; ++e)
+        apply_full<T, VEC, M, EDGE>(p.e[e], adj[q], P[q][share_src(SHARE, e)], off + (uint32_t)q * g.chunk_bytes, valid[q], nt);
 #pragma unroll
-      for (int e = NF; e < NF + NR; ++e) apply_rowsum<T, VEC, M>(p, g, p.e[e], adj[u], P[u][share_src(SHARE, e)], r, ri);
+    for (int e = NF; e < NF + NR; ++e) {
+      A rs = AT::zero();
 #pragma unroll
-      for (int e = 0; e < NC; ++e)
-#pragma unroll
-        for (int v = 0; v < VEC; ++v)
-#pragma unroll
-          for (int i = 0; i < M; ++i) AT::add_prod(colacc[e][v], adj[u][i][v], P[u][share_src(SHARE, NF + NR + e)][i][v]);
-#pragma unroll
-      for (int e = 0; e < NA; ++e)
-#pragma unroll
-        for (int v = 0; v < VEC; ++v)
-#pragma unroll
-          for (int i = 0; i < M; ++i) AT::add_prod(allacc[e], adj[u][i][v], P[u][share_src(SHARE, NF + NR + NC + e)][i][v]);
+      for (int q = 0; q < CU; ++q) rowsum_lane<T, VEC, M>(rs, adj[q], P[q][share_src(SHARE, e)]);
+      rowsum_finish<T, VEC>(p, g, p.e[e], rs, r, ri);
     }
+#pragma unroll
+    for (int e = 0; e < NC; ++e)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v)
+#pragma unroll
+        for (int i = 0; i < M; ++i) AT::add_prod(colacc[e][v], adj[0][i][v], P[0][share_src(SHARE, NF + NR + e)][i][v]);
+#pragma unroll
+    for (int e = 0; e < NA; ++e)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v)
+#pragma unroll
+        for (int i = 0; i < M; ++i) AT::add_prod(allacc[e], adj[0][i][v], P[0][share_src(SHARE, NF + NR + NC + e)][i][v]);
   };
   const int steps = LOOP ? p.steps : 1;
   uint32_t off = g.off0;
-  int k = 0;
-  if (g.interior) {
-    if constexpr (U > 1)
-      for (; k + U <= steps; k += U, off += (uint32_t)U * g.off_step)
-        rows(std::false_type{}, std::integral_constant<int, U>{}, k, off);
-    for (; k < steps; ++k, off += g.off_step) rows(std::false_type{}, std::integral_constant<int, 1>{}, k, off);
-  } else {
-    for (; k < steps; ++k, off += g.off_step) rows(std::true_type{}, std::integral_constant<int, 1>{}, k, off);
-  }
+  if (g.interior)
+    for (int k = 0; k < steps; ++k, off += g.off_step) row_step(std::false_type{}, k, off);
+  else
+    for (int k = 0; k < steps; ++k, off += g.off_step) row_step(std::true_type{}, k, off);
   if constexpr (LOOP) {  // slots were handed out in table order within each class
 #pragma unroll
     for (int e = 0; e < NC; ++e)
@@ -332,35 +330,47 @@ using namespace bd;
 #define BD_HM_LEAN ((1ull << (2 * 2 + 0)) | (1ull << (5 * 2 + 0)) | (1ull << (8 * 2 + 0)))
 // ... and each bias gradient (entries 6..9) reads the planes of its gate (entries 0..3)
 #define BD_HM_SHARE ((1ull << (4 * 6)) | (2ull << (4 * 7)) | (3ull << (4 * 8)) | (4ull << (4 * 9)))
-#define BD_SIGNATURES(X)                                               \
-  X(2, 6, 4, 0, 0, 0ull, 0ull) /* HM-LSTM update, per-row biases */    \
-  X(2, 6, 4, 0, 0, BD_HM_LEAN, BD_HM_SHARE)                            \
-  X(1, 2, 1, 0, 0, 0ull, 0ull) /* tanh(x*y + b) */                     \
-  X(1, 2, 1, 1, 1, 0ull, 0ull) /* branchy5 */                          \
-  X(1, 2, 1, 1, 1, 1ull << 4, 0ull) /* branchy5 without the always-zero plane of t */ \
-  X(1, 4, 0, 0, 0, 0ull, 0ull) /* six-argument cell update */          \
-  X(1, 1, 0, 0, 0, 0ull, 0ull) X(1, 2, 0, 0, 0, 0ull, 0ull) X(1, 3, 0, 0, 0, 0ull, 0ull) X(1, 5, 0, 0, 0, 0ull, 0ull) \
-  X(1, 8, 0, 0, 0, 0ull, 0ull)
+// Last field: 1 = also built for 2 and 4 column chunks per row step.
+#define BD_SIGNATURES(X)                                                  \
+  X(2, 6, 4, 0, 0, 0ull, 0ull, 0) /* HM-LSTM update, per-row biases */    \
+  X(2, 6, 4, 0, 0, BD_HM_LEAN, BD_HM_SHARE, 0)                            \
+  X(1, 2, 1, 0, 0, 0ull, 0ull, 1) /* tanh(x*y + b) */                     \
+  X(1, 2, 1, 1, 1, 0ull, 0ull, 0) /* branchy5 */                          \
+  X(1, 2, 1, 1, 1, 1ull << 4, 0ull, 0) /* branchy5 without the always-zero plane of t */ \
+  X(1, 4, 0, 0, 0, 0ull, 0ull, 0) /* six-argument cell update */          \
+  X(1, 1, 0, 0, 0, 0ull, 0ull, 0) X(1, 2, 0, 0, 0, 0ull, 0ull, 0) X(1, 3, 0, 0, 0, 0ull, 0ull, 0) \
+  X(1, 5, 0, 0, 0, 0ull, 0ull, 0) X(1, 8, 0, 0, 0, 0ull, 0ull, 0)
 
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share) {
-#define BD_SIG_TEST(m, f, r, c, a, ab, sh) \
-  if (M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) return true;
+// chunks: column chunks per row step the caller wants (1, 2 or 4)
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks) {
+#define BD_SIG_TEST(m, f, r, c, a, ab, sh, wide) \
+  if (M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh) && (chunks == 1 || wide)) return true;
   BD_SIGNATURES(BD_SIG_TEST)
 #undef BD_SIG_TEST
   return false;
 }
 
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, bool WIDE>
+static void launch_sig(int chunks, const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
+  if constexpr (WIDE) {
+    if (chunks == 4) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 4>), grid, dim3(kBlock), lds, s, p);
+    if (chunks == 2) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 2>), grid, dim3(kBlock), lds, s, p);
+  }
+  launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 1>), grid, dim3(kBlock), lds, s, p);
+}
+
 hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
+  const int chunks = p.col_chunks > 0 ? p.col_chunks : 1;
   if (signature && widest) {
-#define BD_SIG_GO(m, f, r, c, a, ab, sh)                                                                          \
-  if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {                  \
-    if (dt == BCAST_F32)                                                                                          \
-      launch((bwd_sig_kernel<float, 4, m, f, r, c, a, (ab), (sh)>), grid, dim3(kBlock), lds, s, p);   \
-    else                                                                                                          \
-      launch((bwd_sig_kernel<double, 2, m, f, r, c, a, (ab), (sh)>), grid, dim3(kBlock), lds, s, p);  \
-    return hipGetLastError();                                                                                     \
+#define BD_SIG_GO(m, f, r, c, a, ab, sh, wide)                                                               \
+  if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {             \
+    if (dt == BCAST_F32)                                                                                     \
+      launch_sig<float, 4, m, f, r, c, a, (ab), (sh), (wide) != 0>(chunks, p, grid, lds, s);                 \
+    else                                                                                                     \
+      launch_sig<double, 2, m, f, r, c, a, (ab), (sh), (wide) != 0>(chunks, p, grid, lds, s);                \
+    return hipGetLastError();                                                                                \
   }
     BD_SIGNATURES(BD_SIG_GO)
 #undef BD_SIG_GO

@@ -46,7 +46,7 @@ BD_DECLARE_RECOMPUTE(linear12)
 BD_ARITY_LIST(BD_DECL_ARITY)
 #endif
 
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share);
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks);
 hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
@@ -100,8 +100,8 @@ const OpDesc kOps[] = {
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-constexpr int kNumTune = 10;
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0};
+constexpr int kNumTune = 11;
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1};
 
 // ---- small helpers ---------------------------------------------------------------------------
 inline size_t elem_size(int dt) { return dt == BCAST_F32 ? 4 : 8; }
@@ -589,6 +589,41 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       any_rowwise |= (cls[j] == kGradColSum || cls[j] == kGradAllSum);
       n_rowsum += (cls[j] == kGradRowSum);
     }
+    // the gradient table is ordered by class (full, row-sum, col-sum, all-sum), which is
+    // what the signature kernels expect; within a class the argument order is kept
+    std::vector<int> order;
+    for (int want = kGradFull; want <= kGradAllSum; ++want)
+      for (int j = 0; j < ND; ++j)
+        if (cls[j] == want) {
+          for (int i = 0; i < M; ++i)
+            if (v[M + i * ND + j].p == nullptr && order.size() * M + i < 64) plan.absent |= 1ull << (order.size() * M + i);
+          order.push_back(j);
+          plan.n_cls[want]++;
+        }
+    // entries whose planes are the very views of an earlier entry (a caller that stores
+    // identical planes once): the signature kernels load such planes once
+    for (size_t e = 1; rop == nullptr && e < order.size() && e < 16; ++e)
+      for (size_t src = 0; src < e; ++src) {
+        bool same = true, any = false;
+        for (int i = 0; i < M; ++i) {
+          const PView &a = v[M + i * ND + order[e]], &b = v[M + i * ND + order[src]];
+          same = same && a.p == b.p;
+          any = any || a.p != nullptr;
+        }
+        if (same && any) {
+          plan.share |= (uint64_t)(src + 1) << (4 * e);
+          break;
+        }
+      }
+    // Wide rows with row sums and few planes: a kernel that takes all 2 or 4 column chunks of a
+    // row per block finishes the row sums in the main pass (no partial sums, no second pass).
+    int chunks = 1;
+    if (!rop && !any_rowwise && n_rowsum > 0 && g_tune[1] == 0 && g_tune[5] == 0 && g_tune[10] != 0 &&
+        (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
+        bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
+      chunks = (int)g.n_ct;
+      g.n_ct = 1;
+    }
     const int TY = kBlock >> g.log2_tx;
     // Sums over rows want many rows per block (fewer per-block partials for the second pass,
     // the LDS combine amortised), and measured best is a grid of one block per CU (256 on
@@ -643,6 +678,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.reverse = g_tune[6];
       p.interleave = g_tune[8];
       p.xcd_remap = g_tune[9] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+      p.col_chunks = chunks;
       p.M = M;
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
@@ -670,32 +706,6 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       plan.main_lds.push_back(total);
     };
     reset(cur);
-    // the gradient table is ordered by class (full, row-sum, col-sum, all-sum), which is
-    // what the signature kernels expect; within a class the argument order is kept
-    std::vector<int> order;
-    for (int want = kGradFull; want <= kGradAllSum; ++want)
-      for (int j = 0; j < ND; ++j)
-        if (cls[j] == want) {
-          for (int i = 0; i < M; ++i)
-            if (v[M + i * ND + j].p == nullptr && order.size() * M + i < 64) plan.absent |= 1ull << (order.size() * M + i);
-          order.push_back(j);
-          plan.n_cls[want]++;
-        }
-    // entries whose planes are the very views of an earlier entry (a caller that stores
-    // identical planes once): the signature kernels load such planes once
-    for (size_t e = 1; rop == nullptr && e < order.size() && e < 16; ++e)
-      for (size_t src = 0; src < e; ++src) {
-        bool same = true, any = false;
-        for (int i = 0; i < M; ++i) {
-          const PView &a = v[M + i * ND + order[e]], &b = v[M + i * ND + order[src]];
-          same = same && a.p == b.p;
-          any = any || a.p != nullptr;
-        }
-        if (same && any) {
-          plan.share |= (uint64_t)(src + 1) << (4 * e);
-          break;
-        }
-      }
     for (int j : order) {
       BwdTiledParams trial = cur;
       trial.n_row_slots += (cls[j] == kGradRowSum);
@@ -753,7 +763,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     }
     plan.signature = !rop && plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
-                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share);
+                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
     plan.ws_bytes = ws;
@@ -980,7 +990,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;

@@ -82,6 +82,7 @@ struct BwdTiledParams {
   int32_t n_entries;
   int32_t reverse;  // 1: blocks walk the tiles from the last to the first
   int32_t xcd_remap;   // as in FwdTiledParams
+  int32_t col_chunks;  // column chunks of TX * VEC columns a block covers per row step (0 or 1: one)
   int32_t interleave;  // 1: row tile rt takes row steps rt, rt + n_rt, rt + 2 n_rt, ... instead of a contiguous run
   int32_t n_row_slots, n_col_slots, n_all_slots;
   uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS

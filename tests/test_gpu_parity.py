@@ -44,7 +44,8 @@ def small_args(op, R, C, dtype, seed=0):
 
 OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12"]
 # several tiles, ragged tails, one row / one column / one element, rows wider than a block
-SHAPES = [(1, 1), (1, 7), (5, 1), (3, 5), (64, 16), (7, 33), (129, 260), (2, 4100), (300, 1028), (1, 5000)]
+SHAPES = [(1, 1), (1, 7), (5, 1), (3, 5), (64, 16), (7, 33), (129, 260), (2, 4100), (300, 1028), (1, 5000),
+          (5, 2048), (3, 4096), (7, 3500)]  # rows of two to four (fp64: up to eight) column chunks
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])

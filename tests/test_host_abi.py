@@ -195,6 +195,23 @@ def test_backward_plan_and_workspace():
     assert rc == 0 and info.specialized == 1 and info.rows_per_block == 1  # config 3: class-specialised, no row loop
     assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
                                            ctypes.c_int32(10), B._views(grads)) == 0
+    # config 1: a 4096-wide row is four column chunks; the kernel built for it takes all four in
+    # one block, so the bias gradient's row sums need neither workspace nor second pass
+    adj1 = [fake((4096, 4096))]
+    parts1 = [B.raw_view(4096 + (k + 1) * (1 << 30), (4096, 4096), (4096, 1)) for k in range(3)]
+    grads1 = [fake((4096, 4096)), fake((4096, 4096)), fake((4096, 1))]
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
+                                    ctypes.c_int32(3), B._views(grads1), ctypes.byref(info))
+    assert rc == 0 and info.specialized == 1 and info.n_launches == 1 and info.n_second_pass == 0 and info.grid_x == 1
+    assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
+                                           ctypes.c_int32(3), B._views(grads1)) == 0
+    P.bcast_dual_set_tuning(10, 0)
+    try:
+        rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
+                                        ctypes.c_int32(3), B._views(grads1), ctypes.byref(info))
+        assert rc == 0 and info.n_launches == 2 and info.n_second_pass == 1 and info.grid_x == 4
+    finally:
+        P.bcast_dual_set_tuning(10, 1)
     # gradient shape that is neither the adjoint's nor 1
     bad = grads[:9] + [fake((H, 2))]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
@@ -213,7 +230,7 @@ def test_tuning_keys():
     with pytest.raises(P.BcastError):
         P.bcast_dual_set_tuning(0, 1000)
     with pytest.raises(P.BcastError):
-        P.bcast_dual_set_tuning(11, 0)
+        P.bcast_dual_set_tuning(12, 0)
 
 
 def test_plane_alias_table_agrees_with_the_oracle():
