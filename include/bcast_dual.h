@@ -210,7 +210,12 @@ const char *bcast_status_string(int status);
  *   key 10: 1 (default) = where a kernel was built for it, a backward block takes all 2 or 4
  *          column chunks of a row, so that row sums of rows up to 4 x 1024 (fp64: 4 x 512)
  *          elements finish in the main pass; 0 = one chunk per block, wide rows through the
- *          second pass */
+ *          second pass
+ *   key 11: KiB of (unused) dynamic LDS the forward kernel requests per block when it writes at
+ *          least 2.5 planes for every plane it reads, which limits the blocks resident on a CU
+ *          (160 KiB each): 48 (default) = three, 0 = no limit
+ *   key 12: the same for the main backward and recompute kernels, on top of what they need
+ *          (default 0: measured no gain) */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 

@@ -60,6 +60,11 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_1810_08297_amd.build` "
                               "(or __graft_entry__.build()) first; there is no fallback path")
+        # The library must bind to the HIP runtime that the caller's tensors and streams belong to.
+        # PyTorch ships its own copy: importing it first makes that copy the one already loaded
+        # when the library's dependency on libamdhip64 is resolved (loaded the other way round,
+        # the library gets the system's copy and its launches fail with "no device detected").
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         L.bcast_op_name.restype = ctypes.c_char_p
         L.bcast_status_string.restype = ctypes.c_char_p

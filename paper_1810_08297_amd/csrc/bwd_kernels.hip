@@ -396,6 +396,7 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
 }
 
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s) {
+  (void)hipGetLastError();  // only this launch's error is of interest below
   if (dt == BCAST_F32)
     hipLaunchKernelGGL((bwd_pass2_kernel<float>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
   else

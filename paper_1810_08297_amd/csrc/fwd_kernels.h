@@ -252,18 +252,19 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
 // ---- launch wrappers, one pair per op ------------------------------------------------------
 template <class Op, bool PARTIALS>
 void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
+  const size_t lds = (size_t)p.lds_bytes;
   if (dt == BCAST_F32) {
     if (vec == 4)
-      launch((fwd_tiled_kernel<Op, float, 4, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, float, 4, PARTIALS>), grid, dim3(kBlock), lds, s, p);
     else if (vec == 2)
-      launch((fwd_tiled_kernel<Op, float, 2, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, float, 2, PARTIALS>), grid, dim3(kBlock), lds, s, p);
     else
-      launch((fwd_tiled_kernel<Op, float, 1, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, float, 1, PARTIALS>), grid, dim3(kBlock), lds, s, p);
   } else {
     if (vec > 1)
-      launch((fwd_tiled_kernel<Op, double, 2, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, double, 2, PARTIALS>), grid, dim3(kBlock), lds, s, p);
     else
-      launch((fwd_tiled_kernel<Op, double, 1, PARTIALS>), grid, dim3(kBlock), 0, s, p);
+      launch((fwd_tiled_kernel<Op, double, 1, PARTIALS>), grid, dim3(kBlock), lds, s, p);
   }
 }
 template <class Op>

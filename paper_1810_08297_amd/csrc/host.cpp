@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <array>
+#include <cstdio>
 #include <cstring>
 #include <vector>
 
@@ -100,8 +101,16 @@ const OpDesc kOps[] = {
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-constexpr int kNumTune = 11;
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1};
+constexpr int kNumTune = 13;
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0};
+
+// A failed launch is reported with the runtime's own words on stderr: the status code alone
+// cannot say why.
+int launch_status(hipError_t e) {
+  if (e == hipSuccess) return BCAST_OK;
+  std::fprintf(stderr, "bcast_dual: kernel launch failed: %s\n", hipGetErrorString(e));
+  return BCAST_ERR_LAUNCH_FAILED;
+}
 
 // ---- small helpers ---------------------------------------------------------------------------
 inline size_t elem_size(int dt) { return dt == BCAST_F32 ? 4 : 8; }
@@ -382,7 +391,6 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     if (!tile_rows(s2.R, 1, g)) return BCAST_ERR_LAUNCH_FAILED;  // the forward kernel has no row loop
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
-    p.steps = g.steps;
     p.nt_store = g_tune[2] & 1;
     p.xcd_remap = g_tune[9] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
     p.has_partials = n_planes > 0;
@@ -395,6 +403,16 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     }
     for (int i = 0; i < M; ++i) p.out_p[i] = v[N + i].p;
     for (int k = 0; k < n_planes; ++k) p.part_p[k] = dup[k] ? nullptr : v[N + M + k].p;
+    // A launch that mostly writes (two or more planes read, at least 2.5 written for each) runs fastest
+    // with three blocks, twelve wavefronts, per CU: measured 75 against 81 us on the HM-LSTM
+    // update (7 read, 22 written), 355 against 382 us on 8192 x 8192 branchy5 (2 read, 6 written),
+    // and slower again with two blocks.  Dynamic LDS that the kernel never touches (48 of the
+    // CU's 160 KiB per block) sets that limit.  Balanced and read-heavy launches, the
+    // values-only one among them, want every wavefront they can get and are left alone.
+    int planes_read = 0, planes_written = M;
+    for (int j = 0; j < N; ++j) planes_read += !((p.row_invariant | p.col_invariant) >> j & 1u);
+    for (int k = 0; k < n_planes; ++k) planes_written += p.part_p[k] != nullptr;
+    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? g_tune[11] * 1024 : 0;
     if (want_branch) {
       const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
       p.branch_p = static_cast<uint8_t *>(tv.p);
@@ -703,7 +721,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       cur.lds_col_off = (uint32_t)co;
       cur.lds_all_off = (uint32_t)ao;
       plan.main.push_back(cur);
-      plan.main_lds.push_back(total);
+      plan.main_lds.push_back(std::max<size_t>(total, (size_t)g_tune[12] * 1024));
     };
     reset(cur);
     for (int j : order) {
@@ -874,7 +892,7 @@ int bcast_dual_forward(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcas
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t err = plan.tiled ? kOps[op_id].tiled((int)dt, plan.info.vec, plan.tp, plan.grid, s)
                               : kOps[op_id].generic((int)dt, plan.gp, plan.grid, s);
-  return err == hipSuccess ? BCAST_OK : BCAST_ERR_LAUNCH_FAILED;
+  return launch_status(err);
 }
 
 size_t bcast_dual_backward_workspace(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
@@ -911,18 +929,18 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
     }
     for (size_t k = 0; k < plan.main.size(); ++k) {
       plan.main[k].ws = static_cast<unsigned char *>(workspace);
-      if (bd_bwd_tiled((int)dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
-                       plan.absent, plan.share, plan.main[k], plan.grid, plan.main_lds[k], s) != hipSuccess)
+      if (launch_status(bd_bwd_tiled((int)dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
+                       plan.absent, plan.share, plan.main[k], plan.grid, plan.main_lds[k], s)) != BCAST_OK)
         return BCAST_ERR_LAUNCH_FAILED;
     }
     if (plan.p2_blocks > 0) {
       plan.p2.ws = static_cast<unsigned char *>(workspace);
-      if (bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s) != hipSuccess) return BCAST_ERR_LAUNCH_FAILED;
+      if (launch_status(bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s)) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
     }
   } else {
     for (size_t k = 0; k < plan.generic.size(); ++k)
-      if (bd_bwd_generic((int)dt, plan.generic[k].first, plan.generic[k].second, plan.generic_blocks[k], s) !=
-          hipSuccess)
+      if (launch_status(bd_bwd_generic((int)dt, plan.generic[k].first, plan.generic[k].second, plan.generic_blocks[k], s)) !=
+          BCAST_OK)
         return BCAST_ERR_LAUNCH_FAILED;
   }
   return BCAST_OK;
@@ -960,12 +978,12 @@ int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args,
     if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
   }
   plan.main[0].ws = static_cast<unsigned char *>(workspace);
-  if (kOps[op_id].recompute((int)dt, plan.vec, plan.fixed_pattern, plan.main[0], plan.ra, plan.grid, plan.main_lds[0],
-                            s) != hipSuccess)
+  if (launch_status(kOps[op_id].recompute((int)dt, plan.vec, plan.fixed_pattern, plan.main[0], plan.ra, plan.grid,
+                                          plan.main_lds[0], s)) != BCAST_OK)
     return BCAST_ERR_LAUNCH_FAILED;
   if (plan.p2_blocks > 0) {
     plan.p2.ws = static_cast<unsigned char *>(workspace);
-    if (bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s) != hipSuccess) return BCAST_ERR_LAUNCH_FAILED;
+    if (launch_status(bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s)) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
   }
   return BCAST_OK;
 }
@@ -990,7 +1008,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;
@@ -1036,8 +1054,8 @@ int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *
     if (reinterpret_cast<uintptr_t>(out[k]) % 16 || out_chunk_stride[k] % 4 || out_chunk_stride[k] < 1024) return BCAST_ERR_MISALIGNED;
   }
   if (n_chunks == 0) return BCAST_OK;
-  return bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[7] != 0, g_tune[6] != 0,
-                         static_cast<hipStream_t>(stream)) == hipSuccess ? BCAST_OK : BCAST_ERR_LAUNCH_FAILED;
+  return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[7] != 0,
+                                       g_tune[6] != 0, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -12,6 +12,7 @@ extern hipEvent_t g_launch_events[2];  // armed by bcast_dual_set_launch_events,
 
 template <class K, class... A>
 inline void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, const A &...args) {
+  (void)hipGetLastError();  // the callers read the error state after the launch: an earlier, unrelated call's must not be in it
   if (g_launch_events[0] != nullptr) {
     hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, s, g_launch_events[0], g_launch_events[1], 0u, args...);
     g_launch_events[0] = g_launch_events[1] = nullptr;

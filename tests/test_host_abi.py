@@ -230,7 +230,7 @@ def test_tuning_keys():
     with pytest.raises(P.BcastError):
         P.bcast_dual_set_tuning(0, 1000)
     with pytest.raises(P.BcastError):
-        P.bcast_dual_set_tuning(12, 0)
+        P.bcast_dual_set_tuning(99, 0)
 
 
 def test_plane_alias_table_agrees_with_the_oracle():
