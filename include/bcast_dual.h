@@ -215,7 +215,8 @@ const char *bcast_status_string(int status);
  *          least 2.5 planes for every plane it reads, which limits the blocks resident on a CU
  *          (160 KiB each): 48 (default) = three, 0 = no limit
  *   key 12: the same for the main backward and recompute kernels, on top of what they need
- *          (default 0: measured no gain) */
+ *          (default 0: measured no gain)
+ *   key 13: the same for the stream probe (default 0) */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 
@@ -247,8 +248,8 @@ size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offs
  * plane[k] + b * chunk_stride[k] floats (1024 = a dense plane; larger = planes interleaved in
  * one buffer).  in/out and the stride arrays are HOST arrays (at most 32 entries each) of
  * DEVICE pointers (16-byte aligned) and strides (multiples of 4; output strides >= 1024).
- * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters.  Tuning key 6
- * (chunk order) and key 7 (load policy) apply. */
+ * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters.  Tuning keys 6
+ * (chunk order), 7 (load policy) and 13 (blocks per CU) apply. */
 int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
                             void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream);
 

@@ -417,7 +417,8 @@ hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_
 }
 
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
-                           const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, hipStream_t s) {
+                           const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, size_t lds_bytes,
+                           hipStream_t s) {
   ProbeParams p{};
   p.reverse = reverse;
   p.n_in = n_in;
@@ -432,12 +433,9 @@ hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_st
     p.out_stride[k] = out_stride[k];
   }
   p.sink = n_out > 0 ? p.out[0] : const_cast<float *>(p.in[0]);
-#ifndef BD_PROBE_LDS
-#define BD_PROBE_LDS 0
-#endif
   if (nt_loads)
-    launch(stream_probe_kernel<true>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
+    launch(stream_probe_kernel<true>, dim3((unsigned)n_chunks), dim3(kBlock), lds_bytes, s, p);
   else
-    launch(stream_probe_kernel<false>, dim3((unsigned)n_chunks), dim3(kBlock), BD_PROBE_LDS, s, p);
+    launch(stream_probe_kernel<false>, dim3((unsigned)n_chunks), dim3(kBlock), lds_bytes, s, p);
   return hipGetLastError();
 }

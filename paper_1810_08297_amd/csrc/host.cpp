@@ -53,7 +53,8 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
-                           const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, hipStream_t s);
+                           const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, size_t lds_bytes,
+                           hipStream_t s);
 
 namespace bd {
 hipEvent_t g_launch_events[2] = {nullptr, nullptr};  // see launch.h
@@ -101,8 +102,8 @@ const OpDesc kOps[] = {
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-constexpr int kNumTune = 13;
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0};
+constexpr int kNumTune = 14;
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0};
 
 // A failed launch is reported with the runtime's own words on stderr: the status code alone
 // cannot say why.
@@ -1008,7 +1009,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64, 64};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;
@@ -1055,7 +1056,7 @@ int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *
   }
   if (n_chunks == 0) return BCAST_OK;
   return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[7] != 0,
-                                       g_tune[6] != 0, static_cast<hipStream_t>(stream)));
+                                       g_tune[6] != 0, (size_t)g_tune[13] * 1024, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -27,9 +27,12 @@ def main():
     ap.add_argument("--stagger-bytes", type=int, default=-1,
                     help="place plane k at k * (plane bytes + this) in one buffer instead of using the library's slab layout")
     ap.add_argument("--mix", action="append", default=[], help="R,W: a mix of R read and W written planes (repeatable)")
+    ap.add_argument("--lds-kib", type=int, default=0,
+                    help="KiB of unused dynamic LDS per block: limits the blocks per CU (48 = three); 0 = no limit")
     ap.add_argument("--nt-loads", type=int, default=1, help="1 = nontemporal loads (what the kernels use), 0 = plain")
     a = ap.parse_args()
     P.bcast_dual_set_tuning(7, a.nt_loads)
+    P.bcast_dual_set_tuning(13, a.lds_kib)
     P.bcast_dual_set_tuning(6, 0)
     E = a.rows * a.cols
     assert E % 1024 == 0
@@ -66,7 +69,7 @@ def main():
         return float(np.median([x.elapsed_time(y) for x, y in ts[3:]])) * 1e3
 
     print(f"planes of {a.rows} x {a.cols} fp32 ({E * 4 / 2**20:.0f} MiB), staggered layout: {bool(a.staggered)}, "
-          f"nontemporal loads: {bool(a.nt_loads)}")
+          f"nontemporal loads: {bool(a.nt_loads)}, dynamic LDS per block: {a.lds_kib} KiB")
     print(f"{'mix':>12s} {'back to back':>24s} {'after a 1 GiB copy':>24s}")
     mixes = [tuple(int(x) for x in m.split(",")) for m in a.mix]
     for nin, nout in mixes or ((1, 1), (2, 4), (4, 2), (7, 22), (22, 6), (8, 8), (16, 16), (29, 0), (0, 29)):
