@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a
 # copy kernel of known size); see profiles/hbm_traffic_pmc.md.  Keyed by (workload, kernel).
-MEASURED_TRAFFIC = {("cfg3", "forward"): 487.2e6, ("cfg3", "backward"): 470.4e6,
-                    ("cfg4", "forward"): 2146.4e6, ("cfg4", "backward"): 2154.0e6}
+MEASURED_TRAFFIC = {("cfg3", "forward"): 487.0e6, ("cfg3", "backward"): 470.3e6,
+                    ("cfg4", "forward"): 2146.2e6, ("cfg4", "backward"): 2154.0e6}
 
 
 def build_workload(name, p_index, uniform_run=0):
