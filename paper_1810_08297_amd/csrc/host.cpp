@@ -139,11 +139,19 @@ int check_view(const bcast_tensor &t, size_t esize, bool allow_null, bool writte
   if (t.data == nullptr && !allow_null && !empty) return BCAST_ERR_NULL_POINTER;
   if (reinterpret_cast<uintptr_t>(t.data) % esize != 0) return BCAST_ERR_MISALIGNED;
   out.p = t.data;
+  // Nothing a kernel could address: more than 2^40 elements, or an element 2^44 elements or more
+  // from the view's start (checked in 128 bits, so that absurd extents and strides cannot wrap
+  // the 64-bit index arithmetic further down).
+  unsigned __int128 count = 1, reach = 0;
   for (int d = 0; d < t.ndim; ++d) {
     if (t.shape[d] < 0) return BCAST_ERR_SHAPE_MISMATCH;
     out.shape[d] = t.shape[d];
     out.stride[d] = t.shape[d] == 1 ? 0 : t.stride[d];
     if (out.stride[d] < 0) return BCAST_ERR_BAD_STRIDE;
+    count *= (unsigned __int128)t.shape[d];
+    if (count > ((unsigned __int128)1 << 40)) return BCAST_ERR_SHAPE_MISMATCH;
+    if (t.shape[d] > 1) reach += (unsigned __int128)(t.shape[d] - 1) * (unsigned __int128)out.stride[d];
+    if (reach >= ((unsigned __int128)1 << 44)) return BCAST_ERR_BAD_STRIDE;
   }
   if (written && t.data != nullptr) {
     // every written element must have its own address

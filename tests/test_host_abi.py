@@ -374,3 +374,14 @@ def test_launch_events_argument_check():
     assert L.bcast_dual_set_launch_events(ctypes.c_void_p(4096), None) == -3
     assert L.bcast_dual_set_launch_events(None, ctypes.c_void_p(4096)) == -3
     assert L.bcast_dual_set_launch_events(None, None) == 0  # nothing stays armed
+
+
+def test_absurd_extents_and_strides_are_refused():
+    """Extents and strides that would wrap 64-bit index arithmetic never reach a kernel."""
+    base = 1 << 20
+    huge = B.raw_view(base, (1 << 31, 1 << 31), (0, 0))                # 2^62 virtual copies of one element
+    far = B.raw_view(base + (1 << 34), (4, 4), (1 << 50, 1))            # rows 2^50 elements apart
+    ok = lambda k: _rowmajor(base + (k + 2) * (1 << 34), (4, 4))
+    assert _fwd_plan("cos_x", 0, [huge], [ok(1)], [ok(2)])[0] == -5
+    assert _fwd_plan("cos_x", 0, [far], [ok(1)], [ok(2)])[0] == -10
+    assert _fwd_plan("cos_x", 0, [ok(0)], [ok(1)], [ok(2)])[0] == 0
