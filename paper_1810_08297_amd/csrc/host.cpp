@@ -102,7 +102,12 @@ const OpDesc kOps[] = {
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- tuning overrides ------------------------------------------------------------------------
-constexpr int kNumTune = 14;
+// keys of bcast_dual_set_tuning, in the order the header documents them
+enum TuneKey {
+  kTuneUnused = 0, kTuneBwdRows, kTuneNtStores, kTuneForceGeneric, kTuneMaxVecBytes, kTuneRuntimeTable, kTuneReverse,
+  kTuneProbeNtLoads, kTuneInterleave, kTuneXcdOrder, kTuneColChunks, kTuneFwdLdsKiB, kTuneBwdLdsKiB, kTuneProbeLdsKiB,
+  kNumTune
+};
 int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0};
 
 // A failed launch is reported with the runtime's own words on stderr: the status code alone
@@ -364,7 +369,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
   plan.info.ndim = c.nd;
   for (int d = 0; d < c.nd; ++d) plan.info.shape[d] = c.shape[d];
 
-  bool tiled = (c.nd <= 2) && !g_tune[3];
+  bool tiled = (c.nd <= 2) && !g_tune[kTuneForceGeneric];
   const Shape2 s2 = shape2(c);
   if (tiled && s2.C > 1) {
     for (int j = 0; j < N && tiled; ++j) {
@@ -383,7 +388,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     p.R = s2.R;
     p.C = s2.C;
     // widest vector (16 bytes per lane at most) that every vector-accessed view allows
-    int vw = (int)(std::max<int>(g_tune[4], (int)es) / es);
+    int vw = (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es);
     for (; vw > 1; vw /= 2) {
       bool vec_ok = (s2.C % vw == 0);
       for (size_t t = 0; t < v.size() && vec_ok; ++t) {
@@ -400,8 +405,8 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     if (!tile_rows(s2.R, 1, g)) return BCAST_ERR_LAUNCH_FAILED;  // the forward kernel has no row loop
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
-    p.nt_store = g_tune[2] & 1;
-    p.xcd_remap = g_tune[9] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+    p.nt_store = g_tune[kTuneNtStores] & 1;
+    p.xcd_remap = g_tune[kTuneXcdOrder] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
     p.has_partials = n_planes > 0;
     for (int j = 0; j < N; ++j) {
       const TView tv = tview(c, j, v[j].p);
@@ -421,7 +426,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     int planes_read = 0, planes_written = M;
     for (int j = 0; j < N; ++j) planes_read += !((p.row_invariant | p.col_invariant) >> j & 1u);
     for (int k = 0; k < n_planes; ++k) planes_written += p.part_p[k] != nullptr;
-    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? g_tune[11] * 1024 : 0;
+    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? g_tune[kTuneFwdLdsKiB] * 1024 : 0;
     if (want_branch) {
       const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
       p.branch_p = static_cast<uint8_t *>(tv.p);
@@ -559,7 +564,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
   const size_t g0 = M + M * ND;
 
   const Shape2 s2 = shape2(c);
-  bool tiled = (c.nd <= 2) && !g_tune[3];
+  bool tiled = (c.nd <= 2) && !g_tune[kTuneForceGeneric];
   // class of each gradient in the 2-D picture
   std::vector<int> cls(ND, kGradSkip);
   if (tiled) {
@@ -593,7 +598,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
   plan.tiled = tiled;
   if (rop && !tiled) return BCAST_ERR_UNSUPPORTED;
   if (tiled) {
-    int vw = (int)(std::max<int>(g_tune[4], (int)es) / es);
+    int vw = (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es);
     for (; vw > 1; vw /= 2) {
       bool vec_ok = (s2.C % vw == 0);
       for (size_t t = 0; t < v.size() && vec_ok; ++t) {
@@ -645,7 +650,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // Wide rows with row sums and few planes: a kernel that takes all 2 or 4 column chunks of a
     // row per block finishes the row sums in the main pass (no partial sums, no second pass).
     int chunks = 1;
-    if (!rop && !any_rowwise && n_rowsum > 0 && g_tune[1] == 0 && g_tune[5] == 0 && g_tune[10] != 0 &&
+    if (!rop && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
         (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
         bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
       chunks = (int)g.n_ct;
@@ -659,12 +664,12 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
     const int64_t rows_rowwise = rop != nullptr ? std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512))
                                                 : std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256));
-    int steps = g_tune[1] > 0 ? g_tune[1] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
-    if (!rop && !any_rowwise && g_tune[1] == 0 && g_tune[5] == 0) steps = 1;  // signature kernels without row sums have no row loop
+    int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
+    if (!rop && !any_rowwise && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
       for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
-      plan.fixed_pattern = g_tune[5] == 0 && pattern == rop->recompute_pattern();
+      plan.fixed_pattern = g_tune[kTuneRuntimeTable] == 0 && pattern == rop->recompute_pattern();
       // the fixed-pattern kernels take each argument's broadcast form from its gradient's class:
       // the argument's own strides must say the same (an expanded stride-0 view would not)
       for (int j = 0, jd = 0; j < NA && plan.fixed_pattern; ++j) {
@@ -676,7 +681,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         ++jd;
       }
       if (plan.fixed_pattern && !any_rowwise) {
-        if (g_tune[1] > 1) plan.fixed_pattern = false;  // an explicit rows-per-block override needs the looping kernel
+        if (g_tune[kTuneBwdRows] > 1) plan.fixed_pattern = false;  // an explicit rows-per-block override needs the looping kernel
         else steps = 1;                                  // that kernel has no row loop
       }
     }
@@ -701,10 +706,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.C = s2.C;
       p.log2_tx = g.log2_tx;
       p.steps = g.steps;
-      p.nt_store = (g_tune[2] >> 1) & 1;
-      p.reverse = g_tune[6];
-      p.interleave = g_tune[8];
-      p.xcd_remap = g_tune[9] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+      p.nt_store = (g_tune[kTuneNtStores] >> 1) & 1;
+      p.reverse = g_tune[kTuneReverse];
+      p.interleave = g_tune[kTuneInterleave];
+      p.xcd_remap = g_tune[kTuneXcdOrder] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
       p.col_chunks = chunks;
       p.M = M;
       p.n_ct = g.n_ct;
@@ -730,7 +735,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       cur.lds_col_off = (uint32_t)co;
       cur.lds_all_off = (uint32_t)ao;
       plan.main.push_back(cur);
-      plan.main_lds.push_back(std::max<size_t>(total, (size_t)g_tune[12] * 1024));
+      plan.main_lds.push_back(std::max<size_t>(total, (size_t)g_tune[kTuneBwdLdsKiB] * 1024));
     };
     reset(cur);
     for (int j : order) {
@@ -788,7 +793,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
     }
-    plan.signature = !rop && plan.main.size() == 1 && g_tune[5] == 0 && (int)order.size() * M <= 64 &&
+    plan.signature = !rop && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
@@ -1063,8 +1068,8 @@ int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *
     if (reinterpret_cast<uintptr_t>(out[k]) % 16 || out_chunk_stride[k] % 4 || out_chunk_stride[k] < 1024) return BCAST_ERR_MISALIGNED;
   }
   if (n_chunks == 0) return BCAST_OK;
-  return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[7] != 0,
-                                       g_tune[6] != 0, (size_t)g_tune[13] * 1024, static_cast<hipStream_t>(stream)));
+  return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[kTuneProbeNtLoads] != 0,
+                                       g_tune[kTuneReverse] != 0, (size_t)g_tune[kTuneProbeLdsKiB] * 1024, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"
