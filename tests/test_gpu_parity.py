@@ -225,6 +225,15 @@ def test_second_pass_geometries(dtype):
     want = oracle.backward([big], [Pl] * 3, [(R, 1), (1, C), (1, 1)], threads=8)
     for k in range(3):
         check_close(g.grads[k].cpu().numpy(), want[k], f"cancelling sum {k}")
+    if dtype == np.float64:
+        # 2^70 + 40 ones - 2^70: exact only if partial sums carry more than a double's 53 bits
+        n = 40
+        a = np.ones((1, n + 2)); q = np.ones((1, n + 2))
+        a[0, 0], q[0, 0], a[0, -1], q[0, -1] = 2.0 ** 35, 2.0 ** 35, -(2.0 ** 35), 2.0 ** 35
+        for aa, qq in ((a, q), (a.T.copy(), q.T.copy())):
+            g = gpu_backward([to_dev(aa)], [to_dev(qq)], [(1, 1)])
+            torch.cuda.synchronize()
+            assert float(g.grads[0].cpu()[0, 0]) == float(n)
 
 
 def test_tuned_launch_shapes_agree():

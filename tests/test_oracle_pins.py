@@ -358,6 +358,10 @@ def test_branchy5_branch_constants_and_predicate_precision():
     _, _, b64 = oracle.forward("branchy5", [A32.astype(np.float64), np.ones((1, 3)), np.ones((1, 3)),
                                             s32.astype(np.float64), t32.astype(np.float64)])
     assert b64.tolist() == [[1, 1, 1]]
+    # exact ties in fp64 also take the else branch (strict >); just above the tie takes the other
+    A64 = np.array([[0.5, 0.5 + 2.0 ** -52]], np.float64)
+    _, _, bt = oracle.forward("branchy5", [A64, np.ones((1, 2)), np.ones((1, 2)), np.array([[0.5]]), np.array([[1.0]])])
+    assert bt.tolist() == [[0, 1]]
 
 
 def test_branchy5_closed_form_values():
@@ -420,6 +424,15 @@ def test_sums_are_exact_on_cancelling_data():
     exact = sum(Fraction(float(adj64[i][r, c])) * Fraction(float(P64[i][r, c]))
                 for i in range(2) for r in range(R) for c in range(C))
     assert gs[0, 0] == float(exact)
+    # terms whose partial sums need more bits than any machine format has: 2^70 + 40 ones - 2^70
+    # is 40; a sum that merely runs in a wide format answers 0
+    n = 40
+    a = np.ones((1, n + 2), np.float64)
+    q = np.ones((1, n + 2), np.float64)
+    a[0, 0], q[0, 0] = 2.0 ** 35, 2.0 ** 35
+    a[0, -1], q[0, -1] = -(2.0 ** 35), 2.0 ** 35
+    assert oracle.backward([a], [q], [(1, 1)])[0][0, 0] == float(n)
+    assert oracle.backward([a.T.copy()], [q.T.copy()], [(1, 1)])[0][0, 0] == float(n)
 
 
 def test_plane_order_is_output_major_in_backward():
