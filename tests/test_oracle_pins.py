@@ -154,6 +154,17 @@ def test_prod_tanh_against_tape(n):
                 assert math.isclose(x[j].adj * adj[0][r, c], grads[j][r, c], rel_tol=1e-12, abs_tol=1e-15)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_prod_tanh_tie_takes_the_else_branch(dtype):
+    """g(x) = x if x > 1/2 else -x (Sec. 3.4.1): exactly 1/2 is not greater than 1/2."""
+    x = np.array([[0.5, np.nextafter(dtype(0.5), dtype(1.0)), 0.25]], dtype)
+    outs, parts, br = oracle.forward("prod_tanh", [x])
+    assert br.tolist() == [[0, 1, 0]]
+    want = np.tanh(np.array([-0.5, float(x[0, 1]), -0.25]))
+    np.testing.assert_allclose(outs[0][0], want.astype(dtype), rtol=2e-7 if dtype == np.float32 else 1e-15)
+    assert parts[0][0, 0] < 0 < parts[0][0, 1]  # d tanh(-x)/dx < 0 on the else branch
+
+
 # ----------------------------------------------------------------- finite differences
 @pytest.mark.parametrize("op", OPS)
 def test_partials_match_central_differences(op):
