@@ -673,3 +673,45 @@ def test_launch_events_time_one_kernel_and_disarm():
     assert 1e-3 < timer.ms() < 5.0
     for a, b in zip(ref, bb.grads):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_predicate_ties_and_off_grid_control_values(dtype):
+    """Branch decisions at their edges, bit-exact against the oracle: exact ties of strict
+    comparisons (taken in the working precision), sums that round onto the threshold, control
+    inputs that are neither 0 nor 1 (0.5, 2, -0.0, NaN fall to UPDATE unless z == 1)."""
+    eps = np.finfo(dtype).eps
+    # branchy5: A + s against t, around a tie and around a sum that rounds back onto A
+    A = np.array([[0.5, 0.5, 0.5 + eps, 1.0, 1.0, 1.0 + 2 * eps, -3.0, 7.0]], dtype)
+    s = np.array([[0.5]], dtype)
+    t = np.array([[1.0]], dtype)
+    B = np.full_like(A, 1.5)
+    r = np.full_like(A, -0.75)
+    check_op("branchy5", [A, B, r, s, t], [np.ones_like(A)], what="[tie] ")
+    tiny = np.array([[eps / 4]], dtype)  # 1 + eps/4 rounds to 1: not greater than t = 1
+    fb, _ = check_op("branchy5", [A, B, r, tiny, t], [np.ones_like(A)], what="[rounded sum] ")
+    assert fb.branch.cpu().numpy().tolist()[0][3:6] == [0, 0, 1]
+    # prod_tanh: x exactly 1/2 takes the else branch
+    x = np.array([[0.5, np.nextafter(dtype(0.5), dtype(1)), np.nextafter(dtype(0.5), dtype(0)), 0.25, 0.75, -0.5]], dtype)
+    xs = [x, x[:, ::-1].copy()]
+    o_out, o_parts, o_br = oracle.forward("prod_tanh", xs)  # the library's name for arity 2 is prod_tanh_2
+    fb = gpu_forward("prod_tanh_2", [to_dev(a) for a in xs])
+    torch.cuda.synchronize()
+    assert np.array_equal(fb.branch.cpu().numpy(), o_br) and o_br.tolist() == [[0, 2, 0, 0, 2, 0]]  # 1/2 itself counts as "not above"
+    check_close(fb.outs[0].cpu().numpy(), o_out[0], "[g tie] value")
+    for k in range(2):
+        check_close(fb.partials[k].cpu().numpy(), o_parts[k], f"[g tie] partial {k}")
+    # cell updates: every pair of control values from a set with off-grid members
+    vals = np.array([0.0, 1.0, 0.5, 2.0, -0.0, np.nan, -1.0], dtype)
+    z, zb = [m.reshape(1, -1).astype(dtype) for m in np.meshgrid(vals, vals, indexing="ij")]
+    n = z.shape[1]
+    rng = np.random.default_rng(12)
+    full = lambda: rng.standard_normal((3, n)).astype(dtype)
+    col = lambda: rng.standard_normal((3, 1)).astype(dtype)
+    fb, _ = check_op("hmlstm_update", [full() for _ in range(6)] + [z, zb] + [col() for _ in range(4)], [full(), full()],
+                     what="[control values] ")
+    br = fb.branch.cpu().numpy()[0].reshape(len(vals), len(vals))
+    assert (br[1] == 2).all()                     # z == 1: FLUSH whatever z_below is
+    assert br[0, 0] == 1 and br[0, 4] == 1 and br[4, 0] == 1 and br[4, 4] == 1  # 0 and -0 are both zero: COPY
+    assert br[0, 1] == 0 and br[2, 0] == 0 and br[5, 0] == 0 and br[0, 5] == 0 and br[3, 3] == 0  # the rest: UPDATE
+    check_op("update_c", [full() for _ in range(4)] + [z, zb], [full()], what="[control values] ")
