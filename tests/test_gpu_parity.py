@@ -715,3 +715,35 @@ def test_predicate_ties_and_off_grid_control_values(dtype):
     assert br[0, 0] == 1 and br[0, 4] == 1 and br[4, 0] == 1 and br[4, 4] == 1  # 0 and -0 are both zero: COPY
     assert br[0, 1] == 0 and br[2, 0] == 0 and br[5, 0] == 0 and br[0, 5] == 0 and br[3, 3] == 0  # the rest: UPDATE
     check_op("update_c", [full() for _ in range(4)] + [z, zb], [full()], what="[control values] ")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_saturating_and_tiny_inputs(dtype):
+    """Gate pre-activations far into saturation (|x| up to 1e4), exact zeros, signed zeros and
+    values near the underflow threshold: the stable forms of sigma, tanh and their derivatives
+    must agree with the oracle's direct evaluation in long double."""
+    tiny = np.finfo(dtype).tiny
+    vals = np.array([-1e4, -100.0, -50.0, -20.0, -5.0, -1e-3, -tiny, -0.0, 0.0, tiny, 1e-3, 5.0, 20.0, 50.0, 100.0, 1e4], dtype)
+    n = len(vals)
+    rng = np.random.default_rng(77)
+    pick = lambda: vals[rng.integers(0, n, (24, 4 * n))].astype(dtype)
+    z = (rng.random((1, 4 * n)) < 0.4).astype(dtype)
+    zb = (rng.random((1, 4 * n)) < 0.5).astype(dtype)
+    small = lambda shape: (rng.standard_normal(shape) * 0.1).astype(dtype)
+    adj = [rng.standard_normal((24, 4 * n)).astype(dtype) for _ in range(2)]
+    c = rng.standard_normal((24, 4 * n)).astype(dtype)
+    h = rng.standard_normal((24, 4 * n)).astype(dtype)
+    check_op("hmlstm_update", [pick(), pick(), pick(), pick(), c, h, z, zb] + [small((24, 1)) for _ in range(4)], adj,
+             what="[saturated gates] ")
+    check_op("update_c", [c, pick(), pick(), pick(), z, zb], adj[:1], what="[saturated gates] ")
+    # tanh(x*y + b): products from 1e-6 to 1e8
+    x = pick()
+    y = vals[rng.integers(0, n, (24, 1))].astype(dtype) * dtype(1e-2)
+    check_op("tanh_xy_b", [x, np.broadcast_to(y, x.shape).copy(), small((24, 1))], adj[:1], what="[saturated tanh] ")
+    # branchy5: exp(-A) from e^-80 to e^80, log1p(A^2) from A^2 = tiny to 1e8 (all finite in fp32)
+    A = np.clip(pick(), -80, 80).astype(dtype)
+    A[:, ::7] = vals[rng.integers(0, n, (24, A[:, ::7].shape[1]))]   # some |A| beyond the clip ...
+    A[:, ::7] = np.abs(A[:, ::7])                                      # ... but only where exp(-A) underflows
+    Bv = rng.uniform(0.1, 2, A.shape).astype(dtype)
+    check_op("branchy5", [A, Bv, small((1, A.shape[1])), small((A.shape[0], 1)), np.zeros((1, 1), dtype)], adj[:1],
+             what="[wide A] ")
