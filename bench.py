@@ -41,6 +41,11 @@ def build_workload(name, p_index, uniform_run=0):
                 2: "HM-LSTM update hidden=1024 batch=256",
                 3: f"HM-LSTM update hidden=4096 batch=1024, per-element z ~ Bernoulli({inputs.P_SWEEP[p_index]})",
                 4: "branchy5 8192x8192"}[idx]
+    elif base.startswith("hmlstm_"):  # hmlstm_<hidden>x<batch>: the HM-LSTM update at another size (beyond the five configs)
+        H, Bt = (int(x) for x in base[len("hmlstm_"):].split("x"))
+        args, adj = inputs.hmlstm_inputs(H, Bt, seed=inputs.BASE_SEED + 300 + H + Bt, dtype=dtype, z_per_element=True,
+                                         p=inputs.P_SWEEP[p_index])
+        op, desc = "hmlstm_update", f"HM-LSTM update hidden={H} batch={Bt}, per-element z ~ Bernoulli({inputs.P_SWEEP[p_index]})"
     elif base.startswith("paper_n"):
         n = int(base[len("paper_n"):])
         args, adj = inputs.update_c_inputs(n, seed=inputs.BASE_SEED + 100 + n, dtype=dtype, uniform_run=uniform_run)
@@ -64,7 +69,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--workload", default="cfg3",
+                    help="cfg0..cfg4, cfg4_f64, paper_n<N>, hmlstm_<hidden>x<batch>")
     ap.add_argument("--p-index", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=16)
