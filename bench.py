@@ -46,6 +46,11 @@ def build_workload(name, p_index, uniform_run=0):
         args, adj = inputs.hmlstm_inputs(H, Bt, seed=inputs.BASE_SEED + 300 + H + Bt, dtype=dtype, z_per_element=True,
                                          p=inputs.P_SWEEP[p_index])
         op, desc = "hmlstm_update", f"HM-LSTM update hidden={H} batch={Bt}, per-element z ~ Bernoulli({inputs.P_SWEEP[p_index]})"
+    elif base.startswith("linear12_"):  # the HM-LSTM update's argument list and traffic with trivial arithmetic
+        H, Bt = (int(x) for x in base[len("linear12_"):].split("x"))
+        args, adj = inputs.hmlstm_inputs(H, Bt, seed=inputs.BASE_SEED + 300 + H + Bt, dtype=dtype, z_per_element=True,
+                                         p=inputs.P_SWEEP[p_index])
+        op, desc = "linear12", f"linear12 (HM-LSTM traffic, no transcendental) hidden={H} batch={Bt}"
     elif base.startswith("paper_n"):
         n = int(base[len("paper_n"):])
         args, adj = inputs.update_c_inputs(n, seed=inputs.BASE_SEED + 100 + n, dtype=dtype, uniform_run=uniform_run)
