@@ -355,6 +355,16 @@ def main():
         cpu = {"value": round(reps * take * cols / (c1 - c0), 1), "unit": "elements/s", "cores": threads,
                "kind": "oracle", "sample": f"first {take} of {rows} rows ({take * cols} elements), forward + "
                f"backward {reps} times in {c1 - c0:.2f} s ({threads * (c1 - c0):.0f} core-seconds)"}
+        # the same oracle on one core, on a smaller sample (at most 2^19 elements, once)
+        take1 = max(1, min(take, (1 << 19) // max(1, cols)))
+        sub1 = [x[:take1] if x.shape[0] == rows else x for x in args]
+        shapes1 = [s if s[0] != rows else (take1,) + tuple(s[1:]) for s in shapes]
+        s0 = time.perf_counter()
+        o_out, o_parts, _ = oracle.forward(op, sub1, threads=1)
+        oracle.backward([x[:take1] for x in adj], o_parts, shapes1, threads=1)
+        s1 = time.perf_counter()
+        cpu["single_thread"] = {"value": round(take1 * cols / (s1 - s0), 1), "unit": "elements/s",
+                                "sample": f"first {take1} rows ({take1 * cols} elements), once, {s1 - s0:.2f} s"}
 
     line = {
         "metric": "fused fwd+bwd elements/s, HM-LSTM update" if op == "hmlstm_update"
