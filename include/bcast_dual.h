@@ -181,6 +181,11 @@ size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, in
 int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                   int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
                                   const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream);
+/* How that call would be mapped (no launch); `specialized` = 1 when the kernel compiled for the op's
+ * usual broadcast pattern runs (every argument's form fixed at compile time). */
+int bcast_dual_backward_recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                                       int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
+                                       const bcast_tensor *grads, bcast_plan_info *info);
 
 /* ---- misc ---------------------------------------------------------------------- */
 const char *bcast_status_string(int status);

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     bcast_dual_forward, bcast_dual_forward_plan, bcast_dual_backward_workspace,
     bcast_dual_backward, bcast_dual_backward_plan, bcast_dual_set_tuning,
     bcast_dual_get_tuning, bcast_dual_stream_probe, bcast_dual_slab_layout, status_string, as_view, raw_view, PreparedForward, PreparedBackward, PreparedRecompute,
-    bcast_dual_backward_recompute, bcast_dual_backward_recompute_workspace, bcast_dual_set_launch_events,
+    bcast_dual_backward_recompute, bcast_dual_backward_recompute_workspace, bcast_dual_backward_recompute_plan, bcast_dual_set_launch_events,
 )
 from .helpers import ForwardBuffers, BackwardBuffers, alloc_forward, alloc_backward, alloc_planes, to_slab, alloc_recompute, LaunchTimer  # noqa: F401

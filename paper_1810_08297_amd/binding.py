@@ -50,7 +50,8 @@ EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info"
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
            "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
            "bcast_dual_get_tuning", "bcast_dual_set_launch_events", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
-           "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace")
+           "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace",
+           "bcast_dual_backward_recompute_plan")
 
 
 def lib():
@@ -313,6 +314,16 @@ def bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads) -> int
     return int(lib().bcast_dual_backward_recompute_workspace(
         ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
         ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads)))
+
+
+def bcast_dual_backward_recompute_plan(op_id, args, adjoints, grads) -> dict:
+    dt = _dtype_code(adjoints[0])
+    info = PlanInfo()
+    _check(lib().bcast_dual_backward_recompute_plan(
+        ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
+        ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads),
+        ctypes.byref(info)), "bcast_dual_backward_recompute_plan")
+    return info.as_dict()
 
 
 def bcast_dual_backward_recompute(op_id, args, adjoints, grads, workspace=None, stream=None) -> None:

@@ -978,6 +978,19 @@ size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, in
   return plan.ws_bytes;
 }
 
+int bcast_dual_backward_recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
+                                       int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
+                                       const bcast_tensor *grads, bcast_plan_info *info) {
+  if (info == nullptr) return BCAST_ERR_NULL_POINTER;
+  BwdPlan plan;
+  const int rc = recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, plan);
+  if (rc == BCAST_OK) {
+    *info = plan.info;
+    info->specialized = plan.info.path == 1 && plan.fixed_pattern ? 1 : 0;
+  }
+  return rc;
+}
+
 int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                   int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
                                   const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream) {

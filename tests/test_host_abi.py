@@ -385,3 +385,38 @@ def test_absurd_extents_and_strides_are_refused():
     assert _fwd_plan("cos_x", 0, [huge], [ok(1)], [ok(2)])[0] == -5
     assert _fwd_plan("cos_x", 0, [far], [ok(1)], [ok(2)])[0] == -10
     assert _fwd_plan("cos_x", 0, [ok(0)], [ok(1)], [ok(2)])[0] == 0
+
+
+def test_recompute_plan_picks_the_fixed_pattern_kernels_at_the_benchmark_shapes():
+    L = B.lib()
+    slot = [0]
+
+    def view(shape):
+        slot[0] += 1
+        return _rowmajor(slot[0] * (1 << 34), shape)
+
+    def plan(op_name, shapes, out_shape, n_out, dt=0):
+        op = P.bcast_op_lookup(op_name)
+        args = [view(s) for s in shapes]
+        nondiff = P.bcast_op_info(op)[2]
+        grads = [view(s) for j, s in enumerate(shapes) if not (nondiff >> j) & 1]
+        adj = [view(out_shape) for _ in range(n_out)]
+        info = B.PlanInfo()
+        rc = L.bcast_dual_backward_recompute_plan(ctypes.c_int32(op), ctypes.c_int(dt), ctypes.c_int32(len(args)), B._views(args),
+                                                  ctypes.c_int32(n_out), B._views(adj), ctypes.c_int32(len(grads)),
+                                                  B._views(grads), ctypes.byref(info))
+        return rc, info.as_dict()
+
+    H, Bt = 4096, 1024
+    full, row, col = (H, Bt), (1, Bt), (H, 1)
+    rc, d = plan("hmlstm_update", [full] * 6 + [full, row] + [col] * 4, full, 2)           # config 3
+    assert rc == 0 and d["path"] == 1 and d["specialized"] == 1 and d["n_second_pass"] == 0 and d["rows_per_block"] == 1
+    rc, d = plan("hmlstm_update", [full] * 6 + [row, row] + [col] * 4, full, 2, dt=1)     # configs 0 / 2 shapes, fp64
+    assert rc == 0 and d["specialized"] == 1
+    rc, d = plan("hmlstm_update", [full] * 6 + [row, row] + [col] * 3 + [full], full, 2)  # a full-shape "bias": another pattern
+    assert rc == 0 and d["path"] == 1 and d["specialized"] == 0
+    n = 8192
+    rc, d = plan("branchy5", [(n, n), (n, n), (1, n), (n, 1), (1, 1)], (n, n), 1)         # config 4
+    assert rc == 0 and d["specialized"] == 1 and d["n_second_pass"] == 3 and d["rows_per_block"] == 128
+    rc, d = plan("tanh_xy_b", [(4096, 4096), (4096, 4096), (4096, 1)], (4096, 4096), 1)    # config 1
+    assert rc == 0 and d["specialized"] == 1
