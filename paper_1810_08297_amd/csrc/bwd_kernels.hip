@@ -115,10 +115,16 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 }
 
 // Generic kernel: any number of outputs up to BCAST_MAX_OUTS (MCT = 0) and any mix of
-// gradient classes and absent planes, one gradient at a time.
+// gradient classes and absent planes, read from the table at run time.  Gradients are taken four
+// at a time: the planes of all four are loaded before the first is used, without branches (an
+// absent plane, or a slot past the end of the table, reads the first adjoint's vector instead --
+// memory that is valid and already on its way -- and is then replaced by zeros), so that a
+// wavefront keeps up to 4 M loads in flight instead of M.
 template <class T, int VEC, int MCT>
 __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams p) {
   constexpr int MAXM = MCT > 0 ? MCT : BCAST_MAX_OUTS;
+  constexpr int CH = 4;
+  using LV = typename lane_vec<T, VEC>::type;
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
   const int M = MCT > 0 ? MCT : p.M;
@@ -128,30 +134,58 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
+    const uint32_t off_ld = valid ? off : 0u;  // lanes outside the problem read element 0 and get zeros
+    LV adj_raw[MAXM];  // unpacked only after the first four gradients' loads are on their way
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(p.adj[i < M ? i : 0].p, off_ld));
     T adj[MAXM][VEC];
+    LV raw[CH][MAXM];
+    bool have[CH][MAXM];
+    auto issue = [&](int e0) {
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) {
+      for (int q = 0; q < CH; ++q) {
+        const int e = e0 + q < p.n_entries ? e0 + q : e0;  // a valid table row in any case
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) adj[i][v] = T(0);
-      if (i < M) load_plane<T, VEC, true>(p.adj[i].p, off, valid, adj[i]);
-    }
-    for (int e = 0; e < p.n_entries; ++e) {
-      const BwdEntry &en = p.e[e];
-      T P[MAXM][VEC];
-#pragma unroll
-      for (int i = 0; i < MAXM; ++i) {
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) P[i][v] = T(0);
-        if (i < M && en.P[i].p != nullptr) load_plane<T, VEC, true>(en.P[i].p, off, valid, P[i]);
+        for (int i = 0; i < MAXM; ++i) {
+          const void *plane = i < M ? p.e[e].P[i].p : nullptr;
+          have[q][i] = valid && e0 + q < p.n_entries && plane != nullptr;
+          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(plane != nullptr ? plane : p.adj[0].p, off_ld));
+        }
       }
-      if (en.cls == kGradFull)
-        apply_full<T, VEC, MAXM, true>(en, adj, P, off, valid, nt);
-      else if (en.cls == kGradRowSum)
-        apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
-      else if (en.cls == kGradColSum)
-        apply_colsum<T, VEC, MAXM>(g, en, adj, P);
-      else if (en.cls == kGradAllSum)
-        apply_allsum<T, VEC, MAXM>(g, en, adj, P);
+    };
+    auto apply = [&](int e0) {
+#pragma unroll
+      for (int q = 0; q < CH; ++q) {
+        if (e0 + q >= p.n_entries) break;
+        const BwdEntry &en = p.e[e0 + q];
+        T P[MAXM][VEC];
+#pragma unroll
+        for (int i = 0; i < MAXM; ++i)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) P[i][v] = have[q][i] ? lane_elem<T, VEC>(raw[q][i], v) : T(0);
+        if (en.cls == kGradFull)
+          apply_full<T, VEC, MAXM, true>(en, adj, P, off, valid, nt);
+        else if (en.cls == kGradRowSum)
+          apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
+        else if (en.cls == kGradColSum)
+          apply_colsum<T, VEC, MAXM>(g, en, adj, P);
+        else if (en.cls == kGradAllSum)
+          apply_allsum<T, VEC, MAXM>(g, en, adj, P);
+      }
+    };
+    issue(0);
+    // the adjoints are unpacked behind this point, which no memory access may cross: the
+    // first four gradients' loads are issued before anything waits for the adjoints
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i) asm volatile("" : "+v"(adj_raw[i]) : : "memory");
+#pragma unroll
+    for (int i = 0; i < MAXM; ++i)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) adj[i][v] = (valid && i < M) ? lane_elem<T, VEC>(adj_raw[i], v) : T(0);
+    apply(0);
+    for (int e0 = CH; e0 < p.n_entries; e0 += CH) {
+      issue(e0);
+      apply(e0);
     }
   }
   bwd_finalize<T, VEC>(p, g);

@@ -662,8 +662,13 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // MI355X): 8192 x 8192 runs 381 us at 256 rows per block, 399 us at 128, 434 us at 32.
     // The recompute kernels carry the op's arithmetic and want two blocks per CU to hide it
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
-    const int64_t rows_rowwise = rop != nullptr ? std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512))
-                                                : std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256));
+    // So do the kernels that read the gradient table at run time (8192 x 8192 branchy5 forced onto
+    // them: 419 us at 128 rows per block, 631 us at 256).
+    const bool class_kernel = !rop && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
+                              bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
+                                                   plan.share, 1);
+    const int64_t rows_rowwise = class_kernel ? std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256))
+                                              : std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
     int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
     if (!rop && !any_rowwise && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {

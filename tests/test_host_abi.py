@@ -162,12 +162,13 @@ def test_backward_plan_and_workspace():
     d = info.as_dict()
     assert d["path"] == 1 and d["vec"] == 4 and d["n_second_pass"] == 3 and d["n_launches"] == 2
     n_ct, n_rt = d["grid_x"], d["grid_y"]
-    assert n_ct == 8 and d["rows_per_block"] == 256
+    assert n_ct == 8 and d["rows_per_block"] == 128  # two blocks per CU for the kernels that read the table at run time
     assert d["specialized"] == 0  # every plane at one address: not a layout a class-specialised kernel was built for
     distinct = [B.raw_view(4096 + (k + 1) * (1 << 30), (R, C), (C, 1)) for k in range(5)]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(distinct),
                                     ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
     assert rc == 0 and info.specialized == 1  # config 4 runs the kernel compiled for full, full, col-sum, row-sum, all-sum
+    assert info.rows_per_block == 256 and info.grid_y == 32  # ... as one block per CU
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
                                          ctypes.c_int32(5), B._views(grads))
     assert ws == 8 * (n_rt * C + R * n_ct + n_rt * n_ct)
