@@ -142,6 +142,7 @@ struct BwdGeom {
   int64_t r_step;       // rows from one row step of the block to its next
   bool colvalid, interior;
   uint32_t off0, off_step;
+  uint32_t col_off;      // byte offset of the lane's first column within a row
   int chunk_cols;        // columns one lane arrangement covers: TX * VEC
   uint32_t chunk_bytes;  // ... in bytes
   A *lds_row, *lds_col, *lds_all;
@@ -183,6 +184,7 @@ struct BwdGeom {
     }
     interior = r_first + (p.steps - 1) * r_step + TY <= p.R && (((((int64_t)ct + 1) * cc) << ltx) * VEC) <= p.C;
     // one byte offset per lane and row serves the adjoints, every plane and every full gradient
+    col_off = (uint32_t)c0 * (uint32_t)sizeof(T);
     off0 = (uint32_t)((r_first + ty) * p.row_stride + c0) * (uint32_t)sizeof(T);
     off_step = (uint32_t)(r_step * p.row_stride) * (uint32_t)sizeof(T);
     lds_row = reinterpret_cast<A *>(smem + p.lds_row_off);
@@ -215,6 +217,7 @@ BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) 
 }
 
 // the per-class treatment of one gradient at one row step
+// `off` is the lane's byte offset in the gradient's own view
 template <class T, int VEC, int MAXM, bool EDGE>
 BD_DEV void apply_full(const BwdEntry &en, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], uint32_t off,
                        bool valid, bool nt) {

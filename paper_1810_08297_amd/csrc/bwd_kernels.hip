@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 // absent plane, or a slot past the end of the table, reads the first adjoint's vector instead --
 // memory that is valid and already on its way -- and is then replaced by zeros), so that a
 // wavefront keeps up to 4 M loads in flight instead of M.
-template <class T, int VEC, int MCT>
+template <class T, int VEC, int MCT, bool US>
 __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams p) {
   constexpr int MAXM = MCT > 0 ? MCT : BCAST_MAX_OUTS;
   constexpr int CH = 4;
@@ -134,10 +134,12 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
-    const uint32_t off_ld = valid ? off : 0u;  // lanes outside the problem read element 0 and get zeros
+    // lanes outside the problem read element 0 and get zeros; a view's offset is its own when the
+    // views do not share one row stride
+    auto voff = [&](int64_t sr) { return valid ? view_off<T, US>(off, r, sr, g.col_off) : 0u; };
     LV adj_raw[MAXM];  // unpacked only after the first four gradients' loads are on their way
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(p.adj[i < M ? i : 0].p, off_ld));
+    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(p.adj[i < M ? i : 0].p, voff(p.adj[i < M ? i : 0].sr)));
     T adj[MAXM][VEC];
     LV raw[CH][MAXM];
     bool have[CH][MAXM];
@@ -149,7 +151,8 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
         for (int i = 0; i < MAXM; ++i) {
           const void *plane = i < M ? p.e[e].P[i].p : nullptr;
           have[q][i] = valid && e0 + q < p.n_entries && plane != nullptr;
-          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(plane != nullptr ? plane : p.adj[0].p, off_ld));
+          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(plane != nullptr ? plane : p.adj[0].p,
+                                                                          voff(plane != nullptr ? p.e[e].P[i].sr : p.adj[0].sr)));
         }
       }
     };
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
 #pragma unroll
           for (int v = 0; v < VEC; ++v) P[i][v] = have[q][i] ? lane_elem<T, VEC>(raw[q][i], v) : T(0);
         if (en.cls == kGradFull)
-          apply_full<T, VEC, MAXM, true>(en, adj, P, off, valid, nt);
+          apply_full<T, VEC, MAXM, true>(en, adj, P, view_off<T, US>(off, r, en.g.sr, g.col_off), valid, nt);
         else if (en.cls == kGradRowSum)
           apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
         else if (en.cls == kGradColSum)
@@ -397,7 +400,7 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
   const int chunks = p.col_chunks > 0 ? p.col_chunks : 1;
-  if (signature && widest) {
+  if (signature && widest && p.uniform_stride) {  // the kernels compiled per mix assume one row stride
 #define BD_SIG_GO(m, f, r, c, a, ab, sh, wide)                                                               \
   if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {             \
     if (dt == BCAST_F32)                                                                                     \
@@ -409,7 +412,11 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
     BD_SIGNATURES(BD_SIG_GO)
 #undef BD_SIG_GO
   }
-#define BD_GO(T, V, MM) launch((bwd_tiled_kernel<T, V, MM>), grid, dim3(kBlock), lds, s, p)
+#define BD_GO(T, V, MM)                                                                  \
+  do {                                                                                   \
+    if (p.uniform_stride) launch((bwd_tiled_kernel<T, V, MM, true>), grid, dim3(kBlock), lds, s, p);   \
+    else launch((bwd_tiled_kernel<T, V, MM, false>), grid, dim3(kBlock), lds, s, p);     \
+  } while (0)
 #define BD_LAUNCH(T, V)                \
   do {                                 \
     if (p.M == 1) BD_GO(T, V, 1);      \

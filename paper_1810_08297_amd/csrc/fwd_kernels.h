@@ -79,6 +79,18 @@ BD_DEV T *at(const void *base, uint32_t byte_off) {
   return reinterpret_cast<T *>(const_cast<char *>(static_cast<const char *>(base)) + byte_off);
 }
 
+// Byte offset of a lane's vector at row r of a view whose rows are `sr` elements apart.  With
+// one row stride common to all full-shape views (US) it is the offset computed once per lane;
+// otherwise every view gets its own (32-bit arithmetic: the host admits only views whose last
+// byte lies below 4 GiB).
+template <class T, bool US>
+BD_DEV uint32_t view_off(uint32_t off_uniform, int64_t r, int64_t sr, uint32_t col_off) {
+  if constexpr (US)
+    return off_uniform;
+  else
+    return (uint32_t)r * (uint32_t)sr * (uint32_t)sizeof(T) + col_off;
+}
+
 BD_DEV float or_bits(float a, float b) { return __uint_as_float(__float_as_uint(a) | __float_as_uint(b)); }
 BD_DEV double or_bits(double a, double b) {
   return __longlong_as_double(__double_as_longlong(a) | __double_as_longlong(b));
@@ -112,7 +124,7 @@ BD_DEV int eval_op(const T (&a)[Op::N][VEC], int v, Y *y, std::index_sequence<J.
 // PARTIALS = false is the values-only launch (no plane requested): the op runs on duals
 // without perturbations, so no derivative is computed, and the arguments are loaded with
 // plain loads (a recompute backward pass reads them again soon).
-template <class Op, class T, int VEC, bool PARTIALS>
+template <class Op, class T, int VEC, bool PARTIALS, bool US>
 __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const FwdTiledParams p) {
   constexpr int N = Op::N, M = Op::M;
   constexpr int ND = N - popc(Op::NONDIFF);
@@ -149,7 +161,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
 #pragma unroll
     for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
     if (!((p.col_invariant >> j) & 1u))  // from this row, or (row vectors) from the only row
-      load_vec<T, VEC, ARG_NT>(at<const T>(p.arg_p[j], ((p.row_invariant >> j) & 1u) ? col_off : off), avec[j]);
+      load_vec<T, VEC, ARG_NT>(at<const T>(p.arg_p[j], ((p.row_invariant >> j) & 1u) ? col_off : view_off<T, US>(off, r, p.arg_sr[j], col_off)), avec[j]);
   }
 #pragma unroll
   for (int j = 0; j < N; ++j) {
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      store_vec<T, VEC>(at<T>(p.out_p[i], off), o, nt);
+      store_vec<T, VEC>(at<T>(p.out_p[i], view_off<T, US>(off, r, p.out_sr[i], col_off)), o, nt);
     }
     if constexpr (PARTIALS) {
 #pragma unroll
@@ -188,7 +200,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
           if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-            store_vec<T, VEC>(at<T>(pl, off), o, nt);
+            store_vec<T, VEC>(at<T>(pl, view_off<T, US>(off, r, p.part_sr[i * ND + jd], col_off)), o, nt);
           }
         });
       }
@@ -250,29 +262,39 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
 }
 
 // ---- launch wrappers, one pair per op ------------------------------------------------------
-template <class Op, bool PARTIALS>
+template <class Op, bool PARTIALS, bool US>
 void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)p.lds_bytes;
   if (dt == BCAST_F32) {
     if (vec == 4)
-      launch((fwd_tiled_kernel<Op, float, 4, PARTIALS>), grid, dim3(kBlock), lds, s, p);
-    else if (vec == 2)
-      launch((fwd_tiled_kernel<Op, float, 2, PARTIALS>), grid, dim3(kBlock), lds, s, p);
+      launch((fwd_tiled_kernel<Op, float, 4, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
+    else if (vec == 2 && US)  // views with strides of their own: the widest vector or single elements
+      launch((fwd_tiled_kernel<Op, float, US ? 2 : 1, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
     else
-      launch((fwd_tiled_kernel<Op, float, 1, PARTIALS>), grid, dim3(kBlock), lds, s, p);
+      launch((fwd_tiled_kernel<Op, float, 1, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
   } else {
     if (vec > 1)
-      launch((fwd_tiled_kernel<Op, double, 2, PARTIALS>), grid, dim3(kBlock), lds, s, p);
+      launch((fwd_tiled_kernel<Op, double, 2, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
     else
-      launch((fwd_tiled_kernel<Op, double, 1, PARTIALS>), grid, dim3(kBlock), lds, s, p);
+      launch((fwd_tiled_kernel<Op, double, 1, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
   }
 }
+// vec: what the host planned (for views with strides of their own: the widest vector or 1)
 template <class Op>
 hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
-  if (p.has_partials)
-    launch_fwd_tiled_as<Op, true>(dt, vec, p, grid, s);
-  else
-    launch_fwd_tiled_as<Op, false>(dt, vec, p, grid, s);
+  if (p.uniform_stride) {
+    if (p.has_partials)
+      launch_fwd_tiled_as<Op, true, true>(dt, vec, p, grid, s);
+    else
+      launch_fwd_tiled_as<Op, false, true>(dt, vec, p, grid, s);
+  } else if constexpr (Op::STRIDED) {
+    if (p.has_partials)
+      launch_fwd_tiled_as<Op, true, false>(dt, vec, p, grid, s);
+    else
+      launch_fwd_tiled_as<Op, false, false>(dt, vec, p, grid, s);
+  } else {
+    return hipErrorNotSupported;  // the host sends such ops to the generic kernels
+  }
   return hipGetLastError();
 }
 template <class Op>

@@ -72,6 +72,7 @@ struct OpDesc {
   hipError_t (*generic)(int, const FwdGenericParams &, dim3, hipStream_t);
   hipError_t (*recompute)(int, int, bool, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, hipStream_t);  // may be null
   uint64_t (*recompute_pattern)();
+  bool strided;  // the tiled forward kernel is also built for views with row strides of their own
 };
 
 // HM-LSTM update, planes (c' then h') x (f i o g c h b_f b_i b_o b_g): a bias enters only through
@@ -81,11 +82,11 @@ const int8_t kAliasHmLstm[20] = {0, 1, -1, 3, 4, -1, 0, 1, -1, 3, 10, 11, 12, 13
 const int8_t kAliasBranchy5[5] = {0, 1, 2, 3, -1};
 
 #define BD_OP_ROW(NAME, N, M, NONDIFF, NBR) \
-  {#NAME, N, M, NONDIFF, NBR, nullptr, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME},
+  {#NAME, N, M, NONDIFF, NBR, nullptr, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME, true},
 #define BD_OP_ROW_A(NAME, N, M, NONDIFF, NBR, ALIAS) \
-  {#NAME, N, M, NONDIFF, NBR, ALIAS, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME},
+  {#NAME, N, M, NONDIFF, NBR, ALIAS, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME, true},
 #define BD_ARITY_ROW(K) \
-  {"prod_tanh_" #K, K, 1, 0u, K + 1, nullptr, bd_fwd_tiled_prod_tanh_##K, bd_fwd_generic_prod_tanh_##K, nullptr, nullptr},
+  {"prod_tanh_" #K, K, 1, 0u, K + 1, nullptr, bd_fwd_tiled_prod_tanh_##K, bd_fwd_generic_prod_tanh_##K, nullptr, nullptr, false},
 const OpDesc kOps[] = {
     BD_OP_ROW_A(hmlstm_update, 12, 2, (1u << 6) | (1u << 7), 3, kAliasHmLstm)
     BD_OP_ROW(tanh_xy_b, 3, 1, 0u, 1)
@@ -235,21 +236,24 @@ inline GView gview(const Canon &c, size_t t, void *p) {
   return v;
 }
 
-// Row stride shared by every view that varies along rows and columns, or -1 if they differ
-// or if some element would sit beyond a 32-bit byte offset.
+// Row strides of the views that vary along rows and columns.  Returns the stride they share,
+// -1 if they differ from one another (each view is then addressed with its own), or -2 if some
+// element would sit beyond a 32-bit byte offset (no tiled kernel can address it).
 int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es) {
   if (s2.R == 1) return 0;
   int64_t sr = -1;
+  bool uniform = true;
   for (size_t t = 0; t < v.size(); ++t) {
     if (!v[t].p) continue;
     const TView tv = tview(c, t, nullptr);
     if (tv.sr == 0 || tv.sc == 0) continue;
+    const unsigned __int128 last = ((unsigned __int128)(s2.R - 1) * tv.sr + s2.C) * es;
+    if (last > 0xffffffffULL) return -2;
     if (sr < 0) sr = tv.sr;
-    else if (sr != tv.sr) return -1;
+    else if (sr != tv.sr) uniform = false;
   }
   if (sr < 0) return 0;  // no such view: the offset is never used
-  const unsigned __int128 last = ((unsigned __int128)(s2.R - 1) * sr + s2.C) * es;
-  return last <= 0xffffffffULL ? sr : -1;
+  return uniform ? sr : -1;
 }
 
 struct Geometry {
@@ -379,12 +383,14 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (size_t t = N; t < v.size() && tiled; ++t)
       if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
   }
-  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es) : -1;
-  tiled = tiled && fwd_sr >= 0;
+  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es) : -2;
+  // views with row strides of their own: only the ops built for it (the others go generic)
+  tiled = tiled && (fwd_sr >= 0 || (fwd_sr == -1 && op.strided));
   plan.tiled = tiled;
   if (tiled) {
     FwdTiledParams &p = plan.tp;
-    p.row_stride = fwd_sr;
+    p.uniform_stride = fwd_sr >= 0;
+    p.row_stride = fwd_sr >= 0 ? fwd_sr : 0;
     p.R = s2.R;
     p.C = s2.C;
     // widest vector (16 bytes per lane at most) that every vector-accessed view allows
@@ -399,6 +405,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       }
       if (vec_ok) break;
     }
+    if (!p.uniform_stride && vw != (int)(16 / es)) vw = 1;  // those kernels exist for the widest vector and for 1
     Geometry g;
     g.vec = vw;
     tile_columns(s2.C, g.vec, g);
@@ -415,8 +422,14 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       if (tv.sr == 0) p.row_invariant |= 1u << j;
       if (tv.sc == 0) p.col_invariant |= 1u << j;
     }
-    for (int i = 0; i < M; ++i) p.out_p[i] = v[N + i].p;
-    for (int k = 0; k < n_planes; ++k) p.part_p[k] = dup[k] ? nullptr : v[N + M + k].p;
+    for (int i = 0; i < M; ++i) {
+      p.out_p[i] = v[N + i].p;
+      p.out_sr[i] = tview(c, N + i, nullptr).sr;
+    }
+    for (int k = 0; k < n_planes; ++k) {
+      p.part_p[k] = dup[k] ? nullptr : v[N + M + k].p;
+      p.part_sr[k] = tview(c, N + M + k, nullptr).sr;
+    }
     // A launch that mostly writes (two or more planes read, at least 2.5 written for each) runs fastest
     // with three blocks, twelve wavefronts, per CU: measured 75 against 81 us on the HM-LSTM
     // update (7 read, 22 written), 355 against 382 us on 8192 x 8192 branchy5 (2 read, 6 written),
@@ -593,8 +606,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     for (int j = 0; j < ND; ++j)
       if (cls[j] != kGradFull) fullv[g0 + j].p = nullptr;
     bwd_sr = common_row_stride(c, fullv, s2, es);
-    tiled = bwd_sr >= 0;
+    tiled = bwd_sr >= -1;  // -1: every view addressed with its own row stride
   }
+  const bool uniform_stride = bwd_sr >= 0;
+  if (!uniform_stride) bwd_sr = 0;
   plan.tiled = tiled;
   if (rop && !tiled) return BCAST_ERR_UNSUPPORTED;
   if (tiled) {
@@ -650,7 +665,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // Wide rows with row sums and few planes: a kernel that takes all 2 or 4 column chunks of a
     // row per block finishes the row sums in the main pass (no partial sums, no second pass).
     int chunks = 1;
-    if (!rop && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
+    if (!rop && uniform_stride && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
         (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
         bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
       chunks = (int)g.n_ct;
@@ -664,13 +679,13 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
     // So do the kernels that read the gradient table at run time (8192 x 8192 branchy5 forced onto
     // them: 419 us at 128 rows per block, 631 us at 256).
-    const bool class_kernel = !rop && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
+    const bool class_kernel = !rop && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
                               bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
                                                    plan.share, 1);
     const int64_t rows_rowwise = class_kernel ? std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256))
                                               : std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
     int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
-    if (!rop && !any_rowwise && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0) steps = 1;  // signature kernels without row sums have no row loop
+    if (class_kernel && !any_rowwise && g_tune[kTuneBwdRows] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
       for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
@@ -716,6 +731,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.interleave = g_tune[kTuneInterleave];
       p.xcd_remap = g_tune[kTuneXcdOrder] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
       p.col_chunks = chunks;
+      p.uniform_stride = uniform_stride;
       p.M = M;
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
@@ -798,7 +814,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
     }
-    plan.signature = !rop && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
+    plan.signature = !rop && uniform_stride && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;

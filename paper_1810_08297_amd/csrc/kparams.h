@@ -10,10 +10,12 @@ namespace bd {
 constexpr int kBlock = 256;  // threads per block of every tiled kernel (4 wavefronts)
 
 // A 2-D view used by the tiled kernels: element (r, c) lives at p + r*sr + c*sc.
-// For tensors read or written with vector instructions sc is 0 or 1.  Every view that
-// varies along both rows and columns shares ONE row stride (row_stride of the parameter
-// block) and fits 32-bit byte offsets, so a lane computes a single offset per row and
-// every plane is addressed as (uniform base pointer) + (that offset).
+// For tensors read or written with vector instructions sc is 0 or 1, and every view fits
+// 32-bit byte offsets.  In the usual case every view that varies along both rows and columns
+// shares ONE row stride (row_stride of the parameter block): a lane then computes a single
+// offset per row and every plane is addressed as (uniform base pointer) + (that offset).
+// Otherwise (uniform_stride == 0: arguments or gradients that are slices of wider buffers) a
+// second instantiation of the kernels forms r * sr + column per view.
 struct TView {
   void *p;
   int64_t sr;
@@ -38,7 +40,12 @@ struct FwdTiledParams {
   void *part_p[BCAST_MAX_PLANES];  // nullptr: plane not stored
   uint8_t *branch_p;               // nullptr: not requested
   int64_t branch_sr, branch_sc;
-  int64_t arg_sr[BCAST_MAX_ARGS];  // row stride of the column-invariant arguments
+  int64_t arg_sr[BCAST_MAX_ARGS];  // row stride of every argument, in elements
+  // When the full-shape views do not share one row stride (uniform_stride == 0) every view is
+  // addressed with its own: r * stride + column, still within 32-bit byte offsets.
+  int32_t uniform_stride;
+  int64_t out_sr[BCAST_MAX_OUTS];
+  int64_t part_sr[BCAST_MAX_PLANES];
 };
 
 // A strided view of up to BCAST_MAX_DIMS merged dims for the generic kernels.
@@ -82,6 +89,7 @@ struct BwdTiledParams {
   int32_t n_entries;
   int32_t reverse;  // 1: blocks walk the tiles from the last to the first
   int32_t xcd_remap;   // as in FwdTiledParams
+  int32_t uniform_stride;  // 0: the full-shape views have row strides of their own (TView::sr of each)
   int32_t col_chunks;  // column chunks of TX * VEC columns a block covers per row step (0 or 1: one)
   int32_t interleave;  // 1: row tile rt takes row steps rt, rt + n_rt, rt + 2 n_rt, ... instead of a contiguous run
   int32_t n_row_slots, n_col_slots, n_all_slots;

@@ -9,6 +9,9 @@
 //         (bits of NONDIFF) are plain scalars
 //   y[M]  outputs, duals over all N_d perturbations (narrower results widen on assignment)
 //   returns the branch id taken (0 .. NBR-1)
+// STRIDED: the tiled forward kernel is also built for views whose row strides differ from one
+// another (arguments that are slices of wider buffers); ops without it take the generic strided
+// kernels in that case.
 // RECOMPUTE_PATTERN names the broadcast pattern the recompute-in-reverse kernel is also compiled
 // for without run-time dispatch: 3 bits per differentiable argument, 1 = full shape, 2 = varies
 // along rows only (gradient = row sums), 3 = varies along columns only (column sums), 4 = scalar.
@@ -21,6 +24,7 @@ namespace bd {
 struct OpTanhXyB {
   static constexpr int N = 3, M = 1, NBR = 1;
   static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x89ull;
   template <class Y, class X0, class X1, class B>
   static BD_DEV int apply(Y *y, const X0 &x, const X1 &w, const B &b) {
@@ -38,6 +42,7 @@ struct OpTanhXyB {
 struct OpHmLstmUpdate {
   static constexpr int N = 12, M = 2, NBR = 3;
   static constexpr uint32_t NONDIFF = (1u << 6) | (1u << 7);
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x12489249ull;
   template <class Y, class F, class I, class O, class G, class C, class H, class Z, class BF, class BI,
             class BO, class BG>
@@ -63,6 +68,7 @@ struct OpHmLstmUpdate {
 struct OpUpdateC {
   static constexpr int N = 6, M = 1, NBR = 3;
   static constexpr uint32_t NONDIFF = (1u << 4) | (1u << 5);
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x249ull;
   template <class Y, class C, class F, class I, class G, class Z>
   static BD_DEV int apply(Y *y, const C &c, const F &f, const I &i, const G &g, const Z &z1, const Z &z2) {
@@ -84,6 +90,7 @@ struct OpUpdateC {
 struct OpBranchy5 {
   static constexpr int N = 5, M = 1, NBR = 2;
   static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x44c9ull;
   template <class Y, class A, class B, class R, class S, class TT>
   static BD_DEV int apply(Y *y, const A &a, const B &b, const R &r, const S &s, const TT &t) {
@@ -100,6 +107,7 @@ struct OpBranchy5 {
 struct OpCosX {
   static constexpr int N = 1, M = 1, NBR = 1;
   static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x1ull;
   template <class Y, class X>
   static BD_DEV int apply(Y *y, const X &x) {
@@ -112,6 +120,7 @@ struct OpCosX {
 struct OpScaleXt {
   static constexpr int N = 2, M = 1, NBR = 1;
   static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x21ull;
   template <class Y, class X, class TT>
   static BD_DEV int apply(Y *y, const X &x, const TT &t) {
@@ -124,6 +133,7 @@ struct OpScaleXt {
 struct OpPair3 {
   static constexpr int N = 3, M = 2, NBR = 1;
   static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0xa1ull;
   template <class Y, class X1, class X2, class X3>
   static BD_DEV int apply(Y *y, const X1 &x1, const X2 &x2, const X3 &x3) {
@@ -138,6 +148,7 @@ struct OpPair3 {
 struct OpLinear12 {
   static constexpr int N = 12, M = 2, NBR = 1;
   static constexpr uint32_t NONDIFF = (1u << 6) | (1u << 7);
+  static constexpr bool STRIDED = true;
   static constexpr uint64_t RECOMPUTE_PATTERN = 0x12489249ull;
   template <class Y, class F, class I, class O, class G, class C, class H, class Z, class BF, class BI,
             class BO, class BG>
@@ -154,6 +165,7 @@ template <int ARITY>
 struct OpProdTanh {
   static constexpr int N = ARITY, M = 1, NBR = ARITY + 1;
   static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = false;
   template <class X>
   static BD_DEV X g(const X &x) {
     using T = typename X::value_type;

@@ -29,7 +29,7 @@ constexpr int arg_form(int j) {
   const int cls = (int)((PATTERN >> (3 * jd)) & 7u) - 1;
   return cls == kGradFull ? kFormFull : cls == kGradColSum ? kFormRowVector : cls == kGradRowSum ? kFormColVector : kFormScalar;
 }
-template <class Op, class T, int VEC, uint64_t PATTERN>
+template <class Op, class T, int VEC, uint64_t PATTERN, bool US>
 __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams p, const RecomputeArgs ra) {
   constexpr bool LOOP = PATTERN == 0 || pattern_sums_rows(PATTERN);
   constexpr int N = Op::N, M = Op::M;
@@ -46,7 +46,9 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
-    const uint32_t off_ld = valid ? off : 0u;       // lanes outside the problem read element 0
+    // lanes outside the problem read element 0; a view's offset is its own when the views do not
+    // share one row stride
+    auto voff = [&](int64_t sr) { return valid ? view_off<T, US>(off, r, sr, g.col_off) : 0u; };
     const int64_t r_ld = r < p.R ? r : 0;
     // Arguments.  Where the pattern fixes an argument's broadcast form the matching load is
     // issued unconditionally.  Otherwise (control inputs, run-time pattern) both forms go into
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
       constexpr int form = arg_form<Op, PATTERN>(j);
       avec[j] = LV(T(0));
       if constexpr (form == kFormFull)
-        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], off_ld));
+        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], voff(ra.arg_sr[j])));
       else if constexpr (form == kFormRowVector)
         avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], col_off));
       else if constexpr (form == kFormRuntime) {
@@ -73,10 +75,11 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
           // form does not apply the lane reads the first adjoint's vector instead (valid
           // memory that is loaded anyway) and the result is replaced by zero bits
           const LV x = load_lane_vec<T, VEC>(at<const T>(colinv ? p.adj[0].p : ra.arg_p[j],
-                                                         (colinv || !((ra.row_invariant >> j) & 1u)) ? off_ld : col_off));
+                                                         colinv ? voff(p.adj[0].sr)
+                                                                : ((ra.row_invariant >> j) & 1u) ? col_off : voff(ra.arg_sr[j])));
           avec[j] = colinv ? LV(T(0)) : x;
         } else if (!colinv) {
-          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : off_ld));
+          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : voff(ra.arg_sr[j])));
         }
       }
     });
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
     });
     T adj[M][VEC];
 #pragma unroll
-    for (int i = 0; i < M; ++i) load_plane<T, VEC, true>(p.adj[i].p, off, valid, adj[i]);
+    for (int i = 0; i < M; ++i) load_plane<T, VEC, true>(p.adj[i].p, view_off<T, US>(off, r, p.adj[i].sr, g.col_off), valid, adj[i]);
 #pragma unroll
     for (int j = 0; j < N; ++j)  // the opaque point after the last load
       if (arg_form<Op, PATTERN>(j) == kFormRuntime) {
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
         constexpr int fixed = (int)((PATTERN >> (3 * jd)) & 7u);
         const int cls = fixed ? fixed - 1 : en.cls;
         if (cls == kGradFull)
-          apply_full<T, VEC, M, true>(en, adj, P, off, valid, nt);
+          apply_full<T, VEC, M, true>(en, adj, P, view_off<T, US>(off, r, en.g.sr, g.col_off), valid, nt);
         else if (cls == kGradRowSum)
           apply_rowsum<T, VEC, M>(p, g, en, adj, P, r, ri);
         else if (cls == kGradColSum)
@@ -154,8 +157,23 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
 template <class Op>
 hipError_t launch_bwdr_tiled(int dt, int vec, bool fixed_pattern, const BwdTiledParams &p, const RecomputeArgs &ra,
                              dim3 grid, size_t lds, hipStream_t s) {
-#define BD_GO(T, V, PAT) launch((bwdr_tiled_kernel<Op, T, V, PAT>), grid, dim3(kBlock), lds, s, p, ra)
-  if (dt == BCAST_F32) {
+#define BD_GO(T, V, PAT) launch((bwdr_tiled_kernel<Op, T, V, PAT, true>), grid, dim3(kBlock), lds, s, p, ra)
+#define BD_GO_STRIDED(T, V, PAT) launch((bwdr_tiled_kernel<Op, T, V, PAT, false>), grid, dim3(kBlock), lds, s, p, ra)
+  if (!p.uniform_stride) {  // views with row strides of their own
+    if (dt == BCAST_F32) {
+      if (vec == 4) {
+        if (fixed_pattern) BD_GO_STRIDED(float, 4, Op::RECOMPUTE_PATTERN); else BD_GO_STRIDED(float, 4, 0ull);
+      } else {
+        BD_GO_STRIDED(float, 1, 0ull);
+      }
+    } else {
+      if (vec == 2) {
+        if (fixed_pattern) BD_GO_STRIDED(double, 2, Op::RECOMPUTE_PATTERN); else BD_GO_STRIDED(double, 2, 0ull);
+      } else {
+        BD_GO_STRIDED(double, 1, 0ull);
+      }
+    }
+  } else if (dt == BCAST_F32) {
     if (vec == 4) {
       if (fixed_pattern) BD_GO(float, 4, Op::RECOMPUTE_PATTERN); else BD_GO(float, 4, 0ull);
     } else {
@@ -168,6 +186,7 @@ hipError_t launch_bwdr_tiled(int dt, int vec, bool fixed_pattern, const BwdTiled
       BD_GO(double, 1, 0ull);
     }
   }
+#undef BD_GO_STRIDED
 #undef BD_GO
   return hipGetLastError();
 }

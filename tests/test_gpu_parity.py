@@ -747,3 +747,72 @@ def test_saturating_and_tiny_inputs(dtype):
     Bv = rng.uniform(0.1, 2, A.shape).astype(dtype)
     check_op("branchy5", [A, Bv, small((1, A.shape[1])), small((A.shape[0], 1)), np.zeros((1, 1), dtype)], adj[:1],
              what="[wide A] ")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_views_with_row_strides_of_their_own(dtype):
+    """The usual framework layout: the four gate pre-activations are column slices of one
+    [rows x 4 cols] buffer (row stride 4 cols) while c, h, the outputs and the planes are
+    dense (row stride cols).  The tiled kernels address every view with its own row stride;
+    gradients written into slices of a wider buffer likewise."""
+    R, C = 130, 260
+    rng = np.random.default_rng(91)
+    gates = rng.standard_normal((R, 4 * C)).astype(dtype)
+    f, i, o, g = [gates[:, k * C:(k + 1) * C] for k in range(4)]
+    c, h = [rng.standard_normal((R, C)).astype(dtype) for _ in range(2)]
+    z = (rng.random((R, 1)) < 0.4).astype(dtype)
+    zb = (rng.random((R, 1)) < 0.5).astype(dtype)
+    biases = [(rng.standard_normal((1, C)) * 0.1).astype(dtype) for _ in range(4)]
+    args_np = [np.ascontiguousarray(a) for a in (f, i, o, g)] + [c, h, z, zb] + biases
+    adj_np = [rng.standard_normal((R, C)).astype(dtype) for _ in range(2)]
+    o_out, o_parts, o_br = oracle.forward("hmlstm_update", args_np, threads=8)
+
+    gates_dev = to_dev(gates)
+    dev = [gates_dev[:, k * C:(k + 1) * C] for k in range(4)] + [to_dev(a) for a in args_np[4:]]
+    op_id = P.bcast_op_lookup("hmlstm_update")
+    fb = P.alloc_forward("hmlstm_update", dev, want_branch=True)
+    info = P.bcast_dual_forward_plan(op_id, dev, fb.outs, fb.partials)
+    assert info["path"] == 1 and info["vec"] == (4 if dtype == np.float32 else 2)  # tiled, full vectors
+    fb.run(dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(fb.branch.cpu().numpy(), o_br)
+    for k, (gv, w) in enumerate(zip(fb.outs, o_out)):
+        check_close(gv.cpu().numpy(), w, f"output {k}")
+    for k, (gv, w) in enumerate(zip(fb.partials, o_parts)):
+        check_close(gv.cpu().numpy(), w, f"plane {k}")
+    # backward: adjoints are slices of a wider buffer, gate gradients are written into slices of one
+    adj_wide = to_dev(np.concatenate(adj_np + [np.zeros((R, 7), dtype)], axis=1))
+    adj_dev = [adj_wide[:, :C], adj_wide[:, C:2 * C]]
+    ggates = torch.full((R, 4 * C), float("nan"), dtype=gates_dev.dtype, device="cuda")
+    grads = [ggates[:, k * C:(k + 1) * C] for k in range(4)] + [torch.empty((R, C), dtype=gates_dev.dtype, device="cuda")
+                                                                for _ in range(2)] + \
+            [torch.empty((1, C), dtype=gates_dev.dtype, device="cuda") for _ in range(4)]
+    info = P.bcast_dual_backward_plan(adj_dev, fb.partials, grads)
+    assert info["path"] == 1
+    nbytes = P.bcast_dual_backward_workspace(adj_dev, fb.partials, grads)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    P.bcast_dual_backward(adj_dev, fb.partials, grads, ws)
+    torch.cuda.synchronize()
+    gshapes = [a.shape for a in args_np[:6]] + [b.shape for b in biases]
+    want = oracle.backward(adj_np, [p.cpu().numpy() for p in fb.partials], gshapes, threads=8)
+    for k, (gv, w) in enumerate(zip(grads, want)):
+        check_close(gv.cpu().numpy(), w, f"gradient {k}")
+    # the recompute entry point on the same views
+    rgrads = [torch.empty_like(t) for t in grads]
+    rg_wide = torch.empty((R, 4 * C), dtype=gates_dev.dtype, device="cuda")
+    rgrads[:4] = [rg_wide[:, k * C:(k + 1) * C] for k in range(4)]
+    nbytes = P.bcast_dual_backward_recompute_workspace(op_id, dev, adj_dev, rgrads)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    assert P.bcast_dual_backward_recompute_plan(op_id, dev, adj_dev, rgrads)["path"] == 1
+    P.bcast_dual_backward_recompute(op_id, dev, adj_dev, rgrads, ws)
+    torch.cuda.synchronize()
+    for k, (gv, w) in enumerate(zip(rgrads, want)):
+        check_close(gv.cpu().numpy(), w, f"recomputed gradient {k}")
+    # an op without such kernels takes the generic ones and is still right
+    xs = [to_dev(gates)[:, :C], to_dev(np.ascontiguousarray(c))]
+    f2 = P.alloc_forward("prod_tanh_2", xs)
+    assert P.bcast_dual_forward_plan(P.bcast_op_lookup("prod_tanh_2"), xs, f2.outs, f2.partials)["path"] == 2
+    f2.run(xs)
+    torch.cuda.synchronize()
+    o2, p2, _ = oracle.forward("prod_tanh", [np.ascontiguousarray(f), c], threads=8)
+    check_close(f2.outs[0].cpu().numpy(), o2[0], "prod_tanh_2 value")
