@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--no-lean-extra", action="store_true", help="skip the additional lean-layout measurement")
     ap.add_argument("--unfused-baseline", action="store_true",
                     help="also time the same function as per-primitive library kernels with reverse-mode autograd")
+    ap.add_argument("--transposed", action="store_true",
+                    help="every array transposed (stored row-major again): the HM-LSTM update as [batch x hidden] with "
+                         "[1 x hidden] biases, whose gradients are then sums over rows")
     ap.add_argument("--sliced-gates", action="store_true",
                     help="HM-LSTM workloads: f, i, o, g are column slices of one buffer four times as wide (row "
                          "stride 4 x batch), so that the views no longer share one row stride")
@@ -110,6 +113,10 @@ def main():
 
     torch.cuda.set_device(0)
     op, args, adj, desc, dtype = build_workload(a.workload, a.p_index, a.uniform_run)
+    if a.transposed:
+        args = [np.ascontiguousarray(x.T) for x in args]
+        adj = [np.ascontiguousarray(x.T) for x in adj]
+        desc += ", transposed"
     es = np.dtype(dtype).itemsize
     # every full-shape buffer of the step lives in the library's staggered slab layout
     dev, _slab_a = P.to_slab([torch.from_numpy(x).cuda() for x in args])

@@ -195,6 +195,25 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
 }
 
 // ---- second pass: add the per-block partial sums in a fixed order ------------------------------
+// Adds partials first, first + step, ... below n in that order; the loads go out eight at a time
+// (the partials are few and scattered: one dependent load per addition is all latency).
+template <class T, class A>
+BD_DEV A pass2_sum(const A *ws, int64_t first, int64_t step, int64_t n, int64_t stride) {
+  using AT = acc_traits<T>;
+  constexpr int U = 8;
+  A s = AT::zero();
+  int64_t q = first;
+  for (; q + (U - 1) * step < n; q += U * step) {
+    A t[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) t[u] = ws[(q + u * step) * stride];
+#pragma unroll
+    for (int u = 0; u < U; ++u) AT::add(s, t[u]);
+  }
+  for (; q < n; q += step) AT::add(s, ws[q * stride]);
+  return s;
+}
+
 template <class T>
 __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) {
   using AT = acc_traits<T>;
@@ -211,15 +230,13 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
   if (job.kind == 0) {  // one wavefront per output
     const int64_t out = b * (kBlock / 64) + wave;
     if (out < job.n_out) {
-      A s = AT::zero();
-      for (int64_t q = lane; q < job.n_part; q += 64) AT::add(s, ws[out * job.out_stride + q * job.part_stride]);
+      A s = pass2_sum<T, A>(ws + out * job.out_stride, lane, 64, job.n_part, job.part_stride);
       s = seg_reduce<T, A>(s, 6);
       if (lane == 0) g[out * job.g_stride] = AT::fin(s);
     }
   } else if (job.kind == 1) {  // one block per output
     const int64_t out = b;
-    A s = AT::zero();
-    for (int64_t q = tid; q < job.n_part; q += kBlock) AT::add(s, ws[out * job.out_stride + q * job.part_stride]);
+    A s = pass2_sum<T, A>(ws + out * job.out_stride, tid, kBlock, job.n_part, job.part_stride);
     s = seg_reduce<T, A>(s, 6);
     if (lane == 0) sh[wave] = s;
     __syncthreads();
@@ -228,17 +245,18 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
       for (int w = 1; w < kBlock / 64; ++w) AT::add(t, sh[w]);
       g[out * job.g_stride] = AT::fin(t);
     }
-  } else {  // 64 adjacent outputs x 4 interleaved groups of partials
-    const int64_t out = b * 64 + lane;
+  } else {  // adjacent outputs x interleaved groups of partials: 64 x 4 (kind 2) or 16 x 16 (kind 3)
+    const int log2_outs = job.kind == 2 ? 6 : 4;
+    const int outs = 1 << log2_outs, groups = kBlock >> log2_outs;
+    const int o = tid & (outs - 1), grp = tid >> log2_outs;
+    const int64_t out = b * outs + o;
     A s = AT::zero();
-    if (out < job.n_out)
-      for (int64_t q = wave; q < job.n_part; q += kBlock / 64)
-        AT::add(s, ws[out * job.out_stride + q * job.part_stride]);
+    if (out < job.n_out) s = pass2_sum<T, A>(ws + out * job.out_stride, grp, groups, job.n_part, job.part_stride);
     sh[tid] = s;
     __syncthreads();
-    if (wave == 0 && out < job.n_out) {
-      A t = sh[lane];
-      for (int w = 1; w < kBlock / 64; ++w) AT::add(t, sh[w * 64 + lane]);
+    if (grp == 0 && out < job.n_out) {
+      A t = sh[o];
+      for (int w = 1; w < groups; ++w) AT::add(t, sh[w * outs + o]);
       g[out * job.g_stride] = AT::fin(t);
     }
   }
@@ -371,6 +389,8 @@ using namespace bd;
 #define BD_SIGNATURES(X)                                                  \
   X(2, 6, 4, 0, 0, 0ull, 0ull, 0) /* HM-LSTM update, per-row biases */    \
   X(2, 6, 4, 0, 0, BD_HM_LEAN, BD_HM_SHARE, 0)                            \
+  X(2, 6, 0, 4, 0, 0ull, 0ull, 0) /* HM-LSTM update stored [batch x hidden]: per-column biases */ \
+  X(2, 6, 0, 4, 0, BD_HM_LEAN, BD_HM_SHARE, 0)                            \
   X(1, 2, 1, 0, 0, 0ull, 0ull, 1) /* tanh(x*y + b) */                     \
   X(1, 2, 1, 1, 1, 0ull, 0ull, 0) /* branchy5 */                          \
   X(1, 2, 1, 1, 1, 1ull << 4, 0ull, 0) /* branchy5 without the always-zero plane of t */ \

@@ -682,8 +682,16 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     const bool class_kernel = !rop && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
                               bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
                                                    plan.share, 1);
-    const int64_t rows_rowwise = class_kernel ? std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256))
-                                              : std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
+    // A class kernel that streams many planes per row step is the exception (HM-LSTM update stored
+    // [batch x hidden], 2 adjoints + 20 planes: 8192 x 4096 runs 733 us at two blocks per CU, 995 us at
+    // one; with its 10 distinct planes, 509 us and 457 us).
+    int planes_read = M;
+    for (size_t e = 0; e < order.size(); ++e)
+      for (int i = 0; i < M; ++i)
+        planes_read += v[M + i * ND + order[e]].p != nullptr && !(e < 16 && ((plan.share >> (4 * e)) & 15u));
+    const bool one_per_cu = class_kernel && planes_read < 16;
+    const int64_t rows_rowwise = one_per_cu ? std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256))
+                                            : std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
     int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
     if (class_kernel && !any_rowwise && g_tune[kTuneBwdRows] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
@@ -785,7 +793,9 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       } else if (cls[j] == kGradColSum) {
         en.slot = cur.n_col_slots++;
         en.direct = g.n_rt == 1;
-        job = Pass2Job{en.g.p, en.g.sc, s2.C, g.n_rt, s2.C, 1, 0, 0, ceil_div(s2.C, 64), 2, 0};
+        // many partials per output: 16 outputs per block, each summed by 16 groups of lanes
+        job = g.n_rt <= 32 ? Pass2Job{en.g.p, en.g.sc, s2.C, g.n_rt, s2.C, 1, 0, 0, ceil_div(s2.C, 64), 2, 0}
+                           : Pass2Job{en.g.p, en.g.sc, s2.C, g.n_rt, s2.C, 1, 0, 0, ceil_div(s2.C, 16), 3, 0};
       } else if (cls[j] == kGradAllSum) {
         en.slot = cur.n_all_slots++;
         en.direct = g.n_ct * g.n_rt == 1;

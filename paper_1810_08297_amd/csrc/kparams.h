@@ -121,7 +121,8 @@ struct Pass2Job {
   int64_t ws_off;       // bytes
   int64_t first_block;  // blocks [first_block, first_block + n_blocks) serve this job
   int64_t n_blocks;
-  int32_t kind;         // 0: one wavefront per output, 1: one block per output, 2: 64 outputs x 4 groups per block
+  int32_t kind;         // 0: one wavefront per output, 1: one block per output, 2: 64 outputs x 4 groups per block,
+                        // 3: 16 outputs x 16 groups per block
   int32_t pad;
 };
 struct Pass2Params {

@@ -816,3 +816,43 @@ def test_views_with_row_strides_of_their_own(dtype):
     torch.cuda.synchronize()
     o2, p2, _ = oracle.forward("prod_tanh", [np.ascontiguousarray(f), c], threads=8)
     check_close(f2.outs[0].cpu().numpy(), o2[0], "prod_tanh_2 value")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_hmlstm_stored_batch_by_hidden(dtype):
+    """The HM-LSTM update with every array transposed ([batch x hidden], biases [1 x hidden]): the
+    bias gradients become sums over rows, taken by the kernels compiled for that mix (all planes
+    stored, and the lean layout), with a second pass over many per-block partial sums."""
+    op = "hmlstm_update"
+    H, B = 520, 2100  # [2100 x 520]: a ragged last column chunk, row blocks that do not divide the rows
+    args, adj = inputs.hmlstm_inputs(H, B, seed=77, dtype=dtype, z_per_element=True)
+    args = [np.ascontiguousarray(a.T) for a in args]
+    adj = [np.ascontiguousarray(a.T) for a in adj]
+    bufs = check_op(op, args, adj, threads=16, what="batch x hidden")
+    dev = [to_dev(a) for a in args]
+    adj_dev = [to_dev(a) for a in adj]
+    didx = oracle.diff_arg_indices(op, 12)
+    shapes = [args[j].shape for j in didx]
+    full = P.alloc_forward(op, dev).run(dev)
+    lean = P.alloc_forward(op, dev, lean=True).run(dev)
+    gf = P.alloc_backward(adj_dev, full.partials, shapes).run(adj_dev, full.partials)
+    gl = P.alloc_backward(adj_dev, lean.partials, shapes).run(adj_dev, lean.partials)
+    for parts, g in ((full.partials, gf), (lean.partials, gl)):
+        info = P.bcast_dual_backward_plan(adj_dev, parts, g.grads)
+        assert info["path"] == 1 and info["specialized"] == 1 and info["n_second_pass"] == 4
+        assert info["rows_per_block"] > 1
+    torch.cuda.synchronize()
+    want = oracle.backward(adj, [p.cpu().numpy() for p in full.partials], shapes, threads=16)
+    for k in range(10):
+        check_close(gf.grads[k].cpu().numpy(), want[k], f"grad {k}")
+        assert torch.equal(gf.grads[k], gl.grads[k])
+    # many partial sums per output: one row per block leaves 2100 of them for the second pass
+    P.bcast_dual_set_tuning(1, 1)
+    try:
+        g1 = P.alloc_backward(adj_dev, full.partials, shapes).run(adj_dev, full.partials)
+        torch.cuda.synchronize()
+    finally:
+        P.bcast_dual_set_tuning(1, 0)
+    for k in range(10):
+        check_close(g1.grads[k].cpu().numpy(), want[k], f"one row per block, grad {k}")
+    del bufs

@@ -196,6 +196,21 @@ def test_backward_plan_and_workspace():
     assert rc == 0 and info.specialized == 1 and info.rows_per_block == 1  # config 3: class-specialised, no row loop
     assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
                                            ctypes.c_int32(10), B._views(grads)) == 0
+    # the same update stored [batch x hidden]: bias gradients are sums over rows; the kernel built
+    # for that mix streams 22 planes per row step and runs as two blocks per CU, the lean layout
+    # (12 distinct planes) as one
+    adj_t = [B.raw_view(4096 + (40 + k) * (1 << 30), (Bt, H), (H, 1)) for k in range(2)]
+    parts_t = [B.raw_view(4096 + (k + 1) * (1 << 30), (Bt, H), (H, 1)) for k in range(20)]
+    grads_t = [fake((Bt, H))] * 6 + [fake((1, H))] * 4
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj_t), B._views(parts_t),
+                                    ctypes.c_int32(10), B._views(grads_t), ctypes.byref(info))
+    assert rc == 0 and info.specialized == 1 and info.n_second_pass == 4
+    assert info.grid_x == 4 and info.rows_per_block == 8 and info.grid_y == 128
+    alias = P.bcast_op_plane_alias(P.bcast_op_lookup("hmlstm_update"))
+    lean_t = [None if a < 0 else parts_t[a] for a in alias]
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj_t), B._views(lean_t, adj_t[0]),
+                                    ctypes.c_int32(10), B._views(grads_t), ctypes.byref(info))
+    assert rc == 0 and info.specialized == 1 and info.rows_per_block == 16 and info.grid_y == 64
     # config 1: a 4096-wide row is four column chunks; the kernel built for it takes all four in
     # one block, so the bias gradient's row sums need neither workspace nor second pass
     adj1 = [fake((4096, 4096))]
