@@ -141,8 +141,8 @@ struct BwdGeom {
   int64_t c0, r_first;  // r_first: row of the block's first row step at ty = 0
   int64_t r_step;       // rows from one row step of the block to its next
   bool colvalid, interior;
-  uint32_t off0, off_step;
-  uint32_t col_off;      // byte offset of the lane's first column within a row
+  uint32_t lane_uniform;  // (lane's row within a row step * common row stride + lane's first column) * sizeof(T)
+  uint32_t col_off;       // byte offset of the lane's first column within a row
   int chunk_cols;        // columns one lane arrangement covers: TX * VEC
   uint32_t chunk_bytes;  // ... in bytes
   A *lds_row, *lds_col, *lds_all;
@@ -183,10 +183,10 @@ struct BwdGeom {
       r_step = TY;
     }
     interior = r_first + (p.steps - 1) * r_step + TY <= p.R && (((((int64_t)ct + 1) * cc) << ltx) * VEC) <= p.C;
-    // one byte offset per lane and row serves the adjoints, every plane and every full gradient
+    // with one row stride common to the full-shape views, one byte offset per lane serves the
+    // adjoints, every plane and every full gradient at every row step
     col_off = (uint32_t)c0 * (uint32_t)sizeof(T);
-    off0 = (uint32_t)((r_first + ty) * p.row_stride + c0) * (uint32_t)sizeof(T);
-    off_step = (uint32_t)(r_step * p.row_stride) * (uint32_t)sizeof(T);
+    lane_uniform = ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)c0) * (uint32_t)sizeof(T);
     lds_row = reinterpret_cast<A *>(smem + p.lds_row_off);
     lds_col = reinterpret_cast<A *>(smem + p.lds_col_off);
     lds_all = reinterpret_cast<A *>(smem + p.lds_all_off);
@@ -197,6 +197,14 @@ struct BwdGeom {
   }
   // row of this lane at row step k of the block
   BD_DEV int64_t row(int k) const { return r_first + ty + k * r_step; }
+  // Addressing of row step k.  A step that starts past the last row (only lanes outside the
+  // problem, which read a view's first vector of the step and discard it) is moved to row 0.
+  template <bool US>
+  BD_DEV RowStep<T, US> step(const BwdTiledParams &p, int k) const {
+    int64_t r0 = r_first + k * r_step;
+    r0 = r0 < p.R ? r0 : 0;
+    return RowStep<T, US>{r0, r0 * p.row_stride * (int64_t)sizeof(T), lane_uniform, (uint32_t)ty, col_off};
+  }
   // row behind the block-local row index q = k * TY + ty
   BD_DEV int64_t row_of_local(int q) const {
     const int lty = 8 - ltx;  // kBlock = 256 lanes = TY * TX
@@ -204,7 +212,8 @@ struct BwdGeom {
   }
 };
 
-// one vector of a plane; lanes outside the problem read offset 0 and get zeros
+// one vector of a plane (`base`: the plane at the row step's first row; `off`: the lane's offset
+// from there); lanes outside the problem read offset 0 and get zeros
 template <class T, int VEC, bool EDGE>
 BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) {
   if (EDGE) {
@@ -217,14 +226,14 @@ BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) 
 }
 
 // the per-class treatment of one gradient at one row step
-// `off` is the lane's byte offset in the gradient's own view
+// `gbase`: the gradient's own view at the row step's first row; `off`: the lane's byte offset from there
 template <class T, int VEC, int MAXM, bool EDGE>
-BD_DEV void apply_full(const BwdEntry &en, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], uint32_t off,
+BD_DEV void apply_full(const void *gbase, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], uint32_t off,
                        bool valid, bool nt) {
   T o[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
-  if (!EDGE || valid) store_vec<T, VEC>(at<T>(en.g.p, off), o, nt);
+  if (!EDGE || valid) store_vec<T, VEC>(at<T>(gbase, off), o, nt);
 }
 // row sums in two halves: a lane's own columns first (over as many column chunks as the kernel
 // holds), then once per row step the reduction over the row's lanes and the store

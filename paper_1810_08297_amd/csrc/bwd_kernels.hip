@@ -46,10 +46,12 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
   for (int e = 0; e < (NA > 0 ? NA : 1); ++e) allacc[e] = AT::zero();
 
-  auto row_step = [&](auto edge_tag, int k, uint32_t off) {
+  auto row_step = [&](auto edge_tag, int k) {
     constexpr bool EDGE = decltype(edge_tag)::value;
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
+    const RowStep<T, true> rs = g.template step<true>(p, k);
+    const uint32_t off = rs.lane_uniform;
     T adj[CU][M][VEC], P[CU][NE][M][VEC];
     bool valid[CU];
 #pragma unroll
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
       const uint32_t o = off + (uint32_t)q * g.chunk_bytes;
       valid[q] = r < p.R && g.c0 + (int64_t)q * g.chunk_cols < p.C;
 #pragma unroll
-      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(p.adj[i].p, o, valid[q], adj[q][i]);
+      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE>(rs.base(p.adj[i].p, 0), o, valid[q], adj[q][i]);
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) P[q][e][i][v] = T(0);
           } else {
-            load_plane<T, VEC, EDGE>(p.e[e].P[i].p, o, valid[q], P[q][e][i]);
+            load_plane<T, VEC, EDGE>(rs.base(p.e[e].P[i].p, 0), o, valid[q], P[q][e][i]);
           }
         }
     }
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     for (int q = 0; q < CU; ++q)
 #pragma unroll
       for (int e = 0; e < NF; ++e)
-        apply_full<T, VEC, M, EDGE>(p.e[e], adj[q], P[q][share_src(SHARE, e)], off + (uint32_t)q * g.chunk_bytes, valid[q], nt);
+        apply_full<T, VEC, M, EDGE>(rs.base(p.e[e].g.p, 0), adj[q], P[q][share_src(SHARE, e)], off + (uint32_t)q * g.chunk_bytes, valid[q], nt);
 #pragma unroll
     for (int e = NF; e < NF + NR; ++e) {
       A rs = AT::zero();
@@ -98,11 +100,10 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
         for (int i = 0; i < M; ++i) AT::add_prod(allacc[e], adj[0][i][v], P[0][share_src(SHARE, NF + NR + NC + e)][i][v]);
   };
   const int steps = LOOP ? p.steps : 1;
-  uint32_t off = g.off0;
   if (g.interior)
-    for (int k = 0; k < steps; ++k, off += g.off_step) row_step(std::false_type{}, k, off);
+    for (int k = 0; k < steps; ++k) row_step(std::false_type{}, k);
   else
-    for (int k = 0; k < steps; ++k, off += g.off_step) row_step(std::true_type{}, k, off);
+    for (int k = 0; k < steps; ++k) row_step(std::true_type{}, k);
   if constexpr (LOOP) {  // slots were handed out in table order within each class
 #pragma unroll
     for (int e = 0; e < NC; ++e)
@@ -129,17 +130,17 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
   const BwdGeom<T, VEC> g(p, smem);
   const int M = MCT > 0 ? MCT : p.M;
   const bool nt = p.nt_store != 0;
-  uint32_t off = g.off0;
-  for (int k = 0; k < p.steps; ++k, off += g.off_step) {
+  for (int k = 0; k < p.steps; ++k) {
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
-    // lanes outside the problem read element 0 and get zeros; a view's offset is its own when the
-    // views do not share one row stride
-    auto voff = [&](int64_t sr) { return valid ? view_off<T, US>(off, r, sr, g.col_off) : 0u; };
+    const RowStep<T, US> rs = g.template step<US>(p, k);
+    // lanes outside the problem read the row step's first vector and get zeros; a view's offset is
+    // its own when the views do not share one row stride
+    auto voff = [&](int64_t sr) { return valid ? rs.lane(sr) : 0u; };
     LV adj_raw[MAXM];  // unpacked only after the first four gradients' loads are on their way
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(p.adj[i < M ? i : 0].p, voff(p.adj[i < M ? i : 0].sr)));
+    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(rs.base(p.adj[i < M ? i : 0].p, p.adj[i < M ? i : 0].sr), voff(p.adj[i < M ? i : 0].sr)));
     T adj[MAXM][VEC];
     LV raw[CH][MAXM];
     bool have[CH][MAXM];
@@ -151,8 +152,8 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
         for (int i = 0; i < MAXM; ++i) {
           const void *plane = i < M ? p.e[e].P[i].p : nullptr;
           have[q][i] = valid && e0 + q < p.n_entries && plane != nullptr;
-          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(plane != nullptr ? plane : p.adj[0].p,
-                                                                          voff(plane != nullptr ? p.e[e].P[i].sr : p.adj[0].sr)));
+          const int64_t sr = plane != nullptr ? p.e[e].P[i].sr : p.adj[0].sr;
+          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(rs.base(plane != nullptr ? plane : p.adj[0].p, sr), voff(sr)));
         }
       }
     };
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
 #pragma unroll
           for (int v = 0; v < VEC; ++v) P[i][v] = have[q][i] ? lane_elem<T, VEC>(raw[q][i], v) : T(0);
         if (en.cls == kGradFull)
-          apply_full<T, VEC, MAXM, true>(en, adj, P, view_off<T, US>(off, r, en.g.sr, g.col_off), valid, nt);
+          apply_full<T, VEC, MAXM, true>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt);
         else if (en.cls == kGradRowSum)
           apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
         else if (en.cls == kGradColSum)

@@ -79,17 +79,26 @@ BD_DEV T *at(const void *base, uint32_t byte_off) {
   return reinterpret_cast<T *>(const_cast<char *>(static_cast<const char *>(base)) + byte_off);
 }
 
-// Byte offset of a lane's vector at row r of a view whose rows are `sr` elements apart.  With
-// one row stride common to all full-shape views (US) it is the offset computed once per lane;
-// otherwise every view gets its own (32-bit arithmetic: the host admits only views whose last
-// byte lies below 4 GiB).
+// Where the lanes of one row step find their vectors in a view whose rows are `sr` elements
+// apart: a 64-bit part that is the same for the whole block (the view's base moved to the
+// step's first row; scalar registers) and a 32-bit part of the lane's own (its row within the
+// step and its column).  Views of any size can be addressed this way; the host only has to see
+// that one row step of a view, TY rows, spans less than 4 GiB.  With one row stride common to
+// all full-shape views (US) both parts are computed once and serve every such view.
 template <class T, bool US>
-BD_DEV uint32_t view_off(uint32_t off_uniform, int64_t r, int64_t sr, uint32_t col_off) {
-  if constexpr (US)
-    return off_uniform;
-  else
-    return (uint32_t)r * (uint32_t)sr * (uint32_t)sizeof(T) + col_off;
-}
+struct RowStep {
+  int64_t row0;           // first row of the step
+  int64_t uniform_bytes;  // US: row0 * the common row stride * sizeof(T)
+  uint32_t lane_uniform;  // US: (lane's row in the step * the common row stride + lane's column) * sizeof(T)
+  uint32_t ty, col_off;   // lane's row in the step; lane's column * sizeof(T)
+  // a view that varies along rows and columns
+  BD_DEV const void *base(const void *p, int64_t sr) const {
+    return static_cast<const char *>(p) + (US ? uniform_bytes : row0 * sr * (int64_t)sizeof(T));
+  }
+  BD_DEV uint32_t lane(int64_t sr) const {
+    return US ? lane_uniform : ty * (uint32_t)sr * (uint32_t)sizeof(T) + col_off;
+  }
+};
 
 BD_DEV float or_bits(float a, float b) { return __uint_as_float(__float_as_uint(a) | __float_as_uint(b)); }
 BD_DEV double or_bits(double a, double b) {
@@ -140,11 +149,13 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   const uint32_t rt = bid / nct, ct = bid - rt * nct;
   const int64_t c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
   if (c0 >= p.C) return;
-  const int64_t r = (int64_t)rt * TY + ty;
+  const int64_t r0 = (int64_t)rt * TY;  // the block's first row, the same for all its lanes
+  const int64_t r = r0 + ty;
   if (r >= p.R) return;
   const bool nt = p.nt_store != 0;
   const uint32_t col_off = (uint32_t)c0 * (uint32_t)sizeof(T);
-  const uint32_t off = (uint32_t)(r * p.row_stride + c0) * (uint32_t)sizeof(T);
+  const RowStep<T, US> rs{r0, r0 * p.row_stride * (int64_t)sizeof(T),
+                          ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)c0) * (uint32_t)sizeof(T), (uint32_t)ty, col_off};
 
   // Every argument is fetched in whichever of two forms applies -- a vector for arguments
   // that vary along the columns, one broadcast element otherwise -- into registers of its
@@ -161,7 +172,8 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
 #pragma unroll
     for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
     if (!((p.col_invariant >> j) & 1u))  // from this row, or (row vectors) from the only row
-      load_vec<T, VEC, ARG_NT>(at<const T>(p.arg_p[j], ((p.row_invariant >> j) & 1u) ? col_off : view_off<T, US>(off, r, p.arg_sr[j], col_off)), avec[j]);
+      load_vec<T, VEC, ARG_NT>(((p.row_invariant >> j) & 1u) ? at<const T>(p.arg_p[j], col_off)
+                                                                : at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
   }
 #pragma unroll
   for (int j = 0; j < N; ++j) {
@@ -189,7 +201,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      store_vec<T, VEC>(at<T>(p.out_p[i], view_off<T, US>(off, r, p.out_sr[i], col_off)), o, nt);
+      store_vec<T, VEC>(at<T>(rs.base(p.out_p[i], p.out_sr[i]), rs.lane(p.out_sr[i])), o, nt);
     }
     if constexpr (PARTIALS) {
 #pragma unroll
@@ -200,7 +212,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
           if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-            store_vec<T, VEC>(at<T>(pl, view_off<T, US>(off, r, p.part_sr[i * ND + jd], col_off)), o, nt);
+            store_vec<T, VEC>(at<T>(rs.base(pl, p.part_sr[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd])), o, nt);
           }
         });
       }

@@ -183,6 +183,7 @@ struct Canon {
   std::vector<Dims> strides;  // per tensor, merged dims, outermost first
 };
 
+constexpr int64_t kMaxFused = (int64_t)1 << 28;
 void canonicalize(int D, const Dims &U, const std::vector<Dims> &eff, int key, Canon &c) {
   std::vector<int> order;
   for (int d = 0; d < D; ++d)
@@ -192,7 +193,8 @@ void canonicalize(int D, const Dims &U, const std::vector<Dims> &eff, int key, C
   std::vector<Dims> st(eff.size());
   std::vector<std::vector<int64_t>> cur(eff.size());
   for (int d : order) {
-    bool merge = !shp.empty();
+    // a fused dim stays below 2^28 elements: the tiled kernels address a row with 32-bit byte offsets
+    bool merge = !shp.empty() && shp.back() <= kMaxFused / U[d];
     if (merge)
       for (size_t t = 0; t < eff.size() && merge; ++t) merge = (cur[t].back() == eff[t][d] * U[d]);
     if (merge) {
@@ -203,6 +205,16 @@ void canonicalize(int D, const Dims &U, const std::vector<Dims> &eff, int key, C
       for (size_t t = 0; t < eff.size(); ++t) cur[t].push_back(eff[t][d]);
     }
   }
+  // one dim longer than that (a long vector, or dims the caller had fused already): taken as rows
+  // of equal length if a power of two up to 2^16 divides it suitably
+  if (shp.size() == 1 && shp[0] > kMaxFused)
+    for (int64_t f = 2; f <= 65536; f *= 2)
+      if (shp[0] % f == 0 && shp[0] / f <= kMaxFused) {
+        const int64_t inner = shp[0] / f;
+        shp = {f, inner};
+        for (size_t t = 0; t < eff.size(); ++t) cur[t] = {cur[t][0] * inner, cur[t][0]};
+        break;
+      }
   c.nd = (int)shp.size();
   c.E = 1;
   for (int d = 0; d < c.nd; ++d) {
@@ -237,18 +249,22 @@ inline GView gview(const Canon &c, size_t t, void *p) {
 }
 
 // Row strides of the views that vary along rows and columns.  Returns the stride they share,
-// -1 if they differ from one another (each view is then addressed with its own), or -2 if some
-// element would sit beyond a 32-bit byte offset (no tiled kernel can address it).
+// -1 if they differ from one another (each view is then addressed with its own), or -2 if the
+// rows that one block takes in one step (up to 256 when rows are shorter than 1024 elements,
+// else one) span 4 GiB or more of some view: lanes address a row step with 32-bit byte offsets
+// from its first row.  The size of a view as a whole is not limited by this.
 int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es) {
-  if (s2.R == 1) return 0;
+  if (s2.R == 1) return s2.C * es > 0xffffffffULL ? -2 : 0;
   int64_t sr = -1;
   bool uniform = true;
+  const int64_t rows_in_step = std::min<int64_t>(s2.R, s2.C >= 1024 ? 1 : kBlock);
   for (size_t t = 0; t < v.size(); ++t) {
     if (!v[t].p) continue;
     const TView tv = tview(c, t, nullptr);
-    if (tv.sr == 0 || tv.sc == 0) continue;
-    const unsigned __int128 last = ((unsigned __int128)(s2.R - 1) * tv.sr + s2.C) * es;
+    if (tv.sc == 0) continue;
+    const unsigned __int128 last = ((unsigned __int128)(rows_in_step - 1) * tv.sr + s2.C) * es;
     if (last > 0xffffffffULL) return -2;
+    if (tv.sr == 0) continue;
     if (sr < 0) sr = tv.sr;
     else if (sr != tv.sr) uniform = false;
   }

@@ -10,12 +10,14 @@ namespace bd {
 constexpr int kBlock = 256;  // threads per block of every tiled kernel (4 wavefronts)
 
 // A 2-D view used by the tiled kernels: element (r, c) lives at p + r*sr + c*sc.
-// For tensors read or written with vector instructions sc is 0 or 1, and every view fits
-// 32-bit byte offsets.  In the usual case every view that varies along both rows and columns
-// shares ONE row stride (row_stride of the parameter block): a lane then computes a single
-// offset per row and every plane is addressed as (uniform base pointer) + (that offset).
-// Otherwise (uniform_stride == 0: arguments or gradients that are slices of wider buffers) a
-// second instantiation of the kernels forms r * sr + column per view.
+// For tensors read or written with vector instructions sc is 0 or 1.  A lane's address is a
+// 64-bit part common to its block (base pointer + first row of the block's row step * sr, in
+// scalar registers) plus a 32-bit byte offset of its own (its row within the step and its
+// column): views may be of any size, only the TY rows of one step must span less than 4 GiB.
+// In the usual case every view that varies along both rows and columns shares ONE row stride
+// (row_stride of the parameter block): both parts are then computed once per row step and
+// serve every plane.  Otherwise (uniform_stride == 0: arguments or gradients that are slices
+// of wider buffers) a second instantiation of the kernels forms them per view from its own sr.
 struct TView {
   void *p;
   int64_t sr;
@@ -42,7 +44,7 @@ struct FwdTiledParams {
   int64_t branch_sr, branch_sc;
   int64_t arg_sr[BCAST_MAX_ARGS];  // row stride of every argument, in elements
   // When the full-shape views do not share one row stride (uniform_stride == 0) every view is
-  // addressed with its own: r * stride + column, still within 32-bit byte offsets.
+  // addressed with its own.
   int32_t uniform_stride;
   int64_t out_sr[BCAST_MAX_OUTS];
   int64_t part_sr[BCAST_MAX_PLANES];

@@ -41,14 +41,14 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
   const uint32_t col_off = g.colvalid ? (uint32_t)g.c0 * (uint32_t)sizeof(T) : 0u;
   uint32_t colinv_again = ra.col_invariant;
   asm volatile("" : "+s"(colinv_again));
-  uint32_t off = g.off0;
-  for (int k = 0; k < (LOOP ? p.steps : 1); ++k, off += g.off_step) {
+  for (int k = 0; k < (LOOP ? p.steps : 1); ++k) {
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
-    // lanes outside the problem read element 0; a view's offset is its own when the views do not
-    // share one row stride
-    auto voff = [&](int64_t sr) { return valid ? view_off<T, US>(off, r, sr, g.col_off) : 0u; };
+    const RowStep<T, US> rs = g.template step<US>(p, k);
+    // lanes outside the problem read the row step's first vector; a view's offset is its own when
+    // the views do not share one row stride
+    auto voff = [&](int64_t sr) { return valid ? rs.lane(sr) : 0u; };
     const int64_t r_ld = r < p.R ? r : 0;
     // Arguments.  Where the pattern fixes an argument's broadcast form the matching load is
     // issued unconditionally.  Otherwise (control inputs, run-time pattern) both forms go into
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
       constexpr int form = arg_form<Op, PATTERN>(j);
       avec[j] = LV(T(0));
       if constexpr (form == kFormFull)
-        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], voff(ra.arg_sr[j])));
+        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
       else if constexpr (form == kFormRowVector)
         avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], col_off));
       else if constexpr (form == kFormRuntime) {
@@ -74,12 +74,14 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
           // a control input beside unconditional loads: no branch either -- where the vector
           // form does not apply the lane reads the first adjoint's vector instead (valid
           // memory that is loaded anyway) and the result is replaced by zero bits
-          const LV x = load_lane_vec<T, VEC>(at<const T>(colinv ? p.adj[0].p : ra.arg_p[j],
-                                                         colinv ? voff(p.adj[0].sr)
-                                                                : ((ra.row_invariant >> j) & 1u) ? col_off : voff(ra.arg_sr[j])));
+          const bool rowinv = (ra.row_invariant >> j) & 1u;
+          const LV x = load_lane_vec<T, VEC>(colinv   ? at<const T>(rs.base(p.adj[0].p, p.adj[0].sr), voff(p.adj[0].sr))
+                                             : rowinv ? at<const T>(ra.arg_p[j], col_off)
+                                                      : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
           avec[j] = colinv ? LV(T(0)) : x;
         } else if (!colinv) {
-          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], ((ra.row_invariant >> j) & 1u) ? col_off : voff(ra.arg_sr[j])));
+          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(((ra.row_invariant >> j) & 1u) ? at<const T>(ra.arg_p[j], col_off)
+                                                                                           : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
         }
       }
     });
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
     });
     T adj[M][VEC];
 #pragma unroll
-    for (int i = 0; i < M; ++i) load_plane<T, VEC, true>(p.adj[i].p, view_off<T, US>(off, r, p.adj[i].sr, g.col_off), valid, adj[i]);
+    for (int i = 0; i < M; ++i) load_plane<T, VEC, true>(rs.base(p.adj[i].p, p.adj[i].sr), rs.lane(p.adj[i].sr), valid, adj[i]);
 #pragma unroll
     for (int j = 0; j < N; ++j)  // the opaque point after the last load
       if (arg_form<Op, PATTERN>(j) == kFormRuntime) {
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
         constexpr int fixed = (int)((PATTERN >> (3 * jd)) & 7u);
         const int cls = fixed ? fixed - 1 : en.cls;
         if (cls == kGradFull)
-          apply_full<T, VEC, M, true>(en, adj, P, view_off<T, US>(off, r, en.g.sr, g.col_off), valid, nt);
+          apply_full<T, VEC, M, true>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt);
         else if (cls == kGradRowSum)
           apply_rowsum<T, VEC, M>(p, g, en, adj, P, r, ri);
         else if (cls == kGradColSum)

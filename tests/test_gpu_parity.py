@@ -856,3 +856,84 @@ def test_hmlstm_stored_batch_by_hidden(dtype):
     for k in range(10):
         check_close(g1.grads[k].cpu().numpy(), want[k], f"one row per block, grad {k}")
     del bufs
+
+
+def test_planes_beyond_4_gib():
+    """33 300 x 32 768 fp32: every plane is 4.36 GB, so rows from 32 768 on lie beyond a 32-bit byte
+    offset.  The tiled kernels take the problem (a lane's offset counts from its row step's first
+    row); the oracle evaluates sampled rows on both sides of the 4 GiB line and sampled columns."""
+    op, R, C = "branchy5", 33300, 32768
+    gen = torch.Generator(device="cuda").manual_seed(4321)
+    A = torch.randn((R, C), device="cuda", generator=gen)
+    Bm = torch.rand((R, C), device="cuda", generator=gen) * 1.9 + 0.1
+    r = torch.randn((1, C), device="cuda", generator=gen)
+    s = torch.randn((R, 1), device="cuda", generator=gen)
+    t = torch.randn((1, 1), device="cuda", generator=gen)
+    adj = torch.randn((R, C), device="cuda", generator=gen)
+    dev = [A, Bm, r, s, t]
+    shapes = [tuple(x.shape) for x in dev]
+    fb = P.alloc_forward(op, dev, want_branch=True, staggered=False)
+    assert P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials, fb.branch)["path"] == 1
+    fb.run(dev)
+    bb = P.alloc_backward([adj], fb.partials, shapes, staggered=False)
+    info = P.bcast_dual_backward_plan([adj], fb.partials, bb.grads)
+    assert info["path"] == 1 and info["specialized"] == 1
+    bb.run([adj], fb.partials)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 32767, 32768, 32769, R - 1], rng.integers(0, R, 8)]))
+    cols = np.unique(np.concatenate([[0, C - 1], rng.integers(0, C, 6)]))
+    ridx, cidx = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    host = lambda x: x.cpu().numpy()
+    sub = [host(A[ridx]), host(Bm[ridx]), host(r), host(s[ridx]), host(t)]
+    o_out, o_parts, o_br = oracle.forward(op, sub, threads=16)
+    assert np.array_equal(host(fb.branch[ridx]), o_br)
+    check_close(host(fb.outs[0][ridx]), o_out[0], "value rows")
+    planes_rows = [host(p[ridx]) for p in fb.partials]
+    for k in range(5):
+        check_close(planes_rows[k], o_parts[k], f"plane {k} rows")
+    want = oracle.backward([host(adj[ridx])], planes_rows,
+                           [(len(rows), C), (len(rows), C), (1, C), (len(rows), 1), (1, 1)], threads=16)
+    planes_cols = [host(p[:, cidx]) for p in fb.partials]
+    wantc = oracle.backward([host(adj[:, cidx])], planes_cols,
+                            [(R, len(cols)), (R, len(cols)), (1, len(cols)), (R, 1), (1, 1)], threads=16)
+
+    def check_grads(g, what):
+        check_close(host(g[0][ridx]), want[0], f"{what} g_A rows")
+        check_close(host(g[1][ridx]), want[1], f"{what} g_B rows")
+        check_close(host(g[3][ridx]), want[3], f"{what} g_s rows")
+        check_close(host(g[2][:, cidx]), wantc[2], f"{what} g_r cols")
+        assert float(g[4].item()) == 0.0
+
+    check_grads(bb.grads, "class kernel")
+    # the kernel that reads the gradient table at run time
+    P.bcast_dual_set_tuning(5, 1)
+    try:
+        b2 = P.alloc_backward([adj], fb.partials, shapes, staggered=False)
+        assert P.bcast_dual_backward_plan([adj], fb.partials, b2.grads)["specialized"] == 0
+        b2.run([adj], fb.partials)
+        torch.cuda.synchronize()
+    finally:
+        P.bcast_dual_set_tuning(5, 0)
+    check_grads(b2.grads, "run-time table")
+    assert torch.equal(b2.grads[0], bb.grads[0]) and torch.equal(b2.grads[1], bb.grads[1])
+    del b2
+    # an adjoint with a row stride of its own (rows padded by 64 elements: 4.37 GB)
+    wide = torch.empty((R, C + 64), device="cuda")
+    adj_v = wide[:, :C]
+    adj_v.copy_(adj)
+    b3 = P.alloc_backward([adj_v], fb.partials, shapes, staggered=False)
+    assert P.bcast_dual_backward_plan([adj_v], fb.partials, b3.grads)["path"] == 1
+    b3.run([adj_v], fb.partials)
+    torch.cuda.synchronize()
+    check_grads(b3.grads, "padded adjoint")
+    assert torch.equal(b3.grads[0], bb.grads[0]) and torch.equal(b3.grads[1], bb.grads[1])
+    del b3, wide, adj_v
+    # recompute in reverse: no planes at all
+    for p_ in fb.partials:
+        p_.zero_()
+    rb = P.alloc_recompute(fb.op_id, dev, [adj], shapes, staggered=False)
+    assert P.bcast_dual_backward_recompute_plan(fb.op_id, dev, [adj], rb.grads)["path"] == 1
+    P.bcast_dual_backward_recompute(fb.op_id, dev, [adj], rb.grads, rb.workspace)
+    torch.cuda.synchronize()
+    check_grads(rb.grads, "recompute")

@@ -319,8 +319,8 @@ def _fwd_plan(op_name, dt, args, outs, parts):
 def test_alignment_and_offset_range_pick_the_access_width_and_the_kernel():
     """The planner (no memory is touched: the views point at addresses that are never
     dereferenced) narrows the vector width to what every pointer is aligned to, refuses
-    pointers not aligned to the element, and leaves the tiled kernels -- which address with
-    32-bit byte offsets -- for planes of 4 GiB and more."""
+    pointers not aligned to the element, and keeps the tiled kernels for planes of any size as long
+    as the rows of one block's row step span less than 4 GiB."""
     R, C = 512, 1024
     slot = 1 << 34  # written views must not overlap: every view gets an address range of its own
 
@@ -340,11 +340,32 @@ def test_alignment_and_offset_range_pick_the_access_width_and_the_kernel():
     # a row stride that is not a multiple of the vector width narrows it too
     rc, d = call(0, (R, C), stride=(C + 2, 1))
     assert rc == 0 and d["path"] == 1 and d["vec"] == 2
-    # 40000 x 30000 fp32 = 4.8 GB per plane: byte offsets no longer fit 32 bits
+    # Planes of any size: a lane's 32-bit byte offset counts from the first row of its block's row
+    # step, so only one step of rows has to span less than 4 GiB.  40000 x 30000 fp32 = 4.8 GB per plane:
     rc, d = call(0, (40000, 30000))
+    assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and d["ty"] == 1
+    rc, d = call(1, (70000, 16384))  # 9.2 GB per plane
+    assert rc == 0 and d["path"] == 1 and d["vec"] == 2
+    # short rows far apart: the 256 rows of one step would span 255 * 2^23 * 4 bytes > 4 GiB
+    rc, d = call(0, (4096, 512), stride=(1 << 23, 1))
     assert rc == 0 and d["path"] == 2
-    rc, d = call(0, (32768, 32764))  # 4 294 443 008 bytes < 2^32
-    assert rc == 0 and d["path"] == 1
+    rc, d = call(0, (4096, 512), stride=(1 << 21, 1))
+    assert rc == 0 and d["path"] == 1 and d["ty"] == 2
+    rc, d = call(0, (4096, 1024), stride=(1 << 30, 1))  # one row per step: any row stride
+    assert rc == 0 and d["path"] == 1 and d["ty"] == 1
+    # contiguous dims are fused only up to 2^28 elements, never into a row longer than the lanes
+    # can address: 16 x 4096 x 2^15 (8 GiB fp32) becomes [2^16 x 2^15], not one dim
+    mk = lambda k, shape: _rowmajor((k + 1) * slot * 4, shape)
+    big = (16, 4096, 1 << 15)
+    rc, d = _fwd_plan("cos_x", 0, [mk(0, big)], [mk(1, big)], [mk(2, big)])
+    assert rc == 0 and d["path"] == 1 and d["shape"] == [1 << 16, 1 << 15]
+    # ... and so is a long vector handed over as one dim, if a power of two divides it
+    vec1 = (3 << 29,)
+    rc, d = _fwd_plan("cos_x", 0, [mk(0, vec1)], [mk(1, vec1)], [mk(2, vec1)])
+    assert rc == 0 and d["path"] == 1 and d["shape"] == [8, 3 << 26]
+    odd = ((1 << 31) + 1,)
+    rc, d = _fwd_plan("cos_x", 0, [mk(0, odd)], [mk(1, odd)], [mk(2, odd)])
+    assert rc == 0 and d["path"] == 2
 
 
 def test_recompute_validation_on_the_host():
