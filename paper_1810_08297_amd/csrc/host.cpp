@@ -21,7 +21,7 @@ using namespace bd;
   hipError_t bd_fwd_tiled_##IDENT(int, int, const FwdTiledParams &, dim3, hipStream_t);             \
   hipError_t bd_fwd_generic_##IDENT(int, const FwdGenericParams &, dim3, hipStream_t);
 #define BD_DECLARE_RECOMPUTE(IDENT)                                                                            \
-  hipError_t bd_bwdr_tiled_##IDENT(int, int, bool, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, \
+  hipError_t bd_bwdr_tiled_##IDENT(int, int, int, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t,  \
                                    hipStream_t);                                                               \
   uint64_t bd_bwdr_pattern_##IDENT();
 #define BD_ARITY_LIST(X) \
@@ -70,7 +70,7 @@ struct OpDesc {
   const int8_t *alias;  // per plane: own index, index of an identical earlier plane, or -1 (always zero); nullptr: all distinct
   hipError_t (*tiled)(int, int, const FwdTiledParams &, dim3, hipStream_t);
   hipError_t (*generic)(int, const FwdGenericParams &, dim3, hipStream_t);
-  hipError_t (*recompute)(int, int, bool, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, hipStream_t);  // may be null
+  hipError_t (*recompute)(int, int, int, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, hipStream_t);  // may be null
   uint64_t (*recompute_pattern)();
   bool strided;  // the tiled forward kernel is also built for views with row strides of their own
 };
@@ -507,7 +507,7 @@ struct BwdPlan {
   uint64_t absent = 0;             // bit e*M + i: plane i of table entry e is absent
   uint64_t share = 0;              // 4 bits per table entry e: s + 1 if e has the very planes of an earlier entry s
   RecomputeArgs ra{};              // recompute mode only
-  bool fixed_pattern = false;      // recompute mode: the call has the op's compiled-in broadcast pattern
+  int fixed_pattern = 0;           // recompute mode: 1 = the call has the op's compiled-in broadcast pattern, 2 = that pattern transposed
   std::vector<BwdTiledParams> main;  // usually one launch
   std::vector<size_t> main_lds;
   dim3 grid{1, 1, 1};
@@ -713,7 +713,17 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     if (rop) {
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
       for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
-      plan.fixed_pattern = g_tune[kTuneRuntimeTable] == 0 && pattern == rop->recompute_pattern();
+      auto transposed = [](uint64_t q) {  // rows-only and columns-only swapped
+        uint64_t t = 0;
+        for (int j = 0; j < 20; ++j) {
+          uint64_t cl = (q >> (3 * j)) & 7u;
+          cl = cl == kGradRowSum + 1 ? kGradColSum + 1 : cl == kGradColSum + 1 ? kGradRowSum + 1 : cl;
+          t |= cl << (3 * j);
+        }
+        return t;
+      };
+      plan.fixed_pattern = g_tune[kTuneRuntimeTable] != 0 ? 0 : pattern == rop->recompute_pattern() ? 1
+                           : pattern == transposed(rop->recompute_pattern()) ? 2 : 0;
       // the fixed-pattern kernels take each argument's broadcast form from its gradient's class:
       // the argument's own strides must say the same (an expanded stride-0 view would not)
       for (int j = 0, jd = 0; j < NA && plan.fixed_pattern; ++j) {
@@ -721,11 +731,11 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         const TView tv = tview(c, a0 + j, v[a0 + j].p);
         const bool rows_fixed = cls[jd] == kGradColSum || cls[jd] == kGradAllSum;
         const bool cols_fixed = cls[jd] == kGradRowSum || cls[jd] == kGradAllSum;
-        if ((tv.sr == 0) != rows_fixed || (tv.sc == 0) != cols_fixed) plan.fixed_pattern = false;
+        if ((tv.sr == 0) != rows_fixed || (tv.sc == 0) != cols_fixed) plan.fixed_pattern = 0;
         ++jd;
       }
       if (plan.fixed_pattern && !any_rowwise) {
-        if (g_tune[kTuneBwdRows] > 1) plan.fixed_pattern = false;  // an explicit rows-per-block override needs the looping kernel
+        if (g_tune[kTuneBwdRows] > 1) plan.fixed_pattern = 0;  // an explicit rows-per-block override needs the looping kernel
         else steps = 1;                                  // that kernel has no row loop
       }
     }

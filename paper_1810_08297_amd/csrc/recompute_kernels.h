@@ -8,6 +8,8 @@
 
 namespace bd {
 
+template <class T> struct type_tag { using type = T; };
+
 // PATTERN: 0 = the class of every gradient is read from the table at run time; otherwise 3 bits
 // per differentiable argument (class + 1), and if no class sums over rows the block handles one
 // row step without a loop.
@@ -17,6 +19,17 @@ constexpr bool pattern_sums_rows(uint64_t pattern) {
     if (c == kGradColSum + 1 || c == kGradAllSum + 1) return true;
   }
   return false;
+}
+// the same op with every array transposed: row vectors become column vectors and back
+constexpr uint64_t transpose_pattern(uint64_t pattern) {
+  uint64_t q = 0;
+  for (int jd = 0; jd < 20; ++jd) {
+    uint64_t c = (pattern >> (3 * jd)) & 7u;
+    if (c == kGradRowSum + 1) c = kGradColSum + 1;
+    else if (c == kGradColSum + 1) c = kGradRowSum + 1;
+    q |= c << (3 * jd);
+  }
+  return q;
 }
 // How argument j reaches the lanes when the pattern is fixed at compile time: the class of its
 // gradient says along which dims it varies.  Control inputs have no gradient; their form, and
@@ -156,47 +169,41 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
   bwd_finalize<T, VEC>(p, g);
 }
 
+// fixed: 0 = the pattern is read at run time, 1 = the call has the op's compiled-in pattern,
+// 2 = it has that pattern transposed
 template <class Op>
-hipError_t launch_bwdr_tiled(int dt, int vec, bool fixed_pattern, const BwdTiledParams &p, const RecomputeArgs &ra,
+hipError_t launch_bwdr_tiled(int dt, int vec, int fixed, const BwdTiledParams &p, const RecomputeArgs &ra,
                              dim3 grid, size_t lds, hipStream_t s) {
-#define BD_GO(T, V, PAT) launch((bwdr_tiled_kernel<Op, T, V, PAT, true>), grid, dim3(kBlock), lds, s, p, ra)
-#define BD_GO_STRIDED(T, V, PAT) launch((bwdr_tiled_kernel<Op, T, V, PAT, false>), grid, dim3(kBlock), lds, s, p, ra)
-  if (!p.uniform_stride) {  // views with row strides of their own
-    if (dt == BCAST_F32) {
-      if (vec == 4) {
-        if (fixed_pattern) BD_GO_STRIDED(float, 4, Op::RECOMPUTE_PATTERN); else BD_GO_STRIDED(float, 4, 0ull);
-      } else {
-        BD_GO_STRIDED(float, 1, 0ull);
-      }
-    } else {
-      if (vec == 2) {
-        if (fixed_pattern) BD_GO_STRIDED(double, 2, Op::RECOMPUTE_PATTERN); else BD_GO_STRIDED(double, 2, 0ull);
-      } else {
-        BD_GO_STRIDED(double, 1, 0ull);
-      }
+  constexpr uint64_t PAT = Op::RECOMPUTE_PATTERN, PAT_T = transpose_pattern(Op::RECOMPUTE_PATTERN);
+  auto go = [&](auto type_tag, auto vec_tag, auto us_tag) {
+    using T = typename decltype(type_tag)::type;
+    constexpr int V = decltype(vec_tag)::value;
+    constexpr bool US = decltype(us_tag)::value;
+    if constexpr (V * sizeof(T) == 16) {  // the fixed patterns exist for the widest vector only
+      if (fixed == 1) return launch((bwdr_tiled_kernel<Op, T, V, PAT, US>), grid, dim3(kBlock), lds, s, p, ra);
+      if constexpr (PAT_T != PAT)
+        if (fixed == 2) return launch((bwdr_tiled_kernel<Op, T, V, PAT_T, US>), grid, dim3(kBlock), lds, s, p, ra);
     }
-  } else if (dt == BCAST_F32) {
-    if (vec == 4) {
-      if (fixed_pattern) BD_GO(float, 4, Op::RECOMPUTE_PATTERN); else BD_GO(float, 4, 0ull);
-    } else {
-      BD_GO(float, 1, 0ull);
-    }
+    launch((bwdr_tiled_kernel<Op, T, V, 0ull, US>), grid, dim3(kBlock), lds, s, p, ra);
+  };
+  auto with_stride = [&](auto type_tag, auto vec_tag) {
+    if (p.uniform_stride) go(type_tag, vec_tag, std::true_type{});
+    else go(type_tag, vec_tag, std::false_type{});  // views with row strides of their own
+  };
+  if (dt == BCAST_F32) {
+    if (vec == 4) with_stride(type_tag<float>{}, std::integral_constant<int, 4>{});
+    else with_stride(type_tag<float>{}, std::integral_constant<int, 1>{});
   } else {
-    if (vec == 2) {
-      if (fixed_pattern) BD_GO(double, 2, Op::RECOMPUTE_PATTERN); else BD_GO(double, 2, 0ull);
-    } else {
-      BD_GO(double, 1, 0ull);
-    }
+    if (vec == 2) with_stride(type_tag<double>{}, std::integral_constant<int, 2>{});
+    else with_stride(type_tag<double>{}, std::integral_constant<int, 1>{});
   }
-#undef BD_GO_STRIDED
-#undef BD_GO
   return hipGetLastError();
 }
 
 }  // namespace bd
 
 #define BD_DEFINE_OP_RECOMPUTE(OPTYPE, IDENT)                                                              \
-  hipError_t bd_bwdr_tiled_##IDENT(int dt, int vec, bool fixed, const bd::BwdTiledParams &p,               \
+  hipError_t bd_bwdr_tiled_##IDENT(int dt, int vec, int fixed, const bd::BwdTiledParams &p,                \
                                    const bd::RecomputeArgs &ra, dim3 g, size_t lds, hipStream_t s) {       \
     return bd::launch_bwdr_tiled<OPTYPE>(dt, vec, fixed, p, ra, g, lds, s);                                \
   }                                                                                                        \

@@ -846,6 +846,21 @@ def test_hmlstm_stored_batch_by_hidden(dtype):
     for k in range(10):
         check_close(gf.grads[k].cpu().numpy(), want[k], f"grad {k}")
         assert torch.equal(gf.grads[k], gl.grads[k])
+    # recompute in reverse: the op's compiled-in broadcast pattern, transposed, is compiled in too
+    rb = P.alloc_recompute(full.op_id, dev, adj_dev, shapes)
+    assert P.bcast_dual_backward_recompute_plan(full.op_id, dev, adj_dev, rb.grads)["specialized"] == 1
+    P.bcast_dual_backward_recompute(full.op_id, dev, adj_dev, rb.grads, rb.workspace)
+    P.bcast_dual_set_tuning(5, 1)
+    try:
+        r2 = P.alloc_recompute(full.op_id, dev, adj_dev, shapes)
+        assert P.bcast_dual_backward_recompute_plan(full.op_id, dev, adj_dev, r2.grads)["specialized"] == 0
+        P.bcast_dual_backward_recompute(full.op_id, dev, adj_dev, r2.grads, r2.workspace)
+        torch.cuda.synchronize()
+    finally:
+        P.bcast_dual_set_tuning(5, 0)
+    for k in range(10):
+        check_close(rb.grads[k].cpu().numpy(), want[k], f"recomputed grad {k}")
+        assert torch.equal(rb.grads[k], r2.grads[k]), f"pattern fixed at compile time against run time, grad {k}"
     # many partial sums per output: one row per block leaves 2100 of them for the second pass
     P.bcast_dual_set_tuning(1, 1)
     try:
