@@ -706,9 +706,20 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       for (int i = 0; i < M; ++i)
         planes_read += v[M + i * ND + order[e]].p != nullptr && !(e < 16 && ((plan.share >> (4 * e)) & 15u));
     const bool one_per_cu = class_kernel && planes_read < 16;
-    const int64_t rows_rowwise = one_per_cu ? std::max<int64_t>(8, std::min<int64_t>(256, s2.R * g.n_ct / 256))
-                                            : std::max<int64_t>(8, std::min<int64_t>(128, s2.R * g.n_ct / 512));
-    int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)ceil_div(rows_rowwise, TY) : auto_steps(s2.R, g, 4));
+    // Small problems want about one block per CU whatever the kernel (per-block set-up and the final
+    // combine weigh more than overlap): [512 x 2048] HM-LSTM, 1024 tiles of one row step, runs 23 us at
+    // 4 row steps per block, 26 us at 2, 29 us at 8; [256 x 1024] 11-13 us at 1 or 2, 19 us at 8.
+    const int64_t tiles = ceil_div(s2.R, TY) * g.n_ct;  // row steps x column chunks of the whole problem
+    int64_t steps_rowwise;
+    if (one_per_cu) {
+      steps_rowwise = std::min<int64_t>(256 / TY, tiles / 256);
+    } else {
+      steps_rowwise = tiles / 512;
+      if (steps_rowwise < 8) steps_rowwise = std::min<int64_t>(8, tiles / 256);
+      steps_rowwise = std::min<int64_t>(128 / TY, steps_rowwise);
+    }
+    steps_rowwise = std::max<int64_t>(1, steps_rowwise);
+    int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)steps_rowwise : auto_steps(s2.R, g, 4));
     if (class_kernel && !any_rowwise && g_tune[kTuneBwdRows] == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
