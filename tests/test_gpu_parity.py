@@ -952,3 +952,47 @@ def test_planes_beyond_4_gib():
     P.bcast_dual_backward_recompute(fb.op_id, dev, [adj], rb.grads, rb.workspace)
     torch.cuda.synchronize()
     check_grads(rb.grads, "recompute")
+
+
+def test_long_vector_and_dims_too_long_to_fuse():
+    """A dim of more than 2^28 elements is taken as rows of equal length (here 3 * 2^27 = 2 rows of
+    201 326 592), and contiguous dims are fused only up to that length ([2048 x 1024 x 160] stays
+    [2 097 152 x 160]): the scalar's gradient is a sum over all 402 653 184 / 335 544 320 elements."""
+    op = "scale_xt"
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    for shape, merged in (((3 << 27,), [2, 3 << 26]), ((2048, 1024, 160), [2048 * 1024, 160])):
+        n = int(np.prod(shape))
+        x = torch.randn(shape, device="cuda", generator=gen)
+        t = torch.full((1,) * len(shape), 1.25, device="cuda")
+        adj = torch.randn(shape, device="cuda", generator=gen)
+        dev = [x, t]
+        fb = P.alloc_forward(op, dev, staggered=False)
+        info = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials)
+        assert info["path"] == 1 and info["shape"] == merged, info
+        fb.run(dev)
+        bb = P.alloc_backward([adj], fb.partials, [tuple(x.shape), tuple(t.shape)], staggered=False)
+        info = P.bcast_dual_backward_plan([adj], fb.partials, bb.grads)
+        assert info["path"] == 1 and info["shape"] == merged, info
+        bb.run([adj], fb.partials)
+        torch.cuda.synchronize()
+        flat = lambda z: z.reshape(-1)
+        # elementwise results on slices at the start, across the middle (the seam of the two rows) and at the end
+        for lo, hi in ((0, 4096), (n // 2 - 2048, n // 2 + 2048), (n - 4096, n)):
+            sub = [flat(x)[lo:hi].cpu().numpy(), np.full((1,), 1.25, np.float32)]
+            o_out, o_parts, _ = oracle.forward(op, sub, threads=4)
+            check_close(flat(fb.outs[0])[lo:hi].cpu().numpy(), o_out[0], f"{shape} out [{lo}:{hi}]")
+            for k in range(2):
+                check_close(flat(fb.partials[k])[lo:hi].cpu().numpy(), o_parts[k], f"{shape} plane {k} [{lo}:{hi}]")
+            want = oracle.backward([flat(adj)[lo:hi].cpu().numpy()], [flat(p_)[lo:hi].cpu().numpy() for p_ in fb.partials],
+                                   [(hi - lo,), (hi - lo,)], threads=4)
+            check_close(flat(bb.grads[0])[lo:hi].cpu().numpy(), want[0], f"{shape} g_x [{lo}:{hi}]")
+        # the full sum, by the oracle over every element
+        want = oracle.backward([flat(adj).cpu().numpy()], [flat(p_).cpu().numpy() for p_ in fb.partials], [(n,), (1,)], threads=16)
+        check_close(bb.grads[1].cpu().numpy().reshape(1), want[1].reshape(1), f"{shape} g_t")
+        # recompute in reverse takes the same split
+        rb = P.alloc_recompute(fb.op_id, dev, [adj], [tuple(x.shape), tuple(t.shape)], staggered=False)
+        P.bcast_dual_backward_recompute(fb.op_id, dev, [adj], rb.grads, rb.workspace)
+        torch.cuda.synchronize()
+        assert torch.equal(rb.grads[0], bb.grads[0])
+        check_close(rb.grads[1].cpu().numpy().reshape(1), want[1].reshape(1), f"{shape} recomputed g_t")
+        del x, adj, fb, bb, rb
