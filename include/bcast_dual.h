@@ -173,8 +173,8 @@ int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *
  * each gradient exactly as bcast_dual_backward does.
  * args[n_args] as in forward; adjoints[n_out] of the unified shape; grads[n_grads = N_d] in their
  * argument's shape (NULL data: skipped; any other shape: BCAST_ERR_OUTPUT_SHAPE_MISMATCH).  Available for problems that merge to at most two dims
- * with unit inner stride (the tiled kernels) and for every op except the prod_tanh_K family;
- * otherwise BCAST_ERR_UNSUPPORTED.  Workspace rules as for bcast_dual_backward. */
+ * with unit inner stride (the tiled kernels), for every op (the prod_tanh_K family only where all
+ * full-shape views share one row stride); otherwise BCAST_ERR_UNSUPPORTED.  Workspace rules as for bcast_dual_backward. */
 size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                                int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
                                                const bcast_tensor *grads);

@@ -5,7 +5,10 @@
 D(f).(x_1 .. x_N) with f = prod_i tanh(g(x_i)), g(x) = x if x > 1/2 else -x, every x_j an
 n x n fp32 matrix: the dual-number forward kernel reads N planes and writes 1 + N, and its
 register use grows with N.  Prints per arity the forward and backward times (HIP events on
-the launch stream, median of 50) and the achieved fraction of the HBM peak.
+the launch stream, median of 50) and the achieved fraction of the HBM peak, and beside them
+the other side of the trade-off at the end of Sec. 2.2.3: no planes kept, a values-only
+forward (reads N, writes 1) and a backward that evaluates the dual numbers again (reads
+N + 1, writes N) -- N^2 arithmetic against 2 N planes of traffic.
 """
 from __future__ import annotations
 
@@ -37,7 +40,8 @@ def main():
         torch.cuda.synchronize()
         return float(np.median([x.elapsed_time(y) for x, y in ev[5:]])) * 1e3
 
-    print(f"{'N':>3s} {'fwd us':>9s} {'fwd GB/s':>9s} {'% peak':>7s} {'bwd us':>9s} {'bwd GB/s':>9s} {'% peak':>7s}")
+    print(f"{'N':>3s} {'fwd us':>9s} {'fwd GB/s':>9s} {'% peak':>7s} {'bwd us':>9s} {'bwd GB/s':>9s} {'% peak':>7s} |"
+          f" {'values us':>9s} {'recomp us':>9s} {'GB/s':>8s} {'no planes / planes':>18s}")
     for k in range(1, a.max_arity + 1):
         xs, adj = inputs.prod_tanh_inputs(k, a.n, a.n, seed=inputs.BASE_SEED + 200 + k)
         dev, _s1 = P.to_slab([torch.from_numpy(x).cuda() for x in xs])
@@ -48,9 +52,16 @@ def main():
         tf = median_us(lambda: f.launch())
         tb = median_us(lambda: b.launch())
         fbytes, bbytes = (2 * k + 1) * E * 4, (2 * k + 1) * E * 4
+        fv = P.alloc_forward(f"prod_tanh_{k}", dev, want_partials=False)
+        rb = P.alloc_recompute(fb.op_id, dev, adj_dev, [x.shape for x in xs])
+        v, r = fv.prepare(dev), P.PreparedRecompute(fb.op_id, dev, adj_dev, rb.grads, rb.workspace)
+        tv = median_us(lambda: v.launch())
+        tr = median_us(lambda: r.launch())
+        rbytes = (2 * k + 1) * E * 4
         print(f"{k:3d} {tf:9.2f} {fbytes / tf / 1e3:9.1f} {fbytes / tf / 1e3 / 80:7.1f} {tb:9.2f} "
-              f"{bbytes / tb / 1e3:9.1f} {bbytes / tb / 1e3 / 80:7.1f}", flush=True)
-        del dev, _s1, fb, bb, f, b
+              f"{bbytes / tb / 1e3:9.1f} {bbytes / tb / 1e3 / 80:7.1f} | {tv:9.2f} {tr:9.2f} {rbytes / tr / 1e3:8.1f} "
+              f"{(tv + tr) / (tf + tb):18.2f}", flush=True)
+        del dev, _s1, fb, bb, f, b, fv, rb, v, r
         torch.cuda.empty_cache()
 
 

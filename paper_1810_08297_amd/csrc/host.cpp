@@ -43,7 +43,7 @@ BD_DECLARE_RECOMPUTE(scale_xt)
 BD_DECLARE_RECOMPUTE(pair3)
 BD_DECLARE_RECOMPUTE(linear12)
 #ifndef BD_NO_ARITY
-#define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K)
+#define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K) BD_DECLARE_RECOMPUTE(prod_tanh_##K)
 BD_ARITY_LIST(BD_DECL_ARITY)
 #endif
 
@@ -86,7 +86,8 @@ const int8_t kAliasBranchy5[5] = {0, 1, 2, 3, -1};
 #define BD_OP_ROW_A(NAME, N, M, NONDIFF, NBR, ALIAS) \
   {#NAME, N, M, NONDIFF, NBR, ALIAS, bd_fwd_tiled_##NAME, bd_fwd_generic_##NAME, bd_bwdr_tiled_##NAME, bd_bwdr_pattern_##NAME, true},
 #define BD_ARITY_ROW(K) \
-  {"prod_tanh_" #K, K, 1, 0u, K + 1, nullptr, bd_fwd_tiled_prod_tanh_##K, bd_fwd_generic_prod_tanh_##K, nullptr, nullptr, false},
+  {"prod_tanh_" #K, K, 1, 0u, K + 1, nullptr, bd_fwd_tiled_prod_tanh_##K, bd_fwd_generic_prod_tanh_##K, bd_bwdr_tiled_prod_tanh_##K, \
+   bd_bwdr_pattern_prod_tanh_##K, false},
 const OpDesc kOps[] = {
     BD_OP_ROW_A(hmlstm_update, 12, 2, (1u << 6) | (1u << 7), 3, kAliasHmLstm)
     BD_OP_ROW(tanh_xy_b, 3, 1, 0u, 1)
@@ -627,7 +628,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
   const bool uniform_stride = bwd_sr >= 0;
   if (!uniform_stride) bwd_sr = 0;
   plan.tiled = tiled;
-  if (rop && !tiled) return BCAST_ERR_UNSUPPORTED;
+  if (rop && (!tiled || (!uniform_stride && !rop->strided))) return BCAST_ERR_UNSUPPORTED;
   if (tiled) {
     int vw = (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es);
     for (; vw > 1; vw /= 2) {
@@ -742,7 +743,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         const TView tv = tview(c, a0 + j, v[a0 + j].p);
         const bool rows_fixed = cls[jd] == kGradColSum || cls[jd] == kGradAllSum;
         const bool cols_fixed = cls[jd] == kGradRowSum || cls[jd] == kGradAllSum;
-        if ((tv.sr == 0) != rows_fixed || (tv.sc == 0) != cols_fixed) plan.fixed_pattern = 0;
+        if ((s2.R > 1 && (tv.sr == 0) != rows_fixed) || (s2.C > 1 && (tv.sc == 0) != cols_fixed)) plan.fixed_pattern = 0;
         ++jd;
       }
       if (plan.fixed_pattern && !any_rowwise) {

@@ -166,6 +166,12 @@ struct OpProdTanh {
   static constexpr int N = ARITY, M = 1, NBR = ARITY + 1;
   static constexpr uint32_t NONDIFF = 0u;
   static constexpr bool STRIDED = false;
+  static constexpr uint64_t all_full() {
+    uint64_t q = 0;
+    for (int j = 0; j < ARITY; ++j) q |= 1ull << (3 * j);
+    return q;
+  }
+  static constexpr uint64_t RECOMPUTE_PATTERN = all_full();
   template <class X>
   static BD_DEV X g(const X &x) {
     using T = typename X::value_type;

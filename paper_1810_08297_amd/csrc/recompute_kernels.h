@@ -186,9 +186,10 @@ hipError_t launch_bwdr_tiled(int dt, int vec, int fixed, const BwdTiledParams &p
     }
     launch((bwdr_tiled_kernel<Op, T, V, 0ull, US>), grid, dim3(kBlock), lds, s, p, ra);
   };
+  if (!p.uniform_stride && !Op::STRIDED) return hipErrorNotSupported;  // the host refuses such calls
   auto with_stride = [&](auto type_tag, auto vec_tag) {
     if (p.uniform_stride) go(type_tag, vec_tag, std::true_type{});
-    else go(type_tag, vec_tag, std::false_type{});  // views with row strides of their own
+    else if constexpr (Op::STRIDED) go(type_tag, vec_tag, std::false_type{});  // views with row strides of their own
   };
   if (dt == BCAST_F32) {
     if (vec == 4) with_stride(type_tag<float>{}, std::integral_constant<int, 4>{});

@@ -400,7 +400,20 @@ def test_recompute_validation_on_the_host():
     assert run(op, args, [full()], grads, dt=7) == -7
     assert run(op, args, [full((R, C + 1))], grads) == -6
     assert run(op, args, [full()], [full(), full(), full((1, C))]) == -6  # b is [R x 1]: its gradient too
-    assert run(P.bcast_op_lookup("prod_tanh_3"), [full(), full(), full()], [full()], [full(), full(), full()]) == -12  # no recompute kernel
+    # the arity ops: planned like any other (the plan call launches nothing), but they have no
+    # kernels for views with row strides of their own
+    pt3 = P.bcast_op_lookup("prod_tanh_3")
+    info = B.PlanInfo()
+
+    def plan3(a):
+        adj3, g3 = [full()], [full(), full(), full()]
+        return L.bcast_dual_backward_recompute_plan(ctypes.c_int32(pt3), ctypes.c_int(0), ctypes.c_int32(3), B._views(a),
+                                                    ctypes.c_int32(1), B._views(adj3), ctypes.c_int32(3), B._views(g3),
+                                                    ctypes.byref(info))
+
+    assert plan3([full(), full(), full()]) == 0 and info.path == 1 and info.specialized == 1
+    padded = B.raw_view(base + (1 << 36), (R, C), (C + 8, 1))
+    assert plan3([padded, full(), full()]) == -12
     # a transposed argument has no tiled layout: refused, the cached-plane path still serves it
     assert run(op, [B.raw_view(base, (R, C), (1, R)), full(), args[2]], [full()], grads) == -12
 
