@@ -1023,3 +1023,46 @@ def test_long_vector_and_dims_too_long_to_fuse():
         assert torch.equal(rb.grads[0], bb.grads[0])
         check_close(rb.grads[1].cpu().numpy().reshape(1), want[1].reshape(1), f"{shape} recomputed g_t")
         del x, adj, fb, bb, rb
+
+
+def _random_2d_case(seed, dtype):
+    """A 2-D problem of up to a few million elements -- several row tiles and column chunks, ragged
+    edges -- with every argument's broadcast form (full, row vector, column vector, scalar) drawn at
+    random, control inputs included, and some views with padded rows."""
+    rng = np.random.default_rng(31000 + seed)
+    op = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "pair3", "linear12"][seed % 6]
+    n_args = oracle.op_info(op)[0]
+    R = int(rng.choice([1, 7, 64, 255, 1000, 2047]))
+    C = int(rng.choice([1, 5, 64, 260, 1024, 2048, 4100]))
+    control = {"hmlstm_update": (6, 7), "linear12": (6, 7), "update_c": (4, 5)}.get(op, ())
+    args = []
+    for j in range(n_args):
+        form = 0 if j == 0 else int(rng.choice([0, 0, 1, 2, 3]))  # the first argument spans the output
+        s = [(R, C), (1, C), (R, 1), (1, 1)][form]
+        if j in control:
+            a = (rng.random(s) < 0.45).astype(dtype)
+        else:
+            a = rng.standard_normal(s).astype(dtype)
+        if op == "pair3" and j == 1:
+            a = (np.abs(a) + 0.5).astype(dtype)
+        if op == "branchy5" and j == 1:
+            a = rng.uniform(0.1, 2, s).astype(dtype)
+        args.append(a)
+    adj = [rng.standard_normal((R, C)).astype(dtype) for _ in range(oracle.op_info(op)[1])]
+    padded = rng.random(n_args) < 0.25
+
+    def view(t, k):
+        if padded[k] and t.shape[-1] > 1:  # rows padded by eight elements: a row stride of its own
+            wide = torch.empty(t.shape[0], t.shape[1] + 8, dtype=t.dtype, device=t.device)
+            wide[:, :t.shape[1]] = t
+            return wide[:, :t.shape[1]]
+        return t
+
+    return op, args, adj, view, (R, C), [a.shape for a in args]
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_random_2d_problems_of_many_tiles(dtype):
+    for seed in range(36):
+        op, args, adj, view, shape, forms = _random_2d_case(seed, dtype)
+        check_op(op, args, adj, view=view, threads=16, what=f"[case {seed}: {op} {shape} argument shapes {forms}] ")
