@@ -162,14 +162,15 @@ int check_view(const bcast_tensor &t, size_t esize, bool allow_null, bool writte
   }
   if (written && t.data != nullptr) {
     // every written element must have its own address
-    std::vector<std::pair<int64_t, int64_t>> se;
+    std::array<std::pair<int64_t, int64_t>, BCAST_MAX_DIMS> se;
+    int n = 0;
     for (int d = 0; d < t.ndim; ++d)
-      if (t.shape[d] > 1) se.emplace_back(t.stride[d], t.shape[d]);
-    std::sort(se.begin(), se.end());
+      if (t.shape[d] > 1) se[n++] = {t.stride[d], t.shape[d]};
+    std::sort(se.begin(), se.begin() + n);
     int64_t reach = 0;
-    for (auto &q : se) {
-      if (q.first <= reach) return BCAST_ERR_BAD_STRIDE;
-      reach += (q.second - 1) * q.first;
+    for (int q = 0; q < n; ++q) {
+      if (se[q].first <= reach) return BCAST_ERR_BAD_STRIDE;
+      reach += (se[q].second - 1) * se[q].first;
     }
   }
   return BCAST_OK;
@@ -186,45 +187,51 @@ struct Canon {
 
 constexpr int64_t kMaxFused = (int64_t)1 << 28;
 void canonicalize(int D, const Dims &U, const std::vector<Dims> &eff, int key, Canon &c) {
-  std::vector<int> order;
+  int order[BCAST_MAX_DIMS], n_order = 0;
   for (int d = 0; d < D; ++d)
-    if (U[d] > 1) order.push_back(d);
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return eff[key][a] > eff[key][b]; });
-  std::vector<int64_t> shp;
-  std::vector<Dims> st(eff.size());
-  std::vector<std::vector<int64_t>> cur(eff.size());
-  for (int d : order) {
+    if (U[d] > 1) order[n_order++] = d;
+  std::stable_sort(order, order + n_order, [&](int a, int b) { return eff[key][a] > eff[key][b]; });
+  // merged dims so far: extents in shp, per-tensor strides in cur (no allocation per tensor:
+  // this runs on every call)
+  const size_t nt = eff.size();
+  int64_t shp[BCAST_MAX_DIMS];
+  int n = 0;
+  std::vector<Dims> &cur = c.strides;
+  cur.assign(nt, Dims{{0, 0, 0, 0}});
+  for (int q = 0; q < n_order; ++q) {
+    const int d = order[q];
     // a fused dim stays below 2^28 elements: the tiled kernels address a row with 32-bit byte offsets
-    bool merge = !shp.empty() && shp.back() <= kMaxFused / U[d];
+    bool merge = n > 0 && shp[n - 1] <= kMaxFused / U[d];
     if (merge)
-      for (size_t t = 0; t < eff.size() && merge; ++t) merge = (cur[t].back() == eff[t][d] * U[d]);
+      for (size_t t = 0; t < nt && merge; ++t) merge = (cur[t][n - 1] == eff[t][d] * U[d]);
     if (merge) {
-      shp.back() *= U[d];
-      for (size_t t = 0; t < eff.size(); ++t) cur[t].back() = eff[t][d];
+      shp[n - 1] *= U[d];
+      for (size_t t = 0; t < nt; ++t) cur[t][n - 1] = eff[t][d];
     } else {
-      shp.push_back(U[d]);
-      for (size_t t = 0; t < eff.size(); ++t) cur[t].push_back(eff[t][d]);
+      shp[n] = U[d];
+      for (size_t t = 0; t < nt; ++t) cur[t][n] = eff[t][d];
+      ++n;
     }
   }
   // one dim longer than that (a long vector, or dims the caller had fused already): taken as rows
   // of equal length if a power of two up to 2^16 divides it suitably
-  if (shp.size() == 1 && shp[0] > kMaxFused)
+  if (n == 1 && shp[0] > kMaxFused)
     for (int64_t f = 2; f <= 65536; f *= 2)
       if (shp[0] % f == 0 && shp[0] / f <= kMaxFused) {
         const int64_t inner = shp[0] / f;
-        shp = {f, inner};
-        for (size_t t = 0; t < eff.size(); ++t) cur[t] = {cur[t][0] * inner, cur[t][0]};
+        shp[0] = f;
+        shp[1] = inner;
+        n = 2;
+        for (size_t t = 0; t < nt; ++t) cur[t] = Dims{{cur[t][0] * inner, cur[t][0], 0, 0}};
         break;
       }
-  c.nd = (int)shp.size();
+  c.nd = n;
   c.E = 1;
-  for (int d = 0; d < c.nd; ++d) {
+  c.shape = Dims{{1, 1, 1, 1}};
+  for (int d = 0; d < n; ++d) {
     c.shape[d] = shp[d];
     c.E *= shp[d];
   }
-  c.strides.assign(eff.size(), Dims{{0, 0, 0, 0}});
-  for (size_t t = 0; t < eff.size(); ++t)
-    for (int d = 0; d < c.nd; ++d) c.strides[t][d] = cur[t][d];
 }
 
 // rows / columns of a merged problem of rank <= 2, and one tensor's strides in it
@@ -374,6 +381,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
 
   // effective strides: stride 0 wherever an argument's dim is 1 (virtual copy)
   std::vector<Dims> eff;
+  eff.reserve(v.size() + 1);
   for (auto &pv : v) eff.push_back(pv.p ? pv.stride : v[N].stride);  // absent planes never block a merge
   const bool want_branch = branch_id != nullptr;
   if (want_branch) {  // row-major over the unified shape as given
