@@ -1066,3 +1066,40 @@ def test_random_2d_problems_of_many_tiles(dtype):
     for seed in range(36):
         op, args, adj, view, shape, forms = _random_2d_case(seed, dtype)
         check_op(op, args, adj, view=view, threads=16, what=f"[case {seed}: {op} {shape} argument shapes {forms}] ")
+
+
+def test_two_streams_run_independent_problems():
+    """Calls enqueue only on the stream they are given and share no device state: two problems
+    issued alternately on two streams (default priority) give, bit for bit, what each gives alone
+    -- second reduction passes and their workspaces included."""
+    cases = [("branchy5", 700, 2100, 3), ("hmlstm_update", 1500, 520, 4)]
+    work = []
+    for op, R, C, seed in cases:
+        args, adj = small_args(op, R, C, np.float32, seed=seed)
+        dev, adj_dev = [to_dev(a) for a in args], [to_dev(a) for a in adj]
+        didx = oracle.diff_arg_indices(op, len(args))
+        shapes = [args[j].shape for j in didx]
+        fb = P.alloc_forward(op, dev)
+        bb = P.alloc_backward(adj_dev, fb.partials, shapes)
+        fb.run(dev)
+        bb.run(adj_dev, fb.partials)
+        torch.cuda.synchronize()
+        alone = [t.clone() for t in fb.outs + fb.partials + bb.grads]
+        work.append((dev, adj_dev, fb, bb, alone))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(5):
+        for dev, adj_dev, fb, bb, _ in work:
+            for t in fb.outs + fb.partials + bb.grads:
+                t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for k in range(2):  # forward calls first, then the backward calls, each on its problem's stream
+            dev, adj_dev, fb, bb, _ = work[k]
+            fb.run(dev, stream=streams[k])
+        for k in (1, 0):
+            dev, adj_dev, fb, bb, _ = work[k]
+            bb.run(adj_dev, fb.partials, stream=streams[k])
+        for s_ in streams:
+            s_.synchronize()
+        for dev, adj_dev, fb, bb, alone in work:
+            for got, want in zip(fb.outs + fb.partials + bb.grads, alone):
+                assert torch.equal(got, want), f"repetition {rep}"
