@@ -24,6 +24,58 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c_and_a_c_program_links(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit includes the header, links against the
+    library and calls entry points that touch no device (op table, plan of a call)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "client.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include <string.h>
+#include "bcast_dual.h"
+static bcast_tensor view(void *p, long long r, long long c) {
+  bcast_tensor t; memset(&t, 0, sizeof t);
+  t.data = p; t.ndim = 2; t.shape[0] = r; t.shape[1] = c; t.stride[0] = c; t.stride[1] = 1;
+  return t;
+}
+int main(void) {
+  int32_t op = -1, n_args = 0, n_out = 0, n_br = 0; uint32_t mask = 0;
+  bcast_tensor args[3], outs[1], parts[3];
+  bcast_plan_info info;
+  char *base = (char *)0;  /* addresses are planned with, never dereferenced */
+  int k;
+  if (bcast_op_lookup("tanh_xy_b", &op) != BCAST_OK) return 1;
+  if (bcast_op_info(op, &n_args, &n_out, &mask, &n_br) != BCAST_OK || n_args != 3 || n_out != 1) return 2;
+  args[0] = view(base + (1 << 24), 512, 1024); args[1] = view(base + (2 << 24), 512, 1024);
+  args[2] = view(base + (3 << 24), 512, 1);
+  outs[0] = view(base + (4 << 24), 512, 1024);
+  for (k = 0; k < 3; ++k) parts[k] = view(base + ((5 + k) << 24), 512, 1024);
+  if (bcast_dual_forward_plan(op, BCAST_F32, 3, args, 1, outs, parts, NULL, &info) != BCAST_OK) return 3;
+  printf("%d %d %lld %lld %s\n", (int)info.path, (int)info.vec, (long long)info.shape[0], (long long)info.shape[1],
+         bcast_status_string(BCAST_ERR_WORKSPACE_TOO_SMALL));
+  return 0;
+}
+""")
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(B.LIB_PATH)
+    libname = os.path.basename(B.LIB_PATH)
+    B.lib()  # the library (and the HIP runtime it needs) is loadable here
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+           "-o", str(exe), "-L", libdir, "-l:" + libname, "-Wl,-rpath," + libdir, "-Wl,--allow-shlib-undefined"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    env = dict(os.environ)
+    torch_lib = os.path.join(os.path.dirname(torch.__file__), "lib")
+    env["LD_LIBRARY_PATH"] = os.pathsep.join([torch_lib, "/opt/rocm/lib", env.get("LD_LIBRARY_PATH", "")])
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    path, vec, rows, cols, msg = r.stdout.split(maxsplit=4)
+    assert (int(path), int(vec), int(rows), int(cols)) == (1, 4, 512, 1024) and "workspace" in msg
+
+
 def test_op_table():
     names = [P.bcast_op_name(k) for k in range(P.bcast_op_count())]
     for n in ("hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3",
