@@ -540,3 +540,73 @@ def test_gradients_match_library_reverse_mode_on_select_form(op):
         np.testing.assert_allclose(g.detach().numpy(), w, rtol=1e-13, atol=1e-14)
     for g, w in zip(grads, want):
         np.testing.assert_allclose(g.numpy().reshape(w.shape), w, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- 60-digit arithmetic
+def _dec_values():
+    """The ops' VALUES only, written out in decimal arithmetic of 60 digits (Python's decimal
+    module: its exp and ln are correctly rounded at the context's precision).  `ctl` holds the
+    unperturbed arguments: predicates read those (Sec. 2.2.1: a comparison of dual numbers
+    compares the value parts), so that a perturbed evaluation stays on the branch of the point."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    one = Decimal(1)
+    sig = lambda x: one / (one + (-x).exp())
+    tanh = lambda x: (one - (-2 * x).exp()) / (one + (-2 * x).exp())
+
+    def tanh_xy_b(a, ctl):
+        x, y, b = a
+        return [tanh(x * y + b)]
+
+    def branchy5(a, ctl):
+        A, B, r, s, t = a
+        if ctl[0] + ctl[3] > ctl[4]:
+            return [(-A).exp() * B + r]
+        return [(one + A * A).ln() * r - s]
+
+    def hmlstm_update(a, ctl):
+        f, i, o, g, c, h, z, zb, bf, bi, bo, bg = a
+        if ctl[6] == 1:                        # FLUSH
+            cn = sig(i + bi) * tanh(g + bg)
+        elif ctl[6] == 0 and ctl[7] == 0:      # COPY
+            return [c, h]
+        else:                                  # UPDATE
+            cn = sig(f + bf) * c + sig(i + bi) * tanh(g + bg)
+        return [cn, sig(o + bo) * tanh(cn)]
+
+    return {"tanh_xy_b": (tanh_xy_b, ()), "branchy5": (branchy5, ()), "hmlstm_update": (hmlstm_update, (6, 7))}
+
+
+@pytest.mark.parametrize("op", ["tanh_xy_b", "branchy5", "hmlstm_update"])
+def test_fp64_outputs_match_sixty_digit_values_and_their_difference_quotients(op):
+    """Every value the oracle returns in fp64 is the 60-digit value rounded to fp64, and every
+    partial is the 60-digit central difference quotient of the value function (step 1e-25: the
+    quotient is the derivative to some 45 digits), both to within one unit in the last place.  The
+    derivative formulas of the oracle appear nowhere in this test."""
+    from decimal import Decimal
+    value_fn, control = _dec_values()[op]
+    rng = np.random.default_rng(606)
+    R, C = 5, 7
+    args = random_args(op, R, C, np.float64, rng)
+    outs, parts, _ = oracle.forward(op, args)
+    M = len(outs)
+    diff = [j for j in range(len(args)) if j not in control]
+    nd = len(diff)
+    assert len(parts) == M * nd
+    h = Decimal("1e-25")
+    ulp, tiny = Decimal("2.3e-16"), Decimal("1e-300")
+    for r in range(R):
+        for c in range(C):
+            x = [Decimal(float(np.broadcast_to(a, (R, C))[r, c])) for a in args]
+            vals = value_fn(x, x)
+            for i in range(M):
+                assert abs(Decimal(float(outs[i][r, c])) - vals[i]) <= max(abs(vals[i]) * ulp, tiny), (op, r, c, i)
+            for jd, j in enumerate(diff):
+                up, dn = list(x), list(x)
+                up[j] += h
+                dn[j] -= h
+                vu, vd = value_fn(up, x), value_fn(dn, x)
+                for i in range(M):
+                    want = (vu[i] - vd[i]) / (2 * h)
+                    got = Decimal(float(parts[i * nd + jd][r, c]))
+                    assert abs(got - want) <= max(abs(want) * ulp, Decimal("1e-40")), (op, r, c, i, j, float(got), str(want))
