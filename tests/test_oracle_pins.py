@@ -574,27 +574,65 @@ def _dec_values():
             cn = sig(f + bf) * c + sig(i + bi) * tanh(g + bg)
         return [cn, sig(o + bo) * tanh(cn)]
 
-    return {"tanh_xy_b": (tanh_xy_b, ()), "branchy5": (branchy5, ()), "hmlstm_update": (hmlstm_update, (6, 7))}
+    def update_c(a, ctl):  # the paper's cell update, Sec. 3.2.3: arguments c f i g z1 z2
+        c, f, i, g, z1, z2 = a
+        if ctl[4] == 1:
+            return [sig(i) * tanh(g)]
+        if ctl[4] == 0 and ctl[5] == 0:
+            return [c]
+        return [sig(f) * c + sig(i) * tanh(g)]
+
+    def series(x, first):  # sin (first = 1) or cos (first = 0) by their power series, |x| < 8
+        term = x if first else one
+        total, k = term, first
+        while abs(term) > Decimal("1e-70"):
+            k += 2
+            term = -term * x * x / (k * (k - 1))
+            total += term
+        return total
+
+    def cos_x(a, ctl):
+        return [series(a[0], 0)]
+
+    def scale_xt(a, ctl):
+        return [a[0] * a[1]]
+
+    def pair3(a, ctl):
+        return [a[0] * a[1] + series(a[2], 1), a[0] / a[1] - a[2] * a[2]]
+
+    def prod_tanh(a, ctl):  # Sec. 3.4.1
+        p = one
+        for x, x0 in zip(a, ctl):
+            p *= tanh(x if x0 > Decimal("0.5") else -x)
+        return [p]
+
+    return {"tanh_xy_b": (tanh_xy_b, ()), "branchy5": (branchy5, ()), "hmlstm_update": (hmlstm_update, (6, 7)),
+            "update_c": (update_c, (4, 5)), "cos_x": (cos_x, ()), "scale_xt": (scale_xt, ()), "pair3": (pair3, ()),
+            "prod_tanh": (prod_tanh, ())}
 
 
-@pytest.mark.parametrize("op", ["tanh_xy_b", "branchy5", "hmlstm_update"])
+@pytest.mark.parametrize("op", ["tanh_xy_b", "branchy5", "hmlstm_update", "update_c", "cos_x", "scale_xt", "pair3", "prod_tanh"])
 def test_fp64_outputs_match_sixty_digit_values_and_their_difference_quotients(op):
     """Every value the oracle returns in fp64 is the 60-digit value rounded to fp64, and every
     partial is the 60-digit central difference quotient of the value function (step 1e-25: the
-    quotient is the derivative to some 45 digits), both to within one unit in the last place.  The
-    derivative formulas of the oracle appear nowhere in this test."""
+    quotient is the derivative to some 45 digits), both to within one unit in the last place (two
+    for the ops that call sin and cos).  The derivative formulas of the oracle appear nowhere in
+    this test."""
     from decimal import Decimal
     value_fn, control = _dec_values()[op]
     rng = np.random.default_rng(606)
     R, C = 5, 7
-    args = random_args(op, R, C, np.float64, rng)
+    if op == "prod_tanh":
+        args = [rng.standard_normal((R, C)) + 0.5 for _ in range(4)]
+    else:
+        args = random_args(op, R, C, np.float64, rng)
     outs, parts, _ = oracle.forward(op, args)
     M = len(outs)
     diff = [j for j in range(len(args)) if j not in control]
     nd = len(diff)
     assert len(parts) == M * nd
     h = Decimal("1e-25")
-    ulp, tiny = Decimal("2.3e-16"), Decimal("1e-300")
+    ulp, tiny = Decimal("4.5e-16") if op in ("cos_x", "pair3") else Decimal("2.3e-16"), Decimal("1e-300")
     for r in range(R):
         for c in range(C):
             x = [Decimal(float(np.broadcast_to(a, (R, C))[r, c])) for a in args]
