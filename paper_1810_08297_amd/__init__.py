@@ -12,3 +12,4 @@ from .binding import (  # noqa: F401
     bcast_dual_backward_recompute, bcast_dual_backward_recompute_workspace, bcast_dual_backward_recompute_plan, bcast_dual_set_launch_events,
 )
 from .helpers import ForwardBuffers, BackwardBuffers, alloc_forward, alloc_backward, alloc_planes, to_slab, alloc_recompute, LaunchTimer  # noqa: F401
+from .autograd import broadcast  # noqa: F401

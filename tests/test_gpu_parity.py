@@ -1103,3 +1103,81 @@ def test_two_streams_run_independent_problems():
         for dev, adj_dev, fb, bb, alone in work:
             for got, want in zip(fb.outs + fb.partials + bb.grads, alone):
                 assert torch.equal(got, want), f"repetition {rep}"
+
+
+@pytest.mark.parametrize("planes", ["all", "lean", "none"])
+def test_autograd_node_inside_a_reverse_mode_program(planes):
+    """Mixed mode as Sec. 2.2.3 describes it: the fused broadcast is one node of a surrounding
+    reverse-mode program (torch.autograd here).  The gradients that reach the program's leaves --
+    through the node, a matmul before it and a weighted sum after it -- match those of the same
+    program with the update written as per-primitive torch operations, and the node's own outputs
+    and gradients match the oracle."""
+    from paper_1810_08297_amd.unfused_baseline import FUNCTIONS
+    torch.manual_seed(11)
+    H, Bt, K = 96, 80, 24
+    dev = "cuda"
+    W = torch.randn(4 * H, K, device=dev, requires_grad=True)
+    x = torch.randn(K, Bt, device=dev)
+    c = torch.randn(H, Bt, device=dev, requires_grad=True)
+    h = torch.randn(H, Bt, device=dev, requires_grad=True)
+    z = (torch.rand(1, Bt, device=dev) < 0.4).float()
+    zb = (torch.rand(Bt, device=dev) < 0.5).float()   # rank 1: aligned at the last dim, as torch does
+    biases = [(0.1 * torch.randn(H, 1, device=dev)).requires_grad_() for _ in range(4)]
+    wc, wh = torch.randn(H, Bt, device=dev), torch.randn(H, Bt, device=dev)
+
+    def program(update):
+        gates = W @ x                                    # [4H x B]: the gates are row slices of one buffer
+        f, i, o, g = (gates[k * H:(k + 1) * H] for k in range(4))
+        cn, hn = update(f, i, o, g, c, h, z, zb, *biases)
+        return cn, hn, (cn * wc).sum() + (hn * wh).sum()
+
+    leaves = [W, c, h] + biases
+    cn1, hn1, loss1 = program(lambda *a: P.broadcast("hmlstm_update", *a, planes=planes))
+    g1 = torch.autograd.grad(loss1, leaves)
+    cn2, hn2, loss2 = program(FUNCTIONS["hmlstm_update"][0])
+    g2 = torch.autograd.grad(loss2, leaves)
+    torch.cuda.synchronize()
+    for a, b, what in ((cn1, cn2, "c'"), (hn1, hn2, "h'")):
+        assert torch.allclose(a, b, rtol=1e-5, atol=1e-6), what
+    for a, b, leaf in zip(g1, g2, ["W", "c", "h", "b_f", "b_i", "b_o", "b_g"]):
+        assert a.shape == b.shape
+        assert torch.allclose(a, b, rtol=2e-4, atol=2e-5), (leaf, float((a - b).abs().max()))  # a K = 24 matmul follows
+    # the node alone against the oracle: values, and the gradients for the adjoints wc, wh
+    gates = (W @ x).detach()
+    args = [gates[k * H:(k + 1) * H].contiguous() for k in range(4)] + [c.detach(), h.detach(), z, zb.reshape(1, Bt)] + \
+           [b_.detach() for b_ in biases]
+    host = [a.cpu().numpy() for a in args]
+    o_out, o_parts, _ = oracle.forward("hmlstm_update", host, threads=8)
+    check_close(cn1.detach().cpu().numpy(), o_out[0], "node c'")
+    check_close(hn1.detach().cpu().numpy(), o_out[1], "node h'")
+    leaf_args = [a.clone().requires_grad_(k not in (6, 7)) for k, a in enumerate(args)]
+    outs = P.broadcast("hmlstm_update", *leaf_args, planes=planes)
+    got = torch.autograd.grad(outs, [a for a in leaf_args if a.requires_grad], [wc, wh])
+    didx = oracle.diff_arg_indices("hmlstm_update", 12)
+    want = oracle.backward([wc.cpu().numpy(), wh.cpu().numpy()], o_parts, [host[j].shape for j in didx], threads=8)
+    for k, (a, b) in enumerate(zip(got, want)):
+        check_close(a.cpu().numpy(), b, f"node gradient {k}", rtol=1e-5, atol=2e-6)  # planes here are the oracle's own
+
+
+def test_autograd_node_passes_torch_gradcheck_in_fp64():
+    """torch's own numerical Jacobian check (central differences in fp64) on the node, for a
+    function with a branch and broadcast arguments of every form, in all three storage modes; a
+    gradient that is not asked for is not computed."""
+    torch.manual_seed(5)
+    dev = "cuda"
+    A = torch.randn(6, 9, device=dev, dtype=torch.float64, requires_grad=True)
+    Bm = (torch.rand(6, 9, device=dev, dtype=torch.float64) * 1.9 + 0.1).requires_grad_()
+    r = torch.randn(9, device=dev, dtype=torch.float64, requires_grad=True)          # [9] -> [1 x 9]
+    s = torch.randn(6, 1, device=dev, dtype=torch.float64, requires_grad=True)
+    t = torch.randn((), device=dev, dtype=torch.float64, requires_grad=True)         # a 0-dim scalar
+    for planes in ("all", "lean", "none"):
+        fn = lambda *a: P.broadcast("branchy5", *a, planes=planes)
+        assert torch.autograd.gradcheck(fn, (A, Bm, r, s, t), eps=1e-6, atol=1e-7, rtol=1e-6, nondet_tol=0.0)
+        x = torch.randn(5, 7, device=dev, dtype=torch.float64, requires_grad=True)
+        y = torch.randn(5, 7, device=dev, dtype=torch.float64, requires_grad=True)
+        b = torch.randn(5, 1, device=dev, dtype=torch.float64, requires_grad=True)
+        assert torch.autograd.gradcheck(lambda *a: P.broadcast("tanh_xy_b", *a, planes=planes), (x, y, b),
+                                        eps=1e-6, atol=1e-7, rtol=1e-6, nondet_tol=0.0)
+    out = P.broadcast("tanh_xy_b", x, y.detach(), b)
+    gx, gb = torch.autograd.grad(out.sum(), [x, b])
+    assert gx.shape == x.shape and gb.shape == b.shape
