@@ -169,6 +169,16 @@ def _views(ts: Sequence, like=None):
     return arr
 
 
+def _on_device(*groups):
+    """Launching calls hand these addresses to kernels: every tensor must live in device memory
+    (a host pointer would be a memory fault on the GPU, not an error code).  The plan and
+    workspace queries launch nothing and take any addresses."""
+    for ts in groups:
+        for t in ts or ():
+            if t is not None and not isinstance(t, BcastTensor) and not t.is_cuda and t.numel() > 0:
+                raise ValueError("bcast_dual: tensors of a launching call must be device tensors, got one on " + str(t.device))
+
+
 def _stream_ptr(stream):
     if isinstance(stream, ctypes.c_void_p):
         return stream
@@ -184,6 +194,7 @@ def _stream_ptr(stream):
 def bcast_dual_forward(op_id: int, args: Sequence, outs: Sequence, partials: Optional[Sequence],
                        branch_id=None, stream=None) -> None:
     """Enqueue the dual-number forward kernel.  All buffers are caller-allocated."""
+    _on_device(args, outs, partials, [branch_id])
     dt = _dtype_code(outs[0])
     a = _views(args)
     o = _views(outs)
@@ -218,6 +229,7 @@ def bcast_dual_backward_workspace(adjoints, partials, grads) -> int:
 def bcast_dual_backward(adjoints, partials, grads, workspace=None, stream=None) -> None:
     """Enqueue adjoint x partial with the broadcast-dim reductions.  ``workspace`` is a
     uint8 device tensor of at least bcast_dual_backward_workspace(...) bytes (or None)."""
+    _on_device(adjoints, partials, grads, [workspace])
     dt = _dtype_code(adjoints[0])
     a = _views(adjoints)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
@@ -277,6 +289,7 @@ class PreparedForward:
     The tensors must stay alive and keep their addresses between launches."""
 
     def __init__(self, op_id, args, outs, partials, branch_id=None):
+        _on_device(args, outs, partials, [branch_id])
         self._keep = (args, outs, partials, branch_id)
         self._op = ctypes.c_int32(op_id)
         self._dt = ctypes.c_int(_dtype_code(outs[0]))
@@ -295,6 +308,7 @@ class PreparedBackward:
     """A backward call whose argument block is marshalled once (see PreparedForward)."""
 
     def __init__(self, adjoints, partials, grads, workspace=None):
+        _on_device(adjoints, partials, grads, [workspace])
         self._keep = (adjoints, partials, grads, workspace)
         self._dt = ctypes.c_int(_dtype_code(adjoints[0]))
         self._no, self._a = ctypes.c_int32(len(adjoints)), _views(adjoints)
@@ -328,6 +342,7 @@ def bcast_dual_backward_recompute_plan(op_id, args, adjoints, grads) -> dict:
 
 def bcast_dual_backward_recompute(op_id, args, adjoints, grads, workspace=None, stream=None) -> None:
     """Gradients straight from arguments and adjoints: the dual numbers are evaluated again."""
+    _on_device(args, adjoints, grads, [workspace])
     dt = _dtype_code(adjoints[0])
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
@@ -341,6 +356,7 @@ class PreparedRecompute:
     """A recompute-backward call marshalled once (see PreparedForward)."""
 
     def __init__(self, op_id, args, adjoints, grads, workspace=None):
+        _on_device(args, adjoints, grads, [workspace])
         self._keep = (args, adjoints, grads, workspace)
         self._op = ctypes.c_int32(op_id)
         self._dt = ctypes.c_int(_dtype_code(adjoints[0]))

@@ -126,12 +126,12 @@ def test_forward_validation_errors():
     v.stride[0] = -6
     assert _fwd_status("tanh_xy_b", [v, y, b], out, parts) == -10
     # the real entry point reports the same errors and launches nothing (no GPU here)
-    with pytest.raises(P.BcastError) as e:
-        P.bcast_dual_forward(P.bcast_op_lookup("tanh_xy_b"), [x, y], out, parts, stream=0)
-    assert e.value.status == -2
-    with pytest.raises(P.BcastError) as e:
-        P.bcast_dual_forward(999, [x, y, b], out, parts, stream=0)
-    assert e.value.status == -1
+    def real(op_id, a):  # straight through ctypes: the Python wrapper would refuse host tensors first
+        return B.lib().bcast_dual_forward(ctypes.c_int32(op_id), ctypes.c_int(0), ctypes.c_int32(len(a)), B._views(a),
+                                          ctypes.c_int32(1), B._views(out), B._views(parts), None, None)
+
+    assert real(P.bcast_op_lookup("tanh_xy_b"), [x, y]) == -2
+    assert real(999, [x, y, b]) == -1
     rc = B.lib().bcast_dual_forward(ctypes.c_int32(1), ctypes.c_int(7), ctypes.c_int32(3), B._views([x, y, b]),
                                     ctypes.c_int32(1), B._views(out), B._views(parts), None, None)
     assert rc == -7
@@ -522,3 +522,23 @@ def test_recompute_plan_picks_the_fixed_pattern_kernels_at_the_benchmark_shapes(
     assert rc == 0 and d["specialized"] == 1 and d["n_second_pass"] == 3 and d["rows_per_block"] == 128
     rc, d = plan("tanh_xy_b", [(4096, 4096), (4096, 4096), (4096, 1)], (4096, 4096), 1)    # config 1
     assert rc == 0 and d["specialized"] == 1
+
+
+def test_launching_wrappers_refuse_host_tensors():
+    """A host pointer handed to a kernel would be a GPU memory fault, not an error code: the
+    binding's launching calls check residency before anything reaches the library (the plan
+    queries, which launch nothing, keep taking any addresses)."""
+    x, y, b = _t(4, 6), _t(4, 6), _t(4, 1)
+    out, parts = [_t(4, 6)], [_t(4, 6) for _ in range(3)]
+    op = P.bcast_op_lookup("tanh_xy_b")
+    assert P.bcast_dual_forward_plan(op, [x, y, b], out, parts)["path"] == 1
+    with pytest.raises(ValueError):
+        P.bcast_dual_forward(op, [x, y, b], out, parts)
+    with pytest.raises(ValueError):
+        P.bcast_dual_backward(out, parts, [_t(4, 6), _t(4, 6), _t(4, 1)])
+    with pytest.raises(ValueError):
+        P.bcast_dual_backward_recompute(op, [x, y, b], out, [_t(4, 6), _t(4, 6), _t(4, 1)])
+    with pytest.raises(ValueError):
+        P.PreparedForward(op, [x, y, b], out, parts)
+    with pytest.raises(ValueError):
+        P.broadcast("tanh_xy_b", x, y, b)
