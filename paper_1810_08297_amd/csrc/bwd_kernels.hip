@@ -269,13 +269,7 @@ __global__ __launch_bounds__(kBlock) void bwd_generic_full_kernel(const BwdGener
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e >= p.E) return;
   int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
-  int64_t rem = e;
-#pragma unroll
-  for (int d = BCAST_MAX_DIMS - 1; d >= 0; --d)
-    if (d < p.nd) {
-      idx[d] = rem % p.shape[d];
-      rem /= p.shape[d];
-    }
+  decompose(e, p.E, p.nd, p.shape, idx, [](int) { return true; });
   auto off = [&](const GView &g) {
     int64_t o = 0;
 #pragma unroll
@@ -299,22 +293,12 @@ __global__ __launch_bounds__(kBlock) void bwd_generic_reduce_kernel(const BwdGen
   using A = typename AT::type;
   __shared__ A sh[kBlock / 64];
   int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
-  int64_t rem = blockIdx.x;
-  for (int d = BCAST_MAX_DIMS - 1; d >= 0; --d)
-    if (d < p.nd && !p.reduced[d]) {
-      idx[d] = rem % p.shape[d];
-      rem /= p.shape[d];
-    }
+  decompose(blockIdx.x, p.n_kept, p.nd, p.shape, idx, [&](int d) { return !p.reduced[d]; });
   int64_t goff = 0;
   for (int d = 0; d < BCAST_MAX_DIMS; ++d) goff += idx[d] * p.g.s[d];
   A s = AT::zero();
   for (int64_t q = threadIdx.x; q < p.n_fibre; q += kBlock) {
-    int64_t rq = q;
-    for (int d = BCAST_MAX_DIMS - 1; d >= 0; --d)
-      if (d < p.nd && p.reduced[d]) {
-        idx[d] = rq % p.shape[d];
-        rq /= p.shape[d];
-      }
+    decompose(q, p.n_fibre, p.nd, p.shape, idx, [&](int d) { return p.reduced[d] != 0; });
     for (int i = 0; i < p.M; ++i) {
       if (p.P[i].p == nullptr) continue;
       int64_t oa = 0, op = 0;

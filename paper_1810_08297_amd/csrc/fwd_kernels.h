@@ -232,6 +232,31 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   }
 }
 
+// Linear index -> multi-index over the dims d < nd for which take(d) holds, innermost first.
+// 64-bit division is emulated with some hundred instructions; a count below 2^32 (checked on
+// the uniform bound `count`) takes the 32-bit form instead.
+template <class Take>
+BD_DEV void decompose(int64_t linear, int64_t count, int nd, const int64_t *shape, int64_t *idx, Take take) {
+  if (count <= 0xffffffffLL) {
+    uint32_t rem = (uint32_t)linear;
+#pragma unroll
+    for (int d = BCAST_MAX_DIMS - 1; d >= 0; --d)
+      if (d < nd && take(d)) {
+        const uint32_t s = (uint32_t)shape[d], q = rem / s;
+        idx[d] = rem - q * s;
+        rem = q;
+      }
+  } else {
+    int64_t rem = linear;
+#pragma unroll
+    for (int d = BCAST_MAX_DIMS - 1; d >= 0; --d)
+      if (d < nd && take(d)) {
+        idx[d] = rem % shape[d];
+        rem /= shape[d];
+      }
+  }
+}
+
 // Generic kernel: any rank up to BCAST_MAX_DIMS, any strides; one element per lane.
 template <class Op, class T>
 __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericParams p) {
@@ -241,15 +266,7 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (e >= p.E) return;
   int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
-  {
-    int64_t rem = e;
-#pragma unroll
-    for (int d = BCAST_MAX_DIMS - 1; d >= 0; --d)
-      if (d < p.nd) {
-        idx[d] = rem % p.shape[d];
-        rem /= p.shape[d];
-      }
-  }
+  decompose(e, p.E, p.nd, p.shape, idx, [](int) { return true; });
   auto off = [&](const GView &g) {
     int64_t o = 0;
 #pragma unroll
