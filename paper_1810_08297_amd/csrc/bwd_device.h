@@ -130,8 +130,9 @@ BD_DEV A wave_total(A v) {
 // Two kernels share this scheme.  The signature kernel is compiled for a fixed number of
 // outputs and of gradients of each class (the host sorts the gradient table by class), so
 // every table access is a constant, all loads of a row step are issued before the first
-// use and nothing is decided at run time but the ragged edge.  The generic kernel reads
-// the class of each gradient from the table and takes any mix, one gradient at a time.
+// use and nothing is decided at run time but the ragged edge.  The other kernel reads the
+// class of each gradient from the table at run time and takes any mix, four gradients'
+// planes in flight at a time.
 template <class T, int VEC>
 struct BwdGeom {
   using AT = acc_traits<T>;
