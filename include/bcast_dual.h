@@ -98,6 +98,8 @@ typedef struct {
  *                   branch id 1 = predicate true.
  *   "cos_x"         N=1 (the Dual example of Sec. 2.2.1), "scale_xt" N=2 (x*t),
  *   "pair3"         N=3 -> (x1*x2 + sin x3, x1/x2 - x3*x3)  (R^3 -> R^2, Sec. 2.2.2)
+ *   "elementary4"   N=1 -> (exp x, log1p x, sigma x, tanh x): the elementary functions the other
+ *                   ops are built from (for measuring their accuracy over their whole domain)
  *   "linear12"      N=12, the HM-LSTM argument list with trivial arithmetic:
  *                   (sum of the ten differentiable arguments + z*z_below,
  *                    f*c + i*h + o*g + b_f*b_i + b_o*b_g); for profiling memory behaviour.

@@ -194,6 +194,23 @@ static void op_cos_x(int n, const real *x, const void *xw, int f64, real *y, rea
   J[0] = -sinl(x[0]);
   *br = 0;
 }
+/* the elementary functions the other ops are built from, with their derivatives.  The
+ * derivatives of sigma and tanh are written so that they keep their relative accuracy where the
+ * functions saturate: sigma' = e / (1 + e)^2 with e = exp(-|x|), 1 - tanh^2 = 4 q / (1 + q)^2
+ * with q = exp(-2 |x|) (identities; s (1 - s) and 1 - t^2 cancel there). */
+static void op_elementary4(int n, const real *x, const void *xw, int f64, real *y, real *J, int *br) {
+  (void)n; (void)xw; (void)f64;
+  real e = expl(-fabsl(x[0])), q = expl(-2.0L * fabsl(x[0]));
+  y[0] = expl(x[0]);
+  J[0] = y[0];
+  y[1] = log1pl(x[0]);
+  J[1] = 1.0L / (1.0L + x[0]);
+  y[2] = x[0] >= 0.0L ? 1.0L / (1.0L + e) : e / (1.0L + e);
+  J[2] = e / ((1.0L + e) * (1.0L + e));
+  y[3] = tanhl(x[0]);
+  J[3] = 4.0L * q / ((1.0L + q) * (1.0L + q));
+  *br = 0;
+}
 /* y = x * t : a scalar argument whose partial is not zero */
 static void op_scale_xt(int n, const real *x, const void *xw, int f64, real *y, real *J, int *br) {
   (void)n; (void)xw; (void)f64;
@@ -259,6 +276,7 @@ static const op_desc OPS[] = {
     {"branchy5", 5, 1, 0u, op_branchy5},
     {"update_c", 6, 1, (1u << 4) | (1u << 5), op_update_c},
     {"cos_x", 1, 1, 0u, op_cos_x},
+    {"elementary4", 1, 4, 0u, op_elementary4},
     {"scale_xt", 2, 1, 0u, op_scale_xt},
     {"pair3", 3, 2, 0u, op_pair3},
     {"linear12", HM_N, 2, (1u << A_Z) | (1u << A_ZB), op_linear12},

@@ -34,6 +34,7 @@ BD_DECLARE_OP(cos_x)
 BD_DECLARE_OP(scale_xt)
 BD_DECLARE_OP(pair3)
 BD_DECLARE_OP(linear12)
+BD_DECLARE_OP(elementary4)
 BD_DECLARE_RECOMPUTE(hmlstm_update)
 BD_DECLARE_RECOMPUTE(update_c)
 BD_DECLARE_RECOMPUTE(tanh_xy_b)
@@ -42,6 +43,7 @@ BD_DECLARE_RECOMPUTE(cos_x)
 BD_DECLARE_RECOMPUTE(scale_xt)
 BD_DECLARE_RECOMPUTE(pair3)
 BD_DECLARE_RECOMPUTE(linear12)
+BD_DECLARE_RECOMPUTE(elementary4)
 #ifndef BD_NO_ARITY
 #define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K) BD_DECLARE_RECOMPUTE(prod_tanh_##K)
 BD_ARITY_LIST(BD_DECL_ARITY)
@@ -97,6 +99,7 @@ const OpDesc kOps[] = {
     BD_OP_ROW(scale_xt, 2, 1, 0u, 1)
     BD_OP_ROW(pair3, 3, 2, 0u, 1)
     BD_OP_ROW(linear12, 12, 2, (1u << 6) | (1u << 7), 1)
+    BD_OP_ROW(elementary4, 1, 4, 0u, 1)
 #ifndef BD_NO_ARITY
     BD_ARITY_LIST(BD_ARITY_ROW)
 #endif

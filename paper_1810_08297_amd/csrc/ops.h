@@ -103,6 +103,23 @@ struct OpBranchy5 {
   }
 };
 
+// (exp x, log1p x, sigma x, tanh x): the elementary functions the other ops are built from, each
+// with its derivative -- exposed so that their accuracy can be measured over their whole domain
+struct OpElementary4 {
+  static constexpr int N = 1, M = 4, NBR = 1;
+  static constexpr uint32_t NONDIFF = 0u;
+  static constexpr bool STRIDED = true;
+  static constexpr uint64_t RECOMPUTE_PATTERN = 0x1ull;
+  template <class Y, class X>
+  static BD_DEV int apply(Y *y, const X &x) {
+    y[0] = exp(x);
+    y[1] = log1p(x);
+    y[2] = sigmoid(x);
+    y[3] = tanh(x);
+    return 0;
+  }
+};
+
 // cos(x): the Dual example of Sec. 2.2.1
 struct OpCosX {
   static constexpr int N = 1, M = 1, NBR = 1;

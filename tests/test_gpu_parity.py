@@ -25,6 +25,7 @@ def small_args(op, R, C, dtype, seed=0):
         "branchy5": [full, full, row, col, sc],
         "update_c": [full] * 4 + [row, row],
         "cos_x": [full],
+        "elementary4": [full],
         "scale_xt": [full, sc],
         "pair3": [full, sc, col],
     }[op]
@@ -37,12 +38,14 @@ def small_args(op, R, C, dtype, seed=0):
         args[5] = (rng.random(shp[5]) < 0.5).astype(dtype)
     if op == "pair3":
         args[1] = (np.abs(args[1]) + 0.5).astype(dtype)
+    if op == "elementary4":
+        args[0] = (np.abs(args[0]) * 2 - 0.5).astype(dtype)  # log1p wants x > -1
     n_out = oracle.op_info(op)[1]
     adj = [rng.standard_normal(full).astype(dtype) for _ in range(n_out)]
     return args, adj
 
 
-OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12"]
+OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12", "elementary4"]
 # several tiles, ragged tails, one row / one column / one element, rows wider than a block
 SHAPES = [(1, 1), (1, 7), (5, 1), (3, 5), (64, 16), (7, 33), (129, 260), (2, 4100), (300, 1028), (1, 5000),
           (5, 2048), (3, 4096), (7, 3500)]  # rows of two to four (fp64: up to eight) column chunks
@@ -1181,3 +1184,76 @@ def test_autograd_node_passes_torch_gradcheck_in_fp64():
     out = P.broadcast("tanh_xy_b", x, y.detach(), b)
     gx, gb = torch.autograd.grad(out.sum(), [x, b])
     assert gx.shape == x.shape and gb.shape == b.shape
+
+
+def _elementary_reference(xs):
+    """(exp, log1p, sigma, tanh) and their derivatives at the points xs (exact binary values) in
+    60-digit decimal arithmetic; entries where log1p is undefined (x <= -1) are None."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    one = Decimal(1)
+    vals, ders = [], []
+    for x in xs:
+        d = Decimal(float(x))
+        far = abs(d) > 2000  # beyond every floating-point range: the limits
+        e = (Decimal("Infinity") if d > 0 else Decimal(0)) if far else d.exp()
+        em = Decimal(0) if far else (-abs(d)).exp()
+        q = Decimal(0) if far else (-2 * abs(d)).exp()
+        sg = one / (one + em) if d >= 0 else em / (one + em)
+        th = (one - q) / (one + q) * (1 if d >= 0 else -1)
+        lg = (one + d).ln() if d > -1 else None
+        if abs(d) < Decimal("1e-20"):  # 1 + d and 1 - q would round to 1 and 0 even at 60 digits: the series
+            th = d - d ** 3 / 3 + 2 * d ** 5 / 15
+            lg = d - d * d / 2 + d ** 3 / 3
+        vals.append([e, lg, sg, th])
+        ders.append([e, one / (one + d) if d > -1 else None, em / (one + em) ** 2, 4 * q / (one + q) ** 2])
+    return vals, ders
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_elementary_functions_accuracy_in_ulps(dtype):
+    """exp, log1p, sigma, tanh and their derivatives as the kernels compute them, over the whole
+    range of the working precision -- saturation, tiny arguments, the neighbourhood of log1p's
+    pole, results down to the smallest normal number -- against 60-digit values: every result is
+    within a few units in the last place (far inside the tolerance of the parity tests, which
+    only see arguments of order one)."""
+    from decimal import Decimal
+    f32 = dtype == np.float32
+    big = 87.0 if f32 else 700.0
+    pts = [np.linspace(-big, big, 801), np.linspace(-3, 3, 601),
+           np.concatenate([s * 10.0 ** np.arange(-30 if f32 else -200, 1, 1.5) for s in (1, -0.9)]),
+           -1 + 10.0 ** -np.arange(1, 7 if f32 else 15), 10.0 ** np.arange(1, 30 if f32 else 200, 3.0)]
+    xs = np.unique(np.concatenate(pts).astype(dtype))
+    out_shape = (1, xs.size)
+    dev = [to_dev(xs.reshape(out_shape))]
+    fb = gpu_forward("elementary4", dev, want_branch=False)
+    torch.cuda.synchronize()
+    got_v = [o.cpu().numpy().reshape(-1) for o in fb.outs]
+    got_d = [p.cpu().numpy().reshape(-1) for p in fb.partials]
+    ref_v, ref_d = _elementary_reference(xs)
+    info = np.finfo(dtype)
+    names = ["exp", "log1p", "sigma", "tanh"]
+    worst = {}
+    for k, x in enumerate(xs):
+        for which, got, ref in (("", got_v, ref_v), ("'", got_d, ref_d)):
+            for i in range(4):
+                r = ref[k][i]
+                if r is None:
+                    continue
+                g = got[i][k]
+                rf = float(r)
+                if abs(rf) > info.max:       # overflows the working precision: inf on both sides
+                    assert np.isinf(g) and (g > 0) == (rf > 0), (names[i] + which, float(x), g)
+                    continue
+                if abs(rf) < 8 * info.tiny:  # at the bottom of the range an intermediate is flushed to zero: no ulp bound
+                    assert abs(float(g)) <= 16 * info.tiny, (names[i] + which, float(x), g)
+                    continue
+                ulp = Decimal(float(np.spacing(np.abs(dtype(rf)))))
+                err = float(abs(Decimal(float(g)) - r) / ulp)
+                key = names[i] + which
+                if err > worst.get(key, (0.0, 0.0))[0]:
+                    worst[key] = (err, float(x))
+    print({k: (round(v[0], 2), v[1]) for k, v in worst.items()})
+    limits = {"exp": 2.0, "exp'": 2.0, "log1p": 3.5, "log1p'": 2.0, "sigma": 3.0, "sigma'": 5.0, "tanh": 4.0, "tanh'": 6.0}
+    for key, (err, x) in worst.items():
+        assert err <= limits[key], f"{key}: {err:.2f} ulp at x = {x!r}"

@@ -29,6 +29,7 @@ def shapes_for(op, R, C):
         "branchy5": [full, full, row, col, sc],
         "update_c": [full] * 4 + [row, row],
         "cos_x": [full],
+        "elementary4": [full],
         "scale_xt": [full, sc],
         "pair3": [full, sc, col],
     }[op]
@@ -45,6 +46,8 @@ def random_args(op, R, C, dtype=np.float64, rng=RNG):
         args[5] = (rng.random(shp[5]) < 0.5).astype(dtype)
     if op == "pair3":
         args[1] = np.abs(args[1]) + 0.5  # the divisor stays away from 0
+    if op == "elementary4":
+        args[0] = (np.abs(args[0]) * 2 - 0.5).astype(dtype)  # log1p wants x > -1
     return args
 
 
@@ -83,6 +86,8 @@ def tape_program(op, x):
         return [T.log1p(A * A) * r - s]
     if op == "cos_x":
         return [T.cos(x[0])]
+    if op == "elementary4":
+        return [T.exp(x[0]), T.log1p(x[0]), T.sigmoid(x[0]), T.tanh(x[0])]
     if op == "scale_xt":
         return [x[0] * x[1]]
     if op == "pair3":
@@ -96,7 +101,7 @@ def tape_program(op, x):
     raise KeyError(op)
 
 
-OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12"]
+OPS = ["hmlstm_update", "tanh_xy_b", "branchy5", "update_c", "cos_x", "scale_xt", "pair3", "linear12", "elementary4"]
 
 
 def assert_close(a, b, rtol, atol, what=""):
@@ -594,6 +599,9 @@ def _dec_values():
     def cos_x(a, ctl):
         return [series(a[0], 0)]
 
+    def elementary4(a, ctl):
+        return [a[0].exp(), (one + a[0]).ln(), sig(a[0]), tanh(a[0])]
+
     def scale_xt(a, ctl):
         return [a[0] * a[1]]
 
@@ -607,11 +615,11 @@ def _dec_values():
         return [p]
 
     return {"tanh_xy_b": (tanh_xy_b, ()), "branchy5": (branchy5, ()), "hmlstm_update": (hmlstm_update, (6, 7)),
-            "update_c": (update_c, (4, 5)), "cos_x": (cos_x, ()), "scale_xt": (scale_xt, ()), "pair3": (pair3, ()),
+            "update_c": (update_c, (4, 5)), "cos_x": (cos_x, ()), "elementary4": (elementary4, ()), "scale_xt": (scale_xt, ()), "pair3": (pair3, ()),
             "prod_tanh": (prod_tanh, ())}
 
 
-@pytest.mark.parametrize("op", ["tanh_xy_b", "branchy5", "hmlstm_update", "update_c", "cos_x", "scale_xt", "pair3", "prod_tanh"])
+@pytest.mark.parametrize("op", ["tanh_xy_b", "branchy5", "hmlstm_update", "update_c", "cos_x", "scale_xt", "pair3", "prod_tanh", "elementary4"])
 def test_fp64_outputs_match_sixty_digit_values_and_their_difference_quotients(op):
     """Every value the oracle returns in fp64 is the 60-digit value rounded to fp64, and every
     partial is the 60-digit central difference quotient of the value function (step 1e-25: the
