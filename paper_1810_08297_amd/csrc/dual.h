@@ -68,13 +68,15 @@ template <> struct smath<float> {
   static BD_DEV float cos(float x) { return ::cosf(x); }
   static BD_DEV float abs(float x) { return ::fabsf(x); }
   static BD_DEV float copysign(float m, float s) { return ::copysignf(m, s); }
-  // hardware reciprocal (1 ulp) refined by one Newton step
+  // hardware reciprocal (1 ulp) refined by one Newton step; where the step has no finite result
+  // (d = 0 or infinite: 0 * inf) the hardware's own inf or 0 stands
   static BD_DEV float rcp(float d) {
-    float r = __builtin_amdgcn_rcpf(d);
+    const float r = __builtin_amdgcn_rcpf(d);
 #ifdef BD_RCP_RAW
     return r;
 #else
-    return ::fmaf(::fmaf(-d, r, 1.0f), r, r);
+    const float n = ::fmaf(::fmaf(-d, r, 1.0f), r, r);
+    return __builtin_isfinite(n) ? n : r;
 #endif
   }
 };

@@ -1257,3 +1257,41 @@ def test_elementary_functions_accuracy_in_ulps(dtype):
     limits = {"exp": 2.0, "exp'": 2.0, "log1p": 3.5, "log1p'": 2.0, "sigma": 3.0, "sigma'": 5.0, "tanh": 4.0, "tanh'": 6.0}
     for key, (err, x) in worst.items():
         assert err <= limits[key], f"{key}: {err:.2f} ulp at x = {x!r}"
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_division_accuracy_and_limits(dtype):
+    """x1 / x2 and its partials 1 / x2, -x1 / x2^2 (second output of pair3 with x3 = 0) against exact
+    rational arithmetic: a few units in the last place over twenty orders of magnitude, and the
+    IEEE limits at x2 = +-0 and +-inf (inf and 0 with the right signs, never NaN)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(12)
+    mags = 10.0 ** np.arange(-10, 11, 0.5)
+    x2 = np.concatenate([mags, -mags, rng.standard_normal(400)]).astype(dtype)
+    x2 = x2[x2 != 0]
+    x1 = (rng.standard_normal(x2.size) * 3).astype(dtype)
+    x3 = np.zeros(x2.size, dtype)
+    shape = (1, x2.size)
+    fb = gpu_forward("pair3", [to_dev(a.reshape(shape)) for a in (x1, x2, x3)], want_branch=False)
+    torch.cuda.synchronize()
+    quot = fb.outs[1].cpu().numpy().reshape(-1)
+    d1 = fb.partials[3].cpu().numpy().reshape(-1)   # plane index i * N_d + jd: output 1, argument 0
+    d2 = fb.partials[4].cpu().numpy().reshape(-1)
+    worst = [0.0, 0.0, 0.0]
+    for k in range(x2.size):
+        a, b = Fraction(float(x1[k])), Fraction(float(x2[k]))
+        for n, (got, want) in enumerate(((quot[k], a / b), (d1[k], 1 / b), (d2[k], -a / (b * b)))):
+            w = float(want)
+            ulp = Fraction(float(np.spacing(np.abs(dtype(w)))))
+            worst[n] = max(worst[n], float(abs(Fraction(float(got)) - want) / ulp))
+    print("division, worst ulp:", [round(w, 2) for w in worst])
+    assert worst[0] <= 2.5 and worst[1] <= 2.0 and worst[2] <= 4.0, worst
+    # the limits
+    x2 = np.array([0.0, -0.0, np.inf, -np.inf], dtype)
+    x1 = np.array([2.0, 2.0, 2.0, 2.0], dtype)
+    fb = gpu_forward("pair3", [to_dev(a.reshape(1, 4)) for a in (x1, x2, np.zeros(4, dtype))], want_branch=False)
+    torch.cuda.synchronize()
+    q = fb.outs[1].cpu().numpy().reshape(-1)
+    inv = fb.partials[3].cpu().numpy().reshape(-1)
+    assert q[0] == np.inf and q[1] == -np.inf and q[2] == 0 and q[3] == 0 and np.signbit(q[3]), q
+    assert inv[0] == np.inf and inv[1] == -np.inf and inv[2] == 0 and inv[3] == 0, inv
