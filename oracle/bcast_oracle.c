@@ -374,8 +374,12 @@ int oracle_forward(const char *name, int is_f64, int ndim, const int64_t *out_sh
   return 0;
 }
 
-/* Neumaier-compensated accumulation in long double */
+/* Neumaier-compensated accumulation in long double.  The compensation term estimates the
+ * rounding error of finite additions; once a term or the running sum is infinite or NaN it is
+ * itself inf - inf, so the result is then the plain IEEE sum (an infinity among finite terms
+ * stays that infinity, as Table 1's sum of products says it must). */
 typedef struct { real s, c; } csum;
+static real csum_value(const csum *a) { return isfinite(a->s) ? a->s + a->c : a->s; }
 static void csum_add(csum *a, real v) {
   real t = a->s + v;
   if (fabsl(a->s) >= fabsl(v))
@@ -433,7 +437,7 @@ int oracle_backward(int is_f64, int ndim, const int64_t *out_shape, int M, int N
           csum_add(&acc, load(adjoints[i], e, is_f64) * load(P, e, is_f64));
         }
       }
-      store(grads[j], a, is_f64, acc.s + acc.c);
+      store(grads[j], a, is_f64, csum_value(&acc));
     }
   }
   return 0;

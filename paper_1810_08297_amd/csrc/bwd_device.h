@@ -53,7 +53,8 @@ template <> struct acc_traits<double> {
     a.hi = s;
     a.lo = (a.lo + b.lo) + err;
   }
-  static BD_DEV double fin(dd a) { return a.hi + a.lo; }
+  // an infinite or NaN sum keeps its high part: the error terms of the additions that met it are inf - inf
+  static BD_DEV double fin(dd a) { return __builtin_isfinite(a.hi) ? a.hi + a.lo : a.hi; }
 };
 
 // sum_i adj_i * P_i for one element of a full-shape gradient, rounded once

@@ -59,7 +59,8 @@ template <> struct smath<float> {
     const float u = 1.0f + x;
     const float l2 = __builtin_amdgcn_logf(u);
     float l = l2 * 0.693147182464599609375f;  // ln 2 rounded to float ...
-    l = ::fmaf(l2, -1.904654323148236e-9f, l);  // ... and the remainder of ln 2
+    const float lr = ::fmaf(l2, -1.904654323148236e-9f, l);  // ... and the remainder of ln 2
+    l = __builtin_isfinite(l2) ? lr : l;  // log2 of inf or of 0: the correction would be inf - inf
     const float lost = x - (u - 1.0f);
     return (x > 3.0e38f || u == 0.0f) ? l : ::fmaf(lost, __builtin_amdgcn_rcpf(u), l);  // inf and -1 pass through
 #endif

@@ -1295,3 +1295,66 @@ def test_division_accuracy_and_limits(dtype):
     inv = fb.partials[3].cpu().numpy().reshape(-1)
     assert q[0] == np.inf and q[1] == -np.inf and q[2] == 0 and q[3] == 0 and np.signbit(q[3]), q
     assert inv[0] == np.inf and inv[1] == -np.inf and inv[2] == 0 and inv[3] == 0, inv
+
+
+def _same_with_specials(got, want, what):
+    """NaN where the oracle has NaN, the same infinity where it has one, the usual tolerance elsewhere."""
+    rt, at = TOL[want.dtype]
+    g, w = got.astype(np.float64), want.astype(np.float64)
+    bad = np.isnan(g) != np.isnan(w)
+    bad |= np.isinf(w) & ~np.isnan(g) & (g != w)
+    fin = np.isfinite(w) & ~np.isnan(g)
+    with np.errstate(invalid="ignore"):
+        bad |= fin & ~(np.abs(g - w) <= np.maximum(rt * np.abs(w), at))
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements; first at {tuple(np.argwhere(bad)[0])}: " \
+                          f"got {got[tuple(np.argwhere(bad)[0])]} want {want[tuple(np.argwhere(bad)[0])]}"
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_special_values_propagate_as_in_the_oracle(dtype):
+    """Infinities, NaN, signed zeros, arguments at the edge of exp's range and tiny ones, planted one
+    argument at a time: values, partial planes and branch ids come out as the oracle's do (NaN for
+    NaN, the same infinity, otherwise within tolerance), and so do gradients when adjoints and
+    planes carry them."""
+    specials = [np.inf, -np.inf, np.nan, 1e4, -1e4, 1e-30, -1e-30, 0.0, -0.0, 88.0, -88.0, 104.0, -104.0]
+    for op in ("tanh_xy_b", "branchy5", "hmlstm_update", "update_c", "elementary4"):
+        R, C = 16, 4 * len(specials)
+        args, adj = small_args(op, R, C, dtype, seed=3)
+        control = {"hmlstm_update": (6, 7), "update_c": (4, 5)}.get(op, ())
+        for j in range(len(args)):
+            if j in control:
+                continue
+            planted = [a.copy() for a in args]
+            tgt = planted[j]
+            for k, sv in enumerate(specials):
+                if tgt.shape[1] == 1:
+                    tgt[k % tgt.shape[0], 0] = sv
+                elif tgt.shape[0] == 1:
+                    tgt[0, 4 * k:4 * k + 4] = sv
+                else:
+                    tgt[j % R, 4 * k:4 * k + 4] = sv
+            fb = gpu_forward(op, [to_dev(a) for a in planted])
+            torch.cuda.synchronize()
+            with np.errstate(all="ignore"):
+                o_out, o_parts, o_br = oracle.forward(op, planted, threads=4)
+            assert np.array_equal(fb.branch.cpu().numpy(), o_br), (op, j)
+            for i, (g, w) in enumerate(zip(fb.outs, o_out)):
+                _same_with_specials(g.cpu().numpy(), w, f"{op}, special values in argument {j}, output {i}")
+            for i, (g, w) in enumerate(zip(fb.partials, o_parts)):
+                _same_with_specials(g.cpu().numpy(), w, f"{op}, special values in argument {j}, plane {i}")
+    # backward: special values in an adjoint and in a plane reach exactly the gradients that sum over them
+    args, adj = small_args("branchy5", 24, 260, dtype, seed=5)
+    dev = [to_dev(a) for a in args]
+    fb = gpu_forward("branchy5", dev)
+    torch.cuda.synchronize()
+    planes = [p.cpu().numpy() for p in fb.partials]
+    adj[0][3, 7], adj[0][5, 100], adj[0][9, 200] = np.inf, np.nan, -np.inf
+    planes[0][11, 30] = np.nan
+    planes[2][13, 40] = np.inf
+    shapes = [a.shape for a in args]
+    bb = gpu_backward([to_dev(adj[0])], [to_dev(p) for p in planes], shapes)
+    torch.cuda.synchronize()
+    with np.errstate(all="ignore"):
+        want = oracle.backward(adj, planes, shapes, threads=4)
+    for k in range(5):
+        _same_with_specials(bb.grads[k].cpu().numpy(), want[k], f"gradient {k} with special values")

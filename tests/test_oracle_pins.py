@@ -656,3 +656,24 @@ def test_fp64_outputs_match_sixty_digit_values_and_their_difference_quotients(op
                     want = (vu[i] - vd[i]) / (2 * h)
                     got = Decimal(float(parts[i * nd + jd][r, c]))
                     assert abs(got - want) <= max(abs(want) * ulp, Decimal("1e-40")), (op, r, c, i, j, float(got), str(want))
+
+
+def test_sums_with_infinite_and_nan_terms_follow_ieee():
+    """Table 1's sum of products with non-finite terms: one infinity among finite terms gives that
+    infinity, opposite infinities or a NaN term give NaN, 0 x inf is NaN, and rows without such
+    terms are untouched (the compensation of the summation must not turn inf into NaN)."""
+    R, C = 5, 8
+    adj = [np.ones((R, C))]
+    P = [np.full((R, C), 0.25)]
+    P[0][0, 3] = np.inf                     # row 0: one +inf
+    P[0][1, 2], P[0][1, 6] = np.inf, -np.inf  # row 1: both
+    P[0][2, 5] = np.nan                     # row 2: NaN
+    adj[0][3, 1], P[0][3, 1] = 0.0, np.inf  # row 3: 0 x inf
+    with np.errstate(all="ignore"):
+        rows = oracle.backward(adj, P, [(R, 1)])[0].reshape(-1)
+        full = oracle.backward(adj, P, [(R, C)])[0]
+        cols = oracle.backward(adj, P, [(1, C)])[0].reshape(-1)
+    assert rows[0] == np.inf and np.isnan(rows[1]) and np.isnan(rows[2]) and np.isnan(rows[3]) and rows[4] == 2.0
+    assert full[0, 3] == np.inf and full[1, 6] == -np.inf and np.isnan(full[2, 5]) and np.isnan(full[3, 1]) and full[4, 0] == 0.25
+    assert cols[3] == np.inf and cols[2] == np.inf and cols[6] == -np.inf and np.isnan(cols[5]) and np.isnan(cols[1])
+    assert cols[0] == 1.25 and cols[7] == 1.25
