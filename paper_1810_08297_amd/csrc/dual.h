@@ -80,6 +80,11 @@ template <> struct smath<float> {
     return __builtin_isfinite(n) ? n : r;
 #endif
   }
+  // the same for 1 <= d <= 2 (or NaN), where the step always has its result
+  static BD_DEV float rcp_1to2(float d) {
+    const float r = __builtin_amdgcn_rcpf(d);
+    return ::fmaf(::fmaf(-d, r, 1.0f), r, r);
+  }
 };
 template <> struct smath<double> {
   static BD_DEV double exp(double x) { return ::exp(x); }
@@ -89,13 +94,14 @@ template <> struct smath<double> {
   static BD_DEV double abs(double x) { return ::fabs(x); }
   static BD_DEV double copysign(double m, double s) { return ::copysign(m, s); }
   static BD_DEV double rcp(double d) { return 1.0 / d; }
+  static BD_DEV double rcp_1to2(double d) { return 1.0 / d; }
 };
 
 // sigma(x) and sigma'(x) from e = exp(-|x|): no overflow, no cancellation
 template <class T>
 BD_DEV void sigmoid_vd(T x, T &s, T &ds) {
   T e = smath<T>::exp(-smath<T>::abs(x));
-  T r = smath<T>::rcp(T(1) + e);
+  T r = smath<T>::rcp_1to2(T(1) + e);
   T er = e * r;
   s = x >= T(0) ? r : er;
   ds = er * r;
@@ -107,7 +113,7 @@ BD_DEV void sigmoid_vd(T x, T &s, T &ds) {
 BD_DEV void tanh_vd(float x, float &t, float &dt) {
   const float a = smath<float>::abs(x);
   const float q = smath<float>::exp(-2.0f * a);
-  const float r = smath<float>::rcp(1.0f + q);
+  const float r = smath<float>::rcp_1to2(1.0f + q);
   const float x2 = x * x;
   float s = ::fmaf(x2, -8.86323550e-3f, 2.18694885e-2f);  // -1382/155925, 62/2835
   s = ::fmaf(x2, s, -5.39682540e-2f);                     // -17/315
