@@ -1358,3 +1358,35 @@ def test_special_values_propagate_as_in_the_oracle(dtype):
         want = oracle.backward(adj, planes, shapes, threads=4)
     for k in range(5):
         _same_with_specials(bb.grads[k].cpu().numpy(), want[k], f"gradient {k} with special values")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_cos_and_sin_accuracy_in_ulps(dtype):
+    """cos x and its derivative -sin x (the Dual example of Sec. 2.2.1, op cos_x) against their
+    power series in 60-digit arithmetic, over |x| <= 30 and down to tiny arguments: units in the
+    last place, also next to the zeros of the functions."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 70
+    one = Decimal(1)
+
+    def series(x, first):  # sin (first = 1) or cos (first = 0)
+        term = x if first else one
+        total, k = term, first
+        while abs(term) > Decimal("1e-75") or k < 4:
+            k += 2
+            term = -term * x * x / (k * (k - 1))
+            total += term
+        return total
+
+    xs = np.unique(np.concatenate([np.linspace(-30, 30, 1201), 10.0 ** np.arange(-20, 0, 1.0), [np.pi / 2, np.pi, 3 * np.pi / 2]]).astype(dtype))
+    fb = gpu_forward("cos_x", [to_dev(xs.reshape(1, -1))], want_branch=False)
+    torch.cuda.synchronize()
+    got = [fb.outs[0].cpu().numpy().reshape(-1), fb.partials[0].cpu().numpy().reshape(-1)]
+    worst = [0.0, 0.0]
+    for k, x in enumerate(xs):
+        d = Decimal(float(x))
+        for n, want in enumerate((series(d, 0), -series(d, 1))):
+            ulp = Decimal(float(np.spacing(np.abs(dtype(float(want))))))
+            worst[n] = max(worst[n], float(abs(Decimal(float(got[n][k])) - want) / ulp))
+    print("cos, -sin worst ulp:", [round(w, 2) for w in worst])
+    assert worst[0] <= 2.5 and worst[1] <= 2.5, worst
