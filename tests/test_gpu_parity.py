@@ -1390,3 +1390,34 @@ def test_cos_and_sin_accuracy_in_ulps(dtype):
             worst[n] = max(worst[n], float(abs(Decimal(float(got[n][k])) - want) / ulp))
     print("cos, -sin worst ulp:", [round(w, 2) for w in worst])
     assert worst[0] <= 2.5 and worst[1] <= 2.5, worst
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_cancelling_sums_keep_their_small_terms(dtype):
+    """Sums whose large terms cancel exactly and leave only small ones: products are formed
+    without rounding and accumulated wide enough (double for fp32 data, double-double for fp64)
+    that row sums, column sums and the full sum still come out right -- a plain sum in the
+    working precision would return 0 for most of them."""
+    rng = np.random.default_rng(77)
+    R, C = 96, 2052
+    big = dtype(2.0 ** 20 if dtype == np.float32 else 2.0 ** 58)
+    P = rng.integers(-3, 4, (R, C)).astype(dtype)
+    # +big / -big in 2 x 2 patterns (+ - / - +) scattered over the plane: every row and every column cancels
+    for _ in range(1500):
+        r1, r2 = rng.choice(R, 2, replace=False)
+        c1, c2 = rng.choice(C, 2, replace=False)
+        P[r1, c1] += big
+        P[r1, c2] -= big
+        P[r2, c1] -= big
+        P[r2, c2] += big
+    adj = np.full((R, C), 0.5, dtype)
+    shapes = [(R, C), (R, 1), (1, C), (1, 1)]
+    # one plane serves four gradients of the four classes (the planes of a call need not be distinct for reading)
+    planes = [to_dev(P)] * 4
+    bb = gpu_backward([to_dev(adj)], planes, shapes)
+    torch.cuda.synchronize()
+    want = oracle.backward([adj], [P] * 4, shapes, threads=8)
+    exact_all = float(np.sum(adj.astype(np.longdouble) * P.astype(np.longdouble)))
+    assert float(want[3].reshape(-1)[0]) == exact_all
+    for k, what in enumerate(("elementwise", "row sums", "column sums", "full sum")):
+        assert np.array_equal(bb.grads[k].cpu().numpy(), want[k]), what  # small integers and halves: exact on both sides
