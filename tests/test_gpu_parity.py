@@ -1421,3 +1421,24 @@ def test_cancelling_sums_keep_their_small_terms(dtype):
     assert float(want[3].reshape(-1)[0]) == exact_all
     for k, what in enumerate(("elementwise", "row sums", "column sums", "full sum")):
         assert np.array_equal(bb.grads[k].cpu().numpy(), want[k]), what  # small integers and halves: exact on both sides
+
+
+def test_expanded_adjoint_views():
+    """An upstream adjoint that is itself a broadcast view (what reverse mode hands back from a
+    sum: one value with strides 0, or a row expanded over the rows) gives the gradients of its
+    materialised copy."""
+    args, adj = small_args("branchy5", 37, 130, np.float32, seed=21)
+    dev = [to_dev(a) for a in args]
+    fb = gpu_forward("branchy5", dev)
+    shapes = [a.shape for a in args]
+    for view in (torch.full((1, 1), 0.75, device="cuda").expand(37, 130),
+                 to_dev(adj[0][:1]).expand(37, 130),
+                 to_dev(np.ascontiguousarray(adj[0][:, :1])).expand(37, 130)):
+        assert not view.is_contiguous()
+        got = gpu_backward([view], fb.partials, shapes)
+        ref = gpu_backward([view.contiguous()], fb.partials, shapes)
+        torch.cuda.synchronize()
+        want = oracle.backward([view.cpu().numpy().copy()], [p.cpu().numpy() for p in fb.partials], shapes)
+        for k in range(5):
+            check_close(got.grads[k].cpu().numpy(), want[k], f"expanded adjoint, gradient {k}")
+            check_close(ref.grads[k].cpu().numpy(), want[k], f"materialised adjoint, gradient {k}")
