@@ -433,8 +433,8 @@ int oracle_backward(int is_f64, int ndim, const int64_t *out_shape, int M, int N
         int64_t e = bcast_offset(ndim, idx, out_shape);
         for (int i = 0; i < M; ++i) {
           const void *P = partials[i * Nd + j];
-          if (!P) continue;
-          csum_add(&acc, load(adjoints[i], e, is_f64) * load(P, e, is_f64));
+          /* an absent plane is a plane of zeros: its products are adjoint x 0 (NaN for a non-finite adjoint) */
+          csum_add(&acc, load(adjoints[i], e, is_f64) * (P ? load(P, e, is_f64) : 0.0L));
         }
       }
       store(grads[j], a, is_f64, csum_value(&acc));

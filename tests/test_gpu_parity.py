@@ -1358,6 +1358,20 @@ def test_special_values_propagate_as_in_the_oracle(dtype):
         want = oracle.backward(adj, planes, shapes, threads=4)
     for k in range(5):
         _same_with_specials(bb.grads[k].cpu().numpy(), want[k], f"gradient {k} with special values")
+    # an absent plane is a plane of zeros also for a non-finite adjoint (0 x inf is NaN): lean HM-LSTM layout
+    op, args, adj = inputs.config_inputs(0, dtype=dtype)
+    dev = [to_dev(a) for a in args]
+    lean = P.alloc_forward(op, dev, lean=True).run(dev)
+    adj[0][5, 3], adj[1][7, 2], adj[0][9, 9] = np.inf, np.nan, -np.inf
+    didx = oracle.diff_arg_indices(op, 12)
+    shapes = [args[j].shape for j in didx]
+    adj_dev = [to_dev(a) for a in adj]
+    gl = P.alloc_backward(adj_dev, lean.partials, shapes).run(adj_dev, lean.partials)
+    torch.cuda.synchronize()
+    with np.errstate(all="ignore"):
+        want = oracle.backward(adj, [None if p is None else p.cpu().numpy() for p in lean.partials], shapes, threads=4)
+    for k in range(10):
+        _same_with_specials(gl.grads[k].cpu().numpy(), want[k], f"lean layout, gradient {k} with special values")
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
