@@ -147,7 +147,8 @@ int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const
  * Independent of the op.
  * adjoints[n_out]   upstream adjoints of the M outputs (read), all of one shape S.
  * partials[M*n_grads] the planes forward produced (read), shape S, index i*n_grads + jd.
- *                   A NULL data pointer stands for a plane of zeros.
+ *                   A NULL data pointer stands for a plane of zeros (its products with the
+ *                   adjoint are adjoint x 0: nothing for a finite adjoint, NaN for an infinite one).
  * grads[n_grads]    gradient of each differentiable argument (written), in THAT
  *                   ARGUMENT's shape: every dim equals S's or is 1 (or is a missing
  *                   trailing dim); where it is 1 and S's extent is larger, the products
