@@ -1460,3 +1460,13 @@ def test_expanded_adjoint_views():
         for k in range(5):
             check_close(got.grads[k].cpu().numpy(), want[k], f"expanded adjoint, gradient {k}")
             check_close(ref.grads[k].cpu().numpy(), want[k], f"materialised adjoint, gradient {k}")
+
+
+@pytest.mark.parametrize("shape", [(200000, 3), (65536, 4), (300007, 1), (2, 600000), (1, 1000003)])
+def test_tall_thin_and_long_flat_problems(shape):
+    """Hundreds of thousands of rows of a few elements (256 rows per block step, column sums over
+    all of them through many per-block partial sums) and the transposed extreme."""
+    R, C = shape
+    for op in ("branchy5", "hmlstm_update"):
+        args, adj = small_args(op, R, C, np.float32, seed=R % 97)
+        check_op(op, args, adj, threads=16, what=f"[{R} x {C}] ")
