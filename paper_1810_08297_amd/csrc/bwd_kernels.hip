@@ -264,25 +264,40 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
 }
 
 // ---- generic strided kernels: one gradient per launch ----------------------------------------------
-template <class T>
+template <class T, int VEC>
 __global__ __launch_bounds__(kBlock) void bwd_generic_full_kernel(const BwdGenericParams p) {
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= p.E) return;
+  const int64_t lane = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lane >= p.E / VEC) return;
   int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
-  decompose(e, p.E, p.nd, p.shape, idx, [](int) { return true; });
+  decompose(lane * VEC, p.E, p.nd, p.shape, idx, [](int) { return true; });
+  const int inner = p.nd - 1;
   auto off = [&](const GView &g) {
     int64_t o = 0;
 #pragma unroll
     for (int d = 0; d < BCAST_MAX_DIMS; ++d) o += idx[d] * g.s[d];
     return o;
   };
-  T a[BCAST_MAX_OUTS][1], P[BCAST_MAX_OUTS][1];
+  T a[BCAST_MAX_OUTS][VEC], P[BCAST_MAX_OUTS][VEC];
 #pragma unroll
   for (int i = 0; i < BCAST_MAX_OUTS; ++i) {
-    a[i][0] = (i < p.M) ? static_cast<const T *>(p.adj[i].p)[off(p.adj[i])] : T(0);
-    P[i][0] = (i < p.M && p.P[i].p) ? static_cast<const T *>(p.P[i].p)[off(p.P[i])] : T(0);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) a[i][v] = P[i][v] = T(0);
+    if (i < p.M) {
+      const T *src = static_cast<const T *>(p.adj[i].p) + off(p.adj[i]);
+      if (VEC > 1 && p.adj[i].s[inner] != 0) {
+        load_vec<T, VEC, false>(src, a[i]);
+      } else {  // one element per lane, or an adjoint that is constant along the innermost dim
+        const T x = *src;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) a[i][v] = x;
+      }
+      if (p.P[i].p) load_vec<T, VEC, false>(static_cast<const T *>(p.P[i].p) + off(p.P[i]), P[i]);
+    }
   }
-  static_cast<T *>(p.g.p)[off(p.g)] = wide_dot<T, BCAST_MAX_OUTS, 1>(a, P, 0);
+  T o[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, BCAST_MAX_OUTS, VEC>(a, P, v);
+  store_vec<T, VEC>(static_cast<T *>(p.g.p) + off(p.g), o, false);
 }
 
 // one block per gradient element; the block walks that element's fibre (the dims the
@@ -454,10 +469,12 @@ hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_
   dim3 grid((unsigned)n_blocks);
   if (dt == BCAST_F32) {
     if (reduce) launch((bwd_generic_reduce_kernel<float>), grid, dim3(kBlock), 0, s, p);
-    else launch((bwd_generic_full_kernel<float>), grid, dim3(kBlock), 0, s, p);
+    else if (p.vec == 4) launch((bwd_generic_full_kernel<float, 4>), grid, dim3(kBlock), 0, s, p);
+    else launch((bwd_generic_full_kernel<float, 1>), grid, dim3(kBlock), 0, s, p);
   } else {
     if (reduce) launch((bwd_generic_reduce_kernel<double>), grid, dim3(kBlock), 0, s, p);
-    else launch((bwd_generic_full_kernel<double>), grid, dim3(kBlock), 0, s, p);
+    else if (p.vec == 2) launch((bwd_generic_full_kernel<double, 2>), grid, dim3(kBlock), 0, s, p);
+    else launch((bwd_generic_full_kernel<double, 1>), grid, dim3(kBlock), 0, s, p);
   }
   return hipGetLastError();
 }

@@ -257,37 +257,63 @@ BD_DEV void decompose(int64_t linear, int64_t count, int nd, const int64_t *shap
   }
 }
 
-// Generic kernel: any rank up to BCAST_MAX_DIMS, any strides; one element per lane.
-template <class Op, class T>
+// Generic kernel: any rank up to BCAST_MAX_DIMS, any strides.  A lane takes VEC consecutive
+// elements of the innermost dim: one element in general, a 16-byte vector where the host found
+// that every view is contiguous (or constant) along that dim and aligned for it.
+template <class Op, class T, int VEC>
 __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericParams p) {
   constexpr int N = Op::N, M = Op::M;
   constexpr int ND = N - popc(Op::NONDIFF);
   using Y = Dual<T, (ND >= 32 ? 0xffffffffu : ((1u << ND) - 1u))>;
-  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (e >= p.E) return;
+  const int64_t lane = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lane >= p.E / VEC) return;
   int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
-  decompose(e, p.E, p.nd, p.shape, idx, [](int) { return true; });
+  decompose(lane * VEC, p.E, p.nd, p.shape, idx, [](int) { return true; });
+  const int inner = p.nd - 1;
   auto off = [&](const GView &g) {
     int64_t o = 0;
 #pragma unroll
     for (int d = 0; d < BCAST_MAX_DIMS; ++d) o += idx[d] * g.s[d];
     return o;
   };
-  T a[N][1];
+  T a[N][VEC];
 #pragma unroll
-  for (int j = 0; j < N; ++j) a[j][0] = static_cast<const T *>(p.arg[j].p)[off(p.arg[j])];
-  Y y[M];
-  const int br = eval_op<Op, T, 1>(a, 0, y, std::make_index_sequence<N>{});
+  for (int j = 0; j < N; ++j) {
+    const T *src = static_cast<const T *>(p.arg[j].p) + off(p.arg[j]);
+    if (VEC > 1 && p.arg[j].s[inner] != 0) {
+      load_vec<T, VEC, false>(src, a[j]);
+    } else {  // one element per lane, or an argument that is constant along the innermost dim
+      const T x = *src;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) a[j][v] = x;
+    }
+  }
+  Y y[VEC][M];
+  int br[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) br[v] = eval_op<Op, T, VEC>(a, v, y[v], std::make_index_sequence<N>{});
+  T o[VEC];
 #pragma unroll
   for (int i = 0; i < M; ++i) {
-    static_cast<T *>(p.out[i].p)[off(p.out[i])] = y[i].v;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
+    store_vec<T, VEC>(static_cast<T *>(p.out[i].p) + off(p.out[i]), o, false);
     static_for<0, ND>([&](auto JD) {
       constexpr int jd = decltype(JD)::value;
       const GView &pl = p.part[i * ND + jd];
-      if (pl.p != nullptr) static_cast<T *>(pl.p)[off(pl)] = y[i].template partial<jd>();
+      if (pl.p != nullptr) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
+        store_vec<T, VEC>(static_cast<T *>(pl.p) + off(pl), o, false);
+      }
     });
   }
-  if (p.branch.p != nullptr) static_cast<uint8_t *>(p.branch.p)[off(p.branch)] = (uint8_t)br;
+  if (p.branch.p != nullptr) {
+    uint8_t *bp = static_cast<uint8_t *>(p.branch.p) + off(p.branch);
+    const int64_t bs = VEC > 1 ? p.branch.s[inner] : 0;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) bp[v * bs] = (uint8_t)br[v];
+  }
 }
 
 // ---- launch wrappers, one pair per op ------------------------------------------------------
@@ -328,10 +354,21 @@ hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid,
 }
 template <class Op>
 hipError_t launch_fwd_generic(int dt, const FwdGenericParams &p, dim3 grid, hipStream_t s) {
+  // the vector form exists for the ops that are built in every variant (the host asks for it only then)
+  if constexpr (Op::STRIDED) {
+    if (p.vec > 1) {
+      if (dt == BCAST_F32)
+        launch((fwd_generic_kernel<Op, float, 4>), grid, dim3(kBlock), 0, s, p);
+      else
+        launch((fwd_generic_kernel<Op, double, 2>), grid, dim3(kBlock), 0, s, p);
+      return hipGetLastError();
+    }
+  }
+  if (p.vec > 1) return hipErrorNotSupported;
   if (dt == BCAST_F32)
-    launch((fwd_generic_kernel<Op, float>), grid, dim3(kBlock), 0, s, p);
+    launch((fwd_generic_kernel<Op, float, 1>), grid, dim3(kBlock), 0, s, p);
   else
-    launch((fwd_generic_kernel<Op, double>), grid, dim3(kBlock), 0, s, p);
+    launch((fwd_generic_kernel<Op, double, 1>), grid, dim3(kBlock), 0, s, p);
   return hipGetLastError();
 }
 

@@ -313,6 +313,19 @@ int auto_steps(int64_t R, const Geometry &g, int max_steps) {
   return (int)std::max<int64_t>(1, std::min<int64_t>(s, max_steps));
 }
 
+// Whether a lane of the generic kernels may take `vw` consecutive elements of the innermost dim of
+// view `t` as one vector: the view runs contiguously along that dim (or, where `may_be_constant`,
+// does not vary along it), starts on a vector boundary and keeps to one with every outer stride.
+bool generic_vector_ok(const Canon &c, size_t t, const void *ptr, int vw, size_t es, bool may_be_constant) {
+  const int in = c.nd - 1;
+  const int64_t s_in = c.strides[t][in];
+  if (s_in == 0) return may_be_constant;
+  if (s_in != 1 || reinterpret_cast<uintptr_t>(ptr) % (vw * es) != 0) return false;
+  for (int d = 0; d < in; ++d)
+    if (c.strides[t][d] % vw != 0) return false;
+  return true;
+}
+
 // ---- forward planning ----------------------------------------------------------------------------
 struct FwdPlan {
   bcast_plan_info info{};
@@ -492,11 +505,17 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (int k = 0; k < M * ND; ++k)
       p.part[k] = (k < n_planes && !dup[k]) ? gview(c, N + M + k, v[N + M + k].p) : GView{nullptr, {0, 0, 0, 0}};
     p.branch = want_branch ? gview(c, v.size(), const_cast<uint8_t *>(branch_id)) : GView{nullptr, {0, 0, 0, 0}};
-    const int64_t blocks = ceil_div(c.E, kBlock);
+    // 16-byte vectors along the innermost dim where every view allows them (ops built in every variant)
+    int gv = op.strided && c.nd >= 1 ? (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es) : 1;
+    if (gv != (int)(16 / es) || c.shape[c.nd - 1] % gv != 0) gv = 1;
+    for (size_t t = 0; t < v.size() && gv > 1; ++t)
+      if (v[t].p && !(t >= (size_t)(N + M) && dup[t - N - M]) && !generic_vector_ok(c, t, v[t].p, gv, es, t < (size_t)N)) gv = 1;
+    p.vec = gv;
+    const int64_t blocks = ceil_div(c.E / gv, kBlock);
     if (blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.grid = dim3((unsigned)blocks, 1, 1);
     plan.info.path = 2;
-    plan.info.vec = 1;
+    plan.info.vec = gv;
     plan.info.tx = kBlock;
     plan.info.ty = 1;
     plan.info.rows_per_block = 1;
@@ -911,7 +930,16 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         reduce |= p.reduced[d] != 0;
         (p.reduced[d] ? p.n_fibre : p.n_kept) *= c.shape[d];
       }
-      const int64_t blocks = reduce ? p.n_kept : ceil_div(c.E, kBlock);
+      int gv = !reduce && c.nd >= 1 ? (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es) : 1;
+      if (gv != (int)(16 / es) || c.shape[c.nd - 1] % gv != 0) gv = 1;
+      for (int i = 0; i < M && gv > 1; ++i) {
+        if (!generic_vector_ok(c, i, v[i].p, gv, es, true)) gv = 1;
+        const size_t tp = M + i * ND + j;
+        if (gv > 1 && v[tp].p && !generic_vector_ok(c, tp, v[tp].p, gv, es, false)) gv = 1;
+      }
+      if (gv > 1 && !generic_vector_ok(c, g0 + j, v[g0 + j].p, gv, es, false)) gv = 1;
+      p.vec = gv;
+      const int64_t blocks = reduce ? p.n_kept : ceil_div(c.E / gv, kBlock);
       if (blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
       plan.generic.emplace_back(reduce, p);
       plan.generic_blocks.push_back(blocks);

@@ -58,6 +58,7 @@ struct GView {
 
 struct FwdGenericParams {
   int32_t nd;
+  int32_t vec;  // elements per lane along the innermost dim (1, or the 16-byte vector where every view allows it)
   int64_t shape[BCAST_MAX_DIMS];
   int64_t E;
   GView arg[BCAST_MAX_ARGS];
@@ -136,6 +137,7 @@ struct Pass2Params {
 
 struct BwdGenericParams {
   int32_t nd, M;
+  int32_t vec, pad;  // as in FwdGenericParams (elementwise kernel only)
   int64_t shape[BCAST_MAX_DIMS];
   int64_t E;
   GView adj[BCAST_MAX_OUTS];

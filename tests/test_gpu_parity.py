@@ -1470,3 +1470,39 @@ def test_tall_thin_and_long_flat_problems(shape):
     for op in ("branchy5", "hmlstm_update"):
         args, adj = small_args(op, R, C, np.float32, seed=R % 97)
         check_op(op, args, adj, threads=16, what=f"[{R} x {C}] ")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_rank3_problem_takes_vectors_along_the_innermost_dim(dtype):
+    """An argument broadcast along the middle dim only keeps the problem at rank 3 (no two dims
+    merge): the generic kernels serve it, with 16-byte accesses along the contiguous innermost dim
+    where every view allows them and element by element where one does not."""
+    rng = np.random.default_rng(314)
+    T_, B_, H_ = 6, 10, 64
+    A = rng.standard_normal((T_, B_, H_)).astype(dtype)
+    Bm = rng.uniform(0.1, 2, (T_, B_, H_)).astype(dtype)
+    r = rng.standard_normal((T_, 1, H_)).astype(dtype)      # per step and feature, broadcast over the batch
+    s = rng.standard_normal((1, B_, 1)).astype(dtype)
+    t = rng.standard_normal((1, 1, 1)).astype(dtype)
+    adj = [rng.standard_normal((T_, B_, H_)).astype(dtype)]
+    dev = [to_dev(x) for x in (A, Bm, r, s, t)]
+    fb = P.alloc_forward("branchy5", dev, want_branch=True)
+    info = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials, fb.branch)
+    assert info["path"] == 2 and info["ndim"] == 3 and info["vec"] == (4 if dtype == np.float32 else 2), info
+    check_op("branchy5", [A, Bm, r, s, t], adj, what="rank 3, vectors ")
+    # an innermost extent that is not a multiple of the vector, and a view with padded rows whose
+    # stride is not one either: element by element
+    A2, B2, r2, adj2 = A[..., :63], Bm[..., :63], r[..., :63], [adj[0][..., :63]]
+    dev2 = [to_dev(x) for x in (A2, B2, r2, s, t)]
+    f2 = P.alloc_forward("branchy5", dev2)
+    assert P.bcast_dual_forward_plan(f2.op_id, dev2, f2.outs, f2.partials)["vec"] == 1
+    check_op("branchy5", [A2, B2, r2, s, t], adj2, what="rank 3, elements ")
+
+    def padded(tn, k):  # rows padded by 3 elements: outer strides 67 and 670 keep no vector boundary
+        if k != 0:
+            return tn
+        wide = torch.empty(T_, B_, H_ + 3, dtype=tn.dtype, device=tn.device)
+        wide[..., :H_] = tn
+        return wide[..., :H_]
+
+    check_op("branchy5", [A, Bm, r, s, t], adj, view=padded, what="rank 3, one padded view ")
