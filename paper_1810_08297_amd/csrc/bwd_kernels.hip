@@ -300,38 +300,80 @@ __global__ __launch_bounds__(kBlock) void bwd_generic_full_kernel(const BwdGener
   store_vec<T, VEC>(static_cast<T *>(p.g.p) + off(p.g), o, false);
 }
 
-// one block per gradient element; the block walks that element's fibre (the dims the
-// argument was expanded along) with a fixed lane-to-term assignment
+// Reduced gradients on the generic path: see BwdGenericParams for the two lane arrangements and
+// the cut of a fibre into chunks.  Lane-to-term assignment and the order of all additions are
+// fixed by the geometry alone.
 template <class T>
 __global__ __launch_bounds__(kBlock) void bwd_generic_reduce_kernel(const BwdGenericParams p) {
   using AT = acc_traits<T>;
   using A = typename AT::type;
-  __shared__ A sh[kBlock / 64];
+  __shared__ A sh[kBlock];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t group = (int64_t)blockIdx.x / p.splits, sp = (int64_t)blockIdx.x - group * p.splits;
+  const int64_t q0 = sp * p.chunk, q1 = q0 + p.chunk < p.n_fibre ? q0 + p.chunk : p.n_fibre;
+  const int64_t a = p.lanes_along_kept ? group * 64 + lane : group;  // this lane's gradient element
+  const bool live = a < p.n_kept;
   int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
-  decompose(blockIdx.x, p.n_kept, p.nd, p.shape, idx, [&](int d) { return !p.reduced[d]; });
+  decompose(live ? a : 0, p.n_kept, p.nd, p.shape, idx, [&](int d) { return !p.reduced[d]; });
   int64_t goff = 0;
   for (int d = 0; d < BCAST_MAX_DIMS; ++d) goff += idx[d] * p.g.s[d];
   A s = AT::zero();
-  for (int64_t q = threadIdx.x; q < p.n_fibre; q += kBlock) {
-    decompose(q, p.n_fibre, p.nd, p.shape, idx, [&](int d) { return p.reduced[d] != 0; });
-    for (int i = 0; i < p.M; ++i) {
-      if (p.P[i].p == nullptr) continue;
-      int64_t oa = 0, op = 0;
-      for (int d = 0; d < BCAST_MAX_DIMS; ++d) {
-        oa += idx[d] * p.adj[i].s[d];
-        op += idx[d] * p.P[i].s[d];
+  const int64_t first = p.lanes_along_kept ? wave : tid, step = p.lanes_along_kept ? kBlock / 64 : kBlock;
+  if (live)
+    for (int64_t q = q0 + first; q < q1; q += step) {
+      decompose(q, p.n_fibre, p.nd, p.shape, idx, [&](int d) { return p.reduced[d] != 0; });
+      for (int i = 0; i < p.M; ++i) {
+        if (p.P[i].p == nullptr) continue;
+        int64_t oa = 0, op = 0;
+        for (int d = 0; d < BCAST_MAX_DIMS; ++d) {
+          oa += idx[d] * p.adj[i].s[d];
+          op += idx[d] * p.P[i].s[d];
+        }
+        AT::add_prod(s, static_cast<const T *>(p.adj[i].p)[oa], static_cast<const T *>(p.P[i].p)[op]);
       }
-      AT::add_prod(s, static_cast<const T *>(p.adj[i].p)[oa], static_cast<const T *>(p.P[i].p)[op]);
+    }
+  A total = AT::zero();
+  bool writer;
+  if (p.lanes_along_kept) {  // the four wavefronts' sums of one gradient element, in wavefront order
+    sh[tid] = s;
+    __syncthreads();
+    writer = wave == 0 && live;
+    if (writer) {
+      total = sh[lane];
+      for (int w = 1; w < kBlock / 64; ++w) AT::add(total, sh[w * 64 + lane]);
+    }
+  } else {
+    s = seg_reduce<T, A>(s, 6);
+    if (lane == 0) sh[wave] = s;
+    __syncthreads();
+    writer = tid == 0;
+    if (writer) {
+      total = sh[0];
+      for (int w = 1; w < kBlock / 64; ++w) AT::add(total, sh[w]);
     }
   }
-  s = seg_reduce<T, A>(s, 6);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    A t = sh[0];
-    for (int w = 1; w < kBlock / 64; ++w) AT::add(t, sh[w]);
-    static_cast<T *>(p.g.p)[goff] = AT::fin(t);
+  if (writer) {
+    if (p.splits == 1)
+      static_cast<T *>(p.g.p)[goff] = AT::fin(total);
+    else
+      reinterpret_cast<A *>(p.ws + p.ws_off)[a * p.splits + sp] = total;
   }
+}
+// one lane per gradient element adds that element's partial sums in chunk order
+template <class T>
+__global__ __launch_bounds__(kBlock) void bwd_generic_final_kernel(const BwdGenericParams p) {
+  using AT = acc_traits<T>;
+  using A = typename AT::type;
+  const int64_t a = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (a >= p.n_kept) return;
+  int64_t idx[BCAST_MAX_DIMS] = {0, 0, 0, 0};
+  decompose(a, p.n_kept, p.nd, p.shape, idx, [&](int d) { return !p.reduced[d]; });
+  int64_t goff = 0;
+  for (int d = 0; d < BCAST_MAX_DIMS; ++d) goff += idx[d] * p.g.s[d];
+  const A *part = reinterpret_cast<const A *>(p.ws + p.ws_off) + a * p.splits;
+  A t = part[0];
+  for (int k = 1; k < p.splits; ++k) AT::add(t, part[k]);
+  static_cast<T *>(p.g.p)[goff] = AT::fin(t);
 }
 
 // ---- streaming probe with the tiled kernels' access pattern --------------------------------------------
@@ -465,14 +507,17 @@ hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStrea
   return hipGetLastError();
 }
 
-hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s) {
+// kind: 0 = elementwise (full-shape gradient), 1 = reduction, 2 = sum of a reduction's partial sums
+hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s) {
   dim3 grid((unsigned)n_blocks);
   if (dt == BCAST_F32) {
-    if (reduce) launch((bwd_generic_reduce_kernel<float>), grid, dim3(kBlock), 0, s, p);
+    if (kind == 1) launch((bwd_generic_reduce_kernel<float>), grid, dim3(kBlock), 0, s, p);
+    else if (kind == 2) launch((bwd_generic_final_kernel<float>), grid, dim3(kBlock), 0, s, p);
     else if (p.vec == 4) launch((bwd_generic_full_kernel<float, 4>), grid, dim3(kBlock), 0, s, p);
     else launch((bwd_generic_full_kernel<float, 1>), grid, dim3(kBlock), 0, s, p);
   } else {
-    if (reduce) launch((bwd_generic_reduce_kernel<double>), grid, dim3(kBlock), 0, s, p);
+    if (kind == 1) launch((bwd_generic_reduce_kernel<double>), grid, dim3(kBlock), 0, s, p);
+    else if (kind == 2) launch((bwd_generic_final_kernel<double>), grid, dim3(kBlock), 0, s, p);
     else if (p.vec == 2) launch((bwd_generic_full_kernel<double, 2>), grid, dim3(kBlock), 0, s, p);
     else launch((bwd_generic_full_kernel<double, 1>), grid, dim3(kBlock), 0, s, p);
   }

@@ -53,7 +53,7 @@ bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent
 hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
-hipError_t bd_bwd_generic(int dt, bool reduce, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
+hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
                            const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, size_t lds_bytes,
                            hipStream_t s);
@@ -544,7 +544,7 @@ struct BwdPlan {
   dim3 grid{1, 1, 1};
   Pass2Params p2{};
   int64_t p2_blocks = 0;
-  std::vector<std::pair<bool, BwdGenericParams>> generic;  // (is reduction, params)
+  std::vector<std::pair<int, BwdGenericParams>> generic;  // (0 elementwise / 1 reduction / 2 sum of partial sums, params)
   std::vector<int64_t> generic_blocks;
   size_t ws_bytes = 0;
 };
@@ -910,6 +910,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // the class-specialised kernels exist for the widest vector only
     plan.info.specialized = plan.signature && ((dt == BCAST_F32 && g.vec == 4) || (dt == BCAST_F64 && g.vec == 2));
   } else {
+    size_t gen_ws = 0;  // partial sums of the reductions that are cut into chunks
     for (int j = 0; j < ND; ++j) {
       if (!v[g0 + j].p) continue;
       BwdGenericParams p{};
@@ -939,11 +940,34 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
       if (gv > 1 && !generic_vector_ok(c, g0 + j, v[g0 + j].p, gv, es, false)) gv = 1;
       p.vec = gv;
-      const int64_t blocks = reduce ? p.n_kept : ceil_div(c.E / gv, kBlock);
+      p.splits = 1;
+      int64_t blocks = ceil_div(c.E / gv, kBlock);
+      if (reduce) {
+        // enough blocks to fill the chip: a fibre is cut into chunks (at least 1024 terms each where
+        // the lanes walk it, 64 where they lie along the gradient's elements)
+        p.lanes_along_kept = c.nd >= 1 && !p.reduced[c.nd - 1];
+        const int64_t groups = p.lanes_along_kept ? ceil_div(p.n_kept, 64) : p.n_kept;
+        const int64_t min_chunk = p.lanes_along_kept ? 64 : 1024;
+        int64_t splits = std::min<int64_t>(ceil_div(2048, groups), std::max<int64_t>(1, p.n_fibre / min_chunk));
+        splits = std::max<int64_t>(1, std::min<int64_t>(splits, 4096));
+        p.chunk = ceil_div(p.n_fibre, splits);
+        splits = ceil_div(p.n_fibre, p.chunk);  // no empty chunk
+        p.splits = (int32_t)splits;
+        blocks = groups * splits;
+        if (splits > 1) {
+          p.ws_off = (int64_t)gen_ws;
+          gen_ws += align16((size_t)p.n_kept * splits * as);
+        }
+      }
       if (blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
-      plan.generic.emplace_back(reduce, p);
+      plan.generic.emplace_back(reduce ? 1 : 0, p);
       plan.generic_blocks.push_back(blocks);
+      if (reduce && p.splits > 1) {
+        plan.generic.emplace_back(2, p);
+        plan.generic_blocks.push_back(ceil_div(p.n_kept, kBlock));
+      }
     }
+    plan.ws_bytes = gen_ws;
     plan.info.path = 2;
     plan.info.vec = 1;
     plan.info.tx = kBlock;
@@ -1060,10 +1084,17 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
       if (launch_status(bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s)) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
     }
   } else {
-    for (size_t k = 0; k < plan.generic.size(); ++k)
+    if (plan.ws_bytes > 0) {
+      if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
+      if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
+      if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
+    }
+    for (size_t k = 0; k < plan.generic.size(); ++k) {
+      plan.generic[k].second.ws = static_cast<unsigned char *>(workspace);
       if (launch_status(bd_bwd_generic((int)dt, plan.generic[k].first, plan.generic[k].second, plan.generic_blocks[k], s)) !=
           BCAST_OK)
         return BCAST_ERR_LAUNCH_FAILED;
+    }
   }
   return BCAST_OK;
 }

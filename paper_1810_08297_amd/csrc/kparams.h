@@ -146,6 +146,16 @@ struct BwdGenericParams {
   // reduction geometry: kept dims enumerate gradient elements, reduced dims the fibre
   int32_t reduced[BCAST_MAX_DIMS];
   int64_t n_kept, n_fibre;
+  // The fibre of every gradient element is cut into `splits` chunks of `chunk` terms, one block
+  // each.  lanes_along_kept = 0: the innermost dim is reduced, a block serves one gradient element
+  // and its lanes walk the fibre; 1: the innermost dim is kept, a block serves 64 consecutive
+  // gradient elements (lanes along them: coalesced) with its four wavefronts interleaved over the
+  // chunk.  With one chunk the block writes the gradient, otherwise its partial sum goes to
+  // ws[element * splits + chunk] for the final kernel.
+  int32_t splits, lanes_along_kept;
+  int64_t chunk;
+  int64_t ws_off;  // bytes
+  unsigned char *ws;
 };
 
 }  // namespace bd
