@@ -1506,3 +1506,28 @@ def test_rank3_problem_takes_vectors_along_the_innermost_dim(dtype):
         return wide[..., :H_]
 
     check_op("branchy5", [A, Bm, r, s, t], adj, view=padded, what="rank 3, one padded view ")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_rank3_reductions_of_many_chunks(dtype):
+    """Rank-3 problems large enough that the generic reductions cut their fibres into chunks
+    (partial sums in the workspace, final kernel), in both lane arrangements: fibres along the
+    contiguous dim (gradients [1 x B x 1], [T x 1 x 1], scalar) and gradients along it
+    ([T x 1 x H], [1 x 1 x H])."""
+    rng = np.random.default_rng(2718)
+    T_, B_, H_ = 24, 70, 1030
+    full = (T_, B_, H_)
+    A = rng.standard_normal(full).astype(dtype)
+    Bm = rng.uniform(0.1, 2, full).astype(dtype)
+    adj = [rng.standard_normal(full).astype(dtype)]
+    for rs, ss, ts in (((T_, 1, H_), (1, B_, 1), (1, 1, 1)), ((T_, 1, H_), (1, 1, H_), (T_, 1, 1))):
+        r, s, t = (rng.standard_normal(sh).astype(dtype) for sh in (rs, ss, ts))
+        dev = [to_dev(x) for x in (A, Bm, r, s, t)]
+        fb = gpu_forward("branchy5", dev)
+        shapes = [x.shape for x in (A, Bm, r, s, t)]
+        grads = [torch.empty(sh, dtype=dev[0].dtype, device="cuda") for sh in shapes]
+        adj_dev = [to_dev(adj[0])]
+        info = P.bcast_dual_backward_plan(adj_dev, fb.partials, grads)
+        assert info["path"] == 2 and info["ndim"] == 3 and info["n_launches"] > 5  # some reductions need the final kernel
+        assert P.bcast_dual_backward_workspace(adj_dev, fb.partials, grads) > 0
+        check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what=f"r {rs} s {ss} t {ts} ")
