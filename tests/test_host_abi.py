@@ -542,3 +542,39 @@ def test_launching_wrappers_refuse_host_tensors():
         P.PreparedForward(op, [x, y, b], out, parts)
     with pytest.raises(ValueError):
         P.broadcast("tanh_xy_b", x, y, b)
+
+
+def test_generic_path_plans_chunked_reductions():
+    """A problem that stays at rank 3 runs on the generic kernels: vectors along the innermost dim
+    where the views allow it, and reductions over long fibres cut into chunks, which need
+    workspace for their partial sums and one more small launch each."""
+    T_, B_, H_ = 64, 256, 1024
+    base = [1 << 40]
+
+    def view(shape):
+        base[0] += 1 << 32
+        strides, acc = [], 1
+        for n in reversed(shape):
+            strides.append(acc if n > 1 else 0)
+            acc *= n
+        return B.raw_view(base[0], shape, tuple(reversed(strides)))
+
+    full, rs, ss, ts = (T_, B_, H_), (T_, 1, H_), (1, B_, 1), (1, 1, 1)
+    op = P.bcast_op_lookup("branchy5")
+    args = [view(full), view(full), view(rs), view(ss), view(ts)]
+    outs, parts = [view(full)], [view(full) for _ in range(5)]
+    rc, d = _fwd_plan("branchy5", 0, args, outs, parts)
+    assert rc == 0 and d["path"] == 2 and d["ndim"] == 3 and d["vec"] == 4
+    adj, grads = [view(full)], [view(full), view(full), view(rs), view(ss), view(ts)]
+    info = B.PlanInfo()
+    L = B.lib()
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
+    # two elementwise launches, three reductions, each cut into chunks and followed by its final kernel
+    assert rc == 0 and info.path == 2 and info.n_launches == 2 + 3 + 3
+    ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                         ctypes.c_int32(5), B._views(grads))
+    assert 0 < ws < (1 << 20)
+    rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts), ctypes.c_int32(5),
+                               B._views(grads), None, ctypes.c_size_t(0), None)
+    assert rc == -3  # the workspace is asked for before anything is launched
