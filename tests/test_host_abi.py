@@ -574,7 +574,7 @@ def test_generic_path_plans_chunked_reductions():
     assert rc == 0 and info.path == 2 and info.n_launches == 2 + 3 + 3
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
                                          ctypes.c_int32(5), B._views(grads))
-    assert 0 < ws < (1 << 20)
+    assert 0 < ws < (1 << 22)  # 65536 x 2 partial sums of 8 bytes for the [T x 1 x H] gradient, a few KiB for the others
     rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts), ctypes.c_int32(5),
                                B._views(grads), None, ctypes.c_size_t(0), None)
     assert rc == -3  # the workspace is asked for before anything is launched
