@@ -224,7 +224,9 @@ const char *bcast_status_string(int status);
  *          (160 KiB each): 48 (default) = three, 0 = no limit
  *   key 12: the same for the main backward and recompute kernels, on top of what they need
  *          (default 0: measured no gain)
- *   key 13: the same for the stream probe (default 0) */
+ *   key 13: the same for the stream probe (default 0)
+ *   key 14: 1 (default) = rows longer than 1024 elements may be tiled with 64 or 128 lanes per row
+ *          (4 or 2 rows per block step) where that pads the row less than 256 lanes; 0 = always 256 */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 

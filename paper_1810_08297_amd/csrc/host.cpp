@@ -111,9 +111,9 @@ constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 enum TuneKey {
   kTuneUnused = 0, kTuneBwdRows, kTuneNtStores, kTuneForceGeneric, kTuneMaxVecBytes, kTuneRuntimeTable, kTuneReverse,
   kTuneProbeNtLoads, kTuneInterleave, kTuneXcdOrder, kTuneColChunks, kTuneFwdLdsKiB, kTuneBwdLdsKiB, kTuneProbeLdsKiB,
-  kNumTune
+  kTuneNarrowTiles, kNumTune
 };
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0};
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0, 1};
 
 // A failed launch is reported with the runtime's own words on stderr: the status code alone
 // cannot say why.
@@ -283,15 +283,44 @@ int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Sha
   return uniform ? sr : -1;
 }
 
+// Rows of 1024 elements and more are normally taken one per block step (common_row_stride counts
+// on that); up to four per step are possible only if four rows of every view still span less than 4 GiB.
+bool narrow_tiles_ok(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es) {
+  for (size_t t = 0; t < v.size(); ++t) {
+    if (!v[t].p) continue;
+    const TView tv = tview(c, t, nullptr);
+    if (tv.sc == 0) continue;
+    if (((unsigned __int128)3 * tv.sr + s2.C) * es > 0xffffffffULL) return false;
+  }
+  return true;
+}
+
 struct Geometry {
   int vec = 1, log2_tx = 0, steps = 1;
   int64_t n_ct = 1, n_rt = 1;
 };
 
-// lanes along the columns: the smallest power of two covering the row, at most a block
-void tile_columns(int64_t C, int vec, Geometry &g) {
+// Lanes along the columns: the smallest power of two covering the row, at most a block.  A row
+// longer than a block's 256 lanes is cut into column tiles; a last tile with few lanes in use
+// still costs whole blocks (4096 x 1028 fp32, 257 vectors per row, took 265 us per step against
+// 154 us for 4096 x 1024), so 64 or 128 lanes per row (4 or 2 rows per block step) are taken
+// instead where that pads the row less -- a wavefront still covers 1 KiB of a row.
+void tile_columns(int64_t C, int vec, bool narrow_ok, Geometry &g) {
   const int64_t units = ceil_div(C, vec);
   g.log2_tx = std::min(8, ilog2_ceil(units));
+  if (units > 256 && narrow_ok && g_tune[kTuneNarrowTiles] != 0) {
+    const int64_t padded256 = ceil_div(units, 256) * 256;
+    int64_t best = padded256;
+    int best_l = 8;
+    for (int l = 7; l >= 6; --l) {  // ties go to the wider tile
+      const int64_t padded = ceil_div(units, (int64_t)1 << l) << l;
+      if (padded < best) {
+        best = padded;
+        best_l = l;
+      }
+    }
+    if (best * 10 <= padded256 * 9) g.log2_tx = best_l;  // worth it from a tenth less padding on
+  }
   g.n_ct = ceil_div(units, (int64_t)1 << g.log2_tx);
 }
 // false if the problem needs more blocks than one launch can have
@@ -449,7 +478,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     if (!p.uniform_stride && vw != (int)(16 / es)) vw = 1;  // those kernels exist for the widest vector and for 1
     Geometry g;
     g.vec = vw;
-    tile_columns(s2.C, g.vec, g);
+    tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), g);
     if (!tile_rows(s2.R, 1, g)) return BCAST_ERR_LAUNCH_FAILED;  // the forward kernel has no row loop
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
@@ -676,7 +705,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     Geometry g;
     g.vec = vw;
     plan.vec = g.vec;
-    tile_columns(s2.C, g.vec, g);
+    tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), g);
     bool any_rowwise = false;  // sums over rows: worth many rows per block
     int n_rowsum = 0;
     for (int j = 0; j < ND; ++j) {
@@ -1174,7 +1203,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64, 64};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64, 64, 1};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;
