@@ -82,6 +82,9 @@ typedef struct {
   int32_t specialized; /* backward: 1 if the main pass is a kernel compiled for this call's mix of
                           gradient classes, absent and shared planes; 0 = the kernels that read the
                           gradient table at run time.  forward: 0 */
+  int32_t ragged;      /* 1: the rows do not fit the 16-byte vector (length, start or stride off its
+                          boundary) and the kernels that take it unaligned, with the last columns of
+                          every row singly, are used */
 } bcast_plan_info;
 
 /* ---- op table --------------------------------------------------------------------
@@ -226,7 +229,10 @@ const char *bcast_status_string(int status);
  *          (default 0: measured no gain)
  *   key 13: the same for the stream probe (default 0)
  *   key 14: 1 (default) = rows longer than 1024 elements may be tiled with 64 or 128 lanes per row
- *          (4 or 2 rows per block step) where that pads the row less than 256 lanes; 0 = always 256 */
+ *          (4 or 2 rows per block step) where that pads the row less than 256 lanes; 0 = always 256
+ *   key 15: 1 (default) = rows whose length, start or stride is not a multiple of the 16-byte vector
+ *          are still read and written in such vectors, unaligned, with the last columns of every
+ *          row taken singly; 0 = the widest aligned access that fits (8 or 4 bytes) */
 int bcast_dual_set_tuning(int32_t key, int32_t value);
 int bcast_dual_get_tuning(int32_t key, int32_t *value);
 

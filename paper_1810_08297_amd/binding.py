@@ -30,7 +30,8 @@ class PlanInfo(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("vec", ctypes.c_int32), ("ndim", ctypes.c_int32),
                 ("shape", ctypes.c_int64 * MAX_DIMS), ("tx", ctypes.c_int32), ("ty", ctypes.c_int32),
                 ("rows_per_block", ctypes.c_int32), ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64),
-                ("n_launches", ctypes.c_int32), ("n_second_pass", ctypes.c_int32), ("specialized", ctypes.c_int32)]
+                ("n_launches", ctypes.c_int32), ("n_second_pass", ctypes.c_int32), ("specialized", ctypes.c_int32),
+                ("ragged", ctypes.c_int32)]
 
     def as_dict(self):
         d = {k: getattr(self, k) for k, _ in self._fields_ if k != "shape"}

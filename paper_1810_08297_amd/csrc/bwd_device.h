@@ -143,8 +143,9 @@ struct BwdGeom {
   int64_t c0, r_first;  // r_first: row of the block's first row step at ty = 0
   int64_t r_step;       // rows from one row step of the block to its next
   bool colvalid, interior;
-  uint32_t lane_uniform;  // (lane's row within a row step * common row stride + lane's first column) * sizeof(T)
-  uint32_t col_off;       // byte offset of the lane's first column within a row
+  int shift;              // ragged rows: columns by which the row's last lane moves its loads to the left (see unshift)
+  uint32_t lane_uniform;  // (lane's row within a row step * common row stride + lane's first load column) * sizeof(T)
+  uint32_t col_off;       // byte offset of the lane's first load column within a row
   int chunk_cols;        // columns one lane arrangement covers: TX * VEC
   uint32_t chunk_bytes;  // ... in bytes
   A *lds_row, *lds_col, *lds_all;
@@ -187,8 +188,10 @@ struct BwdGeom {
     interior = r_first + (p.steps - 1) * r_step + TY <= p.R && (((((int64_t)ct + 1) * cc) << ltx) * VEC) <= p.C;
     // with one row stride common to the full-shape views, one byte offset per lane serves the
     // adjoints, every plane and every full gradient at every row step
-    col_off = (uint32_t)c0 * (uint32_t)sizeof(T);
-    lane_uniform = ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)c0) * (uint32_t)sizeof(T);
+    shift = p.ragged && colvalid && c0 + VEC > p.C ? (int)(c0 + VEC - p.C) : 0;
+    const int64_t cl = c0 - shift;  // the lane's first load column
+    col_off = (uint32_t)cl * (uint32_t)sizeof(T);
+    lane_uniform = ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)cl) * (uint32_t)sizeof(T);
     lds_row = reinterpret_cast<A *>(smem + p.lds_row_off);
     lds_col = reinterpret_cast<A *>(smem + p.lds_col_off);
     lds_all = reinterpret_cast<A *>(smem + p.lds_all_off);
@@ -216,26 +219,30 @@ struct BwdGeom {
 
 // one vector of a plane (`base`: the plane at the row step's first row; `off`: the lane's offset
 // from there); lanes outside the problem read offset 0 and get zeros
-template <class T, int VEC, bool EDGE>
+template <class T, int VEC, bool EDGE, bool RAGGED = false>
 BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) {
   if (EDGE) {
-    load_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(base, valid ? off : 0u), x);
+    load_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(base, valid ? off : 0u), x);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) x[v] = valid ? x[v] : T(0);
   } else {
-    load_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(base, off), x);
+    load_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(base, off), x);
   }
 }
 
 // the per-class treatment of one gradient at one row step
 // `gbase`: the gradient's own view at the row step's first row; `off`: the lane's byte offset from there
-template <class T, int VEC, int MAXM, bool EDGE>
+// (RAGGED: `off` is where the lane's loads go, `shift` columns left of its own first column)
+template <class T, int VEC, int MAXM, bool EDGE, bool RAGGED = false>
 BD_DEV void apply_full(const void *gbase, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], uint32_t off,
-                       bool valid, bool nt) {
+                       bool valid, bool nt, int shift = 0) {
   T o[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
-  if (!EDGE || valid) store_vec<T, VEC>(at<T>(gbase, off), o, nt);
+  if (!EDGE || valid) {
+    if constexpr (RAGGED) store_ragged<T, VEC>(at<T>(gbase, off), o, nt, shift);
+    else store_vec<T, VEC>(at<T>(gbase, off), o, nt);
+  }
 }
 // row sums in two halves: a lane's own columns first (over as many column chunks as the kernel
 // holds), then once per row step the reduction over the row's lanes and the store
@@ -328,6 +335,7 @@ BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
       if (g.ty == 0 && g.colvalid) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
+          if (g.c0 + v >= p.C) break;  // ragged rows: the last lane holds fewer than VEC columns
           A s = g.lds_col[(en.slot * kBlock + g.tx) * VEC + v];
           for (int y = 1; y < g.TY; ++y) AT::add(s, g.lds_col[(en.slot * kBlock + y * g.TX + g.tx) * VEC + v]);
           if (en.direct)

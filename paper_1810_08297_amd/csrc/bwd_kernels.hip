@@ -121,7 +121,8 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 // absent plane, or a slot past the end of the table, reads the first adjoint's vector instead --
 // memory that is valid and already on its way -- and is then replaced by zeros), so that a
 // wavefront keeps up to 4 M loads in flight instead of M.
-template <class T, int VEC, int MCT, bool US>
+// RAGGED: rows of any length (at least VEC) and at any element boundary, see unshift.
+template <class T, int VEC, int MCT, bool US, bool RAGGED = false>
 __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams p) {
   constexpr int MAXM = MCT > 0 ? MCT : BCAST_MAX_OUTS;
   constexpr int CH = 4;
@@ -140,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
     auto voff = [&](int64_t sr) { return valid ? rs.lane(sr) : 0u; };
     LV adj_raw[MAXM];  // unpacked only after the first four gradients' loads are on their way
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(rs.base(p.adj[i < M ? i : 0].p, p.adj[i < M ? i : 0].sr), voff(p.adj[i < M ? i : 0].sr)));
+    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(rs.base(p.adj[i < M ? i : 0].p, p.adj[i < M ? i : 0].sr), voff(p.adj[i < M ? i : 0].sr)));
     T adj[MAXM][VEC];
     LV raw[CH][MAXM];
     bool have[CH][MAXM];
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
           const void *plane = i < M ? p.e[e].P[i].p : nullptr;
           have[q][i] = valid && e0 + q < p.n_entries && plane != nullptr;
           const int64_t sr = plane != nullptr ? p.e[e].P[i].sr : p.adj[0].sr;
-          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0>(at<const T>(rs.base(plane != nullptr ? plane : p.adj[0].p, sr), voff(sr)));
+          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(rs.base(plane != nullptr ? plane : p.adj[0].p, sr), voff(sr)));
         }
       }
     };
@@ -167,8 +168,11 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
         for (int i = 0; i < MAXM; ++i)
 #pragma unroll
           for (int v = 0; v < VEC; ++v) P[i][v] = have[q][i] ? lane_elem<T, VEC>(raw[q][i], v) : T(0);
+        if constexpr (RAGGED)
+#pragma unroll
+          for (int i = 0; i < MAXM; ++i) unshift<T, VEC>(P[i], g.shift);
         if (en.cls == kGradFull)
-          apply_full<T, VEC, MAXM, true>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt);
+          apply_full<T, VEC, MAXM, true, RAGGED>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
         else if (en.cls == kGradRowSum)
           apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
         else if (en.cls == kGradColSum)
@@ -186,6 +190,9 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
     for (int i = 0; i < MAXM; ++i)
 #pragma unroll
       for (int v = 0; v < VEC; ++v) adj[i][v] = (valid && i < M) ? lane_elem<T, VEC>(adj_raw[i], v) : T(0);
+    if constexpr (RAGGED)
+#pragma unroll
+      for (int i = 0; i < MAXM; ++i) unshift<T, VEC>(adj[i], g.shift);
     apply(0);
     for (int e0 = CH; e0 < p.n_entries; e0 += CH) {
       issue(e0);
@@ -462,6 +469,19 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
   const int chunks = p.col_chunks > 0 ? p.col_chunks : 1;
+  if (p.ragged) {  // planned for the widest vector and one common row stride only
+    if (!widest || !p.uniform_stride) return hipErrorInvalidValue;
+#define BD_RAGGED(T, V)                                                                                          \
+  do {                                                                                                           \
+    if (p.M == 1) launch((bwd_tiled_kernel<T, V, 1, true, true>), grid, dim3(kBlock), lds, s, p);                \
+    else if (p.M == 2) launch((bwd_tiled_kernel<T, V, 2, true, true>), grid, dim3(kBlock), lds, s, p);           \
+    else launch((bwd_tiled_kernel<T, V, 0, true, true>), grid, dim3(kBlock), lds, s, p);                         \
+  } while (0)
+    if (dt == BCAST_F32) BD_RAGGED(float, 4);
+    else BD_RAGGED(double, 2);
+#undef BD_RAGGED
+    return hipGetLastError();
+  }
   if (signature && widest && p.uniform_stride) {  // the kernels compiled per mix assume one row stride
 #define BD_SIG_GO(m, f, r, c, a, ab, sh, wide)                                                               \
   if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {             \

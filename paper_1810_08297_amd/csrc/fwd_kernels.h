@@ -5,16 +5,30 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kparams.h"
 #include "launch.h"
 #include "ops.h"
 
 namespace bd {
 
+// `type`: a lane's vector, aligned to its size.  `unaligned`: the same vector at any element
+// boundary, for rows whose length or start is not a multiple of the vector (global memory
+// takes multi-dword accesses at dword boundaries; they are only slower across cache lines).
 template <class T, int VEC> struct vec_of;
-template <> struct vec_of<float, 4> { typedef float type __attribute__((ext_vector_type(4))); };
-template <> struct vec_of<float, 2> { typedef float type __attribute__((ext_vector_type(2))); };
-template <> struct vec_of<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
+template <> struct vec_of<float, 4> {
+  typedef float type __attribute__((ext_vector_type(4)));
+  typedef float unaligned __attribute__((ext_vector_type(4), aligned(4)));
+};
+template <> struct vec_of<float, 2> {
+  typedef float type __attribute__((ext_vector_type(2)));
+  typedef float unaligned __attribute__((ext_vector_type(2), aligned(4)));
+};
+template <> struct vec_of<double, 2> {
+  typedef double type __attribute__((ext_vector_type(2)));
+  typedef double unaligned __attribute__((ext_vector_type(2), aligned(8)));
+};
 
 // Cache policy of the streaming loads.  Arguments, adjoints and planes are read once per
 // launch, so their loads carry the nontemporal hint: measured on MI355X the backward kernel
@@ -30,13 +44,13 @@ template <> struct vec_of<double, 2> { typedef double type __attribute__((ext_ve
 #define BD_REC_ARG_NT 0
 #endif
 
-template <class T, int VEC, bool NT = false>
+template <class T, int VEC, bool NT = false, bool UNALIGNED = false>
 BD_DEV void load_vec(const T *p, T (&x)[VEC]) {
   if constexpr (VEC == 1) {
     x[0] = NT ? __builtin_nontemporal_load(p) : *p;
   } else {
-    using V = typename vec_of<T, VEC>::type;
-    V v = NT ? __builtin_nontemporal_load(reinterpret_cast<const V *>(p)) : *reinterpret_cast<const V *>(p);
+    using V = std::conditional_t<UNALIGNED, typename vec_of<T, VEC>::unaligned, typename vec_of<T, VEC>::type>;
+    typename vec_of<T, VEC>::type v = NT ? __builtin_nontemporal_load(reinterpret_cast<const V *>(p)) : *reinterpret_cast<const V *>(p);
 #pragma unroll
     for (int k = 0; k < VEC; ++k) x[k] = v[k];
   }
@@ -45,9 +59,11 @@ BD_DEV void load_vec(const T *p, T (&x)[VEC]) {
 // keep a conditionally loaded vector whole until all loads have been issued.
 template <class T, int VEC> struct lane_vec { using type = typename vec_of<T, VEC>::type; };
 template <class T> struct lane_vec<T, 1> { using type = T; };
-template <class T, int VEC, bool NT = false>
+template <class T, int VEC> struct lane_vec_unaligned { using type = typename vec_of<T, VEC>::unaligned; };
+template <class T> struct lane_vec_unaligned<T, 1> { using type = T; };
+template <class T, int VEC, bool NT = false, bool UNALIGNED = false>
 BD_DEV typename lane_vec<T, VEC>::type load_lane_vec(const T *p) {
-  using V = typename lane_vec<T, VEC>::type;
+  using V = std::conditional_t<UNALIGNED, typename lane_vec_unaligned<T, VEC>::type, typename lane_vec<T, VEC>::type>;
   return NT ? __builtin_nontemporal_load(reinterpret_cast<const V *>(p)) : *reinterpret_cast<const V *>(p);
 }
 template <class T, int VEC>
@@ -55,16 +71,48 @@ BD_DEV T lane_elem(const typename lane_vec<T, VEC>::type &x, int k) {
   if constexpr (VEC == 1) return x; else return x[k];
 }
 
-template <class T, int VEC>
+template <class T, int VEC, bool UNALIGNED = false>
 BD_DEV void store_vec(T *p, const T (&x)[VEC], bool nt) {
   if constexpr (VEC == 1) {
     if (nt) __builtin_nontemporal_store(x[0], p); else *p = x[0];
   } else {
-    using V = typename vec_of<T, VEC>::type;
-    V v;
+    using V = std::conditional_t<UNALIGNED, typename vec_of<T, VEC>::unaligned, typename vec_of<T, VEC>::type>;
+    typename vec_of<T, VEC>::type v;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) v[k] = x[k];
     if (nt) __builtin_nontemporal_store(v, reinterpret_cast<V *>(p)); else *reinterpret_cast<V *>(p) = v;
+  }
+}
+
+// Rows whose length is not a multiple of the vector (RAGGED kernels).  The lane that holds a
+// row's last, partial vector -- columns c0 .. C-1, fewer than VEC -- loads the vector that ENDS
+// with the row instead, `shift` = c0 + VEC - C columns to the left: always whole, always inside
+// the row (C >= VEC).  unshift moves the lane's own columns to the front and clears the rest, so
+// that element v is column c0 + v everywhere, zero past the row's end.
+template <class T, int VEC>
+BD_DEV void unshift(T (&x)[VEC], int shift) {
+  if constexpr (VEC > 1) {
+    T y[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      y[v] = T(0);
+#pragma unroll
+      for (int s = 0; s + v < VEC; ++s) y[v] = shift == s ? x[v + s] : y[v];
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) x[v] = y[v];
+  }
+}
+// `p`: where the lane's loads go (its first column less `shift`).  A whole vector is stored as
+// one; the row's last lane stores its VEC - shift columns one by one.
+template <class T, int VEC>
+BD_DEV void store_ragged(T *p, const T (&x)[VEC], bool nt, int shift) {
+  if (shift == 0) {
+    store_vec<T, VEC, true>(p, x, nt);
+  } else {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v)
+      if (v + shift < VEC) p[shift + v] = x[v];
   }
 }
 
@@ -133,7 +181,8 @@ BD_DEV int eval_op(const T (&a)[Op::N][VEC], int v, Y *y, std::index_sequence<J.
 // PARTIALS = false is the values-only launch (no plane requested): the op runs on duals
 // without perturbations, so no derivative is computed, and the arguments are loaded with
 // plain loads (a recompute backward pass reads them again soon).
-template <class Op, class T, int VEC, bool PARTIALS, bool US>
+// RAGGED: rows of any length (at least VEC) and at any element boundary, see unshift.
+template <class Op, class T, int VEC, bool PARTIALS, bool US, bool RAGGED = false>
 __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const FwdTiledParams p) {
   constexpr int N = Op::N, M = Op::M;
   constexpr int ND = N - popc(Op::NONDIFF);
@@ -153,9 +202,12 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   const int64_t r = r0 + ty;
   if (r >= p.R) return;
   const bool nt = p.nt_store != 0;
-  const uint32_t col_off = (uint32_t)c0 * (uint32_t)sizeof(T);
+  // the row's last lane reads the vector that ends with the row (the host sees that C >= VEC)
+  const int shift = RAGGED && c0 + VEC > p.C ? (int)(c0 + VEC - p.C) : 0;
+  const int64_t cl = c0 - shift;
+  const uint32_t col_off = (uint32_t)cl * (uint32_t)sizeof(T);
   const RowStep<T, US> rs{r0, r0 * p.row_stride * (int64_t)sizeof(T),
-                          ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)c0) * (uint32_t)sizeof(T), (uint32_t)ty, col_off};
+                          ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)cl) * (uint32_t)sizeof(T), (uint32_t)ty, col_off};
 
   // Every argument is fetched in whichever of two forms applies -- a vector for arguments
   // that vary along the columns, one broadcast element otherwise -- into registers of its
@@ -176,9 +228,9 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
       // the streaming hint its few lines were fetched from memory over and over (the HM-LSTM
       // update with z of shape [1 x C], 8192 x 5120: 1097 us, 902 us with plain loads).
       if ((p.row_invariant >> j) & 1u)
-        load_vec<T, VEC, false>(at<const T>(p.arg_p[j], col_off), avec[j]);
+        load_vec<T, VEC, false, RAGGED>(at<const T>(p.arg_p[j], col_off), avec[j]);
       else  // from this row
-        load_vec<T, VEC, ARG_NT>(at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
+        load_vec<T, VEC, ARG_NT, RAGGED>(at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
     }
   }
 #pragma unroll
@@ -193,9 +245,16 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   for (int j = 0; j < N; ++j) asm volatile("" : "+v"(asc[j]));
   T a[N][VEC];
 #pragma unroll
-  for (int j = 0; j < N; ++j)
+  for (int j = 0; j < N; ++j) {
+    if constexpr (RAGGED) unshift<T, VEC>(avec[j], shift);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) a[j][v] = or_bits(avec[j][v], asc[j]);
+  }
+  // stores: whole vectors, or (RAGGED) the row's last columns one by one
+  auto put = [&](T *dst, const T (&o)[VEC]) {
+    if constexpr (RAGGED) store_ragged<T, VEC>(dst, o, nt, shift);
+    else store_vec<T, VEC>(dst, o, nt);
+  };
   {
     Y y[VEC][M];
     int br[VEC];
@@ -207,7 +266,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      store_vec<T, VEC>(at<T>(rs.base(p.out_p[i], p.out_sr[i]), rs.lane(p.out_sr[i])), o, nt);
+      put(at<T>(rs.base(p.out_p[i], p.out_sr[i]), rs.lane(p.out_sr[i])), o);
     }
     if constexpr (PARTIALS) {
 #pragma unroll
@@ -218,14 +277,18 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
           if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-            store_vec<T, VEC>(at<T>(rs.base(pl, p.part_sr[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd])), o, nt);
+            put(at<T>(rs.base(pl, p.part_sr[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd])), o);
           }
         });
       }
     }
     if (p.branch_p != nullptr) {
       uint8_t *bp = p.branch_p + r * p.branch_sr + c0 * p.branch_sc;
-      if (VEC == 4 && p.branch_sc == 1 && (reinterpret_cast<uintptr_t>(bp) & 3u) == 0) {  // four ids in one store
+      if (RAGGED) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+          if (v + shift < VEC) bp[v * p.branch_sc] = (uint8_t)br[v];
+      } else if (VEC == 4 && p.branch_sc == 1 && (reinterpret_cast<uintptr_t>(bp) & 3u) == 0) {  // four ids in one store
         uint32_t w = 0;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) w |= (uint32_t)(br[v] & 0xff) << (8 * v);
@@ -326,6 +389,15 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
 template <class Op, bool PARTIALS, bool US>
 void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)p.lds_bytes;
+  if constexpr (US) {
+    if (p.ragged) {  // planned for the widest vector and one common row stride only
+      if (dt == BCAST_F32)
+        launch((fwd_tiled_kernel<Op, float, 4, PARTIALS, true, true>), grid, dim3(kBlock), lds, s, p);
+      else
+        launch((fwd_tiled_kernel<Op, double, 2, PARTIALS, true, true>), grid, dim3(kBlock), lds, s, p);
+      return;
+    }
+  }
   if (dt == BCAST_F32) {
     if (vec == 4)
       launch((fwd_tiled_kernel<Op, float, 4, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);

@@ -111,9 +111,9 @@ constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 enum TuneKey {
   kTuneUnused = 0, kTuneBwdRows, kTuneNtStores, kTuneForceGeneric, kTuneMaxVecBytes, kTuneRuntimeTable, kTuneReverse,
   kTuneProbeNtLoads, kTuneInterleave, kTuneXcdOrder, kTuneColChunks, kTuneFwdLdsKiB, kTuneBwdLdsKiB, kTuneProbeLdsKiB,
-  kTuneNarrowTiles, kNumTune
+  kTuneNarrowTiles, kTuneRaggedRows, kNumTune
 };
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0, 1};
+int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0, 1, 1};
 
 // A failed launch is reported with the runtime's own words on stderr: the status code alone
 // cannot say why.
@@ -344,6 +344,15 @@ int auto_steps(int64_t R, const Geometry &g, int max_steps) {
   return (int)std::max<int64_t>(1, std::min<int64_t>(s, max_steps));
 }
 
+// Rows that the 16-byte vector does not fit (a length that is no multiple of it, a start or a row
+// stride off its boundary; `vw`: what the aligned kernels could take) go to the kernels that read
+// unaligned vectors and finish every row element by element.  Those exist for the widest vector
+// and views with one common row stride; a row must hold one whole vector.
+bool ragged_rows_ok(int vw, bool uniform_stride, const Shape2 &s2, size_t es) {
+  const int widest = (int)(16 / es);
+  return g_tune[kTuneRaggedRows] != 0 && g_tune[kTuneMaxVecBytes] >= 16 && vw < widest && uniform_stride && s2.C >= widest;
+}
+
 // Whether a lane of the generic kernels may take `vw` consecutive elements of the innermost dim of
 // view `t` as one vector: the view runs contiguously along that dim (or, where `may_be_constant`,
 // does not vary along it), starts on a vector boundary and keeps to one with every outer stride.
@@ -478,6 +487,8 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       if (vec_ok) break;
     }
     if (!p.uniform_stride && vw != (int)(16 / es)) vw = 1;  // those kernels exist for the widest vector and for 1
+    p.ragged = ragged_rows_ok(vw, p.uniform_stride != 0, s2, es);
+    if (p.ragged) vw = (int)(16 / es);
     Geometry g;
     g.vec = vw;
     tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), g);
@@ -521,6 +532,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     plan.grid = dim3((unsigned)(g.n_ct * g.n_rt), 1, 1);
     plan.info.path = 1;
     plan.info.vec = g.vec;
+    plan.info.ragged = p.ragged;
     plan.info.tx = 1 << g.log2_tx;
     plan.info.ty = kBlock >> g.log2_tx;
     plan.info.rows_per_block = plan.info.ty * g.steps;
@@ -704,6 +716,9 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       if (vec_ok) break;
     }
     if (rop && vw != (int)(16 / es)) vw = 1;  // the recompute kernels exist for the widest vector and for 1
+    // rows the vector does not fit: the run-time-table kernel (or the recompute kernel) in its unaligned form
+    const bool ragged = ragged_rows_ok(vw, uniform_stride, s2, es);
+    if (ragged) vw = (int)(16 / es);
     Geometry g;
     g.vec = vw;
     plan.vec = g.vec;
@@ -743,7 +758,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // Wide rows with row sums and few planes: a kernel that takes all 2 or 4 column chunks of a
     // row per block finishes the row sums in the main pass (no partial sums, no second pass).
     int chunks = 1;
-    if (!rop && uniform_stride && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
+    if (!rop && !ragged && uniform_stride && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
         (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
         bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
       chunks = (int)g.n_ct;
@@ -757,7 +772,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
     // So do the kernels that read the gradient table at run time (8192 x 8192 branchy5 forced onto
     // them: 419 us at 128 rows per block, 631 us at 256).
-    const bool class_kernel = !rop && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
+    const bool class_kernel = !rop && !ragged && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
                               bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
                                                    plan.share, 1);
     // A class kernel that streams many planes per row step is the exception (HM-LSTM update stored
@@ -807,6 +822,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if ((s2.R > 1 && (tv.sr == 0) != rows_fixed) || (s2.C > 1 && (tv.sc == 0) != cols_fixed)) plan.fixed_pattern = 0;
         ++jd;
       }
+      if (ragged && plan.fixed_pattern == 2) plan.fixed_pattern = 0;  // the unaligned form exists for the op's own pattern and the run-time one
       if (plan.fixed_pattern && !any_rowwise) {
         if (g_tune[kTuneBwdRows] > 1) plan.fixed_pattern = 0;  // an explicit rows-per-block override needs the looping kernel
         else steps = 1;                                  // that kernel has no row loop
@@ -839,6 +855,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.xcd_remap = g_tune[kTuneXcdOrder] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
       p.col_chunks = chunks;
       p.uniform_stride = uniform_stride;
+      p.ragged = ragged;
       p.M = M;
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
@@ -923,7 +940,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
     }
-    plan.signature = !rop && uniform_stride && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
+    plan.signature = !rop && !ragged && uniform_stride && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
@@ -940,6 +957,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     plan.info.n_second_pass = plan.p2.n_jobs;
     // the class-specialised kernels exist for the widest vector only
     plan.info.specialized = plan.signature && ((dt == BCAST_F32 && g.vec == 4) || (dt == BCAST_F64 && g.vec == 2));
+    plan.info.ragged = ragged;
   } else {
     size_t gen_ws = 0;  // partial sums of the reductions that are cut into chunks
     for (int j = 0; j < ND; ++j) {
@@ -1205,7 +1223,7 @@ const char *bcast_status_string(int status) {
 }
 
 int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64, 64, 1};
+  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64, 64, 1, 1};
   if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
   if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
   g_tune[key] = value;

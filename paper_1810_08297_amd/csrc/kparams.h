@@ -46,6 +46,9 @@ struct FwdTiledParams {
   // When the full-shape views do not share one row stride (uniform_stride == 0) every view is
   // addressed with its own.
   int32_t uniform_stride;
+  // 1: rows of a length or at a start that is not a multiple of the vector; the kernel takes
+  // unaligned vectors and the row's last columns singly (only with uniform_stride, C >= the vector)
+  int32_t ragged;
   int64_t out_sr[BCAST_MAX_OUTS];
   int64_t part_sr[BCAST_MAX_PLANES];
 };
@@ -95,6 +98,7 @@ struct BwdTiledParams {
   int32_t uniform_stride;  // 0: the full-shape views have row strides of their own (TView::sr of each)
   int32_t col_chunks;  // column chunks of TX * VEC columns a block covers per row step (0 or 1: one)
   int32_t interleave;  // 1: row tile rt takes row steps rt, rt + n_rt, rt + 2 n_rt, ... instead of a contiguous run
+  int32_t ragged;      // as in FwdTiledParams (the run-time-table and recompute kernels only)
   int32_t n_row_slots, n_col_slots, n_all_slots;
   uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS
   int64_t n_ct, n_rt;  // column tiles, row tiles; block b = rt * n_ct + ct

@@ -42,7 +42,8 @@ constexpr int arg_form(int j) {
   const int cls = (int)((PATTERN >> (3 * jd)) & 7u) - 1;
   return cls == kGradFull ? kFormFull : cls == kGradColSum ? kFormRowVector : cls == kGradRowSum ? kFormColVector : kFormScalar;
 }
-template <class Op, class T, int VEC, uint64_t PATTERN, bool US>
+// RAGGED: rows of any length (at least VEC) and at any element boundary, see unshift.
+template <class Op, class T, int VEC, uint64_t PATTERN, bool US, bool RAGGED = false>
 __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams p, const RecomputeArgs ra) {
   constexpr bool LOOP = PATTERN == 0 || pattern_sums_rows(PATTERN);
   constexpr int N = Op::N, M = Op::M;
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
   const bool nt = p.nt_store != 0;
-  const uint32_t col_off = g.colvalid ? (uint32_t)g.c0 * (uint32_t)sizeof(T) : 0u;
+  const uint32_t col_off = g.colvalid ? g.col_off : 0u;
   uint32_t colinv_again = ra.col_invariant;
   asm volatile("" : "+s"(colinv_again));
   for (int k = 0; k < (LOOP ? p.steps : 1); ++k) {
@@ -78,9 +79,9 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
       constexpr int form = arg_form<Op, PATTERN>(j);
       avec[j] = LV(T(0));
       if constexpr (form == kFormFull)
-        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
+        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0, RAGGED>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
       else if constexpr (form == kFormRowVector)
-        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(at<const T>(ra.arg_p[j], col_off));
+        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0, RAGGED>(at<const T>(ra.arg_p[j], col_off));
       else if constexpr (form == kFormRuntime) {
         const bool colinv = (ra.col_invariant >> j) & 1u;
         if constexpr (PATTERN != 0) {
@@ -88,12 +89,12 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
           // form does not apply the lane reads the first adjoint's vector instead (valid
           // memory that is loaded anyway) and the result is replaced by zero bits
           const bool rowinv = (ra.row_invariant >> j) & 1u;
-          const LV x = load_lane_vec<T, VEC>(colinv   ? at<const T>(rs.base(p.adj[0].p, p.adj[0].sr), voff(p.adj[0].sr))
+          const LV x = load_lane_vec<T, VEC, false, RAGGED>(colinv   ? at<const T>(rs.base(p.adj[0].p, p.adj[0].sr), voff(p.adj[0].sr))
                                              : rowinv ? at<const T>(ra.arg_p[j], col_off)
                                                       : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
           avec[j] = colinv ? LV(T(0)) : x;
         } else if (!colinv) {
-          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0>(((ra.row_invariant >> j) & 1u) ? at<const T>(ra.arg_p[j], col_off)
+          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0, RAGGED>(((ra.row_invariant >> j) & 1u) ? at<const T>(ra.arg_p[j], col_off)
                                                                                            : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
         }
       }
@@ -118,25 +119,32 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
     });
     T adj[M][VEC];
 #pragma unroll
-    for (int i = 0; i < M; ++i) load_plane<T, VEC, true>(rs.base(p.adj[i].p, p.adj[i].sr), rs.lane(p.adj[i].sr), valid, adj[i]);
+    for (int i = 0; i < M; ++i) load_plane<T, VEC, true, RAGGED>(rs.base(p.adj[i].p, p.adj[i].sr), rs.lane(p.adj[i].sr), valid, adj[i]);
 #pragma unroll
     for (int j = 0; j < N; ++j)  // the opaque point after the last load
       if (arg_form<Op, PATTERN>(j) == kFormRuntime) {
         asm volatile("" : "+v"(asc[j]));
         asm volatile("" : "+v"(avec[j]));
       }
+    if constexpr (RAGGED)
+#pragma unroll
+      for (int i = 0; i < M; ++i) unshift<T, VEC>(adj[i], g.shift);
     T a[N][VEC];
     static_for<0, N>([&](auto J) {
       constexpr int j = decltype(J)::value;
       constexpr int form = arg_form<Op, PATTERN>(j);
+      T x[VEC];
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) x[v] = lane_elem<T, VEC>(avec[j], v);
+      if constexpr (RAGGED) unshift<T, VEC>(x, g.shift);
 #pragma unroll
       for (int v = 0; v < VEC; ++v) {
         if constexpr (form == kFormFull || form == kFormRowVector)
-          a[j][v] = lane_elem<T, VEC>(avec[j], v);
+          a[j][v] = x[v];
         else if constexpr (form == kFormColVector || form == kFormScalar)
           a[j][v] = asc[j];
         else
-          a[j][v] = or_bits(lane_elem<T, VEC>(avec[j], v), asc[j]);
+          a[j][v] = or_bits(x[v], asc[j]);
       }
     });
     Y y[VEC][M];
@@ -152,11 +160,12 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
 #pragma unroll
         for (int i = 0; i < M; ++i)
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) P[i][v] = valid ? y[v][i].template partial<jd>() : T(0);
+          for (int v = 0; v < VEC; ++v)  // nothing from columns past the row's end: 0 x inf would reach the sums
+            P[i][v] = valid && (!RAGGED || v + g.shift < VEC) ? y[v][i].template partial<jd>() : T(0);
         constexpr int fixed = (int)((PATTERN >> (3 * jd)) & 7u);
         const int cls = fixed ? fixed - 1 : en.cls;
         if (cls == kGradFull)
-          apply_full<T, VEC, M, true>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt);
+          apply_full<T, VEC, M, true, RAGGED>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
         else if (cls == kGradRowSum)
           apply_rowsum<T, VEC, M>(p, g, en, adj, P, r, ri);
         else if (cls == kGradColSum)
@@ -179,6 +188,12 @@ hipError_t launch_bwdr_tiled(int dt, int vec, int fixed, const BwdTiledParams &p
     using T = typename decltype(type_tag)::type;
     constexpr int V = decltype(vec_tag)::value;
     constexpr bool US = decltype(us_tag)::value;
+    if constexpr (V * sizeof(T) == 16 && US) {
+      if (p.ragged) {  // planned for the widest vector and one common row stride; the compiled-in pattern or the run-time one
+        if (fixed == 1) return launch((bwdr_tiled_kernel<Op, T, V, PAT, true, true>), grid, dim3(kBlock), lds, s, p, ra);
+        return launch((bwdr_tiled_kernel<Op, T, V, 0ull, true, true>), grid, dim3(kBlock), lds, s, p, ra);
+      }
+    }
     if constexpr (V * sizeof(T) == 16) {  // the fixed patterns exist for the widest vector only
       if (fixed == 1) return launch((bwdr_tiled_kernel<Op, T, V, PAT, US>), grid, dim3(kBlock), lds, s, p, ra);
       if constexpr (PAT_T != PAT)
@@ -187,6 +202,7 @@ hipError_t launch_bwdr_tiled(int dt, int vec, int fixed, const BwdTiledParams &p
     launch((bwdr_tiled_kernel<Op, T, V, 0ull, US>), grid, dim3(kBlock), lds, s, p, ra);
   };
   if (!p.uniform_stride && !Op::STRIDED) return hipErrorNotSupported;  // the host refuses such calls
+  if (p.ragged && !(p.uniform_stride && vec * (dt == BCAST_F32 ? 4 : 8) == 16)) return hipErrorInvalidValue;
   auto with_stride = [&](auto type_tag, auto vec_tag) {
     if (p.uniform_stride) go(type_tag, vec_tag, std::true_type{});
     else if constexpr (Op::STRIDED) go(type_tag, vec_tag, std::false_type{});  // views with row strides of their own

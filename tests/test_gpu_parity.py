@@ -1531,3 +1531,65 @@ def test_rank3_reductions_of_many_chunks(dtype):
         assert info["path"] == 2 and info["ndim"] == 3 and info["n_launches"] > 5  # some reductions need the final kernel
         assert P.bcast_dual_backward_workspace(adj_dev, fb.partials, grads) > 0
         check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what=f"r {rs} s {ss} t {ts} ")
+
+
+def _offset_by_one_element(t, k):
+    """The same values in storage that starts one element past an aligned address (same strides)."""
+    flat = torch.empty(t.numel() + 1, dtype=t.dtype, device=t.device)
+    v = flat[1:].view(t.shape)
+    v.copy_(t)
+    return v
+
+
+RAGGED_CASES = [("hmlstm_update", 3, 5), ("hmlstm_update", 33, 1023), ("hmlstm_update", 130, 1025), ("hmlstm_update", 9, 2051),
+                ("branchy5", 7, 6), ("branchy5", 1, 4099), ("branchy5", 260, 259), ("pair3", 65, 1030), ("pair3", 2, 7),
+                ("tanh_xy_b", 129, 4), ("update_c", 300, 1101), ("elementary4", 5, 777), ("linear12", 1000, 13)]
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_rows_the_vector_does_not_fit(dtype):
+    """Rows whose length is not a multiple of the 16-byte vector, or that start off its boundary, go
+    to the kernels that read unaligned vectors and finish each row element by element (forward,
+    backward from planes, recompute): the plans say so, and everything matches the oracle -- the
+    row's last columns, the sums over rows and columns that must not see anything past a row's end
+    (pair3 divides: the lanes past the end evaluate it on zeros), the branch ids."""
+    vec = 16 // np.dtype(dtype).itemsize
+    for op, R, C in RAGGED_CASES:
+        args, adj = small_args(op, R, C, dtype, seed=R + C)
+        for view in (None, _offset_by_one_element):
+            if view is None and C % vec == 0:
+                continue  # aligned as it stands
+            dev = [to_dev(a) for a in args]
+            if view is not None:
+                dev = [view(t, k) for k, t in enumerate(dev)]
+            adj_dev = [to_dev(a) for a in adj]
+            gshapes = [args[j].shape for j in oracle.diff_arg_indices(op, len(args))]
+            fb = P.alloc_forward(op, dev)
+            bb = P.alloc_backward(adj_dev, fb.partials, gshapes)
+            rb = P.alloc_recompute(fb.op_id, dev, adj_dev, gshapes)
+            plans = [P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials),
+                     P.bcast_dual_backward_recompute_plan(fb.op_id, dev, adj_dev, rb.grads)]
+            for plan in plans:
+                assert plan["path"] == 1 and plan["vec"] == vec and plan["ragged"] == 1, (op, R, C, plan)
+            # the planes and adjoints are aligned: only the row length sends this call there (and where
+            # every gradient has the full shape the rows merge into one)
+            plan = P.bcast_dual_backward_plan(adj_dev, fb.partials, bb.grads)
+            assert plan["path"] == 1 and plan["vec"] == vec and plan["ragged"] == int(plan["shape"][-1] % vec != 0), (op, R, C, plan)
+            check_op(op, args, adj, view=view, what=f"[{R}x{C}{' off by one element' if view else ''}] ", recompute="required")
+
+
+def test_rows_the_vector_does_not_fit_on_the_aligned_kernels():
+    """With tuning key 15 off such rows take the widest aligned access that fits (8 or 4 bytes)."""
+    P.bcast_dual_set_tuning(15, 0)
+    try:
+        for dtype in DTYPES:
+            for op, R, C in (("hmlstm_update", 33, 1023), ("hmlstm_update", 40, 1030), ("branchy5", 260, 259), ("pair3", 2, 7)):
+                args, adj = small_args(op, R, C, dtype, seed=R + C)
+                dev = [to_dev(a) for a in args]
+                fb = P.alloc_forward(op, dev)
+                plan = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials)
+                widest = 16 // np.dtype(dtype).itemsize
+                assert plan["ragged"] == 0 and (plan["vec"] < widest or C % widest == 0)
+                check_op(op, args, adj, what=f"[{R}x{C} aligned accesses] ", recompute="required")
+    finally:
+        P.bcast_dual_set_tuning(15, 1)

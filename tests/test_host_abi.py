@@ -164,8 +164,18 @@ def test_forward_plan_geometry():
     a, o, p = hm(64, 16)
     info = P.bcast_dual_forward_plan(op, a, o, p)
     assert info["tx"] == 4 and info["ty"] == 64 and info["grid_x"] * info["grid_y"] == 1
-    a, o, p = hm(64, 15)  # odd row length: scalar accesses
-    assert P.bcast_dual_forward_plan(op, a, o, p)["vec"] == 1
+    a, o, p = hm(64, 15)  # odd row length: unaligned vectors and a tail, or (tuning key 15 off) scalar accesses
+    info = P.bcast_dual_forward_plan(op, a, o, p)
+    assert info["vec"] == 4 and info["ragged"] == 1
+    P.bcast_dual_set_tuning(15, 0)
+    try:
+        info = P.bcast_dual_forward_plan(op, a, o, p)
+        assert info["vec"] == 1 and info["ragged"] == 0
+    finally:
+        P.bcast_dual_set_tuning(15, 1)
+    a, o, p = hm(64, 3)  # a row shorter than the vector
+    info = P.bcast_dual_forward_plan(op, a, o, p)
+    assert info["vec"] == 1 and info["ragged"] == 0
     a, o, p = hm(64, 16, dtype=torch.float64)
     assert P.bcast_dual_forward_plan(op, a, o, p)["vec"] == 2
     # everything contiguous and full-shape: the two dims merge into one
@@ -382,16 +392,24 @@ def test_alignment_and_offset_range_pick_the_access_width_and_the_kernel():
         args = [mk(0, shifts[0]), mk(1, shifts[1]), _rowmajor(9 * slot, col or (shape[0], 1))]
         return _fwd_plan("tanh_xy_b", dt, args, [mk(2)], [mk(3), mk(4), mk(5)])
 
-    for shift, vec in ((0, 4), (8, 2), (4, 1), (12, 1)):
-        rc, d = call(0, (R, C), (0, shift))
-        assert rc == 0 and d["path"] == 1 and d["vec"] == vec, (shift, d)
-    rc, d = call(1, (R, C), (0, 8))
-    assert rc == 0 and d["vec"] == 1  # fp64: 8-byte alignment allows one element per access
-    assert call(0, (R, C), (2, 0))[0] == -11
-    assert call(1, (R, C), (4, 0))[0] == -11
-    # a row stride that is not a multiple of the vector width narrows it too
-    rc, d = call(0, (R, C), stride=(C + 2, 1))
-    assert rc == 0 and d["path"] == 1 and d["vec"] == 2
+    # by default a pointer or row stride off the 16-byte boundary sends the call to the kernels that
+    # take unaligned vectors; with tuning key 15 off the access narrows to what is aligned
+    for ragged_on in (1, 0):
+        B.bcast_dual_set_tuning(15, ragged_on)
+        try:
+            for shift, vec in ((0, 4), (8, 2), (4, 1), (12, 1)):
+                rc, d = call(0, (R, C), (0, shift))
+                assert rc == 0 and d["path"] == 1, (shift, d)
+                assert (d["vec"], d["ragged"]) == ((4, int(shift != 0)) if ragged_on else (vec, 0)), (shift, d)
+            rc, d = call(1, (R, C), (0, 8))  # fp64: 8-byte alignment allows one element per aligned access
+            assert rc == 0 and (d["vec"], d["ragged"]) == ((2, 1) if ragged_on else (1, 0))
+            assert call(0, (R, C), (2, 0))[0] == -11
+            assert call(1, (R, C), (4, 0))[0] == -11
+            # a row stride that is not a multiple of the vector width
+            rc, d = call(0, (R, C), stride=(C + 2, 1))
+            assert rc == 0 and d["path"] == 1 and (d["vec"], d["ragged"]) == ((4, 1) if ragged_on else (2, 0))
+        finally:
+            B.bcast_dual_set_tuning(15, 1)
     # Planes of any size: a lane's 32-bit byte offset counts from the first row of its block's row
     # step, so only one step of rows has to span less than 4 GiB.  40000 x 30000 fp32 = 4.8 GB per plane:
     rc, d = call(0, (40000, 30000))
