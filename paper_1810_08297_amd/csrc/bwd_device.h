@@ -219,12 +219,15 @@ struct BwdGeom {
 
 // one vector of a plane (`base`: the plane at the row step's first row; `off`: the lane's offset
 // from there); lanes outside the problem read offset 0 and get zeros
+// RAGGED: the vector may lie at any element boundary, and in an edge block the row's last lane,
+// which has loaded `shift` columns to the left of its own, gets its columns moved to the front
 template <class T, int VEC, bool EDGE, bool RAGGED = false>
-BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC]) {
+BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC], int shift = 0) {
   if (EDGE) {
     load_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(base, valid ? off : 0u), x);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) x[v] = valid ? x[v] : T(0);
+    if constexpr (RAGGED) unshift<T, VEC>(x, shift);
   } else {
     load_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(base, off), x);
   }
@@ -240,8 +243,8 @@ BD_DEV void apply_full(const void *gbase, const T (&adj)[MAXM][VEC], const T (&P
 #pragma unroll
   for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
   if (!EDGE || valid) {
-    if constexpr (RAGGED) store_ragged<T, VEC>(at<T>(gbase, off), o, nt, shift);
-    else store_vec<T, VEC>(at<T>(gbase, off), o, nt);
+    if constexpr (RAGGED && EDGE) store_ragged<T, VEC>(at<T>(gbase, off), o, nt, shift);
+    else store_vec<T, VEC, RAGGED>(at<T>(gbase, off), o, nt);
   }
 }
 // row sums in two halves: a lane's own columns first (over as many column chunks as the kernel

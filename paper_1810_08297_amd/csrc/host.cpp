@@ -716,7 +716,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       if (vec_ok) break;
     }
     if (rop && vw != (int)(16 / es)) vw = 1;  // the recompute kernels exist for the widest vector and for 1
-    // rows the vector does not fit: the run-time-table kernel (or the recompute kernel) in its unaligned form
+    // rows the vector does not fit: kernels that take the vector unaligned (no column chunks per block then)
     const bool ragged = ragged_rows_ok(vw, uniform_stride, s2, es);
     if (ragged) vw = (int)(16 / es);
     Geometry g;
@@ -772,7 +772,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
     // So do the kernels that read the gradient table at run time (8192 x 8192 branchy5 forced onto
     // them: 419 us at 128 rows per block, 631 us at 256).
-    const bool class_kernel = !rop && !ragged && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
+    const bool class_kernel = !rop && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
                               bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
                                                    plan.share, 1);
     // A class kernel that streams many planes per row step is the exception (HM-LSTM update stored
@@ -940,7 +940,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
     }
-    plan.signature = !rop && !ragged && uniform_stride && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
+    plan.signature = !rop && uniform_stride && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;

@@ -119,16 +119,13 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
     });
     T adj[M][VEC];
 #pragma unroll
-    for (int i = 0; i < M; ++i) load_plane<T, VEC, true, RAGGED>(rs.base(p.adj[i].p, p.adj[i].sr), rs.lane(p.adj[i].sr), valid, adj[i]);
+    for (int i = 0; i < M; ++i) load_plane<T, VEC, true, RAGGED>(rs.base(p.adj[i].p, p.adj[i].sr), rs.lane(p.adj[i].sr), valid, adj[i], g.shift);
 #pragma unroll
     for (int j = 0; j < N; ++j)  // the opaque point after the last load
       if (arg_form<Op, PATTERN>(j) == kFormRuntime) {
         asm volatile("" : "+v"(asc[j]));
         asm volatile("" : "+v"(avec[j]));
       }
-    if constexpr (RAGGED)
-#pragma unroll
-      for (int i = 0; i < M; ++i) unshift<T, VEC>(adj[i], g.shift);
     T a[N][VEC];
     static_for<0, N>([&](auto J) {
       constexpr int j = decltype(J)::value;
