@@ -203,6 +203,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   if (r >= p.R) return;
   const bool nt = p.nt_store != 0;
   // the row's last lane reads the vector that ends with the row (the host sees that C >= VEC)
+  const bool last_tile = ct + 1 == nct;  // uniform: only these blocks hold a row's end
   const int shift = RAGGED && c0 + VEC > p.C ? (int)(c0 + VEC - p.C) : 0;
   const int64_t cl = c0 - shift;
   const uint32_t col_off = (uint32_t)cl * (uint32_t)sizeof(T);
@@ -246,14 +247,15 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   T a[N][VEC];
 #pragma unroll
   for (int j = 0; j < N; ++j) {
-    if constexpr (RAGGED) unshift<T, VEC>(avec[j], shift);
+    if constexpr (RAGGED)
+      if (last_tile) unshift<T, VEC>(avec[j], shift);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) a[j][v] = or_bits(avec[j][v], asc[j]);
   }
-  // stores: whole vectors, or (RAGGED) the row's last columns one by one
+  // stores: whole vectors, or (RAGGED, in the blocks that hold a row's end) the row's last columns one by one
   auto put = [&](T *dst, const T (&o)[VEC]) {
-    if constexpr (RAGGED) store_ragged<T, VEC>(dst, o, nt, shift);
-    else store_vec<T, VEC>(dst, o, nt);
+    if (RAGGED && last_tile) store_ragged<T, VEC>(dst, o, nt, shift);
+    else store_vec<T, VEC, RAGGED>(dst, o, nt);
   };
   {
     Y y[VEC][M];
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
     }
     if (p.branch_p != nullptr) {
       uint8_t *bp = p.branch_p + r * p.branch_sr + c0 * p.branch_sc;
-      if (RAGGED) {
+      if (RAGGED && last_tile) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v)
           if (v + shift < VEC) bp[v * p.branch_sc] = (uint8_t)br[v];
