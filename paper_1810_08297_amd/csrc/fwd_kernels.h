@@ -188,6 +188,7 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   constexpr int ND = N - popc(Op::NONDIFF);
   using Y = Dual<T, (!PARTIALS ? 0u : ND >= 32 ? 0xffffffffu : ((1u << ND) - 1u))>;
   constexpr bool ARG_NT = PARTIALS && BD_FWD_ARG_NT != 0;
+  constexpr bool ROW_VECTORS_APART = ARG_NT;  // the streaming hint is not for row vectors, see below
   const int ltx = p.log2_tx;
   const int tx = threadIdx.x & ((1 << ltx) - 1);
   const int ty = threadIdx.x >> ltx;
@@ -224,14 +225,32 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   for (int j = 0; j < N; ++j) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
-    if (!((p.col_invariant >> j) & 1u)) {
-      // A row vector is read again by every row of blocks and has to stay in the caches: with
-      // the streaming hint its few lines were fetched from memory over and over (the HM-LSTM
-      // update with z of shape [1 x C], 8192 x 5120: 1097 us, 902 us with plain loads).
-      if ((p.row_invariant >> j) & 1u)
-        load_vec<T, VEC, false, RAGGED>(at<const T>(p.arg_p[j], col_off), avec[j]);
-      else  // from this row
+    if constexpr (ROW_VECTORS_APART) {
+      if (!(((p.col_invariant | p.row_invariant) >> j) & 1u))  // from this row
         load_vec<T, VEC, ARG_NT, RAGGED>(at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
+    } else {
+      if (!((p.col_invariant >> j) & 1u))  // from this row, or (row vectors) from the only row
+        load_vec<T, VEC, ARG_NT, RAGGED>(((p.row_invariant >> j) & 1u) ? at<const T>(p.arg_p[j], col_off)
+                                                                         : at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
+    }
+  }
+  // Row vectors, in the kernels that stream their arguments, are a third form with registers of
+  // its own: loaded plainly, behind a test of its own copy of the mask, merged with the others
+  // after all loads.  Every row of blocks reads them again and they have to stay in the caches:
+  // with the hint their few lines were fetched from memory over and over (the HM-LSTM update with
+  // z of shape [1 x C], 8192 x 5120: 1097 us, about 900 us now).  The hint is part of the instruction;
+  // choosing it per argument in one set of registers put a branch between every two loads
+  // (config 1's forward kernel: 73 instead of 63 us), and loading everything plainly in calls with a
+  // row vector cost config 3, which has one, 5 %.
+  T arow[ROW_VECTORS_APART ? N : 1][VEC];
+  if constexpr (ROW_VECTORS_APART) {
+    uint32_t rowvec = p.row_invariant & ~p.col_invariant;
+    asm volatile("" : "+s"(rowvec));
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) arow[j][v] = T(0);
+      if ((rowvec >> j) & 1u) load_vec<T, VEC, false, RAGGED>(at<const T>(p.arg_p[j], col_off), arow[j]);
     }
   }
 #pragma unroll
@@ -247,6 +266,9 @@ __global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const Fwd
   T a[N][VEC];
 #pragma unroll
   for (int j = 0; j < N; ++j) {
+    if constexpr (ROW_VECTORS_APART)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) avec[j][v] = or_bits(avec[j][v], arow[j][v]);
     if constexpr (RAGGED)
       if (last_tile) unshift<T, VEC>(avec[j], shift);
 #pragma unroll
@@ -388,30 +410,31 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
 }
 
 // ---- launch wrappers, one pair per op ------------------------------------------------------
+template <class T> struct fwd_type { using type = T; };
 template <class Op, bool PARTIALS, bool US>
 void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)p.lds_bytes;
+  auto go = [&](auto type_tag, auto vec_tag, auto ragged_tag) {
+    using T = typename decltype(type_tag)::type;
+    constexpr int V = decltype(vec_tag)::value;
+    constexpr bool RG = decltype(ragged_tag)::value;
+    launch((fwd_tiled_kernel<Op, T, V, PARTIALS, US, RG>), grid, dim3(kBlock), lds, s, p);
+  };
+  using std::integral_constant;
   if constexpr (US) {
     if (p.ragged) {  // planned for the widest vector and one common row stride only
-      if (dt == BCAST_F32)
-        launch((fwd_tiled_kernel<Op, float, 4, PARTIALS, true, true>), grid, dim3(kBlock), lds, s, p);
-      else
-        launch((fwd_tiled_kernel<Op, double, 2, PARTIALS, true, true>), grid, dim3(kBlock), lds, s, p);
+      if (dt == BCAST_F32) go(fwd_type<float>{}, integral_constant<int, 4>{}, std::true_type{});
+      else go(fwd_type<double>{}, integral_constant<int, 2>{}, std::true_type{});
       return;
     }
   }
   if (dt == BCAST_F32) {
-    if (vec == 4)
-      launch((fwd_tiled_kernel<Op, float, 4, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
-    else if (vec == 2 && US)  // views with strides of their own: the widest vector or single elements
-      launch((fwd_tiled_kernel<Op, float, US ? 2 : 1, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
-    else
-      launch((fwd_tiled_kernel<Op, float, 1, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
+    if (vec == 4) go(fwd_type<float>{}, integral_constant<int, 4>{}, std::false_type{});
+    else if (vec == 2 && US) go(fwd_type<float>{}, integral_constant<int, US ? 2 : 1>{}, std::false_type{});  // views with strides of their own: the widest vector or single elements
+    else go(fwd_type<float>{}, integral_constant<int, 1>{}, std::false_type{});
   } else {
-    if (vec > 1)
-      launch((fwd_tiled_kernel<Op, double, 2, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
-    else
-      launch((fwd_tiled_kernel<Op, double, 1, PARTIALS, US>), grid, dim3(kBlock), lds, s, p);
+    if (vec > 1) go(fwd_type<double>{}, integral_constant<int, 2>{}, std::false_type{});
+    else go(fwd_type<double>{}, integral_constant<int, 1>{}, std::false_type{});
   }
 }
 // vec: what the host planned (for views with strides of their own: the widest vector or 1)
