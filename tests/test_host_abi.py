@@ -596,3 +596,40 @@ def test_generic_path_plans_chunked_reductions():
     rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts), ctypes.c_int32(5),
                                B._views(grads), None, ctypes.c_size_t(0), None)
     assert rc == -3  # the workspace is asked for before anything is launched
+
+
+def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
+    """Rows of an odd length keep the 16-byte vector (`ragged`), and the kernel compiled for the
+    call's class mix; a row is no longer finished inside one block over several column chunks (the
+    row's end moves only the last chunk's loads), so row sums over 2 or 4 column tiles go through
+    the second pass; a fixed pattern is kept for the op's own orientation only."""
+    def views(R, C):
+        k = [0]
+
+        def mk(shape):
+            k[0] += 1
+            return _rowmajor(k[0] << 32, shape)
+        return mk
+
+    L = B.lib()
+    info = B.PlanInfo()
+    for C, ragged in ((4096, 0), (4095, 1)):
+        mk = views(512, C)
+        adj, parts = [mk((512, C))], [mk((512, C)) for _ in range(3)]
+        grads = [mk((512, C)), mk((512, C)), mk((512, 1))]  # tanh(x*y + b): full, full, row sums
+        rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                        ctypes.c_int32(3), B._views(grads), ctypes.byref(info))
+        d = info.as_dict()
+        assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and d["ragged"] == ragged and d["specialized"] == 1, d
+        assert (d["grid_x"], d["n_launches"], d["n_second_pass"]) == ((4, 2, 1) if ragged else (1, 1, 0)), d
+    op = P.bcast_op_lookup("tanh_xy_b")
+    for shape_b, C, want in (((512, 1), 1024, (0, 1)), ((512, 1), 1023, (1, 1)), ((1, 1023), 1023, (1, 0))):
+        mk = views(512, C)
+        args = [mk((512, C)), mk((512, C)), mk(shape_b)]
+        adj = [mk((512, C))]
+        grads = [mk((512, C)), mk((512, C)), mk(shape_b)]
+        rc = L.bcast_dual_backward_recompute_plan(ctypes.c_int32(op), ctypes.c_int(0), ctypes.c_int32(3), B._views(args),
+                                                  ctypes.c_int32(1), B._views(adj), ctypes.c_int32(3), B._views(grads),
+                                                  ctypes.byref(info))
+        d = info.as_dict()
+        assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and (d["ragged"], d["specialized"]) == want, (shape_b, C, d)
