@@ -1543,7 +1543,8 @@ def _offset_by_one_element(t, k):
 
 RAGGED_CASES = [("hmlstm_update", 3, 5), ("hmlstm_update", 33, 1023), ("hmlstm_update", 130, 1025), ("hmlstm_update", 9, 2051),
                 ("branchy5", 7, 6), ("branchy5", 1, 4099), ("branchy5", 260, 259), ("pair3", 65, 1030), ("pair3", 2, 7),
-                ("tanh_xy_b", 129, 4), ("update_c", 300, 1101), ("elementary4", 5, 777), ("linear12", 1000, 13)]
+                ("tanh_xy_b", 129, 4), ("update_c", 300, 1101), ("elementary4", 5, 777), ("linear12", 1000, 13),
+                ("branchy5", 700, 4099), ("tanh_xy_b", 1500, 2049)]
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
