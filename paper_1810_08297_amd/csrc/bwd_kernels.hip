@@ -19,9 +19,9 @@ namespace bd {
 // rows are also built for 2 and 4 chunks where few planes are read: a row of up to 4 x 1024
 // elements then lies inside one block and its row sums finish there, with no partial sums and
 // no second pass (tanh(x*y + b) at 4096 x 4096: one launch instead of two).
-// Every vector access is declared at element alignment (the same instructions): the kernels with
-// one column chunk also take rows the vector does not fit, whose last lane is handled in the edge
-// path (see unshift); blocks without a row's end run the interior path as they are.
+// Every vector access is declared at element alignment (the same instructions): the kernels also
+// take rows the vector does not fit, whose last lane is handled in the edge path (see unshift);
+// blocks without a row's end run the interior path as they are.
 constexpr int share_src(uint64_t share, int e) {
   const int s = (int)((share >> (4 * e)) & 15u);
   return s ? s - 1 : e;
@@ -54,16 +54,19 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const RowStep<T, true> rs = g.template step<true>(p, k);
-    const uint32_t off = rs.lane_uniform;
-    const int shift = CU == 1 ? g.shift : 0;  // the host plans ragged rows with one column chunk only
     T adj[CU][M][VEC], P[CU][NE][M][VEC];
     bool valid[CU];
+    int shift[CU];    // ragged rows: by how many columns the row's last lane moves its loads to the left
+    uint32_t off[CU];  // the lane's byte offset in column chunk q (chunk 0's already holds its shift)
 #pragma unroll
     for (int q = 0; q < CU; ++q) {  // every load of the row step is issued before the first use
-      const uint32_t o = off + (uint32_t)q * g.chunk_bytes;
-      valid[q] = r < p.R && g.c0 + (int64_t)q * g.chunk_cols < p.C;
+      const int64_t cq = g.c0 + (int64_t)q * g.chunk_cols;
+      valid[q] = r < p.R && cq < p.C;
+      shift[q] = q == 0 ? g.shift : (EDGE && p.ragged && valid[q] && cq + VEC > p.C ? (int)(cq + VEC - p.C) : 0);
+      off[q] = rs.lane_uniform + (uint32_t)q * g.chunk_bytes - (q == 0 ? 0u : (uint32_t)shift[q] * (uint32_t)sizeof(T));
+      const uint32_t o = off[q];
 #pragma unroll
-      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE, true>(rs.base(p.adj[i].p, 0), o, valid[q], adj[q][i], shift);
+      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE, true>(rs.base(p.adj[i].p, 0), o, valid[q], adj[q][i], shift[q]);
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
@@ -74,7 +77,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) P[q][e][i][v] = T(0);
           } else {
-            load_plane<T, VEC, EDGE, true>(rs.base(p.e[e].P[i].p, 0), o, valid[q], P[q][e][i], shift);
+            load_plane<T, VEC, EDGE, true>(rs.base(p.e[e].P[i].p, 0), o, valid[q], P[q][e][i], shift[q]);
           }
         }
     }
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     for (int q = 0; q < CU; ++q)
 #pragma unroll
       for (int e = 0; e < NF; ++e)
-        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g.p, 0), adj[q], P[q][share_src(SHARE, e)], off + (uint32_t)q * g.chunk_bytes, valid[q], nt, shift);
+        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g.p, 0), adj[q], P[q][share_src(SHARE, e)], off[q], valid[q], nt, shift[q]);
 #pragma unroll
     for (int e = NF; e < NF + NR; ++e) {
       A rs = AT::zero();
@@ -473,7 +476,7 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
                         const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
   const int chunks = p.col_chunks > 0 ? p.col_chunks : 1;
-  if (p.ragged && (!widest || !p.uniform_stride || chunks != 1)) return hipErrorInvalidValue;  // not planned that way
+  if (p.ragged && (!widest || !p.uniform_stride)) return hipErrorInvalidValue;  // not planned that way
   if (signature && widest && p.uniform_stride) {  // the kernels compiled per mix assume one row stride
 #define BD_SIG_GO(m, f, r, c, a, ab, sh, wide)                                                               \
   if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {             \

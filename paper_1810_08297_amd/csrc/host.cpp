@@ -716,7 +716,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       if (vec_ok) break;
     }
     if (rop && vw != (int)(16 / es)) vw = 1;  // the recompute kernels exist for the widest vector and for 1
-    // rows the vector does not fit: kernels that take the vector unaligned (no column chunks per block then)
+    // rows the vector does not fit: kernels that take the vector unaligned
     const bool ragged = ragged_rows_ok(vw, uniform_stride, s2, es);
     if (ragged) vw = (int)(16 / es);
     Geometry g;
@@ -758,7 +758,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // Wide rows with row sums and few planes: a kernel that takes all 2 or 4 column chunks of a
     // row per block finishes the row sums in the main pass (no partial sums, no second pass).
     int chunks = 1;
-    if (!rop && !ragged && uniform_stride && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
+    if (!rop && uniform_stride && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
         (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
         bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
       chunks = (int)g.n_ct;

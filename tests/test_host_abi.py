@@ -599,10 +599,9 @@ def test_generic_path_plans_chunked_reductions():
 
 
 def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
-    """Rows of an odd length keep the 16-byte vector (`ragged`), and the kernel compiled for the
-    call's class mix; a row is no longer finished inside one block over several column chunks (the
-    row's end moves only the last chunk's loads), so row sums over 2 or 4 column tiles go through
-    the second pass; a fixed pattern is kept for the op's own orientation only."""
+    """Rows of an odd length keep the 16-byte vector (`ragged`) and the kernel compiled for the
+    call's class mix, the one that finishes a row of 2 or 4 column chunks inside one block
+    included; the recompute call keeps a fixed pattern for the op's own orientation only."""
     def views(R, C):
         k = [0]
 
@@ -621,7 +620,7 @@ def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
                                         ctypes.c_int32(3), B._views(grads), ctypes.byref(info))
         d = info.as_dict()
         assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and d["ragged"] == ragged and d["specialized"] == 1, d
-        assert (d["grid_x"], d["n_launches"], d["n_second_pass"]) == ((4, 2, 1) if ragged else (1, 1, 0)), d
+        assert (d["grid_x"], d["n_launches"], d["n_second_pass"]) == (1, 1, 0), d
     op = P.bcast_op_lookup("tanh_xy_b")
     for shape_b, C, want in (((512, 1), 1024, (0, 1)), ((512, 1), 1023, (1, 1)), ((1, 1023), 1023, (1, 0))):
         mk = views(512, C)
