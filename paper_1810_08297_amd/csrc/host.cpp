@@ -502,7 +502,9 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       const TView tv = tview(c, j, v[j].p);
       p.arg_p[j] = tv.p;
       p.arg_sr[j] = tv.sr;
-      if (tv.sr == 0) p.row_invariant |= 1u << j;
+      // (a problem of one row has no row vectors: nothing is read by a second row of blocks, and the
+      // kernel keeps the streaming loads of full-shape arguments for it)
+      if (tv.sr == 0 && s2.R > 1) p.row_invariant |= 1u << j;
       if (tv.sc == 0) p.col_invariant |= 1u << j;
     }
     for (int i = 0; i < M; ++i) {
