@@ -1598,3 +1598,25 @@ def test_rows_the_vector_does_not_fit_on_the_aligned_kernels():
                 check_op(op, args, adj, what=f"[{R}x{C} aligned accesses] ", recompute="required")
     finally:
         P.bcast_dual_set_tuning(15, 1)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_lean_plane_layout_on_rows_of_odd_length(dtype):
+    """Shared and absent planes on rows the vector does not fit: the kernel compiled for the lean
+    mix takes them in its edge path; same gradients as with all planes, bit for bit, and as the oracle's."""
+    op = "hmlstm_update"
+    args, adj = small_args(op, 130, 1027, dtype, seed=77)
+    dev, adj_dev = [to_dev(a) for a in args], [to_dev(a) for a in adj]
+    shapes = [args[j].shape for j in oracle.diff_arg_indices(op, 12)]
+    full = P.alloc_forward(op, dev).run(dev)
+    lean = P.alloc_forward(op, dev, lean=True).run(dev)
+    gf = P.alloc_backward(adj_dev, full.partials, shapes).run(adj_dev, full.partials)
+    gl = P.alloc_backward(adj_dev, lean.partials, shapes).run(adj_dev, lean.partials)
+    for plan in (P.bcast_dual_backward_plan(adj_dev, lean.partials, gl.grads), P.bcast_dual_backward_plan(adj_dev, full.partials, gf.grads)):
+        assert plan["path"] == 1 and plan["ragged"] == 1 and plan["specialized"] == 1, plan
+    torch.cuda.synchronize()
+    for a, b in zip(gf.grads, gl.grads):
+        assert torch.equal(a, b)
+    want = oracle.backward(adj, [None if p is None else p.cpu().numpy() for p in lean.partials], shapes, threads=16)
+    for k in range(10):
+        check_close(gl.grads[k].cpu().numpy(), want[k], f"lean grad {k}")
