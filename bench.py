@@ -2,17 +2,21 @@
 """Benchmark of the hot path: fused dual-number forward + adjoint x partial backward.
 
 One "step" = one forward call + one backward call over one batch of synthetic input
-already resident in HBM.  Prints ONE JSON line.  Default workload: the large HM-LSTM
-cell update (hidden 4096, batch 1024, per-element z ~ Bernoulli(0.5)).
+already resident in HBM.  Prints ONE JSON line.  The headline workload is the large HM-LSTM
+cell update (hidden 4096, batch 1024, per-element z ~ Bernoulli(0.5)); the same line carries
+a "configs" object with every benchmark configuration timed the same way in the same run.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 
 Workloads: cfg0 cfg1 cfg2 cfg3 (p via --p-index 0|1|2) cfg4 cfg4_f64, paper_n512 /
-paper_n1024 / paper_n2048 (the paper's own experiment shape, Sec. 3.4).
+paper_n1024 / paper_n2048 (the paper's own experiment shape, Sec. 3.4), hmlstm_<H>x<B>,
+linear12_<H>x<B>.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import hashlib
 import json
 import os
 import sys
@@ -23,10 +27,34 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a
-# copy kernel of known size); see profiles/hbm_traffic_pmc.md.  Keyed by (workload, kernel).
-MEASURED_TRAFFIC = {("cfg3", "forward"): 487.0e6, ("cfg3", "backward"): 470.3e6,
-                    ("cfg4", "forward"): 2146.2e6, ("cfg4", "backward"): 2154.0e6}
+# HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of
+# known size): written by `python -m paper_1810_08297_amd.pmc_traffic`, which also records the
+# kernel names and a hash of the kernel sources the figures were measured on.
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.json")
+
+# the configurations of the "configs" object: (key, workload, p_index)
+ALL_CONFIGS = [("cfg0", "cfg0", 1), ("cfg1", "cfg1", 1), ("cfg2", "cfg2", 1), ("cfg3_p0.05", "cfg3", 0),
+               ("cfg3_p0.5", "cfg3", 1), ("cfg3_p0.95", "cfg3", 2), ("cfg4", "cfg4", 1), ("cfg4_f64", "cfg4_f64", 1)]
+
+
+def source_hash():
+    """sha256 over the library's sources (the same function as in pmc_traffic: a stored traffic
+    figure counts as current only for the sources it was measured on)."""
+    from paper_1810_08297_amd.pmc_traffic import source_hash as h
+    return h()
+
+
+def measured_traffic(workload, role):
+    """(bytes per launch or None, matches the sources built here) for the forward / backward kernel."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None, None
+    rec = table.get("workloads", {}).get(workload, {}).get(role)
+    if rec is None:
+        return None, None
+    return rec["traffic_bytes"], table.get("source_hash") == source_hash()
 
 
 def build_workload(name, p_index, uniform_run=0):
@@ -62,11 +90,126 @@ def build_workload(name, p_index, uniform_run=0):
     return op, args, adj, desc, dtype
 
 
-def algorithmic_words(n_args_full, n_ctrl_full, M, Nd, n_full_grads):
-    """Words per element the method itself must move (vectors and scalars are negligible)."""
-    fwd = n_args_full + n_ctrl_full + M + M * Nd
-    bwd = M + M * Nd + n_full_grads
-    return fwd, bwd
+class Workload:
+    """One workload resident in HBM (every full-shape buffer in the library's staggered slab layout)."""
+
+    def __init__(self, name, p_index, a):
+        import numpy as np
+        import torch
+        import paper_1810_08297_amd as P
+        self.name = name
+        self.op, self.args, self.adj, self.desc, self.dtype = build_workload(name, p_index, a.uniform_run)
+        if a.transposed:
+            self.args = [np.ascontiguousarray(x.T) for x in self.args]
+            self.adj = [np.ascontiguousarray(x.T) for x in self.adj]
+            self.desc += ", transposed"
+        self.es = np.dtype(self.dtype).itemsize
+        self.dev, self._slab_a = P.to_slab([torch.from_numpy(x).cuda() for x in self.args])
+        self.adj_dev, self._slab_b = P.to_slab([torch.from_numpy(x).cuda() for x in self.adj])
+        if a.sliced_gates and self.op in ("hmlstm_update", "linear12"):
+            Bt = self.args[0].shape[1]
+            wide = torch.empty(self.args[0].shape[0], 4 * Bt, dtype=self.dev[0].dtype, device="cuda")
+            for k in range(4):
+                wide[:, k * Bt:(k + 1) * Bt].copy_(self.dev[k])
+                self.dev[k] = wide[:, k * Bt:(k + 1) * Bt]
+            self.desc += ", gates as column slices of one buffer"
+
+
+def measure(w, a, options, sptr, steps, warmup, lean=False, event_every=0):
+    """Warm-up + `steps` timed steps of one workload for one partial-storage layout.  The whole
+    step is timed on the host clock between two device synchronisations; on every `event_every`-th
+    step each of the two launches also stamps a pair of HIP events with the kernel's own begin and
+    end (the library hands them to hipExtLaunchKernelGGL; stream markers around the launches would
+    also hold their own cost and the gap to the next launch, and slow the step they sit in)."""
+    import numpy as np
+    import torch
+    import paper_1810_08297_amd as P
+    fb = P.alloc_forward(w.op, w.dev, want_branch=False, lean=lean, options=options)
+    didx = P.diff_arg_indices(fb.op_id)
+    shapes = [w.args[j].shape for j in didx]
+    bb = P.alloc_backward(w.adj_dev, fb.partials, shapes, options=options)
+    E = int(np.prod(fb.outs[0].shape))
+    M, Nd = len(fb.outs), len(didx)
+    n_full_args = sum(1 for x in w.args if x.size == E)
+    n_full_grads = sum(1 for s_ in shapes if int(np.prod(s_)) == E)
+    n_stored = len({t.data_ptr() for t in fb.partials if t is not None})  # planes that cross the HBM interface
+    fwd_words = n_full_args + M + n_stored
+    bwd_words = M + n_stored + n_full_grads
+    fwd_bytes, bwd_bytes = fwd_words * w.es * E, bwd_words * w.es * E
+    fwd_call = fb.prepare(w.dev)                    # argument blocks marshalled once;
+    bwd_call = bb.prepare(w.adj_dev, fb.partials)   # each launch() is one C-ABI call
+    bplan = P.bcast_dual_backward_plan(w.adj_dev, fb.partials, bb.grads, options=options)
+    for _ in range(warmup):
+        fwd_call.launch(sptr)
+        bwd_call.launch(sptr)
+    torch.cuda.synchronize()
+    if event_every <= 0:  # a few more untimed steps tell a long step from a short one
+        w0 = time.perf_counter()
+        for _ in range(8):
+            fwd_call.launch(sptr)
+            bwd_call.launch(sptr)
+        torch.cuda.synchronize()
+        event_every = 4 if (time.perf_counter() - w0) / 8 >= 100e-6 else 16
+    timers = {k: (P.LaunchTimer(), P.LaunchTimer()) for k in range(0, steps, event_every)}
+    timed = {k: (t[0].options(options), t[1].options(options)) for k, t in timers.items()}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        t = timed.get(k)
+        if t is None:
+            fwd_call.launch(sptr)
+            bwd_call.launch(sptr)
+        else:
+            fwd_call.launch(sptr, t[0])
+            bwd_call.launch(sptr, t[1])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev = list(timers.values())
+    fwd_ms = np.array([t[0].ms() for t in ev])
+    bwd_ms = np.array([t[1].ms() for t in ev])  # the main backward kernel (a second reduction pass is not in it)
+    fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
+    both = (fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
+    return {
+        "E": E, "M": M, "Nd": Nd, "n_stored": n_stored, "shapes": shapes, "wall": wall, "event_every": event_every,
+        "value": E * steps / wall, "ms_per_step": wall * 1e3 / steps,
+        "fwd_avg": fwd_avg, "bwd_avg": bwd_avg, "fwd_bytes": fwd_bytes, "bwd_bytes": bwd_bytes,
+        "bwd_launches": bplan["n_launches"],
+        "detail": {
+            "elements": E,
+            "forward": {"avg_ms": round(fwd_avg, 5), "median_ms": round(float(np.median(fwd_ms)), 5),
+                        "bytes": fwd_bytes, "GBps": round(fwd_bytes / (fwd_avg * 1e-3) / 1e9, 1)},
+            "backward": {"avg_ms": round(bwd_avg, 5), "median_ms": round(float(np.median(bwd_ms)), 5),
+                         "bytes": bwd_bytes, "GBps": round(bwd_bytes / (bwd_avg * 1e-3) / 1e9, 1)},
+            "event_samples": len(ev),
+            "fwd_bwd_GBps_event_time": round(both, 1),
+            "fwd_bwd_frac_of_hbm_peak": round(both / HBM_PEAK_GBS, 4),
+            "elements_per_s_event_time": round(E / ((fwd_avg + bwd_avg) * 1e-3), 1),
+            "bytes_per_element": (fwd_words + bwd_words) * w.es,
+        },
+    }
+
+
+def config_record(run, workload):
+    """One entry of the "configs" object: the whole step on the host clock and the two main kernels on
+    their own event pairs, each against the algorithmic bytes it moves."""
+    step_us = run["ms_per_step"] * 1e3
+    total = run["fwd_bytes"] + run["bwd_bytes"]
+    rec = {
+        "elements": run["E"], "step_us": round(step_us, 2), "elements_per_s": round(run["value"], 1),
+        "algorithmic_bytes": total, "step_GBps": round(total / (step_us * 1e-6) / 1e9, 1),
+        "step_frac": round(total / (step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        "forward_kernel_us": round(run["fwd_avg"] * 1e3, 2), "forward_bytes": run["fwd_bytes"],
+        "forward_frac": round(run["fwd_bytes"] / (run["fwd_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "backward_kernel_us": round(run["bwd_avg"] * 1e3, 2), "backward_bytes": run["bwd_bytes"],
+        "backward_frac": round(run["bwd_bytes"] / (run["bwd_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "backward_launches": run["bwd_launches"], "event_samples": run["detail"]["event_samples"],
+    }
+    for role in ("forward", "backward"):
+        traffic, current = measured_traffic(workload, role)
+        if traffic is not None:
+            rec[f"{role}_traffic"] = traffic
+            rec["traffic_matches_build"] = current
+    return rec
 
 
 def main():
@@ -81,7 +224,10 @@ def main():
     ap.add_argument("--cpu-threads", type=int, default=16)
     ap.add_argument("--uniform-run", type=int, default=0,
                     help="paper_n* workloads: make z1, z2 constant over aligned runs of this many elements")
-    ap.add_argument("--no-lean-extra", action="store_true", help="skip the additional lean-layout measurement")
+    ap.add_argument("--no-lean-extra", action="store_true", help="skip the additional lean-layout and recompute measurements")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the \"configs\" object (every benchmark configuration timed in this run)")
+    ap.add_argument("--configs-steps", type=int, default=60, help="timed steps per entry of the \"configs\" object")
     ap.add_argument("--unfused-baseline", action="store_true",
                     help="also time the same function as per-primitive library kernels with reverse-mode autograd")
     ap.add_argument("--transposed", action="store_true",
@@ -100,8 +246,8 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run the library's 1-in 1-out stream probe on a buffer of this many MiB "
                          "(a copy of known size, for scaling profiler byte counters)")
-    ap.add_argument("--tune", type=lambda t: tuple(int(x) for x in t.split("=")), action="append", default=[],
-                    help="KEY=VALUE launch-shape override (see bcast_dual_set_tuning), repeatable")
+    ap.add_argument("--opt", type=lambda t: (t.split("=")[0], int(t.split("=")[1])), action="append", default=[],
+                    help="FIELD=VALUE of bcast_dual_options for every call of the run (launch-shape sweeps), repeatable")
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -112,105 +258,23 @@ def main():
     import paper_1810_08297_amd as P
 
     torch.cuda.set_device(0)
-    op, args, adj, desc, dtype = build_workload(a.workload, a.p_index, a.uniform_run)
-    if a.transposed:
-        args = [np.ascontiguousarray(x.T) for x in args]
-        adj = [np.ascontiguousarray(x.T) for x in adj]
-        desc += ", transposed"
-    es = np.dtype(dtype).itemsize
-    # every full-shape buffer of the step lives in the library's staggered slab layout
-    dev, _slab_a = P.to_slab([torch.from_numpy(x).cuda() for x in args])
-    adj_dev, _slab_b = P.to_slab([torch.from_numpy(x).cuda() for x in adj])
-    if a.sliced_gates and op in ("hmlstm_update", "linear12"):
-        Bt = args[0].shape[1]
-        wide = torch.empty(args[0].shape[0], 4 * Bt, dtype=dev[0].dtype, device="cuda")
-        for k in range(4):
-            wide[:, k * Bt:(k + 1) * Bt].copy_(dev[k])
-            dev[k] = wide[:, k * Bt:(k + 1) * Bt]
-        desc += ", gates as column slices of one buffer"
-    for key, val in a.tune:
-        P.bcast_dual_set_tuning(key, val)
-    import ctypes
+    options = P.Options(**dict(a.opt)) if a.opt else None
     stream = torch.cuda.current_stream()
     sptr = ctypes.c_void_p(stream.cuda_stream)
 
-    def measure(lean):
-        """warm-up + timed steps for one partial-storage layout; returns the numbers of the run"""
-        fb = P.alloc_forward(op, dev, want_branch=False, lean=lean)
-        didx = P.diff_arg_indices(fb.op_id)
-        shapes = [args[j].shape for j in didx]
-        bb = P.alloc_backward(adj_dev, fb.partials, shapes)
-        E = int(np.prod(fb.outs[0].shape))
-        M, Nd = len(fb.outs), len(didx)
-        n_full_args = sum(1 for x in args if x.size == E)
-        n_full_grads = sum(1 for s_ in shapes if int(np.prod(s_)) == E)
-        n_stored = len({t.data_ptr() for t in fb.partials if t is not None})  # planes that cross the HBM interface
-        fwd_words = n_full_args + M + n_stored
-        bwd_words = M + n_stored + n_full_grads
-        fwd_bytes, bwd_bytes = fwd_words * es * E, bwd_words * es * E
-        fwd_call = fb.prepare(dev)                    # argument blocks marshalled once;
-        bwd_call = bb.prepare(adj_dev, fb.partials)   # each launch() is one C-ABI call
-        for _ in range(a.warmup):
-            fwd_call.launch(sptr)
-            bwd_call.launch(sptr)
-        torch.cuda.synchronize()
-        if a.event_every <= 0:  # a few more untimed steps tell a long step from a short one
-            w0 = time.perf_counter()
-            for _ in range(8):
-                fwd_call.launch(sptr)
-                bwd_call.launch(sptr)
-            torch.cuda.synchronize()
-            a.event_every = 4 if (time.perf_counter() - w0) / 8 >= 100e-6 else 16
-        if a.copy_probe_mib > 0 and not lean:
-            n = a.copy_probe_mib * (1 << 20) // 4
-            src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
-            dst = torch.empty_like(src)
-            for _ in range(3):
-                P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr)
-            torch.cuda.synchronize()
-        # Per-kernel durations: on every `event_every`-th timed step each of the two launches
-        # stamps a pair of HIP events with the kernel's own begin and end (the library arms them
-        # through hipExtLaunchKernelGGL).  Stream markers around the launches would also hold
-        # their own cost and the gap to the next launch, and slow the step they sit in.
-        timers = {k: (P.LaunchTimer(), P.LaunchTimer()) for k in range(0, a.steps, a.event_every)}
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(a.steps):
-            t = timers.get(k)
-            if t is None:
-                fwd_call.launch(sptr)
-                bwd_call.launch(sptr)
-            else:
-                t[0].arm()
-                fwd_call.launch(sptr)
-                t[1].arm()
-                bwd_call.launch(sptr)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        ev = list(timers.values())
-        fwd_ms = np.array([t[0].ms() for t in ev])
-        bwd_ms = np.array([t[1].ms() for t in ev])  # the main backward kernel (a second reduction pass is not in it)
-        fwd_avg, bwd_avg = float(fwd_ms.mean()), float(bwd_ms.mean())
-        both = (fwd_bytes + bwd_bytes) / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
-        return {
-            "E": E, "M": M, "Nd": Nd, "n_stored": n_stored, "shapes": shapes, "wall": wall,
-            "value": E * a.steps / wall, "ms_per_step": wall * 1e3 / a.steps,
-            "fwd_avg": fwd_avg, "bwd_avg": bwd_avg, "fwd_bytes": fwd_bytes, "bwd_bytes": bwd_bytes,
-            "detail": {
-                "elements": E,
-                "forward": {"avg_ms": round(fwd_avg, 5), "median_ms": round(float(np.median(fwd_ms)), 5),
-                            "bytes": fwd_bytes, "GBps": round(fwd_bytes / (fwd_avg * 1e-3) / 1e9, 1)},
-                "backward": {"avg_ms": round(bwd_avg, 5), "median_ms": round(float(np.median(bwd_ms)), 5),
-                             "bytes": bwd_bytes, "GBps": round(bwd_bytes / (bwd_avg * 1e-3) / 1e9, 1)},
-                "event_samples": len(ev),
-                "fwd_bwd_GBps_event_time": round(both, 1),
-                "fwd_bwd_frac_of_hbm_peak": round(both / HBM_PEAK_GBS, 4),
-                "elements_per_s_event_time": round(E / ((fwd_avg + bwd_avg) * 1e-3), 1),
-                "bytes_per_element": (fwd_words + bwd_words) * es,
-            },
-        }
+    w = Workload(a.workload, a.p_index, a)
+    op, args, adj, desc, dtype, es, dev, adj_dev = w.op, w.args, w.adj, w.desc, w.dtype, w.es, w.dev, w.adj_dev
 
-    run = measure(a.lean)
+    run = measure(w, a, options, sptr, a.steps, a.warmup, lean=a.lean, event_every=a.event_every)
+    event_every = run["event_every"]
+    if a.copy_probe_mib > 0:
+        n = a.copy_probe_mib * (1 << 20) // 4
+        src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            P.bcast_dual_stream_probe([src.data_ptr()], [1024], [dst.data_ptr()], [1024], n // 1024, sptr, options)
+        torch.cuda.synchronize()
+        del src, dst
     E, M, Nd, n_stored, shapes = run["E"], run["M"], run["Nd"], run["n_stored"], run["shapes"]
     value, ms_per_step, extra = run["value"], run["ms_per_step"], run["detail"]
     fwd_avg, bwd_avg = run["fwd_avg"], run["bwd_avg"]
@@ -218,18 +282,19 @@ def main():
     dom_bytes = run["fwd_bytes"] if dom == "forward" else run["bwd_bytes"]
     dom_ms = max(fwd_avg, bwd_avg)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic, traffic_current = (None, None) if a.lean else measured_traffic(a.workload, dom)
     roofline = {
         "bound": "hbm", "kernel": f"{dom} ({'fwd_tiled_kernel' if dom == 'forward' else 'bwd_sig_kernel'})",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None if a.lean else MEASURED_TRAFFIC.get((a.workload, dom)),
+        "traffic": traffic, "traffic_matches_build": traffic_current,
         "algorithmic_bytes_per_launch": dom_bytes,
         "avg_launch_ms": round(dom_ms, 5),
     }
     # the same step with the leaner partial store (same outputs and gradients, fewer bytes), for reference
     lean_extra = None
     if not a.lean and not a.no_lean_extra:
-        lr = measure(True)
+        lr = measure(w, a, options, sptr, a.steps, a.warmup, lean=True, event_every=event_every)
         if lr["n_stored"] < n_stored:
             lean_extra = {"value": round(lr["value"], 1), "unit": "elements/s", "ms_per_step": round(lr["ms_per_step"], 5),
                           "planes_stored": lr["n_stored"], **lr["detail"]}
@@ -239,10 +304,10 @@ def main():
     recompute_extra = None
     if not a.lean and not a.no_lean_extra:
         try:
-            fbv = P.alloc_forward(op, dev, want_branch=False, want_partials=False)
-            rb = P.alloc_recompute(fbv.op_id, dev, adj_dev, shapes)
+            fbv = P.alloc_forward(op, dev, want_branch=False, want_partials=False, options=options)
+            rb = P.alloc_recompute(fbv.op_id, dev, adj_dev, shapes, options=options)
             fcall = fbv.prepare(dev)
-            rcall = P.PreparedRecompute(fbv.op_id, dev, adj_dev, rb.grads, rb.workspace)
+            rcall = P.PreparedRecompute(fbv.op_id, dev, adj_dev, rb.grads, rb.workspace, options)
             fcall.launch(sptr)
             rcall.launch(sptr)  # a layout the recompute entry point refuses shows here
         except P.BcastError:
@@ -252,18 +317,17 @@ def main():
                 fcall.launch(sptr)
                 rcall.launch(sptr)
             torch.cuda.synchronize()
-            timers = {k: (P.LaunchTimer(), P.LaunchTimer()) for k in range(0, a.steps, a.event_every)}
+            timers = {k: (P.LaunchTimer(), P.LaunchTimer()) for k in range(0, a.steps, event_every)}
+            timed = {k: (t[0].options(options), t[1].options(options)) for k, t in timers.items()}
             t0 = time.perf_counter()
             for k in range(a.steps):
-                t = timers.get(k)
+                t = timed.get(k)
                 if t is None:
                     fcall.launch(sptr)
                     rcall.launch(sptr)
                 else:
-                    t[0].arm()
-                    fcall.launch(sptr)
-                    t[1].arm()
-                    rcall.launch(sptr)
+                    fcall.launch(sptr, t[0])
+                    rcall.launch(sptr, t[1])
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
             ev = list(timers.values())
@@ -280,13 +344,14 @@ def main():
                                        "GBps": round(r_bytes / (r_ms * 1e-3) / 1e9, 1)},
                 "bytes_per_element": (f_bytes + r_bytes) // E,
             }
+            del fbv, rb, fcall, rcall
 
     # the same step replayed from a HIP graph (one launch of the graph = forward + backward):
     # separates the host's per-call cost from the kernels' for the small, launch-bound configs
     graph_extra = None
     if a.graph:
-        fb = P.alloc_forward(op, dev, want_branch=False, lean=a.lean)
-        bb = P.alloc_backward(adj_dev, fb.partials, shapes)
+        fb = P.alloc_forward(op, dev, want_branch=False, lean=a.lean, options=options)
+        bb = P.alloc_backward(adj_dev, fb.partials, shapes, options=options)
         fcall, bcall = fb.prepare(dev), bb.prepare(adj_dev, fb.partials)
         side = torch.cuda.Stream()
         side.wait_stream(stream)
@@ -385,6 +450,27 @@ def main():
         cpu["single_thread"] = {"value": round(take1 * cols / (s1 - s0), 1), "unit": "elements/s",
                                 "sample": f"first {take1} rows ({take1 * cols} elements), once, {s1 - s0:.2f} s"}
 
+    # every benchmark configuration, timed the same way in this same run (all planes stored, default options
+    # unless --opt); the entry of the headline workload is the headline run itself
+    configs = None
+    if not a.no_configs and not (a.lean or a.transposed or a.sliced_gates or a.uniform_run):
+        configs = {}
+        headline_key = next((k for k, wl, pi in ALL_CONFIGS if wl == a.workload and pi == a.p_index), None)
+        if headline_key:
+            configs[headline_key] = config_record(run, a.workload)
+        del w, dev, adj_dev, run
+        torch.cuda.empty_cache()
+        for key, wl, pi in ALL_CONFIGS:
+            if key == headline_key:
+                continue
+            cw = Workload(wl, pi, a)
+            small = cw.args[0].size <= (1 << 20)
+            cr = measure(cw, a, options, sptr, a.configs_steps * (4 if small else 1), 10, event_every=a.event_every)
+            configs[key] = config_record(cr, wl)
+            del cw, cr
+            torch.cuda.empty_cache()
+        configs = {k: configs[k] for k, _, _ in ALL_CONFIGS if k in configs}
+
     line = {
         "metric": "fused fwd+bwd elements/s, HM-LSTM update" if op == "hmlstm_update"
                   else f"fused fwd+bwd elements/s, {op}",
@@ -394,10 +480,11 @@ def main():
         "config": {"workload": f"{a.workload}: {desc}", "op": op, "elements": E,
                    "partial_planes": M * Nd, "planes_stored": n_stored,
                    "layout": "row-major, staggered slab, " + ("identical planes stored once, zero planes left out"
-                                                              if a.lean else "all planes stored")},
+                                                              if a.lean else "all planes stored"),
+                   "options": dict(a.opt) if a.opt else "defaults"},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra, "lean_layout": lean_extra,
         "recompute_in_reverse": recompute_extra, "graph_replay": graph_extra,
-        "unfused_baseline": unfused_extra,
+        "unfused_baseline": unfused_extra, "configs": configs,
     }
     print(json.dumps(line))
 

@@ -17,6 +17,8 @@
  *  - Every `data` pointer is a DEVICE pointer owned by the caller.  The library
  *    allocates no device memory, never synchronises, and enqueues work only on the
  *    `stream` argument (a hipStream_t; NULL = the default stream).
+ *  - The library holds no mutable state: every call is a function of its arguments,
+ *    and calls from different host threads need no locking.
  *  - Views: `ndim` dims, extents `shape[d]`, strides `stride[d]` in ELEMENTS (may be
  *    any integer >= 0 that keeps the view inside its buffer; ignored where
  *    shape[d] == 1).  Dims an argument lacks are TRAILING size-1 dims, as in the
@@ -58,7 +60,8 @@ typedef enum {
   BCAST_ERR_LAUNCH_FAILED = -9,
   BCAST_ERR_BAD_STRIDE = -10,           /* negative stride, or a written view that overlaps itself */
   BCAST_ERR_MISALIGNED = -11,           /* a data pointer is not aligned to its element size */
-  BCAST_ERR_UNSUPPORTED = -12           /* this entry point has no kernel for the op or the layout */
+  BCAST_ERR_UNSUPPORTED = -12,          /* this entry point has no kernel for the op or the layout */
+  BCAST_ERR_BAD_OPTION = -13            /* a field of bcast_dual_options is outside its documented range */
 } bcast_status;
 
 typedef struct {
@@ -85,7 +88,63 @@ typedef struct {
   int32_t ragged;      /* 1: the rows do not fit the 16-byte vector (length, start or stride off its
                           boundary) and the kernels that take it unaligned, with the last columns of
                           every row singly, are used */
+  int32_t uniform_stride; /* tiled path: 1 if every view the kernels stream row by row has the same row
+                          stride (one address offset per lane then serves them all), 0 if each is addressed
+                          with its own (slices of wider buffers, views that repeat one row) */
 } bcast_plan_info;
+
+/* Per-call options.  Every entry point that plans or launches takes a `const bcast_dual_options *`
+ * as its last argument; NULL means the defaults (the measured best on MI355X), which is what a
+ * caller normally passes.  The library keeps no state between calls and none that two threads
+ * could share: two calls with different options may run concurrently from different host threads.
+ * The fields exist for launch-shape sweeps, for tests that force a particular kernel, and for
+ * timing one launch; fill the struct with bcast_dual_options_default() first, then change fields.
+ * A value outside its range makes the call return BCAST_ERR_BAD_OPTION before anything is launched.
+ * A workspace query, a plan query and the call itself must be given the same options. */
+typedef struct {
+  uint32_t struct_size;     /* sizeof(bcast_dual_options) as the caller compiled it; any other value is refused */
+  int32_t bwd_row_steps;    /* row steps per block of the tiled backward kernels: 0 (default) = automatic, else 1..256 */
+  int32_t nontemporal_stores; /* bit 0: the forward kernel's outputs and planes, bit 1: the backward kernels'
+                               gradients (default 3 = both; measured: no difference) */
+  int32_t force_generic;    /* 1 = the generic strided kernels even where the tiled ones apply (testing); default 0 */
+  int32_t max_vector_bytes; /* widest vector access per lane: 16 (default), 8 or 4 */
+  int32_t runtime_table;    /* 1 = never a backward / recompute kernel compiled for the call's mix of gradient
+                               classes, always the one that reads the gradient table at run time (testing); default 0 */
+  int32_t reverse_tiles;    /* 1 (default) = the tiled backward kernels walk their tiles last to first, starting with
+                               the planes the forward kernel wrote last, which the memory-side cache may still hold */
+  int32_t interleave_rows;  /* rows of a backward block that takes several row steps: 1 (default) = every n-th row
+                               step of the problem (the resident blocks sweep one contiguous band of each plane
+                               together), 0 = one contiguous run of rows per block */
+  int32_t xcd_order;        /* 1 = XCD-aware tile order: the hardware deals consecutive blocks round-robin to the
+                               8 XCDs, and block b then serves tile (b % 8) * (blocks / 8) + b / 8, so that every
+                               XCD gets one contiguous eighth of the tiles; 0 (default) = tile b.  Measured slower:
+                               nothing is reused between blocks, and the eight bands sit a power of two apart */
+  int32_t col_chunks;       /* 1 (default) = where a kernel was built for it, a backward block takes all 2 or 4
+                               column chunks of a row, so that row sums of rows up to 4 x 1024 (fp64: 4 x 512)
+                               elements finish in the main pass; 0 = one chunk per block */
+  int32_t fwd_lds_kib;      /* KiB of (unused) dynamic LDS the forward kernel requests per block when it writes at
+                               least 2.5 planes for every plane it reads, which limits the blocks resident on a CU
+                               (160 KiB each): 48 (default) = three, 0 = no limit; 0..64 */
+  int32_t bwd_lds_kib;      /* the same for the main backward and recompute kernels, on top of what they need
+                               (default 0: measured no gain); 0..64 */
+  int32_t narrow_tiles;     /* 1 (default) = rows longer than 1024 elements may be tiled with 64 or 128 lanes per
+                               row (4 or 2 rows per block step) where that pads the row less than 256 lanes */
+  int32_t ragged_rows;      /* 1 (default) = rows whose length, start or stride is not a multiple of the 16-byte
+                               vector are still read and written in such vectors, unaligned, with the last columns
+                               of every row taken singly; 0 = the widest aligned access that fits (8 or 4 bytes) */
+  int32_t probe_nt_loads;   /* bcast_dual_stream_probe: 1 (default) = nontemporal loads, 0 = plain */
+  int32_t probe_lds_kib;    /* bcast_dual_stream_probe: unused dynamic LDS per block, as fwd_lds_kib (default 0) */
+  /* Timing of one launch by the runtime itself: two hipEvent_t the caller created with timing enabled, both
+   * or neither.  The main-pass kernel of the call (the forward kernel, the main backward or recompute kernel
+   * -- the first one if the gradients need several launches, never the second reduction pass -- or the probe
+   * kernel) stamps them with its own begin and end, so that hipEventElapsedTime(start, stop) is the kernel's
+   * duration with no launch gap in it.  Not for a stream that is being captured into a graph. */
+  void *start_event;
+  void *stop_event;
+} bcast_dual_options;
+
+/* Fills *opt with the defaults (and struct_size). */
+void bcast_dual_options_default(bcast_dual_options *opt);
 
 /* ---- op table --------------------------------------------------------------------
  * Built-in scalar functions (each is already the fused composition, Sec. 2.1.2):
@@ -141,10 +200,10 @@ int bcast_op_plane_alias(int32_t op_id, int32_t *alias);
  * Written views must not have zero strides on dims of extent > 1. */
 int bcast_dual_forward(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                        int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
-                       uint8_t *branch_id, void *stream);
+                       uint8_t *branch_id, void *stream, const bcast_dual_options *opt);
 int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                             int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
-                            const uint8_t *branch_id, bcast_plan_info *info);
+                            const uint8_t *branch_id, bcast_plan_info *info, const bcast_dual_options *opt);
 
 /* ---- backward: adjoint x partial, summed over expanded dims (Table 1) --------------
  * Independent of the op.
@@ -164,13 +223,13 @@ int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const
  * and rounded once; there are no atomics, so results do not depend on scheduling. */
 size_t bcast_dual_backward_workspace(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                                      const bcast_tensor *partials, int32_t n_grads,
-                                     const bcast_tensor *grads);
+                                     const bcast_tensor *grads, const bcast_dual_options *opt);
 int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                         const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
-                        void *workspace, size_t workspace_bytes, void *stream);
+                        void *workspace, size_t workspace_bytes, void *stream, const bcast_dual_options *opt);
 int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                              const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
-                             bcast_plan_info *info);
+                             bcast_plan_info *info, const bcast_dual_options *opt);
 
 /* ---- backward without cached planes: D applied in the reverse pass (Sec. 2.2.3, last paragraph) ----
  * The other side of the paper's memory/compute trade-off: nothing is kept between the passes
@@ -183,68 +242,19 @@ int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *
  * full-shape views share one row stride); otherwise BCAST_ERR_UNSUPPORTED.  Workspace rules as for bcast_dual_backward. */
 size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                                int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
-                                               const bcast_tensor *grads);
+                                               const bcast_tensor *grads, const bcast_dual_options *opt);
 int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                   int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
-                                  const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream);
+                                  const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream,
+                                  const bcast_dual_options *opt);
 /* How that call would be mapped (no launch); `specialized` = 1 when the kernel compiled for the op's
  * usual broadcast pattern runs (every argument's form fixed at compile time). */
 int bcast_dual_backward_recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                        int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
-                                       const bcast_tensor *grads, bcast_plan_info *info);
+                                       const bcast_tensor *grads, bcast_plan_info *info, const bcast_dual_options *opt);
 
 /* ---- misc ---------------------------------------------------------------------- */
 const char *bcast_status_string(int status);
-
-/* Launch-shape overrides for benchmarking sweeps (process-wide, not thread-safe; values
- * outside the documented range are rejected with BCAST_ERR_BAD_ARG_COUNT).
- *   key 0: unused (kept so that the other keys keep their numbers)
- *   key 1: rows per block of the tiled backward kernel (0 = automatic, else 1..256)
- *   key 2: non-temporal stores: bit 0 = the forward kernel's outputs and partials, bit 1 = the
- *          backward kernels' gradients (default 3 = both, 0 = plain stores)
- *   key 3: 1 = force the generic strided kernels (testing)
- *   key 4: widest vector access per lane in bytes: 16 (default), 8 or 4
- *   key 5: 1 = always use the generic tiled backward kernel, never a kernel compiled for
- *          the call's mix of gradient classes (testing)
- *   key 6: 1 (default) = the tiled backward kernel walks its tiles last to first, so that it
- *          starts with the planes the forward kernel wrote last, which the memory-side
- *          cache may still hold; 0 = first to last
- *   key 7: loads of the streaming probe: 1 (default) = nontemporal, as the kernels load their
- *          once-read operands; 0 = plain
- *   key 8: rows of a backward block that takes several row steps: 1 (default) = every n-th
- *          row step of the problem (the resident blocks sweep one contiguous band of each
- *          plane together), 0 = one contiguous run of rows per block
- *   key 9: 1 = XCD-aware tile order in the tiled kernels: the hardware deals consecutive blocks
- *          round-robin to the 8 XCDs, and block b then serves tile (b % 8) * (blocks / 8) + b / 8,
- *          i.e. every XCD gets one contiguous eighth of the tiles; 0 (default) = tile b.  Measured
- *          slower (the eight bands sit a power of two apart in every plane)
- *   key 10: 1 (default) = where a kernel was built for it, a backward block takes all 2 or 4
- *          column chunks of a row, so that row sums of rows up to 4 x 1024 (fp64: 4 x 512)
- *          elements finish in the main pass; 0 = one chunk per block, wide rows through the
- *          second pass
- *   key 11: KiB of (unused) dynamic LDS the forward kernel requests per block when it writes at
- *          least 2.5 planes for every plane it reads, which limits the blocks resident on a CU
- *          (160 KiB each): 48 (default) = three, 0 = no limit
- *   key 12: the same for the main backward and recompute kernels, on top of what they need
- *          (default 0: measured no gain)
- *   key 13: the same for the stream probe (default 0)
- *   key 14: 1 (default) = rows longer than 1024 elements may be tiled with 64 or 128 lanes per row
- *          (4 or 2 rows per block step) where that pads the row less than 256 lanes; 0 = always 256
- *   key 15: 1 (default) = rows whose length, start or stride is not a multiple of the 16-byte vector
- *          are still read and written in such vectors, unaligned, with the last columns of every
- *          row taken singly; 0 = the widest aligned access that fits (8 or 4 bytes) */
-int bcast_dual_set_tuning(int32_t key, int32_t value);
-int bcast_dual_get_tuning(int32_t key, int32_t *value);
-
-/* Timing of one launch by the runtime itself.  start_event and stop_event are two hipEvent_t
- * the caller created (with timing enabled).  The NEXT main-pass kernel this library launches --
- * the forward kernel, the main backward or recompute kernel (not the second reduction pass), or
- * the stream probe -- stamps them with that kernel's own begin and end, so that
- * hipEventElapsedTime(start, stop) is the kernel's duration with no launch gap in it; the pair is
- * then disarmed.  NULL, NULL disarms without a launch; one NULL is BCAST_ERR_NULL_POINTER.
- * Process-wide and not thread-safe, like the tuning keys; not to be armed while the stream is
- * being captured into a graph. */
-int bcast_dual_set_launch_events(void *start_event, void *stop_event);
 
 /* Partial-storage layout.  The planes of one call (outputs, the M x N_d partials, the
  * gradients, and ideally the arguments too) are streamed side by side, every wavefront
@@ -264,10 +274,11 @@ size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offs
  * plane[k] + b * chunk_stride[k] floats (1024 = a dense plane; larger = planes interleaved in
  * one buffer).  in/out and the stride arrays are HOST arrays (at most 32 entries each) of
  * DEVICE pointers (16-byte aligned) and strides (multiples of 4; output strides >= 1024).
- * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters.  Tuning keys 6
- * (chunk order), 7 (load policy) and 13 (blocks per CU) apply. */
+ * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters.  The options
+ * reverse_tiles (chunk order), probe_nt_loads and probe_lds_kib apply. */
 int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
-                            void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream);
+                            void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream,
+                            const bcast_dual_options *opt);
 
 #ifdef __cplusplus
 }

@@ -31,12 +31,47 @@ class PlanInfo(ctypes.Structure):
                 ("shape", ctypes.c_int64 * MAX_DIMS), ("tx", ctypes.c_int32), ("ty", ctypes.c_int32),
                 ("rows_per_block", ctypes.c_int32), ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64),
                 ("n_launches", ctypes.c_int32), ("n_second_pass", ctypes.c_int32), ("specialized", ctypes.c_int32),
-                ("ragged", ctypes.c_int32)]
+                ("ragged", ctypes.c_int32), ("uniform_stride", ctypes.c_int32)]
 
     def as_dict(self):
         d = {k: getattr(self, k) for k, _ in self._fields_ if k != "shape"}
         d["shape"] = list(self.shape)[: self.ndim]
         return d
+
+
+class Options(ctypes.Structure):
+    """bcast_dual_options: per-call launch-shape overrides and the event pair that times one
+    launch.  ``Options()`` holds the library's defaults; keyword arguments change fields."""
+    _fields_ = [("struct_size", ctypes.c_uint32), ("bwd_row_steps", ctypes.c_int32),
+                ("nontemporal_stores", ctypes.c_int32), ("force_generic", ctypes.c_int32),
+                ("max_vector_bytes", ctypes.c_int32), ("runtime_table", ctypes.c_int32),
+                ("reverse_tiles", ctypes.c_int32), ("interleave_rows", ctypes.c_int32),
+                ("xcd_order", ctypes.c_int32), ("col_chunks", ctypes.c_int32), ("fwd_lds_kib", ctypes.c_int32),
+                ("bwd_lds_kib", ctypes.c_int32), ("narrow_tiles", ctypes.c_int32), ("ragged_rows", ctypes.c_int32),
+                ("probe_nt_loads", ctypes.c_int32), ("probe_lds_kib", ctypes.c_int32),
+                ("start_event", ctypes.c_void_p), ("stop_event", ctypes.c_void_p)]
+
+    def __init__(self, **fields):
+        super().__init__()
+        lib().bcast_dual_options_default(ctypes.byref(self))
+        names = {k for k, _ in self._fields_}
+        for k, v in fields.items():
+            if k not in names:
+                raise TypeError(f"bcast_dual_options has no field {k!r}")
+            setattr(self, k, v)
+
+    def replace(self, **fields):
+        """A copy with some fields changed."""
+        o = Options()
+        ctypes.memmove(ctypes.byref(o), ctypes.byref(self), ctypes.sizeof(Options))
+        for k, v in fields.items():
+            setattr(o, k, v)
+        return o
+
+
+def _opt(options):
+    """NULL (the library's defaults) or a pointer to the caller's struct."""
+    return None if options is None else ctypes.byref(options)
 
 
 class BcastError(RuntimeError):
@@ -49,8 +84,8 @@ _lib = None
 
 EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
-           "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_set_tuning",
-           "bcast_dual_get_tuning", "bcast_dual_set_launch_events", "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
+           "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_options_default",
+           "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
            "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace",
            "bcast_dual_backward_recompute_plan")
 
@@ -68,11 +103,35 @@ def lib():
         # the library gets the system's copy and its launches fail with "no device detected").
         import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
-        L.bcast_op_name.restype = ctypes.c_char_p
-        L.bcast_status_string.restype = ctypes.c_char_p
-        L.bcast_dual_backward_workspace.restype = ctypes.c_size_t
-        L.bcast_dual_slab_layout.restype = ctypes.c_size_t
-        L.bcast_dual_backward_recompute_workspace.restype = ctypes.c_size_t
+        # Full prototypes: ctypes then refuses a call with the wrong number of arguments instead of
+        # handing the library whatever the registers hold.
+        i32, i64, cint, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        T, O, PI = ctypes.POINTER(BcastTensor), ctypes.POINTER(Options), ctypes.POINTER(PlanInfo)
+        proto = {
+            "bcast_op_lookup": (cint, [ctypes.c_char_p, ctypes.POINTER(i32)]),
+            "bcast_op_count": (cint, []),
+            "bcast_op_name": (ctypes.c_char_p, [i32]),
+            "bcast_op_info": (cint, [i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_uint32),
+                                     ctypes.POINTER(i32)]),
+            "bcast_op_plane_alias": (cint, [i32, ctypes.POINTER(i32)]),
+            "bcast_dual_options_default": (None, [O]),
+            "bcast_dual_forward": (cint, [i32, cint, i32, T, i32, T, T, vp, vp, O]),
+            "bcast_dual_forward_plan": (cint, [i32, cint, i32, T, i32, T, T, vp, PI, O]),
+            "bcast_dual_backward_workspace": (sz, [cint, i32, T, T, i32, T, O]),
+            "bcast_dual_backward": (cint, [cint, i32, T, T, i32, T, vp, sz, vp, O]),
+            "bcast_dual_backward_plan": (cint, [cint, i32, T, T, i32, T, PI, O]),
+            "bcast_dual_backward_recompute_workspace": (sz, [i32, cint, i32, T, i32, T, i32, T, O]),
+            "bcast_dual_backward_recompute": (cint, [i32, cint, i32, T, i32, T, i32, T, vp, sz, vp, O]),
+            "bcast_dual_backward_recompute_plan": (cint, [i32, cint, i32, T, i32, T, i32, T, PI, O]),
+            "bcast_status_string": (ctypes.c_char_p, [cint]),
+            "bcast_dual_slab_layout": (sz, [sz, i32, ctypes.POINTER(sz)]),
+            "bcast_dual_stream_probe": (cint, [i32, ctypes.POINTER(vp), ctypes.POINTER(i64), i32, ctypes.POINTER(vp),
+                                               ctypes.POINTER(i64), i64, vp, O]),
+        }
+        assert set(proto) == set(EXPORTS)
+        for name, (res, argt) in proto.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, argt
         _lib = L
     return _lib
 
@@ -193,7 +252,7 @@ def _stream_ptr(stream):
 
 # ---- forward ----------------------------------------------------------------------------------
 def bcast_dual_forward(op_id: int, args: Sequence, outs: Sequence, partials: Optional[Sequence],
-                       branch_id=None, stream=None) -> None:
+                       branch_id=None, stream=None, options: Optional[Options] = None) -> None:
     """Enqueue the dual-number forward kernel.  All buffers are caller-allocated."""
     _on_device(args, outs, partials, [branch_id])
     dt = _dtype_code(outs[0])
@@ -202,32 +261,33 @@ def bcast_dual_forward(op_id: int, args: Sequence, outs: Sequence, partials: Opt
     p = _views(partials, o[0]) if partials is not None else None
     _check(lib().bcast_dual_forward(
         ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), a, ctypes.c_int32(len(outs)), o,
-        p, ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None), _stream_ptr(stream)),
-        "bcast_dual_forward")
+        p, ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None), _stream_ptr(stream),
+        _opt(options)), "bcast_dual_forward")
 
 
-def bcast_dual_forward_plan(op_id: int, args, outs, partials, branch_id=None) -> dict:
+def bcast_dual_forward_plan(op_id: int, args, outs, partials, branch_id=None, options: Optional[Options] = None) -> dict:
     dt = _dtype_code(outs[0])
     a, o = _views(args), _views(outs)
     p = _views(partials, o[0]) if partials is not None else None
     info = PlanInfo()
     _check(lib().bcast_dual_forward_plan(
         ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), a, ctypes.c_int32(len(outs)), o,
-        p, ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None), ctypes.byref(info)),
-        "bcast_dual_forward_plan")
+        p, ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None), ctypes.byref(info),
+        _opt(options)), "bcast_dual_forward_plan")
     return info.as_dict()
 
 
 # ---- backward ---------------------------------------------------------------------------------
-def bcast_dual_backward_workspace(adjoints, partials, grads) -> int:
+def bcast_dual_backward_workspace(adjoints, partials, grads, options: Optional[Options] = None) -> int:
     dt = _dtype_code(adjoints[0])
     a = _views(adjoints)
     return int(lib().bcast_dual_backward_workspace(
         ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
-        ctypes.c_int32(len(grads)), _views(grads)))
+        ctypes.c_int32(len(grads)), _views(grads), _opt(options)))
 
 
-def bcast_dual_backward(adjoints, partials, grads, workspace=None, stream=None) -> None:
+def bcast_dual_backward(adjoints, partials, grads, workspace=None, stream=None,
+                        options: Optional[Options] = None) -> None:
     """Enqueue adjoint x partial with the broadcast-dim reductions.  ``workspace`` is a
     uint8 device tensor of at least bcast_dual_backward_workspace(...) bytes (or None)."""
     _on_device(adjoints, partials, grads, [workspace])
@@ -238,44 +298,29 @@ def bcast_dual_backward(adjoints, partials, grads, workspace=None, stream=None) 
     _check(lib().bcast_dual_backward(
         ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
         ctypes.c_int32(len(grads)), _views(grads), ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes),
-        _stream_ptr(stream)), "bcast_dual_backward")
+        _stream_ptr(stream), _opt(options)), "bcast_dual_backward")
 
 
-def bcast_dual_backward_plan(adjoints, partials, grads) -> dict:
+def bcast_dual_backward_plan(adjoints, partials, grads, options: Optional[Options] = None) -> dict:
     dt = _dtype_code(adjoints[0])
     a = _views(adjoints)
     info = PlanInfo()
     _check(lib().bcast_dual_backward_plan(
         ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
-        ctypes.c_int32(len(grads)), _views(grads), ctypes.byref(info)), "bcast_dual_backward_plan")
+        ctypes.c_int32(len(grads)), _views(grads), ctypes.byref(info), _opt(options)), "bcast_dual_backward_plan")
     return info.as_dict()
 
 
 # ---- misc -------------------------------------------------------------------------------------
-def bcast_dual_set_tuning(key: int, value: int) -> None:
-    _check(lib().bcast_dual_set_tuning(ctypes.c_int32(key), ctypes.c_int32(value)), "bcast_dual_set_tuning")
-
-
-def bcast_dual_get_tuning(key: int) -> int:
-    v = ctypes.c_int32()
-    _check(lib().bcast_dual_get_tuning(ctypes.c_int32(key), ctypes.byref(v)), "bcast_dual_get_tuning")
-    return v.value
-
-
-def bcast_dual_set_launch_events(start_event, stop_event) -> None:
-    """start_event/stop_event: hipEvent_t handles (ints or c_void_p), or None, None to disarm."""
-    _check(lib().bcast_dual_set_launch_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event)),
-           "bcast_dual_set_launch_events")
-
-
-def bcast_dual_stream_probe(in_ptrs, in_strides, out_ptrs, out_strides, n_chunks, stream=None) -> None:
+def bcast_dual_stream_probe(in_ptrs, in_strides, out_ptrs, out_strides, n_chunks, stream=None,
+                            options: Optional[Options] = None) -> None:
     """in_ptrs/out_ptrs: device addresses (ints); strides in floats per 4 KiB chunk."""
     def arr(ctype, vals):
         return (ctype * max(1, len(vals)))(*vals)
     _check(lib().bcast_dual_stream_probe(
         ctypes.c_int32(len(in_ptrs)), arr(ctypes.c_void_p, in_ptrs), arr(ctypes.c_int64, in_strides),
         ctypes.c_int32(len(out_ptrs)), arr(ctypes.c_void_p, out_ptrs), arr(ctypes.c_int64, out_strides),
-        ctypes.c_int64(n_chunks), _stream_ptr(stream)), "bcast_dual_stream_probe")
+        ctypes.c_int64(n_chunks), _stream_ptr(stream), _opt(options)), "bcast_dual_stream_probe")
 
 
 def bcast_dual_slab_layout(plane_bytes: int, n_planes: int):
@@ -289,9 +334,10 @@ class PreparedForward:
     """A forward call whose argument block is marshalled once; ``launch`` only enqueues.
     The tensors must stay alive and keep their addresses between launches."""
 
-    def __init__(self, op_id, args, outs, partials, branch_id=None):
+    def __init__(self, op_id, args, outs, partials, branch_id=None, options: Optional[Options] = None):
         _on_device(args, outs, partials, [branch_id])
-        self._keep = (args, outs, partials, branch_id)
+        self._keep = (args, outs, partials, branch_id, options)
+        self._opt = _opt(options)
         self._op = ctypes.c_int32(op_id)
         self._dt = ctypes.c_int(_dtype_code(outs[0]))
         self._na, self._a = ctypes.c_int32(len(args)), _views(args)
@@ -300,17 +346,19 @@ class PreparedForward:
         self._b = ctypes.c_void_p(branch_id.data_ptr() if branch_id is not None else None)
         self._fn = lib().bcast_dual_forward
 
-    def launch(self, stream=None):
+    def launch(self, stream=None, options: Optional[Options] = None):
+        """``options`` here replaces the ones given at construction for this launch (a timed one, say)."""
         _check(self._fn(self._op, self._dt, self._na, self._a, self._no, self._o, self._p, self._b,
-                        _stream_ptr(stream)), "bcast_dual_forward")
+                        _stream_ptr(stream), self._opt if options is None else ctypes.byref(options)), "bcast_dual_forward")
 
 
 class PreparedBackward:
     """A backward call whose argument block is marshalled once (see PreparedForward)."""
 
-    def __init__(self, adjoints, partials, grads, workspace=None):
+    def __init__(self, adjoints, partials, grads, workspace=None, options: Optional[Options] = None):
         _on_device(adjoints, partials, grads, [workspace])
-        self._keep = (adjoints, partials, grads, workspace)
+        self._keep = (adjoints, partials, grads, workspace, options)
+        self._opt = _opt(options)
         self._dt = ctypes.c_int(_dtype_code(adjoints[0]))
         self._no, self._a = ctypes.c_int32(len(adjoints)), _views(adjoints)
         self._p = _views(partials, self._a[0])
@@ -319,29 +367,30 @@ class PreparedBackward:
         self._wsb = ctypes.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0)
         self._fn = lib().bcast_dual_backward
 
-    def launch(self, stream=None):
+    def launch(self, stream=None, options: Optional[Options] = None):
         _check(self._fn(self._dt, self._no, self._a, self._p, self._ng, self._g, self._ws, self._wsb,
-                        _stream_ptr(stream)), "bcast_dual_backward")
+                        _stream_ptr(stream), self._opt if options is None else ctypes.byref(options)), "bcast_dual_backward")
 
 
-def bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads) -> int:
+def bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads, options: Optional[Options] = None) -> int:
     dt = _dtype_code(adjoints[0])
     return int(lib().bcast_dual_backward_recompute_workspace(
         ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
-        ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads)))
+        ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads), _opt(options)))
 
 
-def bcast_dual_backward_recompute_plan(op_id, args, adjoints, grads) -> dict:
+def bcast_dual_backward_recompute_plan(op_id, args, adjoints, grads, options: Optional[Options] = None) -> dict:
     dt = _dtype_code(adjoints[0])
     info = PlanInfo()
     _check(lib().bcast_dual_backward_recompute_plan(
         ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
         ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads),
-        ctypes.byref(info)), "bcast_dual_backward_recompute_plan")
+        ctypes.byref(info), _opt(options)), "bcast_dual_backward_recompute_plan")
     return info.as_dict()
 
 
-def bcast_dual_backward_recompute(op_id, args, adjoints, grads, workspace=None, stream=None) -> None:
+def bcast_dual_backward_recompute(op_id, args, adjoints, grads, workspace=None, stream=None,
+                                  options: Optional[Options] = None) -> None:
     """Gradients straight from arguments and adjoints: the dual numbers are evaluated again."""
     _on_device(args, adjoints, grads, [workspace])
     dt = _dtype_code(adjoints[0])
@@ -350,15 +399,17 @@ def bcast_dual_backward_recompute(op_id, args, adjoints, grads, workspace=None, 
     _check(lib().bcast_dual_backward_recompute(
         ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(args)), _views(args),
         ctypes.c_int32(len(adjoints)), _views(adjoints), ctypes.c_int32(len(grads)), _views(grads),
-        ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), _stream_ptr(stream)), "bcast_dual_backward_recompute")
+        ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes), _stream_ptr(stream), _opt(options)),
+        "bcast_dual_backward_recompute")
 
 
 class PreparedRecompute:
     """A recompute-backward call marshalled once (see PreparedForward)."""
 
-    def __init__(self, op_id, args, adjoints, grads, workspace=None):
+    def __init__(self, op_id, args, adjoints, grads, workspace=None, options: Optional[Options] = None):
         _on_device(args, adjoints, grads, [workspace])
-        self._keep = (args, adjoints, grads, workspace)
+        self._keep = (args, adjoints, grads, workspace, options)
+        self._opt = _opt(options)
         self._op = ctypes.c_int32(op_id)
         self._dt = ctypes.c_int(_dtype_code(adjoints[0]))
         self._na, self._a = ctypes.c_int32(len(args)), _views(args)
@@ -368,6 +419,7 @@ class PreparedRecompute:
         self._wsb = ctypes.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0)
         self._fn = lib().bcast_dual_backward_recompute
 
-    def launch(self, stream=None):
+    def launch(self, stream=None, options: Optional[Options] = None):
         _check(self._fn(self._op, self._dt, self._na, self._a, self._no, self._o, self._ng, self._g, self._ws,
-                        self._wsb, _stream_ptr(stream)), "bcast_dual_backward_recompute")
+                        self._wsb, _stream_ptr(stream), self._opt if options is None else ctypes.byref(options)),
+               "bcast_dual_backward_recompute")

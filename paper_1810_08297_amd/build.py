@@ -43,26 +43,6 @@ def _compile(src, extra):
     return obj
 
 
-def build_variant(name: str, flags, jobs: int = 4) -> str:
-    """Development aid: a second library (core ops only) built with extra -D flags."""
-    out = os.path.join(HERE, f"libbcast_dual_{name}.so")
-    objdir = os.path.join(OBJ, name)
-    os.makedirs(objdir, exist_ok=True)
-    srcs = ["host.cpp", "bwd_kernels.hip", "ops_core.hip", "ops_misc.hip"]
-
-    def one(src):
-        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-        cmd = ["hipcc", *HIPCC_FLAGS, "-DBD_NO_ARITY", *flags, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
-        r = subprocess.run(cmd, capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
-        return obj
-    with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(one, srcs))
-    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out])
-    return out
-
-
 def build(force: bool = True, jobs: int = 8, extra_flags=()) -> str:
     """Compile everything (always, unless force=False and the library is newer than
     every source) and return the library path."""

@@ -224,12 +224,12 @@ struct BwdGeom {
 template <class T, int VEC, bool EDGE, bool RAGGED = false>
 BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC], int shift = 0) {
   if (EDGE) {
-    load_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(base, valid ? off : 0u), x);
+    load_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(base, valid ? off : 0u), x);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) x[v] = valid ? x[v] : T(0);
     if constexpr (RAGGED) unshift<T, VEC>(x, shift);
   } else {
-    load_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(base, off), x);
+    load_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(base, off), x);
   }
 }
 

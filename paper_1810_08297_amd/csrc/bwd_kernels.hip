@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include "bwd_device.h"
+#include "launch.h"
 
 namespace bd {
 
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
     auto voff = [&](int64_t sr) { return valid ? rs.lane(sr) : 0u; };
     LV adj_raw[MAXM];  // unpacked only after the first four gradients' loads are on their way
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(rs.base(p.adj[i < M ? i : 0].p, p.adj[i < M ? i : 0].sr), voff(p.adj[i < M ? i : 0].sr)));
+    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(rs.base(p.adj[i < M ? i : 0].p, p.adj[i < M ? i : 0].sr), voff(p.adj[i < M ? i : 0].sr)));
     T adj[MAXM][VEC];
     LV raw[CH][MAXM];
     bool have[CH][MAXM];
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
           const void *plane = i < M ? p.e[e].P[i].p : nullptr;
           have[q][i] = valid && e0 + q < p.n_entries && plane != nullptr;
           const int64_t sr = plane != nullptr ? p.e[e].P[i].sr : p.adj[0].sr;
-          raw[q][i] = load_lane_vec<T, VEC, BD_BWD_LD_NT != 0, RAGGED>(at<const T>(rs.base(plane != nullptr ? plane : p.adj[0].p, sr), voff(sr)));
+          raw[q][i] = load_lane_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(rs.base(plane != nullptr ? plane : p.adj[0].p, sr), voff(sr)));
         }
       }
     };
@@ -337,13 +338,14 @@ __global__ __launch_bounds__(kBlock) void bwd_generic_reduce_kernel(const BwdGen
     for (int64_t q = q0 + first; q < q1; q += step) {
       decompose(q, p.n_fibre, p.nd, p.shape, idx, [&](int d) { return p.reduced[d] != 0; });
       for (int i = 0; i < p.M; ++i) {
-        if (p.P[i].p == nullptr) continue;
         int64_t oa = 0, op = 0;
         for (int d = 0; d < BCAST_MAX_DIMS; ++d) {
           oa += idx[d] * p.adj[i].s[d];
           op += idx[d] * p.P[i].s[d];
         }
-        AT::add_prod(s, static_cast<const T *>(p.adj[i].p)[oa], static_cast<const T *>(p.P[i].p)[op]);
+        // an absent plane is a plane of zeros: its product with a non-finite adjoint is NaN, as in the tiled kernels
+        const T plane = p.P[i].p != nullptr ? static_cast<const T *>(p.P[i].p)[op] : T(0);
+        AT::add_prod(s, static_cast<const T *>(p.adj[i].p)[oa], plane);
       }
     }
   A total = AT::zero();
@@ -464,7 +466,7 @@ bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent
 }
 
 template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, bool WIDE>
-static void launch_sig(int chunks, const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
+static void launch_sig(int chunks, const BwdTiledParams &p, dim3 grid, size_t lds, const Launch &s) {
   if constexpr (WIDE) {
     if (chunks == 4) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 4>), grid, dim3(kBlock), lds, s, p);
     if (chunks == 2) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 2>), grid, dim3(kBlock), lds, s, p);
@@ -473,7 +475,7 @@ static void launch_sig(int chunks, const BwdTiledParams &p, dim3 grid, size_t ld
 }
 
 hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
-                        const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s) {
+                        const BwdTiledParams &p, dim3 grid, size_t lds, const Launch &s) {
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
   const int chunks = p.col_chunks > 0 ? p.col_chunks : 1;
   if (p.ragged && (!widest || !p.uniform_stride)) return hipErrorInvalidValue;  // not planned that way
@@ -525,17 +527,17 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
   return hipGetLastError();
 }
 
-hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s) {
+hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, const Launch &s) {
   (void)hipGetLastError();  // only this launch's error is of interest below
   if (dt == BCAST_F32)
-    hipLaunchKernelGGL((bwd_pass2_kernel<float>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
+    hipLaunchKernelGGL((bwd_pass2_kernel<float>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s.stream, p);
   else
-    hipLaunchKernelGGL((bwd_pass2_kernel<double>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s, p);
+    hipLaunchKernelGGL((bwd_pass2_kernel<double>), dim3((unsigned)n_blocks), dim3(kBlock), 0, s.stream, p);
   return hipGetLastError();
 }
 
 // kind: 0 = elementwise (full-shape gradient), 1 = reduction, 2 = sum of a reduction's partial sums
-hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s) {
+hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n_blocks, const Launch &s) {
   dim3 grid((unsigned)n_blocks);
   if (dt == BCAST_F32) {
     if (kind == 1) launch((bwd_generic_reduce_kernel<float>), grid, dim3(kBlock), 0, s, p);
@@ -553,7 +555,7 @@ hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n
 
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
                            const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, size_t lds_bytes,
-                           hipStream_t s) {
+                           const Launch &s) {
   ProbeParams p{};
   p.reverse = reverse;
   p.n_in = n_in;

@@ -35,27 +35,22 @@ template <class T> struct smath;
 template <> struct smath<float> {
   // 2^(x log2 e): the rounding error of the product and of the float constant is folded
   // back in as 2^t (1 + err ln 2); v_exp_f32 is accurate to 1 ulp.  About 1.5 ulp overall.
-  // Outside the range of finite results the correction is left out (inf * 0 and inf - inf
-  // would turn the limits into NaN): underflow gives 0, overflow and +inf give inf, -inf gives 0.
+  // Where 2^t is not finite (it overflows from t = 128 on, the residual can have either sign
+  // there and inf * err + inf would be NaN for a negative one) or the argument is infinite
+  // (the residual is inf - inf) the correction is left out: underflow gives 0, overflow and
+  // +inf give inf, -inf gives 0.
   static BD_DEV float exp(float x) {
-#ifdef BD_LIBM_EXP
-    return ::expf(x);
-#else
     const float L2E = 1.44269504088896340736f;
     float t = x * L2E;
     float e = ::fmaf(x, L2E, -t);
     e = ::fmaf(x, 1.925963033500e-8f, e);
     float p = __builtin_amdgcn_exp2f(t);
-    return ::fabsf(t) < 160.0f ? ::fmaf(p, e * 0.6931471805599453f, p) : p;
-#endif
+    return (::fabsf(t) < 160.0f && __builtin_isfinite(p)) ? ::fmaf(p, e * 0.6931471805599453f, p) : p;
   }
   // log(u) + (x - (u - 1)) / u with u = fl(1 + x): the second term gives back what the
   // rounding of 1 + x dropped, so tiny x return x and nothing cancels.  log(u) is the hardware
   // log2 (1 ulp) times ln 2, the constant's own rounding error folded in.  About 2 ulp.
   static BD_DEV float log1p(float x) {
-#ifdef BD_LIBM_LOG1P
-    return ::log1pf(x);
-#else
     const float u = 1.0f + x;
     const float l2 = __builtin_amdgcn_logf(u);
     float l = l2 * 0.693147182464599609375f;  // ln 2 rounded to float ...
@@ -63,7 +58,6 @@ template <> struct smath<float> {
     l = __builtin_isfinite(l2) ? lr : l;  // log2 of inf or of 0: the correction would be inf - inf
     const float lost = x - (u - 1.0f);
     return (x > 3.0e38f || u == 0.0f) ? l : ::fmaf(lost, __builtin_amdgcn_rcpf(u), l);  // inf and -1 pass through
-#endif
   }
   static BD_DEV float sin(float x) { return ::sinf(x); }
   static BD_DEV float cos(float x) { return ::cosf(x); }
@@ -73,12 +67,8 @@ template <> struct smath<float> {
   // (d = 0 or infinite: 0 * inf) the hardware's own inf or 0 stands
   static BD_DEV float rcp(float d) {
     const float r = __builtin_amdgcn_rcpf(d);
-#ifdef BD_RCP_RAW
-    return r;
-#else
     const float n = ::fmaf(::fmaf(-d, r, 1.0f), r, r);
     return __builtin_isfinite(n) ? n : r;
-#endif
   }
   // the same for 1 <= d <= 2 (or NaN), where the step always has its result
   static BD_DEV float rcp_1to2(float d) {

@@ -33,16 +33,11 @@ template <> struct vec_of<double, 2> {
 // Cache policy of the streaming loads.  Arguments, adjoints and planes are read once per
 // launch, so their loads carry the nontemporal hint: measured on MI355X the backward kernel
 // drops from 101 to 78 us on the HM-LSTM workload (lines that will not be reused no longer
-// displace the freshly written planes from the memory-side cache).  0 = plain loads.
-#ifndef BD_FWD_ARG_NT
-#define BD_FWD_ARG_NT 1
-#endif
-#ifndef BD_BWD_LD_NT
-#define BD_BWD_LD_NT 1
-#endif
-#ifndef BD_REC_ARG_NT
-#define BD_REC_ARG_NT 0
-#endif
+// displace the freshly written planes from the memory-side cache).  The recompute kernels read
+// the arguments the values-only forward launch has just read, and load them plainly.
+constexpr bool kFwdArgNt = true;   // arguments of the plane-writing forward kernel
+constexpr bool kBwdLoadNt = true;  // adjoints and planes in the backward kernels
+constexpr bool kRecArgNt = false;  // arguments in the recompute kernels
 
 template <class T, int VEC, bool NT = false, bool UNALIGNED = false>
 BD_DEV void load_vec(const T *p, T (&x)[VEC]) {
@@ -173,21 +168,16 @@ BD_DEV int eval_op(const T (&a)[Op::N][VEC], int v, Y *y, std::index_sequence<J.
 // only row.  There is deliberately no row loop: with ~30 plane pointers live across a loop
 // the scalar register file overflows, and one short-lived block per row tile measured as
 // fast as longer-lived ones.
-#ifndef BD_FWD_WAVES
-#define BD_FWD_ATTR
-#else
-#define BD_FWD_ATTR __attribute__((amdgpu_waves_per_eu(BD_FWD_WAVES, BD_FWD_WAVES)))
-#endif
 // PARTIALS = false is the values-only launch (no plane requested): the op runs on duals
 // without perturbations, so no derivative is computed, and the arguments are loaded with
 // plain loads (a recompute backward pass reads them again soon).
 // RAGGED: rows of any length (at least VEC) and at any element boundary, see unshift.
 template <class Op, class T, int VEC, bool PARTIALS, bool US, bool RAGGED = false>
-__global__ __launch_bounds__(kBlock) BD_FWD_ATTR void fwd_tiled_kernel(const FwdTiledParams p) {
+__global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams p) {
   constexpr int N = Op::N, M = Op::M;
   constexpr int ND = N - popc(Op::NONDIFF);
   using Y = Dual<T, (!PARTIALS ? 0u : ND >= 32 ? 0xffffffffu : ((1u << ND) - 1u))>;
-  constexpr bool ARG_NT = PARTIALS && BD_FWD_ARG_NT != 0;
+  constexpr bool ARG_NT = PARTIALS && kFwdArgNt;
   constexpr bool ROW_VECTORS_APART = ARG_NT;  // the streaming hint is not for row vectors, see below
   const int ltx = p.log2_tx;
   const int tx = threadIdx.x & ((1 << ltx) - 1);
@@ -412,7 +402,7 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
 // ---- launch wrappers, one pair per op ------------------------------------------------------
 template <class T> struct fwd_type { using type = T; };
 template <class Op, bool PARTIALS, bool US>
-void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
+void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, const Launch &s) {
   const size_t lds = (size_t)p.lds_bytes;
   auto go = [&](auto type_tag, auto vec_tag, auto ragged_tag) {
     using T = typename decltype(type_tag)::type;
@@ -439,7 +429,7 @@ void launch_fwd_tiled_as(int dt, int vec, const FwdTiledParams &p, dim3 grid, hi
 }
 // vec: what the host planned (for views with strides of their own: the widest vector or 1)
 template <class Op>
-hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid, hipStream_t s) {
+hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid, const Launch &s) {
   if (p.uniform_stride) {
     if (p.has_partials)
       launch_fwd_tiled_as<Op, true, true>(dt, vec, p, grid, s);
@@ -456,7 +446,7 @@ hipError_t launch_fwd_tiled(int dt, int vec, const FwdTiledParams &p, dim3 grid,
   return hipGetLastError();
 }
 template <class Op>
-hipError_t launch_fwd_generic(int dt, const FwdGenericParams &p, dim3 grid, hipStream_t s) {
+hipError_t launch_fwd_generic(int dt, const FwdGenericParams &p, dim3 grid, const Launch &s) {
   // the vector form exists for the ops that are built in every variant (the host asks for it only then)
   if constexpr (Op::STRIDED) {
     if (p.vec > 1) {
@@ -479,9 +469,9 @@ hipError_t launch_fwd_generic(int dt, const FwdGenericParams &p, dim3 grid, hipS
 
 // Defines the two extern launch functions of one op in the translation unit that uses it.
 #define BD_DEFINE_OP(OPTYPE, IDENT)                                                                  \
-  hipError_t bd_fwd_tiled_##IDENT(int dt, int vec, const bd::FwdTiledParams &p, dim3 g, hipStream_t s) { \
+  hipError_t bd_fwd_tiled_##IDENT(int dt, int vec, const bd::FwdTiledParams &p, dim3 g, const bd::Launch &s) { \
     return bd::launch_fwd_tiled<OPTYPE>(dt, vec, p, g, s);                                           \
   }                                                                                                  \
-  hipError_t bd_fwd_generic_##IDENT(int dt, const bd::FwdGenericParams &p, dim3 g, hipStream_t s) {  \
+  hipError_t bd_fwd_generic_##IDENT(int dt, const bd::FwdGenericParams &p, dim3 g, const bd::Launch &s) {  \
     return bd::launch_fwd_generic<OPTYPE>(dt, p, g, s);                                              \
   }

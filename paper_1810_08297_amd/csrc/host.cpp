@@ -13,16 +13,17 @@
 
 #include "bcast_dual.h"
 #include "kparams.h"
+#include "launch_types.h"
 
 using namespace bd;
 
 // ---- launchers defined in the kernel translation units ----------------------------------
 #define BD_DECLARE_OP(IDENT)                                                                        \
-  hipError_t bd_fwd_tiled_##IDENT(int, int, const FwdTiledParams &, dim3, hipStream_t);             \
-  hipError_t bd_fwd_generic_##IDENT(int, const FwdGenericParams &, dim3, hipStream_t);
+  hipError_t bd_fwd_tiled_##IDENT(int, int, const FwdTiledParams &, dim3, const Launch &);             \
+  hipError_t bd_fwd_generic_##IDENT(int, const FwdGenericParams &, dim3, const Launch &);
 #define BD_DECLARE_RECOMPUTE(IDENT)                                                                            \
   hipError_t bd_bwdr_tiled_##IDENT(int, int, int, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t,  \
-                                   hipStream_t);                                                               \
+                                   const Launch &);                                                               \
   uint64_t bd_bwdr_pattern_##IDENT();
 #define BD_ARITY_LIST(X) \
   X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18)
@@ -44,23 +45,17 @@ BD_DECLARE_RECOMPUTE(scale_xt)
 BD_DECLARE_RECOMPUTE(pair3)
 BD_DECLARE_RECOMPUTE(linear12)
 BD_DECLARE_RECOMPUTE(elementary4)
-#ifndef BD_NO_ARITY
 #define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K) BD_DECLARE_RECOMPUTE(prod_tanh_##K)
 BD_ARITY_LIST(BD_DECL_ARITY)
-#endif
 
 bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks);
 hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
-                        const BwdTiledParams &p, dim3 grid, size_t lds, hipStream_t s);
-hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, hipStream_t s);
-hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n_blocks, hipStream_t s);
+                        const BwdTiledParams &p, dim3 grid, size_t lds, const Launch &s);
+hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, const Launch &s);
+hipError_t bd_bwd_generic(int dt, int kind, const BwdGenericParams &p, int64_t n_blocks, const Launch &s);
 hipError_t bd_stream_probe(int n_in, const void *const *in, const int64_t *in_stride, int n_out, void *const *out,
                            const int64_t *out_stride, int64_t n_chunks, bool nt_loads, bool reverse, size_t lds_bytes,
-                           hipStream_t s);
-
-namespace bd {
-hipEvent_t g_launch_events[2] = {nullptr, nullptr};  // see launch.h
-}
+                           const Launch &s);
 
 namespace {
 
@@ -70,9 +65,9 @@ struct OpDesc {
   uint32_t nondiff;
   int n_branches;
   const int8_t *alias;  // per plane: own index, index of an identical earlier plane, or -1 (always zero); nullptr: all distinct
-  hipError_t (*tiled)(int, int, const FwdTiledParams &, dim3, hipStream_t);
-  hipError_t (*generic)(int, const FwdGenericParams &, dim3, hipStream_t);
-  hipError_t (*recompute)(int, int, int, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, hipStream_t);  // may be null
+  hipError_t (*tiled)(int, int, const FwdTiledParams &, dim3, const Launch &);
+  hipError_t (*generic)(int, const FwdGenericParams &, dim3, const Launch &);
+  hipError_t (*recompute)(int, int, int, const BwdTiledParams &, const RecomputeArgs &, dim3, size_t, const Launch &);  // may be null
   uint64_t (*recompute_pattern)();
   bool strided;  // the tiled forward kernel is also built for views with row strides of their own
 };
@@ -100,20 +95,50 @@ const OpDesc kOps[] = {
     BD_OP_ROW(pair3, 3, 2, 0u, 1)
     BD_OP_ROW(linear12, 12, 2, (1u << 6) | (1u << 7), 1)
     BD_OP_ROW(elementary4, 1, 4, 0u, 1)
-#ifndef BD_NO_ARITY
     BD_ARITY_LIST(BD_ARITY_ROW)
-#endif
 };
 constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
-// ---- tuning overrides ------------------------------------------------------------------------
-// keys of bcast_dual_set_tuning, in the order the header documents them
-enum TuneKey {
-  kTuneUnused = 0, kTuneBwdRows, kTuneNtStores, kTuneForceGeneric, kTuneMaxVecBytes, kTuneRuntimeTable, kTuneReverse,
-  kTuneProbeNtLoads, kTuneInterleave, kTuneXcdOrder, kTuneColChunks, kTuneFwdLdsKiB, kTuneBwdLdsKiB, kTuneProbeLdsKiB,
-  kTuneNarrowTiles, kTuneRaggedRows, kNumTune
-};
-int g_tune[kNumTune] = {0, 0, 3, 0, 16, 0, 1, 1, 1, 0, 1, 48, 0, 0, 1, 1};
+// ---- per-call options ------------------------------------------------------------------------
+using Opt = bcast_dual_options;
+
+void default_options(Opt &o) {
+  std::memset(&o, 0, sizeof o);
+  o.struct_size = (uint32_t)sizeof(Opt);
+  o.nontemporal_stores = 3;
+  o.max_vector_bytes = 16;
+  o.reverse_tiles = 1;
+  o.interleave_rows = 1;
+  o.col_chunks = 1;
+  o.fwd_lds_kib = 48;
+  o.narrow_tiles = 1;
+  o.ragged_rows = 1;
+  o.probe_nt_loads = 1;
+}
+
+// NULL: the defaults; otherwise a checked copy
+int resolve_options(const bcast_dual_options *in, Opt &o) {
+  if (in == nullptr) {
+    default_options(o);
+    return BCAST_OK;
+  }
+  if (in->struct_size != sizeof(Opt)) return BCAST_ERR_BAD_OPTION;
+  o = *in;
+  auto in_range = [](int32_t v, int32_t lo, int32_t hi) { return v >= lo && v <= hi; };
+  const bool ok = in_range(o.bwd_row_steps, 0, 256) && in_range(o.nontemporal_stores, 0, 3) && in_range(o.force_generic, 0, 1) &&
+                  (o.max_vector_bytes == 4 || o.max_vector_bytes == 8 || o.max_vector_bytes == 16) && in_range(o.runtime_table, 0, 1) &&
+                  in_range(o.reverse_tiles, 0, 1) && in_range(o.interleave_rows, 0, 1) && in_range(o.xcd_order, 0, 1) &&
+                  in_range(o.col_chunks, 0, 1) && in_range(o.fwd_lds_kib, 0, 64) && in_range(o.bwd_lds_kib, 0, 64) &&
+                  in_range(o.narrow_tiles, 0, 1) && in_range(o.ragged_rows, 0, 1) && in_range(o.probe_nt_loads, 0, 1) &&
+                  in_range(o.probe_lds_kib, 0, 64) && ((o.start_event == nullptr) == (o.stop_event == nullptr));
+  return ok ? BCAST_OK : BCAST_ERR_BAD_OPTION;
+}
+
+// stream and (for the call's main-pass kernel only) the caller's event pair
+Launch on_stream(void *stream, const Opt *timed = nullptr) {
+  return Launch{static_cast<hipStream_t>(stream), timed ? static_cast<hipEvent_t>(timed->start_event) : nullptr,
+                timed ? static_cast<hipEvent_t>(timed->stop_event) : nullptr};
+}
 
 // A failed launch is reported with the runtime's own words on stderr: the status code alone
 // cannot say why.
@@ -264,7 +289,12 @@ inline GView gview(const Canon &c, size_t t, void *p) {
 // rows that one block takes in one step (up to 256 when rows are shorter than 1024 elements,
 // else one) span 4 GiB or more of some view: lanes address a row step with 32-bit byte offsets
 // from its first row.  The size of a view as a whole is not limited by this.
-int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es) {
+// Views [0, n_streamed) are the ones a kernel streams row by row with the common stride (the
+// adjoints and planes of a backward call): one of them that repeats a single row (row stride 0
+// with more than one row -- an expanded view) has a row stride of its own like any other and
+// breaks the uniformity.  Views past that index with row stride 0 are row vectors, which the
+// kernels address apart, and are skipped.
+int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es, size_t n_streamed) {
   if (s2.R == 1) return s2.C * es > 0xffffffffULL ? -2 : 0;
   int64_t sr = -1;
   bool uniform = true;
@@ -275,12 +305,15 @@ int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Sha
     if (tv.sc == 0) continue;
     const unsigned __int128 last = ((unsigned __int128)(rows_in_step - 1) * tv.sr + s2.C) * es;
     if (last > 0xffffffffULL) return -2;
-    if (tv.sr == 0) continue;
+    if (tv.sr == 0) {
+      if (t < n_streamed) uniform = false;
+      continue;
+    }
     if (sr < 0) sr = tv.sr;
     else if (sr != tv.sr) uniform = false;
   }
-  if (sr < 0) return 0;  // no such view: the offset is never used
-  return uniform ? sr : -1;
+  if (!uniform) return -1;
+  return sr < 0 ? 0 : sr;  // no such view: the offset is never used
 }
 
 // Rows of 1024 elements and more are normally taken one per block step (common_row_stride counts
@@ -305,10 +338,10 @@ struct Geometry {
 // still costs whole blocks (4096 x 1028 fp32, 257 vectors per row, took 265 us per step against
 // 154 us for 4096 x 1024), so 64 or 128 lanes per row (4 or 2 rows per block step) are taken
 // instead where that pads the row less -- a wavefront still covers 1 KiB of a row.
-void tile_columns(int64_t C, int vec, bool narrow_ok, Geometry &g) {
+void tile_columns(int64_t C, int vec, bool narrow_ok, const Opt &o, Geometry &g) {
   const int64_t units = ceil_div(C, vec);
   g.log2_tx = std::min(8, ilog2_ceil(units));
-  if (units > 256 && narrow_ok && g_tune[kTuneNarrowTiles] != 0) {
+  if (units > 256 && narrow_ok && o.narrow_tiles != 0) {
     const int64_t padded256 = ceil_div(units, 256) * 256;
     int64_t best = padded256;
     int best_l = 8;
@@ -348,9 +381,9 @@ int auto_steps(int64_t R, const Geometry &g, int max_steps) {
 // stride off its boundary; `vw`: what the aligned kernels could take) go to the kernels that read
 // unaligned vectors and finish every row element by element.  Those exist for the widest vector
 // and views with one common row stride; a row must hold one whole vector.
-bool ragged_rows_ok(int vw, bool uniform_stride, const Shape2 &s2, size_t es) {
+bool ragged_rows_ok(int vw, bool uniform_stride, const Shape2 &s2, size_t es, const Opt &o) {
   const int widest = (int)(16 / es);
-  return g_tune[kTuneRaggedRows] != 0 && g_tune[kTuneMaxVecBytes] >= 16 && vw < widest && uniform_stride && s2.C >= widest;
+  return o.ragged_rows != 0 && o.max_vector_bytes >= 16 && vw < widest && uniform_stride && s2.C >= widest;
 }
 
 // Whether a lane of the generic kernels may take `vw` consecutive elements of the innermost dim of
@@ -377,7 +410,7 @@ struct FwdPlan {
 
 int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args, int32_t n_out,
                  const bcast_tensor *outs, const bcast_tensor *partials, const uint8_t *branch_id,
-                 FwdPlan &plan) {
+                 const Opt &o, FwdPlan &plan) {
   if (op_id < 0 || op_id >= kNumOps) return BCAST_ERR_INVALID_OP;
   if (dt != BCAST_F32 && dt != BCAST_F64) return BCAST_ERR_BAD_DTYPE;
   const OpDesc &op = kOps[op_id];
@@ -454,7 +487,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
   plan.info.ndim = c.nd;
   for (int d = 0; d < c.nd; ++d) plan.info.shape[d] = c.shape[d];
 
-  bool tiled = (c.nd <= 2) && !g_tune[kTuneForceGeneric];
+  bool tiled = (c.nd <= 2) && !o.force_generic;
   const Shape2 s2 = shape2(c);
   if (tiled && s2.C > 1) {
     for (int j = 0; j < N && tiled; ++j) {
@@ -464,7 +497,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (size_t t = N; t < v.size() && tiled; ++t)
       if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
   }
-  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es) : -2;
+  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es, 0) : -2;
   // views with row strides of their own: only the ops built for it (the others go generic)
   tiled = tiled && (fwd_sr >= 0 || (fwd_sr == -1 && op.strided));
   plan.tiled = tiled;
@@ -475,7 +508,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     p.R = s2.R;
     p.C = s2.C;
     // widest vector (16 bytes per lane at most) that every vector-accessed view allows
-    int vw = (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es);
+    int vw = (int)(std::max<int>(o.max_vector_bytes, (int)es) / es);
     for (; vw > 1; vw /= 2) {
       bool vec_ok = (s2.C % vw == 0);
       for (size_t t = 0; t < v.size() && vec_ok; ++t) {
@@ -487,16 +520,16 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       if (vec_ok) break;
     }
     if (!p.uniform_stride && vw != (int)(16 / es)) vw = 1;  // those kernels exist for the widest vector and for 1
-    p.ragged = ragged_rows_ok(vw, p.uniform_stride != 0, s2, es);
+    p.ragged = ragged_rows_ok(vw, p.uniform_stride != 0, s2, es, o);
     if (p.ragged) vw = (int)(16 / es);
     Geometry g;
     g.vec = vw;
-    tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), g);
+    tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), o, g);
     if (!tile_rows(s2.R, 1, g)) return BCAST_ERR_LAUNCH_FAILED;  // the forward kernel has no row loop
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
-    p.nt_store = g_tune[kTuneNtStores] & 1;
-    p.xcd_remap = g_tune[kTuneXcdOrder] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+    p.nt_store = o.nontemporal_stores & 1;
+    p.xcd_remap = o.xcd_order != 0 && (g.n_ct * g.n_rt) % 8 == 0;
     p.has_partials = n_planes > 0;
     for (int j = 0; j < N; ++j) {
       const TView tv = tview(c, j, v[j].p);
@@ -524,7 +557,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     int planes_read = 0, planes_written = M;
     for (int j = 0; j < N; ++j) planes_read += !((p.row_invariant | p.col_invariant) >> j & 1u);
     for (int k = 0; k < n_planes; ++k) planes_written += p.part_p[k] != nullptr;
-    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? g_tune[kTuneFwdLdsKiB] * 1024 : 0;
+    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? o.fwd_lds_kib * 1024 : 0;
     if (want_branch) {
       const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
       p.branch_p = static_cast<uint8_t *>(tv.p);
@@ -535,6 +568,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     plan.info.path = 1;
     plan.info.vec = g.vec;
     plan.info.ragged = p.ragged;
+    plan.info.uniform_stride = p.uniform_stride;
     plan.info.tx = 1 << g.log2_tx;
     plan.info.ty = kBlock >> g.log2_tx;
     plan.info.rows_per_block = plan.info.ty * g.steps;
@@ -551,7 +585,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       p.part[k] = (k < n_planes && !dup[k]) ? gview(c, N + M + k, v[N + M + k].p) : GView{nullptr, {0, 0, 0, 0}};
     p.branch = want_branch ? gview(c, v.size(), const_cast<uint8_t *>(branch_id)) : GView{nullptr, {0, 0, 0, 0}};
     // 16-byte vectors along the innermost dim where every view allows them (ops built in every variant)
-    int gv = op.strided && c.nd >= 1 ? (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es) : 1;
+    int gv = op.strided && c.nd >= 1 ? (int)(std::max<int>(o.max_vector_bytes, (int)es) / es) : 1;
     if (gv != (int)(16 / es) || c.shape[c.nd - 1] % gv != 0) gv = 1;
     for (size_t t = 0; t < v.size() && gv > 1; ++t)
       if (v[t].p && !(t >= (size_t)(N + M) && dup[t - N - M]) && !generic_vector_ok(c, t, v[t].p, gv, es, t < (size_t)N)) gv = 1;
@@ -598,7 +632,7 @@ struct BwdPlan {
 // op's n_args arguments are read (and must broadcast to the adjoints' shape), and only the
 // tiled kernels are available.
 int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bcast_tensor *partials,
-                  int32_t n_grads, const bcast_tensor *grads, BwdPlan &plan, const OpDesc *rop = nullptr,
+                  int32_t n_grads, const bcast_tensor *grads, const Opt &o, BwdPlan &plan, const OpDesc *rop = nullptr,
                   const bcast_tensor *args = nullptr) {
   if (dt != BCAST_F32 && dt != BCAST_F64) return BCAST_ERR_BAD_DTYPE;
   if (n_out < 1 || n_out > BCAST_MAX_OUTS || n_grads < 1 || n_grads > BCAST_MAX_ARGS ||
@@ -669,7 +703,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
   const size_t g0 = M + M * ND;
 
   const Shape2 s2 = shape2(c);
-  bool tiled = (c.nd <= 2) && !g_tune[kTuneForceGeneric];
+  bool tiled = (c.nd <= 2) && !o.force_generic;
   // class of each gradient in the 2-D picture
   std::vector<int> cls(ND, kGradSkip);
   if (tiled) {
@@ -697,7 +731,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     std::vector<PView> fullv = v;
     for (int j = 0; j < ND; ++j)
       if (cls[j] != kGradFull) fullv[g0 + j].p = nullptr;
-    bwd_sr = common_row_stride(c, fullv, s2, es);
+    bwd_sr = common_row_stride(c, fullv, s2, es, (size_t)(M + M * ND));
     tiled = bwd_sr >= -1;  // -1: every view addressed with its own row stride
   }
   const bool uniform_stride = bwd_sr >= 0;
@@ -705,7 +739,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
   plan.tiled = tiled;
   if (rop && (!tiled || (!uniform_stride && !rop->strided))) return BCAST_ERR_UNSUPPORTED;
   if (tiled) {
-    int vw = (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es);
+    int vw = (int)(std::max<int>(o.max_vector_bytes, (int)es) / es);
     for (; vw > 1; vw /= 2) {
       bool vec_ok = (s2.C % vw == 0);
       for (size_t t = 0; t < v.size() && vec_ok; ++t) {
@@ -719,12 +753,12 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     }
     if (rop && vw != (int)(16 / es)) vw = 1;  // the recompute kernels exist for the widest vector and for 1
     // rows the vector does not fit: kernels that take the vector unaligned
-    const bool ragged = ragged_rows_ok(vw, uniform_stride, s2, es);
+    const bool ragged = ragged_rows_ok(vw, uniform_stride, s2, es, o);
     if (ragged) vw = (int)(16 / es);
     Geometry g;
     g.vec = vw;
     plan.vec = g.vec;
-    tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), g);
+    tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), o, g);
     bool any_rowwise = false;  // sums over rows: worth many rows per block
     int n_rowsum = 0;
     for (int j = 0; j < ND; ++j) {
@@ -749,7 +783,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         bool same = true, any = false;
         for (int i = 0; i < M; ++i) {
           const PView &a = v[M + i * ND + order[e]], &b = v[M + i * ND + order[src]];
-          same = same && a.p == b.p;
+          same = same && a.p == b.p && (a.p == nullptr || a.stride == b.stride);
           any = any || a.p != nullptr;
         }
         if (same && any) {
@@ -760,7 +794,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // Wide rows with row sums and few planes: a kernel that takes all 2 or 4 column chunks of a
     // row per block finishes the row sums in the main pass (no partial sums, no second pass).
     int chunks = 1;
-    if (!rop && uniform_stride && !any_rowwise && n_rowsum > 0 && g_tune[kTuneBwdRows] == 0 && g_tune[kTuneRuntimeTable] == 0 && g_tune[kTuneColChunks] != 0 &&
+    if (!rop && uniform_stride && !any_rowwise && n_rowsum > 0 && o.bwd_row_steps == 0 && o.runtime_table == 0 && o.col_chunks != 0 &&
         (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
         bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
       chunks = (int)g.n_ct;
@@ -774,7 +808,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
     // So do the kernels that read the gradient table at run time (8192 x 8192 branchy5 forced onto
     // them: 419 us at 128 rows per block, 631 us at 256).
-    const bool class_kernel = !rop && uniform_stride && g_tune[kTuneRuntimeTable] == 0 && g.vec == (int)(16 / es) &&
+    const bool class_kernel = !rop && uniform_stride && o.runtime_table == 0 && g.vec == (int)(16 / es) &&
                               bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
                                                    plan.share, 1);
     // A class kernel that streams many planes per row step is the exception (HM-LSTM update stored
@@ -798,8 +832,8 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       steps_rowwise = std::min<int64_t>(128 / TY, steps_rowwise);
     }
     steps_rowwise = std::max<int64_t>(1, steps_rowwise);
-    int steps = g_tune[kTuneBwdRows] > 0 ? g_tune[kTuneBwdRows] : (any_rowwise ? (int)steps_rowwise : auto_steps(s2.R, g, 4));
-    if (class_kernel && !any_rowwise && g_tune[kTuneBwdRows] == 0) steps = 1;  // signature kernels without row sums have no row loop
+    int steps = o.bwd_row_steps > 0 ? o.bwd_row_steps : (any_rowwise ? (int)steps_rowwise : auto_steps(s2.R, g, 4));
+    if (class_kernel && !any_rowwise && o.bwd_row_steps == 0) steps = 1;  // signature kernels without row sums have no row loop
     if (rop) {
       uint64_t pattern = 0;  // 3 bits per differentiable argument: class + 1
       for (int j = 0; j < ND; ++j) pattern |= (uint64_t)(cls[j] + 1) << (3 * j);
@@ -812,7 +846,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         }
         return t;
       };
-      plan.fixed_pattern = g_tune[kTuneRuntimeTable] != 0 ? 0 : pattern == rop->recompute_pattern() ? 1
+      plan.fixed_pattern = o.runtime_table != 0 ? 0 : pattern == rop->recompute_pattern() ? 1
                            : pattern == transposed(rop->recompute_pattern()) ? 2 : 0;
       // the fixed-pattern kernels take each argument's broadcast form from its gradient's class:
       // the argument's own strides must say the same (an expanded stride-0 view would not)
@@ -826,7 +860,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
       if (ragged && plan.fixed_pattern == 2) plan.fixed_pattern = 0;  // the unaligned form exists for the op's own pattern and the run-time one
       if (plan.fixed_pattern && !any_rowwise) {
-        if (g_tune[kTuneBwdRows] > 1) plan.fixed_pattern = 0;  // an explicit rows-per-block override needs the looping kernel
+        if (o.bwd_row_steps > 1) plan.fixed_pattern = 0;  // an explicit rows-per-block override needs the looping kernel
         else steps = 1;                                  // that kernel has no row loop
       }
     }
@@ -851,10 +885,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.C = s2.C;
       p.log2_tx = g.log2_tx;
       p.steps = g.steps;
-      p.nt_store = (g_tune[kTuneNtStores] >> 1) & 1;
-      p.reverse = g_tune[kTuneReverse];
-      p.interleave = g_tune[kTuneInterleave];
-      p.xcd_remap = g_tune[kTuneXcdOrder] != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+      p.nt_store = (o.nontemporal_stores >> 1) & 1;
+      p.reverse = o.reverse_tiles;
+      p.interleave = o.interleave_rows;
+      p.xcd_remap = o.xcd_order != 0 && (g.n_ct * g.n_rt) % 8 == 0;
       p.col_chunks = chunks;
       p.uniform_stride = uniform_stride;
       p.ragged = ragged;
@@ -882,7 +916,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       cur.lds_col_off = (uint32_t)co;
       cur.lds_all_off = (uint32_t)ao;
       plan.main.push_back(cur);
-      plan.main_lds.push_back(std::max<size_t>(total, (size_t)g_tune[kTuneBwdLdsKiB] * 1024));
+      plan.main_lds.push_back(std::max<size_t>(total, (size_t)o.bwd_lds_kib * 1024));
     };
     reset(cur);
     for (int j : order) {
@@ -942,7 +976,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
     }
-    plan.signature = !rop && uniform_stride && plan.main.size() == 1 && g_tune[kTuneRuntimeTable] == 0 && (int)order.size() * M <= 64 &&
+    plan.signature = !rop && uniform_stride && plan.main.size() == 1 && o.runtime_table == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
                      bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
@@ -960,6 +994,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // the class-specialised kernels exist for the widest vector only
     plan.info.specialized = plan.signature && ((dt == BCAST_F32 && g.vec == 4) || (dt == BCAST_F64 && g.vec == 2));
     plan.info.ragged = ragged;
+    plan.info.uniform_stride = uniform_stride;
   } else {
     size_t gen_ws = 0;  // partial sums of the reductions that are cut into chunks
     for (int j = 0; j < ND; ++j) {
@@ -982,7 +1017,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         reduce |= p.reduced[d] != 0;
         (p.reduced[d] ? p.n_fibre : p.n_kept) *= c.shape[d];
       }
-      int gv = !reduce && c.nd >= 1 ? (int)(std::max<int>(g_tune[kTuneMaxVecBytes], (int)es) / es) : 1;
+      int gv = !reduce && c.nd >= 1 ? (int)(std::max<int>(o.max_vector_bytes, (int)es) / es) : 1;
       if (gv != (int)(16 / es) || c.shape[c.nd - 1] % gv != 0) gv = 1;
       for (int i = 0; i < M && gv > 1; ++i) {
         if (!generic_vector_ok(c, i, v[i].p, gv, es, true)) gv = 1;
@@ -1069,111 +1104,134 @@ int bcast_op_plane_alias(int32_t op_id, int32_t *alias) {
   return BCAST_OK;
 }
 
+void bcast_dual_options_default(bcast_dual_options *opt) {
+  if (opt != nullptr) default_options(*opt);
+}
+
 int bcast_dual_forward_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                             int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
-                            const uint8_t *branch_id, bcast_plan_info *info) {
+                            const uint8_t *branch_id, bcast_plan_info *info, const bcast_dual_options *opt) {
   if (info == nullptr) return BCAST_ERR_NULL_POINTER;
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
   FwdPlan plan;
-  const int rc = plan_forward(op_id, (int)dt, n_args, args, n_out, outs, partials, branch_id, plan);
+  const int rc = plan_forward(op_id, (int)dt, n_args, args, n_out, outs, partials, branch_id, o, plan);
   if (rc == BCAST_OK) *info = plan.info;
   return rc;
 }
 
 int bcast_dual_forward(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                        int32_t n_out, const bcast_tensor *outs, const bcast_tensor *partials,
-                       uint8_t *branch_id, void *stream) {
+                       uint8_t *branch_id, void *stream, const bcast_dual_options *opt) {
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
   FwdPlan plan;
-  const int rc = plan_forward(op_id, (int)dt, n_args, args, n_out, outs, partials, branch_id, plan);
+  const int rc = plan_forward(op_id, (int)dt, n_args, args, n_out, outs, partials, branch_id, o, plan);
   if (rc != BCAST_OK) return rc;
   if (plan.info.path == 0) return BCAST_OK;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t err = plan.tiled ? kOps[op_id].tiled((int)dt, plan.info.vec, plan.tp, plan.grid, s)
-                              : kOps[op_id].generic((int)dt, plan.gp, plan.grid, s);
+  const Launch L = on_stream(stream, &o);
+  hipError_t err = plan.tiled ? kOps[op_id].tiled((int)dt, plan.info.vec, plan.tp, plan.grid, L)
+                              : kOps[op_id].generic((int)dt, plan.gp, plan.grid, L);
   return launch_status(err);
 }
 
 size_t bcast_dual_backward_workspace(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                                      const bcast_tensor *partials, int32_t n_grads,
-                                     const bcast_tensor *grads) {
+                                     const bcast_tensor *grads, const bcast_dual_options *opt) {
+  Opt o;
+  if (resolve_options(opt, o) != BCAST_OK) return 0;
   BwdPlan plan;
-  if (plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, plan) != BCAST_OK) return 0;
+  if (plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, o, plan) != BCAST_OK) return 0;
   return plan.ws_bytes;
 }
 
 int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                              const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
-                             bcast_plan_info *info) {
+                             bcast_plan_info *info, const bcast_dual_options *opt) {
   if (info == nullptr) return BCAST_ERR_NULL_POINTER;
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
   BwdPlan plan;
-  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, plan);
+  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, o, plan);
   if (rc == BCAST_OK) *info = plan.info;
   return rc;
 }
 
-int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
-                        const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
-                        void *workspace, size_t workspace_bytes, void *stream) {
-  BwdPlan plan;
-  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, plan);
-  if (rc != BCAST_OK) return rc;
-  if (plan.info.path == 0) return BCAST_OK;
-  hipStream_t s = static_cast<hipStream_t>(stream);
+// workspace checks shared by the launching calls
+static int check_workspace(const BwdPlan &plan, const void *workspace, size_t workspace_bytes) {
+  if (plan.ws_bytes == 0) return BCAST_OK;
+  if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
+  if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
+  return BCAST_OK;
+}
+
+// enqueue what plan_backward laid out (cached planes; tiled or generic)
+static int run_backward(int dt, BwdPlan &plan, void *workspace, void *stream, const Opt &o) {
+  const Launch timed = on_stream(stream, &o), plain = on_stream(stream);
   if (plan.tiled) {
-    if (plan.ws_bytes > 0) {
-      if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
-      if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
-      if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
-    }
     for (size_t k = 0; k < plan.main.size(); ++k) {
       plan.main[k].ws = static_cast<unsigned char *>(workspace);
-      if (launch_status(bd_bwd_tiled((int)dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
-                       plan.absent, plan.share, plan.main[k], plan.grid, plan.main_lds[k], s)) != BCAST_OK)
+      if (launch_status(bd_bwd_tiled(dt, plan.vec, plan.signature, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3],
+                                     plan.absent, plan.share, plan.main[k], plan.grid, plan.main_lds[k], k == 0 ? timed : plain)) != BCAST_OK)
         return BCAST_ERR_LAUNCH_FAILED;
     }
     if (plan.p2_blocks > 0) {
       plan.p2.ws = static_cast<unsigned char *>(workspace);
-      if (launch_status(bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s)) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
+      if (launch_status(bd_bwd_pass2(dt, plan.p2, plan.p2_blocks, plain)) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
     }
   } else {
-    if (plan.ws_bytes > 0) {
-      if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
-      if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
-      if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
-    }
     for (size_t k = 0; k < plan.generic.size(); ++k) {
       plan.generic[k].second.ws = static_cast<unsigned char *>(workspace);
-      if (launch_status(bd_bwd_generic((int)dt, plan.generic[k].first, plan.generic[k].second, plan.generic_blocks[k], s)) !=
-          BCAST_OK)
+      if (launch_status(bd_bwd_generic(dt, plan.generic[k].first, plan.generic[k].second, plan.generic_blocks[k],
+                                       k == 0 ? timed : plain)) != BCAST_OK)
         return BCAST_ERR_LAUNCH_FAILED;
     }
   }
   return BCAST_OK;
 }
 
+int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                        const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                        void *workspace, size_t workspace_bytes, void *stream, const bcast_dual_options *opt) {
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
+  BwdPlan plan;
+  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, o, plan);
+  if (rc != BCAST_OK) return rc;
+  if (plan.info.path == 0) return BCAST_OK;
+  if (int wrc = check_workspace(plan, workspace, workspace_bytes)) return wrc;
+  return run_backward((int)dt, plan, workspace, stream, o);
+}
+
 static int recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args, int32_t n_out,
-                          const bcast_tensor *adjoints, int32_t n_grads, const bcast_tensor *grads, BwdPlan &plan) {
+                          const bcast_tensor *adjoints, int32_t n_grads, const bcast_tensor *grads, const Opt &o, BwdPlan &plan) {
   if (op_id < 0 || op_id >= kNumOps) return BCAST_ERR_INVALID_OP;
   const OpDesc &op = kOps[op_id];
   if (n_args != op.n_args || n_out != op.n_out || n_grads != op.n_args - __builtin_popcount(op.nondiff))
     return BCAST_ERR_BAD_ARG_COUNT;
   if (op.recompute == nullptr) return BCAST_ERR_UNSUPPORTED;
-  return plan_backward((int)dt, n_out, adjoints, nullptr, n_grads, grads, plan, &op, args);
+  return plan_backward((int)dt, n_out, adjoints, nullptr, n_grads, grads, o, plan, &op, args);
 }
 
 size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                                int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
-                                               const bcast_tensor *grads) {
+                                               const bcast_tensor *grads, const bcast_dual_options *opt) {
+  Opt o;
+  if (resolve_options(opt, o) != BCAST_OK) return 0;
   BwdPlan plan;
-  if (recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, plan) != BCAST_OK) return 0;
+  if (recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, o, plan) != BCAST_OK) return 0;
   return plan.ws_bytes;
 }
 
 int bcast_dual_backward_recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                        int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
-                                       const bcast_tensor *grads, bcast_plan_info *info) {
+                                       const bcast_tensor *grads, bcast_plan_info *info, const bcast_dual_options *opt) {
   if (info == nullptr) return BCAST_ERR_NULL_POINTER;
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
   BwdPlan plan;
-  const int rc = recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, plan);
+  const int rc = recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, o, plan);
   if (rc == BCAST_OK) {
     *info = plan.info;
     info->specialized = plan.info.path == 1 && plan.fixed_pattern ? 1 : 0;
@@ -1183,24 +1241,22 @@ int bcast_dual_backward_recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_
 
 int bcast_dual_backward_recompute(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,
                                   int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
-                                  const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream) {
+                                  const bcast_tensor *grads, void *workspace, size_t workspace_bytes, void *stream,
+                                  const bcast_dual_options *opt) {
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
   BwdPlan plan;
-  const int rc = recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, plan);
+  const int rc = recompute_plan(op_id, dt, n_args, args, n_out, adjoints, n_grads, grads, o, plan);
   if (rc != BCAST_OK) return rc;
   if (plan.info.path == 0 || plan.main.empty()) return BCAST_OK;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (plan.ws_bytes > 0) {
-    if (workspace == nullptr) return BCAST_ERR_NULL_POINTER;
-    if (workspace_bytes < plan.ws_bytes) return BCAST_ERR_WORKSPACE_TOO_SMALL;
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return BCAST_ERR_MISALIGNED;
-  }
+  if (int wrc = check_workspace(plan, workspace, workspace_bytes)) return wrc;
   plan.main[0].ws = static_cast<unsigned char *>(workspace);
   if (launch_status(kOps[op_id].recompute((int)dt, plan.vec, plan.fixed_pattern, plan.main[0], plan.ra, plan.grid,
-                                          plan.main_lds[0], s)) != BCAST_OK)
+                                          plan.main_lds[0], on_stream(stream, &o))) != BCAST_OK)
     return BCAST_ERR_LAUNCH_FAILED;
   if (plan.p2_blocks > 0) {
     plan.p2.ws = static_cast<unsigned char *>(workspace);
-    if (launch_status(bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, s)) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
+    if (launch_status(bd_bwd_pass2((int)dt, plan.p2, plan.p2_blocks, on_stream(stream))) != BCAST_OK) return BCAST_ERR_LAUNCH_FAILED;
   }
   return BCAST_OK;
 }
@@ -1220,28 +1276,9 @@ const char *bcast_status_string(int status) {
     case BCAST_ERR_BAD_STRIDE: return "negative stride or self-overlapping written view";
     case BCAST_ERR_MISALIGNED: return "pointer not aligned";
     case BCAST_ERR_UNSUPPORTED: return "layout or op not supported by this entry point";
+    case BCAST_ERR_BAD_OPTION: return "an option is outside its range, or the options struct has the wrong size";
     default: return "unknown status";
   }
-}
-
-int bcast_dual_set_tuning(int32_t key, int32_t value) {
-  static const int lo[kNumTune] = {0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, hi[kNumTune] = {64, 256, 3, 1, 16, 16, 1, 1, 1, 1, 1, 64, 64, 64, 1, 1};
-  if (key < 0 || key >= kNumTune || value < lo[key] || value > hi[key]) return BCAST_ERR_BAD_ARG_COUNT;
-  if (key == 4 && (value & (value - 1)) != 0) return BCAST_ERR_BAD_ARG_COUNT;
-  g_tune[key] = value;
-  return BCAST_OK;
-}
-int bcast_dual_set_launch_events(void *start_event, void *stop_event) {
-  if ((start_event == nullptr) != (stop_event == nullptr)) return BCAST_ERR_NULL_POINTER;
-  bd::g_launch_events[0] = static_cast<hipEvent_t>(start_event);
-  bd::g_launch_events[1] = static_cast<hipEvent_t>(stop_event);
-  return BCAST_OK;
-}
-
-int bcast_dual_get_tuning(int32_t key, int32_t *value) {
-  if (key < 0 || key >= kNumTune || value == nullptr) return BCAST_ERR_BAD_ARG_COUNT;
-  *value = g_tune[key];
-  return BCAST_OK;
 }
 
 size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offsets) {
@@ -1258,7 +1295,10 @@ size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offs
 }
 
 int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
-                            void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream) {
+                            void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream,
+                            const bcast_dual_options *opt) {
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
   if (n_in < 0 || n_in > 32 || n_out < 0 || n_out > 32 || n_in + n_out == 0) return BCAST_ERR_BAD_ARG_COUNT;
   if ((n_in && (!in || !in_chunk_stride)) || (n_out && (!out || !out_chunk_stride))) return BCAST_ERR_NULL_POINTER;
   if (n_chunks < 0 || n_chunks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
@@ -1271,8 +1311,8 @@ int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *
     if (reinterpret_cast<uintptr_t>(out[k]) % 16 || out_chunk_stride[k] % 4 || out_chunk_stride[k] < 1024) return BCAST_ERR_MISALIGNED;
   }
   if (n_chunks == 0) return BCAST_OK;
-  return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, g_tune[kTuneProbeNtLoads] != 0,
-                                       g_tune[kTuneReverse] != 0, (size_t)g_tune[kTuneProbeLdsKiB] * 1024, static_cast<hipStream_t>(stream)));
+  return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, o.probe_nt_loads != 0,
+                                       o.reverse_tiles != 0, (size_t)o.probe_lds_kib * 1024, on_stream(stream, &o)));
 }
 
 }  // extern "C"

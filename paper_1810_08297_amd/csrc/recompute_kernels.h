@@ -79,9 +79,9 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
       constexpr int form = arg_form<Op, PATTERN>(j);
       avec[j] = LV(T(0));
       if constexpr (form == kFormFull)
-        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0, RAGGED>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
+        avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
       else if constexpr (form == kFormRowVector)
-        avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0, RAGGED>(at<const T>(ra.arg_p[j], col_off));
+        avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(at<const T>(ra.arg_p[j], col_off));
       else if constexpr (form == kFormRuntime) {
         const bool colinv = (ra.col_invariant >> j) & 1u;
         if constexpr (PATTERN != 0) {
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
                                                       : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
           avec[j] = colinv ? LV(T(0)) : x;
         } else if (!colinv) {
-          avec[j] = load_lane_vec<T, VEC, BD_REC_ARG_NT != 0, RAGGED>(((ra.row_invariant >> j) & 1u) ? at<const T>(ra.arg_p[j], col_off)
+          avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(((ra.row_invariant >> j) & 1u) ? at<const T>(ra.arg_p[j], col_off)
                                                                                            : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
         }
       }
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
 // 2 = it has that pattern transposed
 template <class Op>
 hipError_t launch_bwdr_tiled(int dt, int vec, int fixed, const BwdTiledParams &p, const RecomputeArgs &ra,
-                             dim3 grid, size_t lds, hipStream_t s) {
+                             dim3 grid, size_t lds, const Launch &s) {
   constexpr uint64_t PAT = Op::RECOMPUTE_PATTERN, PAT_T = transpose_pattern(Op::RECOMPUTE_PATTERN);
   auto go = [&](auto type_tag, auto vec_tag, auto us_tag) {
     using T = typename decltype(type_tag)::type;
@@ -218,7 +218,7 @@ hipError_t launch_bwdr_tiled(int dt, int vec, int fixed, const BwdTiledParams &p
 
 #define BD_DEFINE_OP_RECOMPUTE(OPTYPE, IDENT)                                                              \
   hipError_t bd_bwdr_tiled_##IDENT(int dt, int vec, int fixed, const bd::BwdTiledParams &p,                \
-                                   const bd::RecomputeArgs &ra, dim3 g, size_t lds, hipStream_t s) {       \
+                                   const bd::RecomputeArgs &ra, dim3 g, size_t lds, const bd::Launch &s) {       \
     return bd::launch_bwdr_tiled<OPTYPE>(dt, vec, fixed, p, ra, g, lds, s);                                \
   }                                                                                                        \
   uint64_t bd_bwdr_pattern_##IDENT() { return OPTYPE::RECOMPUTE_PATTERN; }

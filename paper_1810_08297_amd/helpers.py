@@ -14,14 +14,15 @@ class ForwardBuffers:
     partials: List = field(default_factory=list)   # M*N_d planes, index i*N_d + jd
     branch: Optional[object] = None                # uint8, unified shape
     slab: Optional[object] = None                  # keeps the memory of outs/partials alive
+    options: Optional[B.Options] = None            # bcast_dual_options of every call (None = defaults)
 
     def run(self, args, stream=None):
-        B.bcast_dual_forward(self.op_id, args, self.outs, self.partials, self.branch, stream)
+        B.bcast_dual_forward(self.op_id, args, self.outs, self.partials, self.branch, stream, self.options)
         return self
 
     def prepare(self, args):
         """Marshal the call once; the returned object's launch() only enqueues the kernel."""
-        return B.PreparedForward(self.op_id, args, self.outs, self.partials, self.branch)
+        return B.PreparedForward(self.op_id, args, self.outs, self.partials, self.branch, self.options)
 
 
 @dataclass
@@ -29,13 +30,14 @@ class BackwardBuffers:
     grads: List = field(default_factory=list)      # N_d tensors in their argument's shape
     workspace: Optional[object] = None
     slab: Optional[object] = None
+    options: Optional[B.Options] = None            # the workspace was sized for these
 
     def run(self, adjoints, partials, stream=None):
-        B.bcast_dual_backward(adjoints, partials, self.grads, self.workspace, stream)
+        B.bcast_dual_backward(adjoints, partials, self.grads, self.workspace, stream, self.options)
         return self
 
     def prepare(self, adjoints, partials):
-        return B.PreparedBackward(adjoints, partials, self.grads, self.workspace)
+        return B.PreparedBackward(adjoints, partials, self.grads, self.workspace, self.options)
 
 
 def unified_shape(args):
@@ -86,7 +88,7 @@ def to_slab(tensors, staggered: bool = True):
 
 
 def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: bool = True,
-                  staggered: bool = True, lean: bool = False) -> ForwardBuffers:
+                  staggered: bool = True, lean: bool = False, options: Optional[B.Options] = None) -> ForwardBuffers:
     """``lean``: planes the op table declares identical share one buffer and planes it declares
     zero are left out (None); forward and backward give the same results with fewer bytes moved."""
     import torch
@@ -97,35 +99,38 @@ def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: 
     br = torch.empty(shape, dtype=torch.uint8, device=args[0].device) if want_branch else None
     if not want_partials:
         outs, slab = alloc_planes([shape] * m, args[0].dtype, args[0].device, staggered)
-        return ForwardBuffers(op_id, outs, None, br, slab)
+        return ForwardBuffers(op_id, outs, None, br, slab, options)
     alias = B.bcast_op_plane_alias(op_id) if lean else list(range(m * nd))
     own = [k for k in range(m * nd) if alias[k] == k]
     planes, slab = alloc_planes([shape] * (m + len(own)), args[0].dtype, args[0].device, staggered)
     store = dict(zip(own, planes[m:]))
     parts = [None if alias[k] < 0 else store[alias[k]] for k in range(m * nd)]
-    return ForwardBuffers(op_id, planes[:m], parts, br, slab)
+    return ForwardBuffers(op_id, planes[:m], parts, br, slab, options)
 
 
-def alloc_backward(adjoints, partials, grad_shapes, staggered: bool = True) -> BackwardBuffers:
+def alloc_backward(adjoints, partials, grad_shapes, staggered: bool = True,
+                   options: Optional[B.Options] = None) -> BackwardBuffers:
     import torch
     grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered)
-    nbytes = B.bcast_dual_backward_workspace(adjoints, partials, grads)
+    nbytes = B.bcast_dual_backward_workspace(adjoints, partials, grads, options)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
-    return BackwardBuffers(grads, ws, slab)
+    return BackwardBuffers(grads, ws, slab, options)
 
 
-def alloc_recompute(op_id: int, args, adjoints, grad_shapes, staggered: bool = True) -> BackwardBuffers:
+def alloc_recompute(op_id: int, args, adjoints, grad_shapes, staggered: bool = True,
+                    options: Optional[B.Options] = None) -> BackwardBuffers:
     """Gradient buffers and workspace for bcast_dual_backward_recompute."""
     import torch
     grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered)
-    nbytes = B.bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads)
+    nbytes = B.bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads, options)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
-    return BackwardBuffers(grads, ws, slab)
+    return BackwardBuffers(grads, ws, slab, options)
 
 
 class LaunchTimer:
-    """A pair of HIP events for `bcast_dual_set_launch_events`: `arm()` before the call whose
-    main kernel is to be timed, `ms()` after the stream has been synchronised."""
+    """A pair of HIP events for the `start_event` / `stop_event` fields of bcast_dual_options:
+    pass `timer.options(base)` to the call whose main kernel is to be timed, read `ms()` after
+    the stream has been synchronised."""
 
     _hip = None
 
@@ -138,9 +143,9 @@ class LaunchTimer:
             if LaunchTimer._hip.hipEventCreate(ctypes.byref(ev)) != 0:
                 raise RuntimeError("hipEventCreate failed")
 
-    def arm(self):
-        from . import binding
-        binding.bcast_dual_set_launch_events(self._start.value, self._stop.value)
+    def options(self, base: Optional[B.Options] = None) -> B.Options:
+        """`base` (or the defaults) with this timer's events in it."""
+        return (base or B.Options()).replace(start_event=self._start.value, stop_event=self._stop.value)
 
     def ms(self) -> float:
         import ctypes

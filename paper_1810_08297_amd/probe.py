@@ -31,9 +31,7 @@ def main():
                     help="KiB of unused dynamic LDS per block: limits the blocks per CU (48 = three); 0 = no limit")
     ap.add_argument("--nt-loads", type=int, default=1, help="1 = nontemporal loads (what the kernels use), 0 = plain")
     a = ap.parse_args()
-    P.bcast_dual_set_tuning(7, a.nt_loads)
-    P.bcast_dual_set_tuning(13, a.lds_kib)
-    P.bcast_dual_set_tuning(6, 0)
+    opt_fwd = P.Options(probe_nt_loads=a.nt_loads, probe_lds_kib=a.lds_kib, reverse_tiles=0)  # chunks first to last
     E = a.rows * a.cols
     assert E % 1024 == 0
     chunks = E // 1024
@@ -75,7 +73,7 @@ def main():
     for nin, nout in mixes or ((1, 1), (2, 4), (4, 2), (7, 22), (22, 6), (8, 8), (16, 16), (29, 0), (0, 29)):
         ip, k1 = planes(nin)
         op, k2 = planes(nout)
-        fn = lambda: P.bcast_dual_stream_probe(ip, [1024] * nin, op, [1024] * nout, chunks)
+        fn = lambda: P.bcast_dual_stream_probe(ip, [1024] * nin, op, [1024] * nout, chunks, options=opt_fwd)
         byt = (nin + nout) * E * 4
         t1 = timed(fn)
         t2 = timed(fn, before=lambda: big_b.copy_(big_a))
@@ -94,11 +92,10 @@ def main():
         for it in range(40):
             e0, e1, e2 = ev(), ev(), ev()
             e0.record()
-            P.bcast_dual_set_tuning(6, 0)
-            P.bcast_dual_stream_probe(args, [1024] * 7, outs, [1024] * 22, chunks)
+            P.bcast_dual_stream_probe(args, [1024] * 7, outs, [1024] * 22, chunks, options=opt_fwd)
             e1.record()
-            P.bcast_dual_set_tuning(6, reverse)
-            P.bcast_dual_stream_probe(adj + outs[2:], [1024] * 22, grads, [1024] * 6, chunks)
+            P.bcast_dual_stream_probe(adj + outs[2:], [1024] * 22, grads, [1024] * 6, chunks,
+                                      options=opt_fwd.replace(reverse_tiles=reverse))
             e2.record()
             tf.append((e0, e1))
             tb.append((e1, e2))
@@ -108,7 +105,6 @@ def main():
         print(f"alternating, backward-like {'last to first' if reverse else 'first to last'}: forward-like 7r+22w {f:.1f} us "
               f"{29 * E * 4 / f / 1e3:.1f} GB/s | backward-like 22r+6w {b:.1f} us {28 * E * 4 / b / 1e3:.1f} GB/s | "
               f"step {f + b:.1f} us {57 * E * 4 / (f + b) / 1e3:.1f} GB/s")
-    P.bcast_dual_set_tuning(6, 1)
 
 
 if __name__ == "__main__":

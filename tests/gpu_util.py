@@ -32,17 +32,17 @@ def check_close(got, want, what, rtol=None, atol=None):
                              f"gpu {g[k]!r} oracle {w[k]!r} err {err[k]:.3e} tol {tol[k]:.3e}")
 
 
-def gpu_forward(op, args_dev, want_branch=True, partial_mask=None):
+def gpu_forward(op, args_dev, want_branch=True, partial_mask=None, options=None):
     """Allocate buffers, run the forward kernel.  partial_mask[k] False -> plane k not stored."""
-    fb = P.alloc_forward(op, args_dev, want_branch=want_branch)
+    fb = P.alloc_forward(op, args_dev, want_branch=want_branch, options=options)
     if partial_mask is not None:
         fb.partials = [p if keep else None for p, keep in zip(fb.partials, partial_mask)]
     fb.run(args_dev)
     return fb
 
 
-def gpu_backward(adj_dev, partials_dev, grad_shapes):
-    bb = P.alloc_backward(adj_dev, partials_dev, grad_shapes)
+def gpu_backward(adj_dev, partials_dev, grad_shapes, options=None):
+    bb = P.alloc_backward(adj_dev, partials_dev, grad_shapes, options=options)
     bb.run(adj_dev, partials_dev)
     return bb
 
@@ -52,11 +52,12 @@ def full_rank(a, nd):
     return a.reshape(a.shape + (1,) * (nd - a.ndim))
 
 
-def check_op(op, args_np, adj_np, *, threads=8, view=None, what="", recompute=True):
+def check_op(op, args_np, adj_np, *, threads=8, view=None, what="", recompute=True, options=None):
     """Forward + backward parity of one op on one set of host arrays.
 
     `view(dev_tensor, k)` may re-lay out argument k on the device (strides, transposes)
-    without changing its values.  Returns the GPU buffers for extra checks.
+    without changing its values.  `options`: the bcast_dual_options of every call.  Returns the
+    GPU buffers for extra checks.
     """
     dt = args_np[0].dtype
     nd = max(a.ndim for a in args_np)
@@ -65,7 +66,7 @@ def check_op(op, args_np, adj_np, *, threads=8, view=None, what="", recompute=Tr
     args_dev = [to_dev(a) for a in args_np]
     if view is not None:
         args_dev = [view(t, k) for k, t in enumerate(args_dev)]
-    fb = gpu_forward(op, args_dev)
+    fb = gpu_forward(op, args_dev, options=options)
     torch.cuda.synchronize()
     assert np.array_equal(fb.branch.cpu().numpy(), o_br), f"{what}{op}: branch ids differ"
     for i, (g, w) in enumerate(zip(fb.outs, o_out)):
@@ -76,7 +77,7 @@ def check_op(op, args_np, adj_np, *, threads=8, view=None, what="", recompute=Tr
     didx = oracle.diff_arg_indices(op, len(args_np))
     gshapes = [args_np[j].shape for j in didx]
     adj_dev = [to_dev(a) for a in adj_np]
-    bb = gpu_backward(adj_dev, fb.partials, gshapes)
+    bb = gpu_backward(adj_dev, fb.partials, gshapes, options=options)
     torch.cuda.synchronize()
     gpu_planes = [p.cpu().numpy() for p in fb.partials]
     want = oracle.backward(adj_np, gpu_planes, [full_rank(args_np[j], nd).shape for j in didx], threads=threads)
@@ -85,8 +86,8 @@ def check_op(op, args_np, adj_np, *, threads=8, view=None, what="", recompute=Tr
     # the recompute-in-reverse entry point must give the same gradients without any planes
     if recompute:
         try:
-            rb = P.alloc_recompute(fb.op_id, args_dev, adj_dev, gshapes)
-            P.bcast_dual_backward_recompute(fb.op_id, args_dev, adj_dev, rb.grads, rb.workspace)
+            rb = P.alloc_recompute(fb.op_id, args_dev, adj_dev, gshapes, options=options)
+            P.bcast_dual_backward_recompute(fb.op_id, args_dev, adj_dev, rb.grads, rb.workspace, options=options)
         except P.BcastError as e:
             assert e.status == -12, e  # only "unsupported layout/op" is an acceptable refusal
             assert recompute != "required", f"{what}{op}: recompute refused"

@@ -45,6 +45,7 @@ int main(void) {
   int32_t op = -1, n_args = 0, n_out = 0, n_br = 0; uint32_t mask = 0;
   bcast_tensor args[3], outs[1], parts[3];
   bcast_plan_info info;
+  bcast_dual_options opt;
   char *base = (char *)0;  /* addresses are planned with, never dereferenced */
   int k;
   if (bcast_op_lookup("tanh_xy_b", &op) != BCAST_OK) return 1;
@@ -53,7 +54,10 @@ int main(void) {
   args[2] = view(base + (3 << 24), 512, 1);
   outs[0] = view(base + (4 << 24), 512, 1024);
   for (k = 0; k < 3; ++k) parts[k] = view(base + ((5 + k) << 24), 512, 1024);
-  if (bcast_dual_forward_plan(op, BCAST_F32, 3, args, 1, outs, parts, NULL, &info) != BCAST_OK) return 3;
+  bcast_dual_options_default(&opt);
+  if (opt.struct_size != sizeof opt) return 4;
+  if (bcast_dual_forward_plan(op, BCAST_F32, 3, args, 1, outs, parts, NULL, &info, &opt) != BCAST_OK) return 3;
+  if (bcast_dual_forward_plan(op, BCAST_F32, 3, args, 1, outs, parts, NULL, &info, NULL) != BCAST_OK) return 5;
   printf("%d %d %lld %lld %s\n", (int)info.path, (int)info.vec, (long long)info.shape[0], (long long)info.shape[1],
          bcast_status_string(BCAST_ERR_WORKSPACE_TOO_SMALL));
   return 0;
@@ -128,12 +132,12 @@ def test_forward_validation_errors():
     # the real entry point reports the same errors and launches nothing (no GPU here)
     def real(op_id, a):  # straight through ctypes: the Python wrapper would refuse host tensors first
         return B.lib().bcast_dual_forward(ctypes.c_int32(op_id), ctypes.c_int(0), ctypes.c_int32(len(a)), B._views(a),
-                                          ctypes.c_int32(1), B._views(out), B._views(parts), None, None)
+                                          ctypes.c_int32(1), B._views(out), B._views(parts), None, None, None)
 
     assert real(P.bcast_op_lookup("tanh_xy_b"), [x, y]) == -2
     assert real(999, [x, y, b]) == -1
     rc = B.lib().bcast_dual_forward(ctypes.c_int32(1), ctypes.c_int(7), ctypes.c_int32(3), B._views([x, y, b]),
-                                    ctypes.c_int32(1), B._views(out), B._views(parts), None, None)
+                                    ctypes.c_int32(1), B._views(out), B._views(parts), None, None, None)
     assert rc == -7
 
 
@@ -164,15 +168,11 @@ def test_forward_plan_geometry():
     a, o, p = hm(64, 16)
     info = P.bcast_dual_forward_plan(op, a, o, p)
     assert info["tx"] == 4 and info["ty"] == 64 and info["grid_x"] * info["grid_y"] == 1
-    a, o, p = hm(64, 15)  # odd row length: unaligned vectors and a tail, or (tuning key 15 off) scalar accesses
+    a, o, p = hm(64, 15)  # odd row length: unaligned vectors and a tail, or (option ragged_rows off) scalar accesses
     info = P.bcast_dual_forward_plan(op, a, o, p)
     assert info["vec"] == 4 and info["ragged"] == 1
-    P.bcast_dual_set_tuning(15, 0)
-    try:
-        info = P.bcast_dual_forward_plan(op, a, o, p)
-        assert info["vec"] == 1 and info["ragged"] == 0
-    finally:
-        P.bcast_dual_set_tuning(15, 1)
+    info = P.bcast_dual_forward_plan(op, a, o, p, options=P.Options(ragged_rows=0))
+    assert info["vec"] == 1 and info["ragged"] == 0
     a, o, p = hm(64, 3)  # a row shorter than the vector
     info = P.bcast_dual_forward_plan(op, a, o, p)
     assert info["vec"] == 1 and info["ragged"] == 0
@@ -219,7 +219,7 @@ def test_backward_plan_and_workspace():
     L = B.lib()
     info = B.PlanInfo()
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info), None)
     assert rc == 0
     d = info.as_dict()
     assert d["path"] == 1 and d["vec"] == 4 and d["n_second_pass"] == 3 and d["n_launches"] == 2
@@ -228,21 +228,21 @@ def test_backward_plan_and_workspace():
     assert d["specialized"] == 0  # every plane at one address: not a layout a class-specialised kernel was built for
     distinct = [B.raw_view(4096 + (k + 1) * (1 << 30), (R, C), (C, 1)) for k in range(5)]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(distinct),
-                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info), None)
     assert rc == 0 and info.specialized == 1  # config 4 runs the kernel compiled for full, full, col-sum, row-sum, all-sum
     assert info.rows_per_block == 256 and info.grid_y == 32  # ... as one block per CU
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                                         ctypes.c_int32(5), B._views(grads))
+                                         ctypes.c_int32(5), B._views(grads), None)
     assert ws == 8 * (n_rt * C + R * n_ct + n_rt * n_ct)
     ws64 = L.bcast_dual_backward_workspace(ctypes.c_int(1), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                                           ctypes.c_int32(5), B._views(grads))
+                                           ctypes.c_int32(5), B._views(grads), None)
     assert ws64 > ws
     # too small a workspace is refused before any launch
     rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                               ctypes.c_int32(5), B._views(grads), ctypes.c_void_p(4096), ctypes.c_size_t(64), None)
+                               ctypes.c_int32(5), B._views(grads), ctypes.c_void_p(4096), ctypes.c_size_t(64), None, None)
     assert rc == -8
     rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                               ctypes.c_int32(5), B._views(grads), None, ctypes.c_size_t(0), None)
+                               ctypes.c_int32(5), B._views(grads), None, ctypes.c_size_t(0), None, None)
     assert rc == -3
     # HM-LSTM at batch <= 1024: bias row sums finish inside the main pass
     H, Bt = 4096, 1024
@@ -250,14 +250,14 @@ def test_backward_plan_and_workspace():
     parts = [fake((H, Bt))] * 20
     grads = [fake((H, Bt))] * 6 + [fake((H, 1))] * 4
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
-                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
+                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info), None)
     assert rc == 0 and info.n_launches == 1 and info.n_second_pass == 0
     parts_distinct = [B.raw_view(4096 + (k + 1) * (1 << 30), (H, Bt), (Bt, 1)) for k in range(20)]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts_distinct),
-                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
+                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info), None)
     assert rc == 0 and info.specialized == 1 and info.rows_per_block == 1  # config 3: class-specialised, no row loop
     assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
-                                           ctypes.c_int32(10), B._views(grads)) == 0
+                                           ctypes.c_int32(10), B._views(grads), None) == 0
     # the same update stored [batch x hidden]: bias gradients are sums over rows; the kernel built
     # for that mix streams 22 planes per row step and runs as two blocks per CU, the lean layout
     # (12 distinct planes) as one
@@ -265,13 +265,13 @@ def test_backward_plan_and_workspace():
     parts_t = [B.raw_view(4096 + (k + 1) * (1 << 30), (Bt, H), (H, 1)) for k in range(20)]
     grads_t = [fake((Bt, H))] * 6 + [fake((1, H))] * 4
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj_t), B._views(parts_t),
-                                    ctypes.c_int32(10), B._views(grads_t), ctypes.byref(info))
+                                    ctypes.c_int32(10), B._views(grads_t), ctypes.byref(info), None)
     assert rc == 0 and info.specialized == 1 and info.n_second_pass == 4
     assert info.grid_x == 4 and info.rows_per_block == 8 and info.grid_y == 128
     alias = P.bcast_op_plane_alias(P.bcast_op_lookup("hmlstm_update"))
     lean_t = [None if a < 0 else parts_t[a] for a in alias]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj_t), B._views(lean_t, adj_t[0]),
-                                    ctypes.c_int32(10), B._views(grads_t), ctypes.byref(info))
+                                    ctypes.c_int32(10), B._views(grads_t), ctypes.byref(info), None)
     assert rc == 0 and info.specialized == 1 and info.rows_per_block == 16 and info.grid_y == 64
     # config 1: a 4096-wide row is four column chunks; the kernel built for it takes all four in
     # one block, so the bias gradient's row sums need neither workspace nor second pass
@@ -279,36 +279,130 @@ def test_backward_plan_and_workspace():
     parts1 = [B.raw_view(4096 + (k + 1) * (1 << 30), (4096, 4096), (4096, 1)) for k in range(3)]
     grads1 = [fake((4096, 4096)), fake((4096, 4096)), fake((4096, 1))]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
-                                    ctypes.c_int32(3), B._views(grads1), ctypes.byref(info))
+                                    ctypes.c_int32(3), B._views(grads1), ctypes.byref(info), None)
     assert rc == 0 and info.specialized == 1 and info.n_launches == 1 and info.n_second_pass == 0 and info.grid_x == 1
     assert L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
-                                           ctypes.c_int32(3), B._views(grads1)) == 0
-    P.bcast_dual_set_tuning(10, 0)
-    try:
-        rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
-                                        ctypes.c_int32(3), B._views(grads1), ctypes.byref(info))
-        assert rc == 0 and info.n_launches == 2 and info.n_second_pass == 1 and info.grid_x == 4
-    finally:
-        P.bcast_dual_set_tuning(10, 1)
+                                           ctypes.c_int32(3), B._views(grads1), None) == 0
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj1), B._views(parts1),
+                                    ctypes.c_int32(3), B._views(grads1), ctypes.byref(info), ctypes.byref(P.Options(col_chunks=0)))
+    assert rc == 0 and info.n_launches == 2 and info.n_second_pass == 1 and info.grid_x == 4
     # gradient shape that is neither the adjoint's nor 1
     bad = grads[:9] + [fake((H, 2))]
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(2), B._views(adj), B._views(parts),
-                                    ctypes.c_int32(10), B._views(bad), ctypes.byref(info))
+                                    ctypes.c_int32(10), B._views(bad), ctypes.byref(info), None)
     assert rc == -6
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(5), B._views(adj * 3), B._views(parts),
-                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info))
+                                    ctypes.c_int32(10), B._views(grads), ctypes.byref(info), None)
     assert rc == -2
 
 
-def test_tuning_keys():
-    assert P.bcast_dual_get_tuning(2) == 3 and P.bcast_dual_get_tuning(6) == 1
-    P.bcast_dual_set_tuning(0, 3)
-    assert P.bcast_dual_get_tuning(0) == 3
-    P.bcast_dual_set_tuning(0, 0)
-    with pytest.raises(P.BcastError):
-        P.bcast_dual_set_tuning(0, 1000)
-    with pytest.raises(P.BcastError):
-        P.bcast_dual_set_tuning(99, 0)
+def test_expanded_read_views_break_the_common_row_stride():
+    """A plane or an adjoint that repeats one row over all rows (row stride 0, an expanded view) is a view
+    with a row stride of its own: the kernels built for ONE common row stride would address it with the
+    others' stride and run past its single row.  The plan must not be the uniform-stride one, whichever
+    view it is (the first adjoint is the planner's sort key; any other used to slip through)."""
+    R, C = 512, 1024
+    slot = 1 << 30
+    full = lambda k: B.raw_view(4096 + k * slot, (R, C), (C, 1))
+    rowrep = lambda k: B.raw_view(4096 + k * slot, (R, C), (0, 1))
+    grads3 = [full(10), full(11), B.raw_view(4096 + 12 * slot, (R, 1), (1, 1))]
+
+    def plan(adj, parts, grads):
+        info = B.PlanInfo()
+        rc = B.lib().bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(len(adj)), B._views(adj), B._views(parts),
+                                              ctypes.c_int32(len(grads)), B._views(grads), ctypes.byref(info), None)
+        assert rc == 0
+        return info.as_dict()
+
+    def plan_recompute(op, args, adj, grads):
+        info = B.PlanInfo()
+        rc = B.lib().bcast_dual_backward_recompute_plan(ctypes.c_int32(op), ctypes.c_int(0), ctypes.c_int32(len(args)), B._views(args),
+                                                        ctypes.c_int32(len(adj)), B._views(adj), ctypes.c_int32(len(grads)),
+                                                        B._views(grads), ctypes.byref(info), None)
+        assert rc == 0
+        return info.as_dict()
+
+    base = plan([full(0)], [full(1), full(2), full(3)], grads3)
+    assert base["path"] == 1 and base["specialized"] == 1 and base["uniform_stride"] == 1
+    for k in range(3):  # each plane in turn
+        parts = [full(1), full(2), full(3)]
+        parts[k] = rowrep(1 + k)
+        d = plan([full(0)], parts, grads3)
+        assert d["path"] == 2 or (d["specialized"] == 0 and d["uniform_stride"] == 0), (k, d)
+    # M = 2: a row-expanded SECOND adjoint
+    grads2 = [full(10), full(11)]
+    d = plan([full(0), full(5)], [full(1), full(2), full(3), full(4)], grads2)
+    assert d["path"] == 1 and d["uniform_stride"] == 1
+    d = plan([full(0), rowrep(5)], [full(1), full(2), full(3), full(4)], grads2)
+    assert d["path"] == 2 or (d["specialized"] == 0 and d["uniform_stride"] == 0), d
+    # an expanded plane that starts where a full plane starts is not "the same plane stored once"
+    d = plan([full(0)], [full(1), rowrep(1), full(3)], grads3)
+    assert d["path"] == 2 or (d["specialized"] == 0 and d["uniform_stride"] == 0), d
+    # the recompute entry point streams the adjoints the same way
+    op = P.bcast_op_lookup("pair3")
+    args = [full(20), full(21), full(22)]
+    g3 = [full(10), full(11), full(12)]
+    d = plan_recompute(op, args, [full(0), full(5)], g3)
+    assert d["path"] == 1 and d["uniform_stride"] == 1
+    d = plan_recompute(op, args, [full(0), rowrep(5)], g3)
+    assert d["uniform_stride"] == 0, d
+
+
+def test_options_defaults_ranges_and_struct_size():
+    """NULL options and a default-filled struct plan alike; a field outside its range, a struct of another
+    size or half an event pair are refused with BCAST_ERR_BAD_OPTION before anything else is looked at."""
+    o = P.Options()
+    assert o.struct_size == ctypes.sizeof(P.Options) and (o.nontemporal_stores, o.reverse_tiles, o.fwd_lds_kib) == (3, 1, 48)
+    assert (o.max_vector_bytes, o.interleave_rows, o.col_chunks, o.narrow_tiles, o.ragged_rows, o.probe_nt_loads) == (16, 1, 1, 1, 1, 1)
+    assert (o.bwd_row_steps, o.force_generic, o.runtime_table, o.xcd_order, o.bwd_lds_kib, o.probe_lds_kib) == (0,) * 6
+    assert o.start_event is None and o.stop_event is None
+    x, y, b = _t(64, 2048), _t(64, 2048), _t(64, 1)
+    outs, parts = [_t(64, 2048)], [_t(64, 2048) for _ in range(3)]
+    op = P.bcast_op_lookup("tanh_xy_b")
+    assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts) == P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=o)
+    assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=P.Options(force_generic=1))["path"] == 2
+    bad = [P.Options(bwd_row_steps=257), P.Options(bwd_row_steps=-1), P.Options(nontemporal_stores=4), P.Options(max_vector_bytes=12),
+           P.Options(fwd_lds_kib=65), P.Options(force_generic=2), P.Options(struct_size=ctypes.sizeof(P.Options) - 8),
+           P.Options(start_event=4096), P.Options(stop_event=4096)]
+    for opt in bad:
+        with pytest.raises(P.BcastError) as e:
+            P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=opt)
+        assert e.value.status == -13
+        with pytest.raises(P.BcastError) as e:
+            P.bcast_dual_backward_plan(outs, parts, [x, y, b], options=opt)
+        assert e.value.status == -13
+        assert P.bcast_dual_backward_workspace(outs, parts, [x, y, b], options=opt) == 0
+    assert "option" in P.status_string(-13)
+    with pytest.raises(TypeError):
+        P.Options(no_such_field=1)
+
+
+def test_calls_from_two_threads_with_different_options_do_not_interfere():
+    """The library keeps no state between calls: plans made concurrently from two host threads, each with
+    options of its own, come out as they do alone."""
+    import threading
+    x, y, b = _t(300, 1100), _t(300, 1100), _t(300, 1)
+    outs, parts = [_t(300, 1100)], [_t(300, 1100) for _ in range(3)]
+    op = P.bcast_op_lookup("tanh_xy_b")
+    opts = [P.Options(), P.Options(force_generic=1), P.Options(max_vector_bytes=4), P.Options(bwd_row_steps=5, runtime_table=1)]
+    alone = [(P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=o),
+              P.bcast_dual_backward_plan(outs, parts, [x, y, b], options=o)) for o in opts]
+    assert len({str(a) for a in alone}) == len(opts)  # the options do change the plan
+    wrong = []
+
+    def worker(k):
+        for _ in range(300):
+            got = (P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=opts[k]),
+                   P.bcast_dual_backward_plan(outs, parts, [x, y, b], options=opts[k]))
+            if got != alone[k]:
+                wrong.append(k)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(len(opts))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not wrong
 
 
 def test_plane_alias_table_agrees_with_the_oracle():
@@ -370,11 +464,12 @@ def _rowmajor(ptr, shape):
     return B.raw_view(ptr, shape, list(reversed(st)))
 
 
-def _fwd_plan(op_name, dt, args, outs, parts):
+def _fwd_plan(op_name, dt, args, outs, parts, opt=None):
     info = B.PlanInfo()
     rc = B.lib().bcast_dual_forward_plan(ctypes.c_int32(P.bcast_op_lookup(op_name)), ctypes.c_int(dt),
                                          ctypes.c_int32(len(args)), B._views(args), ctypes.c_int32(len(outs)),
-                                         B._views(outs), B._views(parts), None, ctypes.byref(info))
+                                         B._views(outs), B._views(parts), None, ctypes.byref(info),
+                                         None if opt is None else ctypes.byref(opt))
     return rc, info.as_dict()
 
 
@@ -386,30 +481,27 @@ def test_alignment_and_offset_range_pick_the_access_width_and_the_kernel():
     R, C = 512, 1024
     slot = 1 << 34  # written views must not overlap: every view gets an address range of its own
 
-    def call(dt, shape, shifts=(0, 0), col=None, stride=None):
+    def call(dt, shape, shifts=(0, 0), col=None, stride=None, opt=None):
         mk = (lambda k, sh=0: B.raw_view((k + 1) * slot + sh, shape, stride)) if stride else \
              (lambda k, sh=0: _rowmajor((k + 1) * slot + sh, shape))
         args = [mk(0, shifts[0]), mk(1, shifts[1]), _rowmajor(9 * slot, col or (shape[0], 1))]
-        return _fwd_plan("tanh_xy_b", dt, args, [mk(2)], [mk(3), mk(4), mk(5)])
+        return _fwd_plan("tanh_xy_b", dt, args, [mk(2)], [mk(3), mk(4), mk(5)], opt)
 
     # by default a pointer or row stride off the 16-byte boundary sends the call to the kernels that
-    # take unaligned vectors; with tuning key 15 off the access narrows to what is aligned
+    # take unaligned vectors; with the option ragged_rows off the access narrows to what is aligned
     for ragged_on in (1, 0):
-        B.bcast_dual_set_tuning(15, ragged_on)
-        try:
-            for shift, vec in ((0, 4), (8, 2), (4, 1), (12, 1)):
-                rc, d = call(0, (R, C), (0, shift))
-                assert rc == 0 and d["path"] == 1, (shift, d)
-                assert (d["vec"], d["ragged"]) == ((4, int(shift != 0)) if ragged_on else (vec, 0)), (shift, d)
-            rc, d = call(1, (R, C), (0, 8))  # fp64: 8-byte alignment allows one element per aligned access
-            assert rc == 0 and (d["vec"], d["ragged"]) == ((2, 1) if ragged_on else (1, 0))
-            assert call(0, (R, C), (2, 0))[0] == -11
-            assert call(1, (R, C), (4, 0))[0] == -11
-            # a row stride that is not a multiple of the vector width
-            rc, d = call(0, (R, C), stride=(C + 2, 1))
-            assert rc == 0 and d["path"] == 1 and (d["vec"], d["ragged"]) == ((4, 1) if ragged_on else (2, 0))
-        finally:
-            B.bcast_dual_set_tuning(15, 1)
+        opt = P.Options(ragged_rows=ragged_on)
+        for shift, vec in ((0, 4), (8, 2), (4, 1), (12, 1)):
+            rc, d = call(0, (R, C), (0, shift), opt=opt)
+            assert rc == 0 and d["path"] == 1, (shift, d)
+            assert (d["vec"], d["ragged"]) == ((4, int(shift != 0)) if ragged_on else (vec, 0)), (shift, d)
+        rc, d = call(1, (R, C), (0, 8), opt=opt)  # fp64: 8-byte alignment allows one element per aligned access
+        assert rc == 0 and (d["vec"], d["ragged"]) == ((2, 1) if ragged_on else (1, 0))
+        assert call(0, (R, C), (2, 0), opt=opt)[0] == -11
+        assert call(1, (R, C), (4, 0), opt=opt)[0] == -11
+        # a row stride that is not a multiple of the vector width
+        rc, d = call(0, (R, C), stride=(C + 2, 1), opt=opt)
+        assert rc == 0 and d["path"] == 1 and (d["vec"], d["ragged"]) == ((4, 1) if ragged_on else (2, 0))
     # Planes of any size: a lane's 32-bit byte offset counts from the first row of its block's row
     # step, so only one step of rows has to span less than 4 GiB.  40000 x 30000 fp32 = 4.8 GB per plane:
     rc, d = call(0, (40000, 30000))
@@ -455,12 +547,12 @@ def test_recompute_validation_on_the_host():
     def ws(op_id, a, adj, g, dt=0):
         return L.bcast_dual_backward_recompute_workspace(ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(a)),
                                                          B._views(a), ctypes.c_int32(len(adj)), B._views(adj),
-                                                         ctypes.c_int32(len(g)), B._views(g))
+                                                         ctypes.c_int32(len(g)), B._views(g), None)
 
     def run(op_id, a, adj, g, dt=0):
         return L.bcast_dual_backward_recompute(ctypes.c_int32(op_id), ctypes.c_int(dt), ctypes.c_int32(len(a)), B._views(a),
                                                ctypes.c_int32(len(adj)), B._views(adj), ctypes.c_int32(len(g)),
-                                               B._views(g), None, ctypes.c_size_t(0), None)
+                                               B._views(g), None, ctypes.c_size_t(0), None, None)
 
     assert ws(op, args, [full()], grads) == 0  # row sums of 256 columns finish inside the main pass
     assert run(999, args, [full()], grads) == -1
@@ -479,21 +571,13 @@ def test_recompute_validation_on_the_host():
         adj3, g3 = [full()], [full(), full(), full()]
         return L.bcast_dual_backward_recompute_plan(ctypes.c_int32(pt3), ctypes.c_int(0), ctypes.c_int32(3), B._views(a),
                                                     ctypes.c_int32(1), B._views(adj3), ctypes.c_int32(3), B._views(g3),
-                                                    ctypes.byref(info))
+                                                    ctypes.byref(info), None)
 
     assert plan3([full(), full(), full()]) == 0 and info.path == 1 and info.specialized == 1
     padded = B.raw_view(base + (1 << 36), (R, C), (C + 8, 1))
     assert plan3([padded, full(), full()]) == -12
     # a transposed argument has no tiled layout: refused, the cached-plane path still serves it
     assert run(op, [B.raw_view(base, (R, C), (1, R)), full(), args[2]], [full()], grads) == -12
-
-
-def test_launch_events_argument_check():
-    L = B.lib()
-    assert L.bcast_dual_set_launch_events(None, None) == 0
-    assert L.bcast_dual_set_launch_events(ctypes.c_void_p(4096), None) == -3
-    assert L.bcast_dual_set_launch_events(None, ctypes.c_void_p(4096)) == -3
-    assert L.bcast_dual_set_launch_events(None, None) == 0  # nothing stays armed
 
 
 def test_absurd_extents_and_strides_are_refused():
@@ -524,7 +608,7 @@ def test_recompute_plan_picks_the_fixed_pattern_kernels_at_the_benchmark_shapes(
         info = B.PlanInfo()
         rc = L.bcast_dual_backward_recompute_plan(ctypes.c_int32(op), ctypes.c_int(dt), ctypes.c_int32(len(args)), B._views(args),
                                                   ctypes.c_int32(n_out), B._views(adj), ctypes.c_int32(len(grads)),
-                                                  B._views(grads), ctypes.byref(info))
+                                                  B._views(grads), ctypes.byref(info), None)
         return rc, info.as_dict()
 
     H, Bt = 4096, 1024
@@ -587,14 +671,14 @@ def test_generic_path_plans_chunked_reductions():
     info = B.PlanInfo()
     L = B.lib()
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info))
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info), None)
     # two elementwise launches, three reductions, each cut into chunks and followed by its final kernel
     assert rc == 0 and info.path == 2 and info.n_launches == 2 + 3 + 3
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                                         ctypes.c_int32(5), B._views(grads))
+                                         ctypes.c_int32(5), B._views(grads), None)
     assert 0 < ws < (1 << 22)  # 65536 x 2 partial sums of 8 bytes for the [T x 1 x H] gradient, a few KiB for the others
     rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts), ctypes.c_int32(5),
-                               B._views(grads), None, ctypes.c_size_t(0), None)
+                               B._views(grads), None, ctypes.c_size_t(0), None, None)
     assert rc == -3  # the workspace is asked for before anything is launched
 
 
@@ -617,7 +701,7 @@ def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
         adj, parts = [mk((512, C))], [mk((512, C)) for _ in range(3)]
         grads = [mk((512, C)), mk((512, C)), mk((512, 1))]  # tanh(x*y + b): full, full, row sums
         rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
-                                        ctypes.c_int32(3), B._views(grads), ctypes.byref(info))
+                                        ctypes.c_int32(3), B._views(grads), ctypes.byref(info), None)
         d = info.as_dict()
         assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and d["ragged"] == ragged and d["specialized"] == 1, d
         assert (d["grid_x"], d["n_launches"], d["n_second_pass"]) == (1, 1, 0), d
@@ -629,6 +713,6 @@ def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
         grads = [mk((512, C)), mk((512, C)), mk(shape_b)]
         rc = L.bcast_dual_backward_recompute_plan(ctypes.c_int32(op), ctypes.c_int(0), ctypes.c_int32(3), B._views(args),
                                                   ctypes.c_int32(1), B._views(adj), ctypes.c_int32(3), B._views(grads),
-                                                  ctypes.byref(info))
+                                                  ctypes.byref(info), None)
         d = info.as_dict()
         assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and (d["ragged"], d["specialized"]) == want, (shape_b, C, d)

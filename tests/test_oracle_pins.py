@@ -526,7 +526,7 @@ def test_gradients_match_library_reverse_mode_on_select_form(op):
     torch.autograd in fp64 on the CPU.  Agreement says the branch handling, the broadcast
     reduction and every closed-form partial of the oracle are what plain reverse mode gives."""
     import torch
-    from paper_1810_08297_amd.unfused_baseline import UnfusedStep
+    from select_form import values_and_gradients
     rng = np.random.default_rng(77)
     R, C = 23, 41
     full, row, col, sc = (R, C), (1, C), (R, 1), (1, 1)
@@ -540,7 +540,7 @@ def test_gradients_match_library_reverse_mode_on_select_form(op):
     o_out, o_parts, _ = oracle.forward(op, args, threads=2)
     didx = oracle.diff_arg_indices(op, len(args))
     want = oracle.backward(adj, o_parts, [args[j].shape for j in didx], threads=2)
-    outs, grads = UnfusedStep(op, [torch.from_numpy(a) for a in args], [torch.from_numpy(a) for a in adj]).run()
+    outs, grads = values_and_gradients(op, [torch.from_numpy(a) for a in args], [torch.from_numpy(a) for a in adj])
     for g, w in zip(outs, o_out):
         np.testing.assert_allclose(g.detach().numpy(), w, rtol=1e-13, atol=1e-14)
     for g, w in zip(grads, want):
@@ -677,3 +677,45 @@ def test_sums_with_infinite_and_nan_terms_follow_ieee():
     assert full[0, 3] == np.inf and full[1, 6] == -np.inf and np.isnan(full[2, 5]) and np.isnan(full[3, 1]) and full[4, 0] == 0.25
     assert cols[3] == np.inf and cols[2] == np.inf and cols[6] == -np.inf and np.isnan(cols[5]) and np.isnan(cols[1])
     assert cols[0] == 1.25 and cols[7] == 1.25
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_absent_plane_is_a_plane_of_zeros_also_for_nonfinite_adjoints(dtype):
+    """Table 1's product adjoint x partial with a plane the caller did not store (None): the plane
+    counts as zeros IN EVERY RESPECT, so a call with None and the same call with an explicit plane of
+    zeros give the same bits -- also where the adjoint is infinite or NaN (inf x 0 = NaN, not "no
+    term") -- for full-shape, row-sum, column-sum and all-sum gradients.  A backward that skipped
+    absent planes would return 0 or the other outputs' finite sum there."""
+    rng = np.random.default_rng(5)
+    R, C = 6, 7
+    shapes = [(R, C), (R, 1), (1, C), (1, 1)]
+    for M in (1, 2):
+        adj = [rng.standard_normal((R, C)).astype(dtype) for _ in range(M)]
+        adj[0][1, 2] = np.inf
+        adj[0][3, 4] = -np.inf
+        adj[0][4, 0] = np.nan
+        if M == 2:
+            adj[1][2, 5] = np.inf
+        nd = len(shapes)
+        planes = [rng.standard_normal((R, C)).astype(dtype) for _ in range(M * nd)]
+        for absent_output in range(M):
+            with_none = list(planes)
+            with_zero = list(planes)
+            for jd in range(nd):
+                with_none[absent_output * nd + jd] = None
+                with_zero[absent_output * nd + jd] = np.zeros((R, C), dtype)
+            with np.errstate(all="ignore"):
+                a = oracle.backward(adj, with_none, shapes)
+                b = oracle.backward(adj, with_zero, shapes)
+            for ga, gb, shp in zip(a, b, shapes):
+                assert np.array_equal(ga.view(np.uint32 if dtype == np.float32 else np.uint64),
+                                      gb.view(np.uint32 if dtype == np.float32 else np.uint64)), (M, absent_output, shp)
+            full, rows, cols, tot = a
+            if absent_output == 0:  # the absent planes meet the non-finite adjoints of output 0
+                assert np.isnan(full[1, 2]) and np.isnan(full[3, 4]) and np.isnan(full[4, 0])
+                assert np.isnan(rows[1, 0]) and np.isnan(rows[3, 0]) and np.isnan(rows[4, 0]) and np.isfinite(rows[0, 0])
+                assert np.isnan(cols[0, 2]) and np.isnan(cols[0, 4]) and np.isnan(cols[0, 0]) and np.isfinite(cols[0, 1])
+                assert np.isnan(tot[0, 0])
+                assert np.isfinite(full[0, 0]) and (M == 1 or np.isfinite(rows[5, 0]))
+            else:  # output 1's planes are absent: its one infinite adjoint, at (2, 5), gives NaN there
+                assert np.isnan(full[2, 5]) and np.isnan(rows[2, 0]) and np.isnan(cols[0, 5]) and np.isnan(tot[0, 0])
