@@ -324,7 +324,7 @@ def _config4_every_element(dtype):
     assert float(bb.grads[4].item()) == 0.0
     assert bool((fb.partials[4] == 0).all())
     br = fb.branch.cpu().numpy()
-    assert 0.3 < br.mean() < 0.7  # both branches occur throughout
+    assert 0.01 < br.mean() < 0.99  # both branches occur (how often depends on the drawn threshold t)
 
 
 def test_config4_full_size_fp32():
