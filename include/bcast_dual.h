@@ -18,7 +18,8 @@
  *    allocates no device memory, never synchronises, and enqueues work only on the
  *    `stream` argument (a hipStream_t; NULL = the default stream).
  *  - The library holds no mutable state: every call is a function of its arguments,
- *    and calls from different host threads need no locking.
+ *    and calls from different host threads need no locking.  (The one exception is stated
+ *    where it applies: bcast_dual_backward_noalloc and its per-GPU scratch array.)
  *  - Views: `ndim` dims, extents `shape[d]`, strides `stride[d]` in ELEMENTS (may be
  *    any integer >= 0 that keeps the view inside its buffer; ignored where
  *    shape[d] == 1).  Dims an argument lacks are TRAILING size-1 dims, as in the
@@ -230,6 +231,27 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
 int bcast_dual_backward_plan(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
                              const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
                              bcast_plan_info *info, const bcast_dual_options *opt);
+
+/* ---- backward for callers that cannot allocate --------------------------------------------------
+ * For callers that have no way to provide a workspace: code that runs while a HIP graph is being
+ * captured, tight serving loops, harnesses that forbid hipMalloc.  The same call as
+ * bcast_dual_backward -- same arguments otherwise, same kernels, same results bit for bit -- with the
+ * scratch memory of the second reduction pass taken from an array of BCAST_NOALLOC_SCRATCH_BYTES that
+ * is part of the library's device image (one copy per GPU, held until the process ends) instead of a
+ * caller's buffer.  The call allocates and frees nothing on the device (no hipMalloc / hipFree, no
+ * allocating library routine).
+ *  - A call whose partial sums need more than BCAST_NOALLOC_SCRATCH_BYTES (what
+ *    bcast_dual_backward_workspace reports for the same arguments and options) returns
+ *    BCAST_ERR_WORKSPACE_TOO_SMALL and launches nothing; every benchmark configuration needs under 6 MiB.
+ *  - The device of `stream` must be the current device.  The first call on a device looks the array's
+ *    address up (hipGetSymbolAddress) and keeps it; make that first call outside graph capture.
+ *  - All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *    different threads) race on it and must be serialised by the caller.  Nothing has to be cleared
+ *    between calls: every partial sum the second pass reads is written by the main pass of the same call. */
+#define BCAST_NOALLOC_SCRATCH_BYTES (16u << 20)
+int bcast_dual_backward_noalloc(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                                const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                                void *stream, const bcast_dual_options *opt);
 
 /* ---- backward without cached planes: D applied in the reverse pass (Sec. 2.2.3, last paragraph) ----
  * The other side of the paper's memory/compute trade-off: nothing is kept between the passes

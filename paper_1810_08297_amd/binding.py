@@ -84,7 +84,7 @@ _lib = None
 
 EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info", "bcast_dual_forward",
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
-           "bcast_dual_backward_plan", "bcast_status_string", "bcast_dual_options_default",
+           "bcast_dual_backward_plan", "bcast_dual_backward_noalloc", "bcast_status_string", "bcast_dual_options_default",
            "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
            "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace",
            "bcast_dual_backward_recompute_plan")
@@ -120,6 +120,7 @@ def lib():
             "bcast_dual_backward_workspace": (sz, [cint, i32, T, T, i32, T, O]),
             "bcast_dual_backward": (cint, [cint, i32, T, T, i32, T, vp, sz, vp, O]),
             "bcast_dual_backward_plan": (cint, [cint, i32, T, T, i32, T, PI, O]),
+            "bcast_dual_backward_noalloc": (cint, [cint, i32, T, T, i32, T, vp, O]),
             "bcast_dual_backward_recompute_workspace": (sz, [i32, cint, i32, T, i32, T, i32, T, O]),
             "bcast_dual_backward_recompute": (cint, [i32, cint, i32, T, i32, T, i32, T, vp, sz, vp, O]),
             "bcast_dual_backward_recompute_plan": (cint, [i32, cint, i32, T, i32, T, i32, T, PI, O]),
@@ -299,6 +300,20 @@ def bcast_dual_backward(adjoints, partials, grads, workspace=None, stream=None,
         ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
         ctypes.c_int32(len(grads)), _views(grads), ctypes.c_void_p(ws_ptr), ctypes.c_size_t(ws_bytes),
         _stream_ptr(stream), _opt(options)), "bcast_dual_backward")
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20  # BCAST_NOALLOC_SCRATCH_BYTES
+
+
+def bcast_dual_backward_noalloc(adjoints, partials, grads, stream=None, options: Optional[Options] = None) -> None:
+    """bcast_dual_backward without a workspace argument: the second pass's scratch memory is the
+    library's own static per-GPU array (for callers that cannot allocate)."""
+    _on_device(adjoints, partials, grads)
+    dt = _dtype_code(adjoints[0])
+    a = _views(adjoints)
+    _check(lib().bcast_dual_backward_noalloc(
+        ctypes.c_int(dt), ctypes.c_int32(len(adjoints)), a, _views(partials, a[0]),
+        ctypes.c_int32(len(grads)), _views(grads), _stream_ptr(stream), _opt(options)), "bcast_dual_backward_noalloc")
 
 
 def bcast_dual_backward_plan(adjoints, partials, grads, options: Optional[Options] = None) -> dict:

@@ -3,10 +3,11 @@
 // size-1 dims are virtually copied and arguments are indexed directly, never materialised),
 // launch geometry, and the extern "C" entry points.  Nothing here touches device memory;
 // everything is validated before the first launch.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <array>
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 #include <vector>
@@ -1202,6 +1203,54 @@ int bcast_dual_backward(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoi
   if (plan.info.path == 0) return BCAST_OK;
   if (int wrc = check_workspace(plan, workspace, workspace_bytes)) return wrc;
   return run_backward((int)dt, plan, workspace, stream, o);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// Scratch memory of the second reduction pass as part of the device image: one copy per GPU.  On the
+// host this name only stands for the symbol; the memory's address on a GPU comes from
+// hipGetSymbolAddress, once per device, and that pointer is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[BCAST_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];  // per device, written once (every writer stores the same address)
+
+int scratch_of_current_device(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    std::fprintf(stderr, "bcast_dual: no current device for the static scratch array: %s\n", hipGetErrorString(e));
+    return BCAST_ERR_LAUNCH_FAILED;
+  }
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      std::fprintf(stderr, "bcast_dual: hipGetSymbolAddress of the static scratch array failed on device %d: %s\n", dev,
+                   hipGetErrorString(e));
+      return BCAST_ERR_LAUNCH_FAILED;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return BCAST_OK;
+}
+}  // namespace
+
+int bcast_dual_backward_noalloc(bcast_dtype dt, int32_t n_out, const bcast_tensor *adjoints,
+                                const bcast_tensor *partials, int32_t n_grads, const bcast_tensor *grads,
+                                void *stream, const bcast_dual_options *opt) {
+  Opt o;
+  if (int rc = resolve_options(opt, o)) return rc;
+  BwdPlan plan;
+  const int rc = plan_backward((int)dt, n_out, adjoints, partials, n_grads, grads, o, plan);
+  if (rc != BCAST_OK) return rc;
+  if (plan.info.path == 0) return BCAST_OK;
+  if (plan.ws_bytes > (size_t)BCAST_NOALLOC_SCRATCH_BYTES) return BCAST_ERR_WORKSPACE_TOO_SMALL;
+  void *ws = nullptr;
+  if (plan.ws_bytes > 0)
+    if (int src = scratch_of_current_device(&ws)) return src;
+  return run_backward((int)dt, plan, ws, stream, o);
 }
 
 static int recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args, int32_t n_out,

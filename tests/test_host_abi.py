@@ -716,3 +716,25 @@ def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
                                                   ctypes.byref(info), None)
         d = info.as_dict()
         assert rc == 0 and d["path"] == 1 and d["vec"] == 4 and (d["ragged"], d["specialized"]) == want, (shape_b, C, d)
+
+
+def test_noalloc_backward_refuses_what_exceeds_its_scratch_array():
+    """A call whose partial sums need more than the library's static scratch array holds is refused with
+    BCAST_ERR_WORKSPACE_TOO_SMALL before anything is launched (the views point at addresses never touched)."""
+    R, C = 1 << 15, 1 << 15
+    view = lambda k: B.raw_view(4096 + k * (1 << 34), (R, C), (C, 1))
+    grads = [B.raw_view(4096 + 9 * (1 << 34), (1, C), (C, 1))]
+    opt = P.Options(bwd_row_steps=1)  # one row per block: a partial sum per row and column
+    L = B.lib()
+    need = L.bcast_dual_backward_workspace(ctypes.c_int(1), ctypes.c_int32(1), B._views([view(0)]), B._views([view(1)]),
+                                           ctypes.c_int32(1), B._views(grads), ctypes.byref(opt))
+    assert need > P.NOALLOC_SCRATCH_BYTES
+    rc = L.bcast_dual_backward_noalloc(ctypes.c_int(1), ctypes.c_int32(1), B._views([view(0)]), B._views([view(1)]),
+                                       ctypes.c_int32(1), B._views(grads), None, ctypes.byref(opt))
+    assert rc == -8
+    # validation comes first, as in bcast_dual_backward
+    rc = L.bcast_dual_backward_noalloc(ctypes.c_int(7), ctypes.c_int32(1), B._views([view(0)]), B._views([view(1)]),
+                                       ctypes.c_int32(1), B._views(grads), None, None)
+    assert rc == -7
+    header = open(os.path.join(ROOT, "include", "bcast_dual.h")).read()
+    assert f"#define BCAST_NOALLOC_SCRATCH_BYTES ({P.NOALLOC_SCRATCH_BYTES >> 20}u << 20)" in header
