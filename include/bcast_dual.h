@@ -111,8 +111,12 @@ typedef struct {
   int32_t max_vector_bytes; /* widest vector access per lane: 16 (default), 8 or 4 */
   int32_t runtime_table;    /* 1 = never a backward / recompute kernel compiled for the call's mix of gradient
                                classes, always the one that reads the gradient table at run time (testing); default 0 */
-  int32_t reverse_tiles;    /* 1 (default) = the tiled backward kernels walk their tiles last to first, starting with
-                               the planes the forward kernel wrote last, which the memory-side cache may still hold */
+  int32_t reverse_tiles;    /* order in which the blocks of the tiled backward kernels take their tiles: 0 = first to
+                               last; 1 = last to first, starting with the planes the forward kernel wrote last, which
+                               the memory-side cache may still hold; 2 (default) = last to first in groups of eight
+                               blocks, each block keeping its place within its group -- the hardware deals consecutive
+                               blocks round-robin to the 8 XCDs, so a tile then stays on the XCD (its L2, its
+                               address-translation cache) that wrote it in the forward kernel */
   int32_t interleave_rows;  /* rows of a backward block that takes several row steps: 1 (default) = every n-th row
                                step of the problem (the resident blocks sweep one contiguous band of each plane
                                together), 0 = one contiguous run of rows per block */
@@ -125,7 +129,8 @@ typedef struct {
                                elements finish in the main pass; 0 = one chunk per block */
   int32_t fwd_lds_kib;      /* KiB of (unused) dynamic LDS the forward kernel requests per block when it writes at
                                least 2.5 planes for every plane it reads, which limits the blocks resident on a CU
-                               (160 KiB each): 48 (default) = three, 0 = no limit; 0..64 */
+                               (160 KiB each): -1 (default) = automatic (48 = three blocks for fp32, 40 = four for
+                               fp64), 0 = no limit; -1..64 */
   int32_t bwd_lds_kib;      /* the same for the main backward and recompute kernels, on top of what they need
                                (default 0: measured no gain); 0..64 */
   int32_t narrow_tiles;     /* 1 (default) = rows longer than 1024 elements may be tiled with 64 or 128 lanes per
@@ -297,7 +302,7 @@ size_t bcast_dual_slab_layout(size_t plane_bytes, int32_t n_planes, size_t *offs
  * one buffer).  in/out and the stride arrays are HOST arrays (at most 32 entries each) of
  * DEVICE pointers (16-byte aligned) and strides (multiples of 4; output strides >= 1024).
  * n_in = 1, n_out = 1 is a plain copy, used to scale profiler byte counters.  The options
- * reverse_tiles (chunk order), probe_nt_loads and probe_lds_kib apply. */
+ * reverse_tiles (1 = chunks last to first, else first to last), probe_nt_loads and probe_lds_kib apply. */
 int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *in_chunk_stride, int32_t n_out,
                             void *const *out, const int64_t *out_chunk_stride, int64_t n_chunks, void *stream,
                             const bcast_dual_options *opt);

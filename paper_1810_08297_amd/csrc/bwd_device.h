@@ -164,7 +164,15 @@ struct BwdGeom {
     // the forward kernel wrote last are the ones still held by the memory-side cache.
     bid = blockIdx.x;
     if (p.xcd_remap) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);
-    if (p.reverse) bid = gridDim.x - 1 - bid;
+    if (p.reverse == 1) {
+      bid = gridDim.x - 1 - bid;
+    } else if (p.reverse == 2) {
+      // last to first in groups of eight, each block keeping its place within its group: the
+      // hardware deals consecutive blocks round-robin to the 8 XCDs, so a tile then stays on the
+      // XCD (its L2, its address-translation cache) whose forward block wrote it
+      const uint32_t full = gridDim.x & ~7u;
+      if (bid < full) bid = full - 8u - (bid & ~7u) + (bid & 7u);
+    }
     rt = bid / nct;
     ct = bid - rt * nct;
     // a block covers p.col_chunks consecutive column chunks of TX * VEC columns (1 unless the

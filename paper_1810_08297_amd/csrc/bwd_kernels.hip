@@ -27,7 +27,10 @@ constexpr int share_src(uint64_t share, int e) {
   const int s = (int)((share >> (4 * e)) & 15u);
   return s ? s - 1 : e;
 }
-template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, int CU>
+// US: every streamed view shares one row stride (the usual case); the kernels for the HM-LSTM mixes are
+// also built with US = false, where each adjoint, plane and gradient is addressed with its own -- planes
+// interleaved by row in one slab, gradients written into slices of a wider buffer.
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, int CU, bool US = true>
 __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
   using AT = acc_traits<T>;
   using A = typename AT::type;
@@ -54,20 +57,22 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     constexpr bool EDGE = decltype(edge_tag)::value;
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
-    const RowStep<T, true> rs = g.template step<true>(p, k);
+    const RowStep<T, US> rs = g.template step<US>(p, k);
     T adj[CU][M][VEC], P[CU][NE][M][VEC];
     bool valid[CU];
     int shift[CU];    // ragged rows: by how many columns the row's last lane moves its loads to the left
-    uint32_t off[CU];  // the lane's byte offset in column chunk q (chunk 0's already holds its shift)
+    uint32_t chunk[CU];  // byte offset of column chunk q from the lane's own place in chunk 0 (which already holds chunk 0's shift)
+    // a view's byte offset for this lane in chunk q: one value for all views, or from the view's own row stride
+    auto off = [&](int64_t sr, int q) { return rs.lane(sr) + chunk[q]; };
 #pragma unroll
     for (int q = 0; q < CU; ++q) {  // every load of the row step is issued before the first use
       const int64_t cq = g.c0 + (int64_t)q * g.chunk_cols;
       valid[q] = r < p.R && cq < p.C;
       shift[q] = q == 0 ? g.shift : (EDGE && p.ragged && valid[q] && cq + VEC > p.C ? (int)(cq + VEC - p.C) : 0);
-      off[q] = rs.lane_uniform + (uint32_t)q * g.chunk_bytes - (q == 0 ? 0u : (uint32_t)shift[q] * (uint32_t)sizeof(T));
-      const uint32_t o = off[q];
+      chunk[q] = (uint32_t)q * g.chunk_bytes - (q == 0 ? 0u : (uint32_t)shift[q] * (uint32_t)sizeof(T));
 #pragma unroll
-      for (int i = 0; i < M; ++i) load_plane<T, VEC, EDGE, true>(rs.base(p.adj[i].p, 0), o, valid[q], adj[q][i], shift[q]);
+      for (int i = 0; i < M; ++i)
+        load_plane<T, VEC, EDGE, true>(rs.base(p.adj[i].p, p.adj[i].sr), off(p.adj[i].sr, q), valid[q], adj[q][i], shift[q]);
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) P[q][e][i][v] = T(0);
           } else {
-            load_plane<T, VEC, EDGE, true>(rs.base(p.e[e].P[i].p, 0), o, valid[q], P[q][e][i], shift[q]);
+            load_plane<T, VEC, EDGE, true>(rs.base(p.e[e].P[i].p, p.e[e].P[i].sr), off(p.e[e].P[i].sr, q), valid[q], P[q][e][i], shift[q]);
           }
         }
     }
@@ -86,7 +91,8 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     for (int q = 0; q < CU; ++q)
 #pragma unroll
       for (int e = 0; e < NF; ++e)
-        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g.p, 0), adj[q], P[q][share_src(SHARE, e)], off[q], valid[q], nt, shift[q]);
+        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g.p, p.e[e].g.sr), adj[q], P[q][share_src(SHARE, e)], off(p.e[e].g.sr, q), valid[q], nt,
+                                          shift[q]);
 #pragma unroll
     for (int e = NF; e < NF + NR; ++e) {
       A rs = AT::zero();
@@ -443,30 +449,34 @@ using namespace bd;
 #define BD_HM_LEAN ((1ull << (2 * 2 + 0)) | (1ull << (5 * 2 + 0)) | (1ull << (8 * 2 + 0)))
 // ... and each bias gradient (entries 6..9) reads the planes of its gate (entries 0..3)
 #define BD_HM_SHARE ((1ull << (4 * 6)) | (2ull << (4 * 7)) | (3ull << (4 * 8)) | (4ull << (4 * 9)))
-// Last field: 1 = also built for 2 and 4 column chunks per row step.
+// Last two fields: 1 = also built for 2 and 4 column chunks per row step; 1 = also built for views with row
+// strides of their own.
 #define BD_SIGNATURES(X)                                                  \
-  X(2, 6, 4, 0, 0, 0ull, 0ull, 0) /* HM-LSTM update, per-row biases */    \
-  X(2, 6, 4, 0, 0, BD_HM_LEAN, BD_HM_SHARE, 0)                            \
-  X(2, 6, 0, 4, 0, 0ull, 0ull, 0) /* HM-LSTM update stored [batch x hidden]: per-column biases */ \
-  X(2, 6, 0, 4, 0, BD_HM_LEAN, BD_HM_SHARE, 0)                            \
-  X(1, 2, 1, 0, 0, 0ull, 0ull, 1) /* tanh(x*y + b) */                     \
-  X(1, 2, 1, 1, 1, 0ull, 0ull, 0) /* branchy5 */                          \
-  X(1, 2, 1, 1, 1, 1ull << 4, 0ull, 0) /* branchy5 without the always-zero plane of t */ \
-  X(1, 4, 0, 0, 0, 0ull, 0ull, 0) /* six-argument cell update */          \
-  X(1, 1, 0, 0, 0, 0ull, 0ull, 0) X(1, 2, 0, 0, 0, 0ull, 0ull, 0) X(1, 3, 0, 0, 0, 0ull, 0ull, 0) \
-  X(1, 5, 0, 0, 0, 0ull, 0ull, 0) X(1, 8, 0, 0, 0, 0ull, 0ull, 0)
+  X(2, 6, 4, 0, 0, 0ull, 0ull, 0, 1) /* HM-LSTM update, per-row biases */ \
+  X(2, 6, 4, 0, 0, BD_HM_LEAN, BD_HM_SHARE, 0, 1)                         \
+  X(2, 6, 0, 4, 0, 0ull, 0ull, 0, 0) /* HM-LSTM update stored [batch x hidden]: per-column biases */ \
+  X(2, 6, 0, 4, 0, BD_HM_LEAN, BD_HM_SHARE, 0, 0)                         \
+  X(1, 2, 1, 0, 0, 0ull, 0ull, 1, 0) /* tanh(x*y + b) */                  \
+  X(1, 2, 1, 1, 1, 0ull, 0ull, 0, 0) /* branchy5 */                       \
+  X(1, 2, 1, 1, 1, 1ull << 4, 0ull, 0, 0) /* branchy5 without the always-zero plane of t */ \
+  X(1, 4, 0, 0, 0, 0ull, 0ull, 0, 0) /* six-argument cell update */       \
+  X(1, 1, 0, 0, 0, 0ull, 0ull, 0, 0) X(1, 2, 0, 0, 0, 0ull, 0ull, 0, 0) X(1, 3, 0, 0, 0, 0ull, 0ull, 0, 0) \
+  X(1, 5, 0, 0, 0, 0ull, 0ull, 0, 0) X(1, 8, 0, 0, 0, 0ull, 0ull, 0, 0)
 
-// chunks: column chunks per row step the caller wants (1, 2 or 4)
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks) {
-#define BD_SIG_TEST(m, f, r, c, a, ab, sh, wide) \
-  if (M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh) && (chunks == 1 || wide)) return true;
+// chunks: column chunks per row step the caller wants (1, 2 or 4); strided: for views with row strides of their own
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks, bool strided) {
+#define BD_SIG_TEST(m, f, r, c, a, ab, sh, wide, str) \
+  if (M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh) && (chunks == 1 || wide) && (!strided || str)) return true;
   BD_SIGNATURES(BD_SIG_TEST)
 #undef BD_SIG_TEST
   return false;
 }
 
-template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, bool WIDE>
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, bool WIDE, bool STRIDED>
 static void launch_sig(int chunks, const BwdTiledParams &p, dim3 grid, size_t lds, const Launch &s) {
+  if constexpr (STRIDED) {
+    if (!p.uniform_stride) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 1, false>), grid, dim3(kBlock), lds, s, p);
+  }
   if constexpr (WIDE) {
     if (chunks == 4) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 4>), grid, dim3(kBlock), lds, s, p);
     if (chunks == 2) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 2>), grid, dim3(kBlock), lds, s, p);
@@ -479,13 +489,13 @@ hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc,
   const bool widest = (dt == BCAST_F32 && vec == 4) || (dt == BCAST_F64 && vec == 2);
   const int chunks = p.col_chunks > 0 ? p.col_chunks : 1;
   if (p.ragged && (!widest || !p.uniform_stride)) return hipErrorInvalidValue;  // not planned that way
-  if (signature && widest && p.uniform_stride) {  // the kernels compiled per mix assume one row stride
-#define BD_SIG_GO(m, f, r, c, a, ab, sh, wide)                                                               \
-  if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh)) {             \
+  if (signature && widest) {  // (the host asks for it with views of differing row strides only where such a kernel was built)
+#define BD_SIG_GO(m, f, r, c, a, ab, sh, wide, str)                                                          \
+  if (p.M == m && nf == f && nr == r && nc == c && na == a && absent == (ab) && share == (sh) && (p.uniform_stride || str)) { \
     if (dt == BCAST_F32)                                                                                     \
-      launch_sig<float, 4, m, f, r, c, a, (ab), (sh), (wide) != 0>(chunks, p, grid, lds, s);                 \
+      launch_sig<float, 4, m, f, r, c, a, (ab), (sh), (wide) != 0, (str) != 0>(chunks, p, grid, lds, s);     \
     else                                                                                                     \
-      launch_sig<double, 2, m, f, r, c, a, (ab), (sh), (wide) != 0>(chunks, p, grid, lds, s);                \
+      launch_sig<double, 2, m, f, r, c, a, (ab), (sh), (wide) != 0, (str) != 0>(chunks, p, grid, lds, s);    \
     return hipGetLastError();                                                                                \
   }
     BD_SIGNATURES(BD_SIG_GO)

@@ -49,7 +49,7 @@ BD_DECLARE_RECOMPUTE(elementary4)
 #define BD_DECL_ARITY(K) BD_DECLARE_OP(prod_tanh_##K) BD_DECLARE_RECOMPUTE(prod_tanh_##K)
 BD_ARITY_LIST(BD_DECL_ARITY)
 
-bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks);
+bool bd_bwd_has_signature(int M, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share, int chunks, bool strided);
 hipError_t bd_bwd_tiled(int dt, int vec, bool signature, int nf, int nr, int nc, int na, uint64_t absent, uint64_t share,
                         const BwdTiledParams &p, dim3 grid, size_t lds, const Launch &s);
 hipError_t bd_bwd_pass2(int dt, const Pass2Params &p, int64_t n_blocks, const Launch &s);
@@ -108,10 +108,10 @@ void default_options(Opt &o) {
   o.struct_size = (uint32_t)sizeof(Opt);
   o.nontemporal_stores = 3;
   o.max_vector_bytes = 16;
-  o.reverse_tiles = 1;
+  o.reverse_tiles = 2;
   o.interleave_rows = 1;
   o.col_chunks = 1;
-  o.fwd_lds_kib = 48;
+  o.fwd_lds_kib = -1;
   o.narrow_tiles = 1;
   o.ragged_rows = 1;
   o.probe_nt_loads = 1;
@@ -128,8 +128,8 @@ int resolve_options(const bcast_dual_options *in, Opt &o) {
   auto in_range = [](int32_t v, int32_t lo, int32_t hi) { return v >= lo && v <= hi; };
   const bool ok = in_range(o.bwd_row_steps, 0, 256) && in_range(o.nontemporal_stores, 0, 3) && in_range(o.force_generic, 0, 1) &&
                   (o.max_vector_bytes == 4 || o.max_vector_bytes == 8 || o.max_vector_bytes == 16) && in_range(o.runtime_table, 0, 1) &&
-                  in_range(o.reverse_tiles, 0, 1) && in_range(o.interleave_rows, 0, 1) && in_range(o.xcd_order, 0, 1) &&
-                  in_range(o.col_chunks, 0, 1) && in_range(o.fwd_lds_kib, 0, 64) && in_range(o.bwd_lds_kib, 0, 64) &&
+                  in_range(o.reverse_tiles, 0, 2) && in_range(o.interleave_rows, 0, 1) && in_range(o.xcd_order, 0, 1) &&
+                  in_range(o.col_chunks, 0, 1) && in_range(o.fwd_lds_kib, -1, 64) && in_range(o.bwd_lds_kib, 0, 64) &&
                   in_range(o.narrow_tiles, 0, 1) && in_range(o.ragged_rows, 0, 1) && in_range(o.probe_nt_loads, 0, 1) &&
                   in_range(o.probe_lds_kib, 0, 64) && ((o.start_event == nullptr) == (o.stop_event == nullptr));
   return ok ? BCAST_OK : BCAST_ERR_BAD_OPTION;
@@ -558,7 +558,9 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     int planes_read = 0, planes_written = M;
     for (int j = 0; j < N; ++j) planes_read += !((p.row_invariant | p.col_invariant) >> j & 1u);
     for (int k = 0; k < n_planes; ++k) planes_written += p.part_p[k] != nullptr;
-    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? o.fwd_lds_kib * 1024 : 0;
+    // fp64 runs best with four blocks (cfg 4 in fp64: 722 against 750 us with three, 770 with no limit).
+    const int lds_kib = o.fwd_lds_kib >= 0 ? o.fwd_lds_kib : (es == 8 ? 40 : 48);
+    p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? lds_kib * 1024 : 0;
     if (want_branch) {
       const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
       p.branch_p = static_cast<uint8_t *>(tv.p);
@@ -797,7 +799,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     int chunks = 1;
     if (!rop && uniform_stride && !any_rowwise && n_rowsum > 0 && o.bwd_row_steps == 0 && o.runtime_table == 0 && o.col_chunks != 0 &&
         (g.n_ct == 2 || g.n_ct == 4) && g.vec == (int)(16 / es) &&
-        bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct)) {
+        bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, (int)g.n_ct, false)) {
       chunks = (int)g.n_ct;
       g.n_ct = 1;
     }
@@ -809,9 +811,9 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // (same problem: 314 us at 128 rows per block, 478 us at 256).
     // So do the kernels that read the gradient table at run time (8192 x 8192 branchy5 forced onto
     // them: 419 us at 128 rows per block, 631 us at 256).
-    const bool class_kernel = !rop && uniform_stride && o.runtime_table == 0 && g.vec == (int)(16 / es) &&
+    const bool class_kernel = !rop && o.runtime_table == 0 && g.vec == (int)(16 / es) &&
                               bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent,
-                                                   plan.share, 1);
+                                                   plan.share, 1, !uniform_stride);
     // A class kernel that streams many planes per row step is the exception (HM-LSTM update stored
     // [batch x hidden], 2 adjoints + 20 planes: 8192 x 4096 runs 733 us at two blocks per CU, 995 us at
     // one; with its 10 distinct planes, 509 us and 457 us).
@@ -977,9 +979,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
     }
-    plan.signature = !rop && uniform_stride && plan.main.size() == 1 && o.runtime_table == 0 && (int)order.size() * M <= 64 &&
+    plan.signature = !rop && plan.main.size() == 1 && o.runtime_table == 0 && (int)order.size() * M <= 64 &&
                      (any_rowwise || g.steps == 1) &&  // those kernels loop over rows only when they sum over rows
-                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks);
+                     bd_bwd_has_signature(M, plan.n_cls[0], plan.n_cls[1], plan.n_cls[2], plan.n_cls[3], plan.absent, plan.share, chunks,
+                                          !uniform_stride);
     if (p2_blocks > 0x7fffffffLL) return BCAST_ERR_LAUNCH_FAILED;
     plan.p2_blocks = p2_blocks;
     plan.ws_bytes = ws;
@@ -1361,7 +1364,7 @@ int bcast_dual_stream_probe(int32_t n_in, const void *const *in, const int64_t *
   }
   if (n_chunks == 0) return BCAST_OK;
   return launch_status(bd_stream_probe(n_in, in, in_chunk_stride, n_out, out, out_chunk_stride, n_chunks, o.probe_nt_loads != 0,
-                                       o.reverse_tiles != 0, (size_t)o.probe_lds_kib * 1024, on_stream(stream, &o)));
+                                       o.reverse_tiles == 1, (size_t)o.probe_lds_kib * 1024, on_stream(stream, &o)));
 }
 
 }  // extern "C"

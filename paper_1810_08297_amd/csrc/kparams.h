@@ -93,7 +93,7 @@ struct BwdTiledParams {
   int64_t R, C;
   int32_t log2_tx, steps, nt_store, M;
   int32_t n_entries;
-  int32_t reverse;  // 1: blocks walk the tiles from the last to the first
+  int32_t reverse;  // 1: blocks walk the tiles from the last to the first; 2: the same in groups of eight blocks, each keeping its place in its group
   int32_t xcd_remap;   // as in FwdTiledParams
   int32_t uniform_stride;  // 0: the full-shape views have row strides of their own (TView::sr of each)
   int32_t col_chunks;  // column chunks of TX * VEC columns a block covers per row step (0 or 1: one)

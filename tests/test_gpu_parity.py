@@ -266,7 +266,7 @@ def test_tuned_launch_shapes_agree():
     give results within tolerance of the oracle."""
     args, adj = small_args("branchy5", 333, 1100, np.float32, seed=6)
     for bwd_steps in (1, 7, 256):
-        for interleave, reverse in ((1, 1), (0, 0)):
+        for interleave, reverse in ((1, 1), (0, 0), (1, 2), (0, 2)):
             check_op("branchy5", args, adj, what=f"[row steps {bwd_steps} interleave {interleave} reverse {reverse}] ",
                      options=P.Options(bwd_row_steps=bwd_steps, interleave_rows=interleave, reverse_tiles=reverse))
     first_to_last = P.Options(interleave_rows=0, reverse_tiles=0)

@@ -352,7 +352,7 @@ def test_options_defaults_ranges_and_struct_size():
     """NULL options and a default-filled struct plan alike; a field outside its range, a struct of another
     size or half an event pair are refused with BCAST_ERR_BAD_OPTION before anything else is looked at."""
     o = P.Options()
-    assert o.struct_size == ctypes.sizeof(P.Options) and (o.nontemporal_stores, o.reverse_tiles, o.fwd_lds_kib) == (3, 1, 48)
+    assert o.struct_size == ctypes.sizeof(P.Options) and (o.nontemporal_stores, o.reverse_tiles, o.fwd_lds_kib) == (3, 2, -1)
     assert (o.max_vector_bytes, o.interleave_rows, o.col_chunks, o.narrow_tiles, o.ragged_rows, o.probe_nt_loads) == (16, 1, 1, 1, 1, 1)
     assert (o.bwd_row_steps, o.force_generic, o.runtime_table, o.xcd_order, o.bwd_lds_kib, o.probe_lds_kib) == (0,) * 6
     assert o.start_event is None and o.stop_event is None
@@ -362,7 +362,7 @@ def test_options_defaults_ranges_and_struct_size():
     assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts) == P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=o)
     assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=P.Options(force_generic=1))["path"] == 2
     bad = [P.Options(bwd_row_steps=257), P.Options(bwd_row_steps=-1), P.Options(nontemporal_stores=4), P.Options(max_vector_bytes=12),
-           P.Options(fwd_lds_kib=65), P.Options(force_generic=2), P.Options(struct_size=ctypes.sizeof(P.Options) - 8),
+           P.Options(fwd_lds_kib=65), P.Options(fwd_lds_kib=-2), P.Options(reverse_tiles=3), P.Options(force_generic=2), P.Options(struct_size=ctypes.sizeof(P.Options) - 8),
            P.Options(start_event=4096), P.Options(stop_event=4096)]
     for opt in bad:
         with pytest.raises(P.BcastError) as e:
