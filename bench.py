@@ -104,8 +104,9 @@ class Workload:
             self.adj = [np.ascontiguousarray(x.T) for x in self.adj]
             self.desc += ", transposed"
         self.es = np.dtype(self.dtype).itemsize
-        self.dev, self._slab_a = P.to_slab([torch.from_numpy(x).cuda() for x in self.args])
-        self.adj_dev, self._slab_b = P.to_slab([torch.from_numpy(x).cuda() for x in self.adj])
+        self.layout = getattr(a, "layout", "staggered")
+        self.dev, self._slab_a = P.to_slab([torch.from_numpy(x).cuda() for x in self.args], layout=self.layout)
+        self.adj_dev, self._slab_b = P.to_slab([torch.from_numpy(x).cuda() for x in self.adj], layout=self.layout)
         if a.sliced_gates and self.op in ("hmlstm_update", "linear12"):
             Bt = self.args[0].shape[1]
             wide = torch.empty(self.args[0].shape[0], 4 * Bt, dtype=self.dev[0].dtype, device="cuda")
@@ -124,10 +125,10 @@ def measure(w, a, options, sptr, steps, warmup, lean=False, event_every=0):
     import numpy as np
     import torch
     import paper_1810_08297_amd as P
-    fb = P.alloc_forward(w.op, w.dev, want_branch=False, lean=lean, options=options)
+    fb = P.alloc_forward(w.op, w.dev, want_branch=False, lean=lean, options=options, layout=w.layout)
     didx = P.diff_arg_indices(fb.op_id)
     shapes = [w.args[j].shape for j in didx]
-    bb = P.alloc_backward(w.adj_dev, fb.partials, shapes, options=options)
+    bb = P.alloc_backward(w.adj_dev, fb.partials, shapes, options=options, layout=w.layout)
     E = int(np.prod(fb.outs[0].shape))
     M, Nd = len(fb.outs), len(didx)
     n_full_args = sum(1 for x in w.args if x.size == E)
@@ -246,6 +247,9 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run the library's 1-in 1-out stream probe on a buffer of this many MiB "
                          "(a copy of known size, for scaling profiler byte counters)")
+    ap.add_argument("--layout", choices=["staggered", "interleaved", "plain"], default="staggered",
+                    help="how the full-shape buffers of a group (arguments; outputs + planes; adjoints; gradients) share "
+                         "a slab: separate planes staggered by one page each (default), interleaved by row, or plain")
     ap.add_argument("--opt", type=lambda t: (t.split("=")[0], int(t.split("=")[1])), action="append", default=[],
                     help="FIELD=VALUE of bcast_dual_options for every call of the run (launch-shape sweeps), repeatable")
     a = ap.parse_args()
@@ -453,7 +457,7 @@ def main():
     # every benchmark configuration, timed the same way in this same run (all planes stored, default options
     # unless --opt); the entry of the headline workload is the headline run itself
     configs = None
-    if not a.no_configs and not (a.lean or a.transposed or a.sliced_gates or a.uniform_run):
+    if not a.no_configs and not (a.lean or a.transposed or a.sliced_gates or a.uniform_run or a.layout != "staggered"):
         configs = {}
         headline_key = next((k for k, wl, pi in ALL_CONFIGS if wl == a.workload and pi == a.p_index), None)
         if headline_key:
@@ -479,8 +483,8 @@ def main():
         "vs_baseline": None, "dtype": "f64" if dtype == np.float64 else "f32", "data": "synthetic",
         "config": {"workload": f"{a.workload}: {desc}", "op": op, "elements": E,
                    "partial_planes": M * Nd, "planes_stored": n_stored,
-                   "layout": "row-major, staggered slab, " + ("identical planes stored once, zero planes left out"
-                                                              if a.lean else "all planes stored"),
+                   "layout": f"row-major, {a.layout} slab, " + ("identical planes stored once, zero planes left out"
+                                                                 if a.lean else "all planes stored"),
                    "options": dict(a.opt) if a.opt else "defaults"},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra, "lean_layout": lean_extra,
         "recompute_in_reverse": recompute_extra, "graph_replay": graph_extra,

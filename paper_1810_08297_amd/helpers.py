@@ -57,18 +57,30 @@ def _numel(shape):
     return n
 
 
-def alloc_planes(shapes, dtype, device, staggered: bool = True):
-    """Contiguous tensors of the given shapes.  With ``staggered`` the ones that share the
-    largest size are carved out of one slab in the library's staggered layout
-    (bcast_dual_slab_layout); the rest are ordinary allocations.  Returns (tensors, slab)."""
+def alloc_planes(shapes, dtype, device, staggered: bool = True, layout: Optional[str] = None):
+    """Tensors of the given shapes.  The ones that share the largest size are carved out of one slab:
+    layout "staggered" (the default; `staggered=False` = "plain"): each a contiguous plane, in the
+    library's staggered layout (bcast_dual_slab_layout); layout "interleaved": the planes interleaved
+    along their first dim -- row r of plane k follows row r of plane k - 1 -- so that a block that
+    writes one row step of every plane writes one contiguous run (views with a row stride of
+    n_planes x the row length; measured faster where some twenty planes that exceed the memory-side
+    cache are streamed at once).  The rest are ordinary allocations.  Returns (tensors, slab)."""
     import torch
+    layout = layout or ("staggered" if staggered else "plain")
+    if layout not in ("staggered", "plain", "interleaved"):
+        raise ValueError(f"unknown layout {layout!r}")
     es = torch.empty((), dtype=dtype).element_size()
     shapes = [tuple(int(x) for x in s) for s in shapes]
     big = max((_numel(s) for s in shapes), default=0)
-    idx = [k for k, s in enumerate(shapes) if _numel(s) == big] if staggered and big > 0 else []
+    idx = [k for k, s in enumerate(shapes) if _numel(s) == big] if layout != "plain" and big > 0 else []
     out = [None] * len(shapes)
     slab = None
-    if idx:
+    if idx and layout == "interleaved" and len({shapes[k] for k in idx}) == 1 and len(shapes[idx[0]]) >= 2:
+        shp = shapes[idx[0]]
+        slab = torch.empty((shp[0], len(idx)) + shp[1:], dtype=dtype, device=device)
+        for n, k in enumerate(idx):
+            out[k] = slab[:, n]
+    elif idx:
         total, offs = B.bcast_dual_slab_layout(big * es, len(idx))
         slab = torch.empty(total, dtype=torch.uint8, device=device)
         for n, k in enumerate(idx):
@@ -79,16 +91,17 @@ def alloc_planes(shapes, dtype, device, staggered: bool = True):
     return out, slab
 
 
-def to_slab(tensors, staggered: bool = True):
-    """Copy tensors (same dtype and device) into freshly allocated staggered planes."""
-    out, slab = alloc_planes([t.shape for t in tensors], tensors[0].dtype, tensors[0].device, staggered)
+def to_slab(tensors, staggered: bool = True, layout: Optional[str] = None):
+    """Copy tensors (same dtype and device) into freshly allocated planes of the given layout (see alloc_planes)."""
+    out, slab = alloc_planes([t.shape for t in tensors], tensors[0].dtype, tensors[0].device, staggered, layout)
     for o, t in zip(out, tensors):
         o.copy_(t)
     return out, slab
 
 
 def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: bool = True,
-                  staggered: bool = True, lean: bool = False, options: Optional[B.Options] = None) -> ForwardBuffers:
+                  staggered: bool = True, lean: bool = False, options: Optional[B.Options] = None,
+                  layout: Optional[str] = None) -> ForwardBuffers:
     """``lean``: planes the op table declares identical share one buffer and planes it declares
     zero are left out (None); forward and backward give the same results with fewer bytes moved."""
     import torch
@@ -98,30 +111,30 @@ def alloc_forward(op_name: str, args, want_branch: bool = False, want_partials: 
     shape = unified_shape(args)
     br = torch.empty(shape, dtype=torch.uint8, device=args[0].device) if want_branch else None
     if not want_partials:
-        outs, slab = alloc_planes([shape] * m, args[0].dtype, args[0].device, staggered)
+        outs, slab = alloc_planes([shape] * m, args[0].dtype, args[0].device, staggered, layout)
         return ForwardBuffers(op_id, outs, None, br, slab, options)
     alias = B.bcast_op_plane_alias(op_id) if lean else list(range(m * nd))
     own = [k for k in range(m * nd) if alias[k] == k]
-    planes, slab = alloc_planes([shape] * (m + len(own)), args[0].dtype, args[0].device, staggered)
+    planes, slab = alloc_planes([shape] * (m + len(own)), args[0].dtype, args[0].device, staggered, layout)
     store = dict(zip(own, planes[m:]))
     parts = [None if alias[k] < 0 else store[alias[k]] for k in range(m * nd)]
     return ForwardBuffers(op_id, planes[:m], parts, br, slab, options)
 
 
 def alloc_backward(adjoints, partials, grad_shapes, staggered: bool = True,
-                   options: Optional[B.Options] = None) -> BackwardBuffers:
+                   options: Optional[B.Options] = None, layout: Optional[str] = None) -> BackwardBuffers:
     import torch
-    grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered)
+    grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered, layout)
     nbytes = B.bcast_dual_backward_workspace(adjoints, partials, grads, options)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
     return BackwardBuffers(grads, ws, slab, options)
 
 
 def alloc_recompute(op_id: int, args, adjoints, grad_shapes, staggered: bool = True,
-                    options: Optional[B.Options] = None) -> BackwardBuffers:
+                    options: Optional[B.Options] = None, layout: Optional[str] = None) -> BackwardBuffers:
     """Gradient buffers and workspace for bcast_dual_backward_recompute."""
     import torch
-    grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered)
+    grads, slab = alloc_planes(grad_shapes, adjoints[0].dtype, adjoints[0].device, staggered, layout)
     nbytes = B.bcast_dual_backward_recompute_workspace(op_id, args, adjoints, grads, options)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=adjoints[0].device) if nbytes else None
     return BackwardBuffers(grads, ws, slab, options)

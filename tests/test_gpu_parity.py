@@ -1066,6 +1066,45 @@ def test_two_streams_run_independent_problems():
                 assert torch.equal(got, want), f"repetition {rep}"
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_planes_interleaved_by_row(dtype):
+    """Outputs and planes interleaved by row in one slab (and the arguments, adjoints and gradients likewise,
+    each group in a slab of its own): the groups have different row strides, the HM-LSTM mixes still get their
+    compiled-per-mix backward kernel (built for views with strides of their own), and every result has the
+    bits of the default layout."""
+    for op, R, C, lean in (("hmlstm_update", 300, 1024, False), ("hmlstm_update", 130, 2052, True), ("branchy5", 260, 1100, False)):
+        args, adj = small_args(op, R, C, dtype, seed=R + C)
+        dev, adj_dev = [to_dev(a) for a in args], [to_dev(a) for a in adj]
+        shapes = [args[j].shape for j in oracle.diff_arg_indices(op, len(args))]
+        ref = P.alloc_forward(op, dev, want_branch=True, lean=lean).run(dev)
+        refb = P.alloc_backward(adj_dev, ref.partials, shapes).run(adj_dev, ref.partials)
+        dev_i, _k1 = P.to_slab(dev, layout="interleaved")
+        adj_i, _k2 = P.to_slab(adj_dev, layout="interleaved")
+        fb = P.alloc_forward(op, dev_i, want_branch=True, lean=lean, layout="interleaved")
+        assert fb.outs[0].stride(0) > C and not fb.outs[0].is_contiguous()
+        fplan = P.bcast_dual_forward_plan(fb.op_id, dev_i, fb.outs, fb.partials, fb.branch)
+        assert fplan["path"] == 1 and fplan["uniform_stride"] == 0
+        fb.run(dev_i)
+        bb = P.alloc_backward(adj_i, fb.partials, shapes, layout="interleaved")
+        bplan = P.bcast_dual_backward_plan(adj_i, fb.partials, bb.grads)
+        assert bplan["path"] == 1 and bplan["uniform_stride"] == 0
+        if op == "hmlstm_update" and C % (16 // np.dtype(dtype).itemsize) == 0:
+            assert bplan["specialized"] == 1, bplan
+        bb.run(adj_i, fb.partials)
+        torch.cuda.synchronize()
+        assert torch.equal(fb.branch, ref.branch)
+        for k, (g, w) in enumerate(zip(fb.outs + [p for p in fb.partials if p is not None], ref.outs + [p for p in ref.partials if p is not None])):
+            assert torch.equal(g, w), f"{op} output or plane {k}"
+        for k, (g, w) in enumerate(zip(bb.grads, refb.grads)):
+            if g.numel() == R * C:
+                assert torch.equal(g, w), f"{op} gradient {k}"
+            else:  # sums taken by another kernel may round differently
+                check_close(g.cpu().numpy(), w.cpu().numpy(), f"{op} reduced gradient {k}")
+        want = oracle.backward(adj, [None if p is None else p.cpu().numpy() for p in fb.partials], shapes, threads=8)
+        for k, (g, w) in enumerate(zip(bb.grads, want)):
+            check_close(g.cpu().numpy(), w, f"{op} gradient {k} against the oracle")
+
+
 def test_two_host_threads_with_different_options():
     """The library holds no state between calls: two host threads, each launching its own problem on its own
     stream with options of its own (one forces the generic kernels and plain stores, the other the run-time
