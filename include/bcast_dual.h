@@ -74,7 +74,8 @@ typedef struct {
 
 /* How a call was (or would be) mapped onto the GPU; filled by the *_plan calls. */
 typedef struct {
-  int32_t path;     /* 0 nothing to do, 1 tiled 2-D kernels, 2 generic strided kernels */
+  int32_t path;     /* 0 nothing to do, 1 tiled kernels (the problem merges to two dims, or to three: then a batch
+                       of two-dim slices), 2 generic strided kernels */
   int32_t vec;      /* elements per lane per memory instruction */
   int32_t ndim;     /* rank after dropping size-1 dims and merging mergeable dims */
   int64_t shape[BCAST_MAX_DIMS]; /* merged output extents, outermost first */
@@ -264,7 +265,7 @@ int bcast_dual_backward_noalloc(bcast_dtype dt, int32_t n_out, const bcast_tenso
  * and the adjoints, evaluates b on dual numbers again and reduces sum_i adj_i * dY_i/dX_jd into
  * each gradient exactly as bcast_dual_backward does.
  * args[n_args] as in forward; adjoints[n_out] of the unified shape; grads[n_grads = N_d] in their
- * argument's shape (NULL data: skipped; any other shape: BCAST_ERR_OUTPUT_SHAPE_MISMATCH).  Available for problems that merge to at most two dims
+ * argument's shape (NULL data: skipped; any other shape: BCAST_ERR_OUTPUT_SHAPE_MISMATCH).  Available for problems that merge to at most three dims
  * with unit inner stride (the tiled kernels), for every op (the prod_tanh_K family only where all
  * full-shape views share one row stride); otherwise BCAST_ERR_UNSUPPORTED.  Workspace rules as for bcast_dual_backward. */
 size_t bcast_dual_backward_recompute_workspace(int32_t op_id, bcast_dtype dt, int32_t n_args, const bcast_tensor *args,

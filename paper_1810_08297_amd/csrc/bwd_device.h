@@ -139,7 +139,8 @@ struct BwdGeom {
   using AT = acc_traits<T>;
   using A = typename AT::type;
   int tid, ltx, TX, tx, ty, TY, wpr, rows_pb;
-  uint32_t bid, rt, ct;
+  uint32_t bid, rt, ct;  // bid: the block's index within its slice
+  int64_t slice, O;      // the block's slice of a 3-D problem and the number of slices (0 and 1 for two dims)
   int64_t c0, r_first;  // r_first: row of the block's first row step at ty = 0
   int64_t r_step;       // rows from one row step of the block to its next
   bool colvalid, interior;
@@ -172,6 +173,13 @@ struct BwdGeom {
       // XCD (its L2, its address-translation cache) whose forward block wrote it
       const uint32_t full = gridDim.x & ~7u;
       if (bid < full) bid = full - 8u - (bid & ~7u) + (bid & 7u);
+    }
+    slice = 0;
+    O = p.O;
+    if (p.O > 1) {  // a 3-D problem: the grid holds the blocks of slice 0, then those of slice 1, ...
+      const uint32_t sl = bid / (uint32_t)p.tiles_per_slice;
+      bid -= sl * (uint32_t)p.tiles_per_slice;
+      slice = sl;
     }
     rt = bid / nct;
     ct = bid - rt * nct;
@@ -216,7 +224,7 @@ struct BwdGeom {
   BD_DEV RowStep<T, US> step(const BwdTiledParams &p, int k) const {
     int64_t r0 = r_first + k * r_step;
     r0 = r0 < p.R ? r0 : 0;
-    return RowStep<T, US>{r0, r0 * p.row_stride * (int64_t)sizeof(T), lane_uniform, (uint32_t)ty, col_off};
+    return RowStep<T, US>{r0, slice, (slice * p.outer_stride + r0 * p.row_stride) * (int64_t)sizeof(T), lane_uniform, (uint32_t)ty, col_off};
   }
   // row behind the block-local row index q = k * TY + ty
   BD_DEV int64_t row_of_local(int q) const {
@@ -276,17 +284,17 @@ BD_DEV void rowsum_finish(const BwdTiledParams &p, const BwdGeom<T, VEC> &g, con
       if (g.ltx > 6)
         g.lds_row[(en.slot * g.rows_pb + ri) * g.wpr + (g.tx >> 6)] = rs;
       else if (en.direct)
-        static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(rs);
+        static_cast<T *>(en.g.p)[g.slice * en.g.so + r * en.g.sr] = AT::fin(rs);
       else
-        reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = rs;
+        reinterpret_cast<A *>(p.ws + en.ws_off)[(r * g.O + g.slice) * p.n_ct + g.ct] = rs;
     }
   } else {  // several rows per wavefront: segmented butterfly
     rs = seg_reduce<T, A>(rs, g.ltx);
     if (g.tx == 0 && r < p.R) {
       if (en.direct)
-        static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(rs);
+        static_cast<T *>(en.g.p)[g.slice * en.g.so + r * en.g.sr] = AT::fin(rs);
       else
-        reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = rs;
+        reinterpret_cast<A *>(p.ws + en.ws_off)[(r * g.O + g.slice) * p.n_ct + g.ct] = rs;
     }
   }
 }
@@ -337,9 +345,9 @@ BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
           A s = g.lds_row[(en.slot * g.rows_pb + q) * g.wpr];
           for (int w = 1; w < g.wpr; ++w) AT::add(s, g.lds_row[(en.slot * g.rows_pb + q) * g.wpr + w]);
           if (en.direct)
-            static_cast<T *>(en.g.p)[r * en.g.sr] = AT::fin(s);
+            static_cast<T *>(en.g.p)[g.slice * en.g.so + r * en.g.sr] = AT::fin(s);
           else
-            reinterpret_cast<A *>(p.ws + en.ws_off)[r * p.n_ct + g.ct] = s;
+            reinterpret_cast<A *>(p.ws + en.ws_off)[(r * g.O + g.slice) * p.n_ct + g.ct] = s;
         }
       }
     } else if (en.cls == kGradColSum) {
@@ -350,9 +358,9 @@ BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
           A s = g.lds_col[(en.slot * kBlock + g.tx) * VEC + v];
           for (int y = 1; y < g.TY; ++y) AT::add(s, g.lds_col[(en.slot * kBlock + y * g.TX + g.tx) * VEC + v]);
           if (en.direct)
-            static_cast<T *>(en.g.p)[(g.c0 + v) * en.g.sc] = AT::fin(s);
+            static_cast<T *>(en.g.p)[g.slice * en.g.so + (g.c0 + v) * en.g.sc] = AT::fin(s);
           else
-            reinterpret_cast<A *>(p.ws + en.ws_off)[(int64_t)g.rt * p.C + g.c0 + v] = s;
+            reinterpret_cast<A *>(p.ws + en.ws_off)[((int64_t)g.rt * g.O + g.slice) * p.C + g.c0 + v] = s;
         }
       }
     } else if (en.cls == kGradAllSum) {
@@ -365,9 +373,9 @@ BD_DEV void bwd_finalize(const BwdTiledParams &p, const BwdGeom<T, VEC> &g) {
         A t = g.lds_all[en.slot * kBlock];
         for (int w = 1; w < kBlock / 64; ++w) AT::add(t, g.lds_all[en.slot * kBlock + w]);
         if (en.direct)
-          static_cast<T *>(en.g.p)[0] = AT::fin(t);
+          static_cast<T *>(en.g.p)[g.slice * en.g.so] = AT::fin(t);
         else
-          reinterpret_cast<A *>(p.ws + en.ws_off)[g.bid] = t;
+          reinterpret_cast<A *>(p.ws + en.ws_off)[(int64_t)g.bid * g.O + g.slice] = t;
       }
     }
   }

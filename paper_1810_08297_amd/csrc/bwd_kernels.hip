@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
       chunk[q] = (uint32_t)q * g.chunk_bytes - (q == 0 ? 0u : (uint32_t)shift[q] * (uint32_t)sizeof(T));
 #pragma unroll
       for (int i = 0; i < M; ++i)
-        load_plane<T, VEC, EDGE, true>(rs.base(p.adj[i].p, p.adj[i].sr), off(p.adj[i].sr, q), valid[q], adj[q][i], shift[q]);
+        load_plane<T, VEC, EDGE, true>(rs.base(p.adj[i]), off(p.adj[i].sr, q), valid[q], adj[q][i], shift[q]);
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) P[q][e][i][v] = T(0);
           } else {
-            load_plane<T, VEC, EDGE, true>(rs.base(p.e[e].P[i].p, p.e[e].P[i].sr), off(p.e[e].P[i].sr, q), valid[q], P[q][e][i], shift[q]);
+            load_plane<T, VEC, EDGE, true>(rs.base(p.e[e].P[i]), off(p.e[e].P[i].sr, q), valid[q], P[q][e][i], shift[q]);
           }
         }
     }
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     for (int q = 0; q < CU; ++q)
 #pragma unroll
       for (int e = 0; e < NF; ++e)
-        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g.p, p.e[e].g.sr), adj[q], P[q][share_src(SHARE, e)], off(p.e[e].g.sr, q), valid[q], nt,
+        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g), adj[q], P[q][share_src(SHARE, e)], off(p.e[e].g.sr, q), valid[q], nt,
                                           shift[q]);
 #pragma unroll
     for (int e = NF; e < NF + NR; ++e) {
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
     auto voff = [&](int64_t sr) { return valid ? rs.lane(sr) : 0u; };
     LV adj_raw[MAXM];  // unpacked only after the first four gradients' loads are on their way
 #pragma unroll
-    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(rs.base(p.adj[i < M ? i : 0].p, p.adj[i < M ? i : 0].sr), voff(p.adj[i < M ? i : 0].sr)));
+    for (int i = 0; i < MAXM; ++i) adj_raw[i] = load_lane_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(rs.base(p.adj[i < M ? i : 0]), voff(p.adj[i < M ? i : 0].sr)));
     T adj[MAXM][VEC];
     LV raw[CH][MAXM];
     bool have[CH][MAXM];
@@ -167,8 +167,8 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
         for (int i = 0; i < MAXM; ++i) {
           const void *plane = i < M ? p.e[e].P[i].p : nullptr;
           have[q][i] = valid && e0 + q < p.n_entries && plane != nullptr;
-          const int64_t sr = plane != nullptr ? p.e[e].P[i].sr : p.adj[0].sr;
-          raw[q][i] = load_lane_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(rs.base(plane != nullptr ? plane : p.adj[0].p, sr), voff(sr)));
+          const SView &src = plane != nullptr ? p.e[e].P[i] : p.adj[0];
+          raw[q][i] = load_lane_vec<T, VEC, kBwdLoadNt, RAGGED>(at<const T>(rs.base(src), voff(src.sr)));
         }
       }
     };
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
 #pragma unroll
           for (int i = 0; i < MAXM; ++i) unshift<T, VEC>(P[i], g.shift);
         if (en.cls == kGradFull)
-          apply_full<T, VEC, MAXM, true, RAGGED>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
+          apply_full<T, VEC, MAXM, true, RAGGED>(rs.base(en.g), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
         else if (en.cls == kGradRowSum)
           apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
         else if (en.cls == kGradColSum)
@@ -248,13 +248,22 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
   const int64_t b = (int64_t)blockIdx.x - job.first_block;
   const A *ws = reinterpret_cast<const A *>(p.ws + job.ws_off);
   T *g = static_cast<T *>(job.g);
+  // where output `out` of the job lives: outputs that keep the outer dim of a 3-D problem are numbered
+  // (slice, inner) or (inner, slice), whichever order their partial sums have in the workspace
+  auto g_at = [&](int64_t out) -> T & {
+    if (job.n_outer <= 1) return g[out * job.g_stride];
+    const int64_t n_inner = job.n_out / job.n_outer;
+    const int64_t sl = job.outer_major ? out / n_inner : out % job.n_outer;
+    const int64_t in = job.outer_major ? out - sl * n_inner : out / job.n_outer;
+    return g[sl * job.g_outer_stride + in * job.g_stride];
+  };
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (job.kind == 0) {  // one wavefront per output
     const int64_t out = b * (kBlock / 64) + wave;
     if (out < job.n_out) {
       A s = pass2_sum<T, A>(ws + out * job.out_stride, lane, 64, job.n_part, job.part_stride);
       s = seg_reduce<T, A>(s, 6);
-      if (lane == 0) g[out * job.g_stride] = AT::fin(s);
+      if (lane == 0) g_at(out) = AT::fin(s);
     }
   } else if (job.kind == 1) {  // one block per output
     const int64_t out = b;
@@ -265,7 +274,7 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
     if (tid == 0) {
       A t = sh[0];
       for (int w = 1; w < kBlock / 64; ++w) AT::add(t, sh[w]);
-      g[out * job.g_stride] = AT::fin(t);
+      g_at(out) = AT::fin(t);
     }
   } else {  // adjacent outputs x interleaved groups of partials: 64 x 4 (kind 2) or 16 x 16 (kind 3)
     const int log2_outs = job.kind == 2 ? 6 : 4;
@@ -279,7 +288,7 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
     if (grp == 0 && out < job.n_out) {
       A t = sh[o];
       for (int w = 1; w < groups; ++w) AT::add(t, sh[w * outs + o]);
-      g[out * job.g_stride] = AT::fin(t);
+      g_at(out) = AT::fin(t);
     }
   }
 }

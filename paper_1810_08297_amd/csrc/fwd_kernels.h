@@ -130,14 +130,17 @@ BD_DEV T *at(const void *base, uint32_t byte_off) {
 // all full-shape views (US) both parts are computed once and serve every such view.
 template <class T, bool US>
 struct RowStep {
-  int64_t row0;           // first row of the step
-  int64_t uniform_bytes;  // US: row0 * the common row stride * sizeof(T)
+  int64_t row0;           // first row of the step (within the block's slice)
+  int64_t slice;          // the block's index along the outer dim of a 3-D problem (0 otherwise)
+  int64_t uniform_bytes;  // US: (slice * the common outer stride + row0 * the common row stride) * sizeof(T)
   uint32_t lane_uniform;  // US: (lane's row in the step * the common row stride + lane's column) * sizeof(T)
   uint32_t ty, col_off;   // lane's row in the step; lane's column * sizeof(T)
-  // a view that varies along rows and columns
-  BD_DEV const void *base(const void *p, int64_t sr) const {
-    return static_cast<const char *>(p) + (US ? uniform_bytes : row0 * sr * (int64_t)sizeof(T));
+  // a view that varies along rows and columns: its rows `sr`, its slices `so` elements apart
+  BD_DEV const void *base(const void *p, int64_t sr, int64_t so) const {
+    return static_cast<const char *>(p) + (US ? uniform_bytes : (slice * so + row0 * sr) * (int64_t)sizeof(T));
   }
+  BD_DEV const void *base(const TView &v) const { return base(v.p, v.sr, v.so); }
+  BD_DEV const void *base(const SView &v) const { return base(v.p, v.sr, v.so); }
   BD_DEV uint32_t lane(int64_t sr) const {
     return US ? lane_uniform : ty * (uint32_t)sr * (uint32_t)sizeof(T) + col_off;
   }
@@ -162,7 +165,8 @@ BD_DEV int eval_op(const T (&a)[Op::N][VEC], int v, Y *y, std::index_sequence<J.
   return Op::apply(y, make_arg<Op, T, (int)J, (Y::mask != 0u)>(a[J][v])...);
 }
 
-// Tiled 2-D kernel.  Block = 256 lanes arranged TY x TX over TY rows; a lane owns VEC
+// Tiled kernel for problems of two merged dims, or of three (a batch of 2-D slices: see TView).
+// Block = 256 lanes arranged TY x TX over TY rows of one slice; a lane owns VEC
 // consecutive columns of one row.  Stride-0 arguments are served from registers: a column
 // vector or scalar is one broadcast load per lane, a row vector one vector load from its
 // only row.  There is deliberately no row loop: with ~30 plane pointers live across a loop
@@ -186,6 +190,12 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   const uint32_t nct = (uint32_t)p.n_ct;
   uint32_t bid = blockIdx.x;
   if (p.xcd_remap) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);  // the host sets this only for grids of 8 n blocks
+  uint32_t slice32 = 0;
+  if (p.O > 1) {  // a 3-D problem: the grid holds the blocks of slice 0, then those of slice 1, ...
+    slice32 = bid / (uint32_t)p.tiles_per_slice;
+    bid -= slice32 * (uint32_t)p.tiles_per_slice;
+  }
+  const int64_t slice = slice32;
   const uint32_t rt = bid / nct, ct = bid - rt * nct;
   const int64_t c0 = ((((int64_t)ct) << ltx) + tx) * VEC;
   if (c0 >= p.C) return;
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   const int shift = RAGGED && c0 + VEC > p.C ? (int)(c0 + VEC - p.C) : 0;
   const int64_t cl = c0 - shift;
   const uint32_t col_off = (uint32_t)cl * (uint32_t)sizeof(T);
-  const RowStep<T, US> rs{r0, r0 * p.row_stride * (int64_t)sizeof(T),
+  const RowStep<T, US> rs{r0, slice, (slice * p.outer_stride + r0 * p.row_stride) * (int64_t)sizeof(T),
                           ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)cl) * (uint32_t)sizeof(T), (uint32_t)ty, col_off};
 
   // Every argument is fetched in whichever of two forms applies -- a vector for arguments
@@ -217,11 +227,11 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
     if constexpr (ROW_VECTORS_APART) {
       if (!(((p.col_invariant | p.row_invariant) >> j) & 1u))  // from this row
-        load_vec<T, VEC, ARG_NT, RAGGED>(at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
+        load_vec<T, VEC, ARG_NT, RAGGED>(at<const T>(rs.base(p.arg_p[j], p.arg_sr[j], p.arg_so[j]), rs.lane(p.arg_sr[j])), avec[j]);
     } else {
       if (!((p.col_invariant >> j) & 1u))  // from this row, or (row vectors) from the only row
-        load_vec<T, VEC, ARG_NT, RAGGED>(((p.row_invariant >> j) & 1u) ? at<const T>(p.arg_p[j], col_off)
-                                                                         : at<const T>(rs.base(p.arg_p[j], p.arg_sr[j]), rs.lane(p.arg_sr[j])), avec[j]);
+        load_vec<T, VEC, ARG_NT, RAGGED>(((p.row_invariant >> j) & 1u) ? at<const T>(static_cast<const T *>(p.arg_p[j]) + slice * p.arg_so[j], col_off)
+                                                                         : at<const T>(rs.base(p.arg_p[j], p.arg_sr[j], p.arg_so[j]), rs.lane(p.arg_sr[j])), avec[j]);
     }
   }
   // Row vectors, in the kernels that stream their arguments, are a third form with registers of
@@ -240,14 +250,14 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int j = 0; j < N; ++j) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) arow[j][v] = T(0);
-      if ((rowvec >> j) & 1u) load_vec<T, VEC, false, RAGGED>(at<const T>(p.arg_p[j], col_off), arow[j]);
+      if ((rowvec >> j) & 1u) load_vec<T, VEC, false, RAGGED>(at<const T>(static_cast<const T *>(p.arg_p[j]) + slice * p.arg_so[j], col_off), arow[j]);
     }
   }
 #pragma unroll
   for (int j = 0; j < N; ++j) {
     asc[j] = T(0);
     if ((colinv_again >> j) & 1u)  // one value for the row (column vectors) or for everything (scalars)
-      asc[j] = static_cast<const T *>(p.arg_p[j])[((p.row_invariant >> j) & 1u) ? 0 : r * p.arg_sr[j]];
+      asc[j] = static_cast<const T *>(p.arg_p[j])[slice * p.arg_so[j] + (((p.row_invariant >> j) & 1u) ? 0 : r * p.arg_sr[j])];
   }
   // the merge below must not sink into the conditional loads above (each load would then be
   // waited for on its own): the broadcast values pass through an opaque point after all loads
@@ -280,7 +290,7 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      put(at<T>(rs.base(p.out_p[i], p.out_sr[i]), rs.lane(p.out_sr[i])), o);
+      put(at<T>(rs.base(p.out_p[i], p.out_sr[i], p.out_so[i]), rs.lane(p.out_sr[i])), o);
     }
     if constexpr (PARTIALS) {
 #pragma unroll
@@ -291,13 +301,13 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
           if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-            put(at<T>(rs.base(pl, p.part_sr[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd])), o);
+            put(at<T>(rs.base(pl, p.part_sr[i * ND + jd], p.part_so[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd])), o);
           }
         });
       }
     }
     if (p.branch_p != nullptr) {
-      uint8_t *bp = p.branch_p + r * p.branch_sr + c0 * p.branch_sc;
+      uint8_t *bp = p.branch_p + slice * p.branch_so + r * p.branch_sr + c0 * p.branch_sc;
       if (RAGGED && last_tile) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v)

@@ -263,21 +263,28 @@ void canonicalize(int D, const Dims &U, const std::vector<Dims> &eff, int key, C
   }
 }
 
-// rows / columns of a merged problem of rank <= 2, and one tensor's strides in it
+// slices / rows / columns of a merged problem of rank <= 3 (a problem of three dims is a batch of O
+// two-dim slices for the tiled kernels), and one tensor's strides in it
 struct Shape2 {
-  int64_t R = 1, C = 1;
+  int64_t O = 1, R = 1, C = 1;
 };
 inline Shape2 shape2(const Canon &c) {
   Shape2 s;
   if (c.nd == 1) s.C = c.shape[0];
   if (c.nd == 2) { s.R = c.shape[0]; s.C = c.shape[1]; }
+  if (c.nd == 3) { s.O = c.shape[0]; s.R = c.shape[1]; s.C = c.shape[2]; }
   return s;
 }
 inline TView tview(const Canon &c, size_t t, void *p) {
-  TView v{p, 0, 0};
+  TView v{p, 0, 0, 0};
   if (c.nd == 1) v.sc = c.strides[t][0];
   if (c.nd == 2) { v.sr = c.strides[t][0]; v.sc = c.strides[t][1]; }
+  if (c.nd == 3) { v.so = c.strides[t][0]; v.sr = c.strides[t][1]; v.sc = c.strides[t][2]; }
   return v;
+}
+inline SView sview(const Canon &c, size_t t, void *p) {
+  const TView v = tview(c, t, p);
+  return SView{v.p, v.sr, v.so};
 }
 inline GView gview(const Canon &c, size_t t, void *p) {
   GView v{p, {0, 0, 0, 0}};
@@ -295,9 +302,13 @@ inline GView gview(const Canon &c, size_t t, void *p) {
 // with more than one row -- an expanded view) has a row stride of its own like any other and
 // breaks the uniformity.  Views past that index with row stride 0 are row vectors, which the
 // kernels address apart, and are skipped.
-int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es, size_t n_streamed) {
-  if (s2.R == 1) return s2.C * es > 0xffffffffULL ? -2 : 0;
-  int64_t sr = -1;
+// With three dims the same holds for the strides between slices: `outer` receives the one the
+// views share (views that repeat one slice break the uniformity among the streamed ones like
+// views that repeat one row).
+int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Shape2 &s2, size_t es, size_t n_streamed, int64_t *outer) {
+  *outer = 0;
+  if (s2.R == 1 && s2.O == 1) return s2.C * es > 0xffffffffULL ? -2 : 0;
+  int64_t sr = -1, so = -1;
   bool uniform = true;
   const int64_t rows_in_step = std::min<int64_t>(s2.R, s2.C >= 1024 ? 1 : kBlock);
   for (size_t t = 0; t < v.size(); ++t) {
@@ -306,14 +317,23 @@ int64_t common_row_stride(const Canon &c, const std::vector<PView> &v, const Sha
     if (tv.sc == 0) continue;
     const unsigned __int128 last = ((unsigned __int128)(rows_in_step - 1) * tv.sr + s2.C) * es;
     if (last > 0xffffffffULL) return -2;
-    if (tv.sr == 0) {
+    if (tv.sr == 0 && s2.R > 1) {  // a row vector (of each slice): addressed apart, unless it is a streamed view
       if (t < n_streamed) uniform = false;
       continue;
     }
-    if (sr < 0) sr = tv.sr;
-    else if (sr != tv.sr) uniform = false;
+    if (tv.so == 0 && s2.O > 1) {  // the same rows for every slice: rows with a stride, slices without
+      uniform = false;
+      continue;
+    }
+    if (sr < 0) {
+      sr = tv.sr;
+      so = tv.so;
+    } else if (sr != tv.sr || so != tv.so) {
+      uniform = false;
+    }
   }
   if (!uniform) return -1;
+  *outer = so < 0 ? 0 : so;
   return sr < 0 ? 0 : sr;  // no such view: the offset is never used
 }
 
@@ -488,7 +508,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
   plan.info.ndim = c.nd;
   for (int d = 0; d < c.nd; ++d) plan.info.shape[d] = c.shape[d];
 
-  bool tiled = (c.nd <= 2) && !o.force_generic;
+  bool tiled = (c.nd <= 3) && !o.force_generic;
   const Shape2 s2 = shape2(c);
   if (tiled && s2.C > 1) {
     for (int j = 0; j < N && tiled; ++j) {
@@ -498,7 +518,8 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (size_t t = N; t < v.size() && tiled; ++t)
       if (v[t].p) tiled = (tview(c, t, nullptr).sc == 1);
   }
-  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es, 0) : -2;
+  int64_t fwd_so = 0;
+  const int64_t fwd_sr = tiled ? common_row_stride(c, v, s2, es, 0, &fwd_so) : -2;
   // views with row strides of their own: only the ops built for it (the others go generic)
   tiled = tiled && (fwd_sr >= 0 || (fwd_sr == -1 && op.strided));
   plan.tiled = tiled;
@@ -506,6 +527,8 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     FwdTiledParams &p = plan.tp;
     p.uniform_stride = fwd_sr >= 0;
     p.row_stride = fwd_sr >= 0 ? fwd_sr : 0;
+    p.outer_stride = fwd_sr >= 0 ? fwd_so : 0;
+    p.O = s2.O;
     p.R = s2.R;
     p.C = s2.C;
     // widest vector (16 bytes per lane at most) that every vector-accessed view allows
@@ -516,7 +539,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
         if (!v[t].p) continue;
         const TView tv = tview(c, t, v[t].p);
         if (tv.sc == 0 && s2.C > 1) continue;  // a broadcast load: one element
-        vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0);
+        vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0) && (s2.O == 1 || tv.so % vw == 0);
       }
       if (vec_ok) break;
     }
@@ -527,15 +550,18 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     g.vec = vw;
     tile_columns(s2.C, g.vec, narrow_tiles_ok(c, v, s2, es), o, g);
     if (!tile_rows(s2.R, 1, g)) return BCAST_ERR_LAUNCH_FAILED;  // the forward kernel has no row loop
+    if (g.n_ct * g.n_rt > 0x7fffffffLL / s2.O) return BCAST_ERR_LAUNCH_FAILED;
+    p.tiles_per_slice = g.n_ct * g.n_rt;
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
     p.nt_store = o.nontemporal_stores & 1;
-    p.xcd_remap = o.xcd_order != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+    p.xcd_remap = o.xcd_order != 0 && (s2.O * g.n_ct * g.n_rt) % 8 == 0;
     p.has_partials = n_planes > 0;
     for (int j = 0; j < N; ++j) {
       const TView tv = tview(c, j, v[j].p);
       p.arg_p[j] = tv.p;
       p.arg_sr[j] = tv.sr;
+      p.arg_so[j] = tv.so;
       // (a problem of one row has no row vectors: nothing is read by a second row of blocks, and the
       // kernel keeps the streaming loads of full-shape arguments for it)
       if (tv.sr == 0 && s2.R > 1) p.row_invariant |= 1u << j;
@@ -544,10 +570,12 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     for (int i = 0; i < M; ++i) {
       p.out_p[i] = v[N + i].p;
       p.out_sr[i] = tview(c, N + i, nullptr).sr;
+      p.out_so[i] = tview(c, N + i, nullptr).so;
     }
     for (int k = 0; k < n_planes; ++k) {
       p.part_p[k] = dup[k] ? nullptr : v[N + M + k].p;
       p.part_sr[k] = tview(c, N + M + k, nullptr).sr;
+      p.part_so[k] = tview(c, N + M + k, nullptr).so;
     }
     // A launch that mostly writes (two or more planes read, at least 2.5 written for each) runs fastest
     // with three blocks, twelve wavefronts, per CU: measured 75 against 81 us on the HM-LSTM
@@ -566,8 +594,9 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
       p.branch_p = static_cast<uint8_t *>(tv.p);
       p.branch_sr = tv.sr;
       p.branch_sc = tv.sc;
+      p.branch_so = tv.so;
     }
-    plan.grid = dim3((unsigned)(g.n_ct * g.n_rt), 1, 1);
+    plan.grid = dim3((unsigned)(s2.O * g.n_ct * g.n_rt), 1, 1);
     plan.info.path = 1;
     plan.info.vec = g.vec;
     plan.info.ragged = p.ragged;
@@ -576,7 +605,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     plan.info.ty = kBlock >> g.log2_tx;
     plan.info.rows_per_block = plan.info.ty * g.steps;
     plan.info.grid_x = g.n_ct;
-    plan.info.grid_y = g.n_rt;
+    plan.info.grid_y = g.n_rt * s2.O;
   } else {
     FwdGenericParams &p = plan.gp;
     p.nd = c.nd;
@@ -706,9 +735,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
   const size_t g0 = M + M * ND;
 
   const Shape2 s2 = shape2(c);
-  bool tiled = (c.nd <= 2) && !o.force_generic;
-  // class of each gradient in the 2-D picture
+  bool tiled = (c.nd <= 3) && !o.force_generic;
+  // class of each gradient in the 2-D picture of one slice, and whether it is summed over the slices too
   std::vector<int> cls(ND, kGradSkip);
+  std::vector<char> outer_sum(ND, 0);
   if (tiled) {
     for (int j = 0; j < ND; ++j) {
       if (!v[g0 + j].p) continue;
@@ -716,6 +746,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       const bool rows_red = s2.R > 1 && tv.sr == 0;
       const bool cols_red = s2.C > 1 && tv.sc == 0;
       cls[j] = rows_red ? (cols_red ? kGradAllSum : kGradColSum) : (cols_red ? kGradRowSum : kGradFull);
+      outer_sum[j] = s2.O > 1 && tv.so == 0;
+      // a gradient with the shape of a slice, summed over the slices only, would need partial sums as
+      // large as the problem: left to the generic kernels
+      if (cls[j] == kGradFull && outer_sum[j]) tiled = false;
     }
     if (s2.C > 1) {
       for (int t = 0; t < M + M * ND && tiled; ++t)
@@ -728,17 +762,17 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       }
     }
   }
-  int64_t bwd_sr = -1;
+  int64_t bwd_sr = -1, bwd_so = 0;
   if (tiled) {
     // reduced gradients are addressed on their own; only full-shape views share the offset
     std::vector<PView> fullv = v;
     for (int j = 0; j < ND; ++j)
       if (cls[j] != kGradFull) fullv[g0 + j].p = nullptr;
-    bwd_sr = common_row_stride(c, fullv, s2, es, (size_t)(M + M * ND));
+    bwd_sr = common_row_stride(c, fullv, s2, es, (size_t)(M + M * ND), &bwd_so);
     tiled = bwd_sr >= -1;  // -1: every view addressed with its own row stride
   }
   const bool uniform_stride = bwd_sr >= 0;
-  if (!uniform_stride) bwd_sr = 0;
+  if (!uniform_stride) bwd_sr = bwd_so = 0;
   plan.tiled = tiled;
   if (rop && (!tiled || (!uniform_stride && !rop->strided))) return BCAST_ERR_UNSUPPORTED;
   if (tiled) {
@@ -750,7 +784,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         if (t >= g0 && t < a0 && cls[t - g0] != kGradFull) continue;  // reduced gradients are stored by element
         const TView tv = tview(c, t, v[t].p);
         if (t >= a0 && tv.sc == 0 && s2.C > 1) continue;              // a broadcast load: one element
-        vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0);
+        vec_ok = (reinterpret_cast<uintptr_t>(tv.p) % (vw * es) == 0) && (s2.R == 1 || tv.sr % vw == 0) && (s2.O == 1 || tv.so % vw == 0);
       }
       if (vec_ok) break;
     }
@@ -825,7 +859,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // Small problems want about one block per CU whatever the kernel (per-block set-up and the final
     // combine weigh more than overlap): [512 x 2048] HM-LSTM, 1024 tiles of one row step, runs 23 us at
     // 4 row steps per block, 26 us at 2, 29 us at 8; [256 x 1024] 11-13 us at 1 or 2, 19 us at 8.
-    const int64_t tiles = ceil_div(s2.R, TY) * g.n_ct;  // row steps x column chunks of the whole problem
+    const int64_t tiles = ceil_div(s2.R, TY) * g.n_ct * s2.O;  // row steps x column chunks of the whole problem
     int64_t steps_rowwise;
     if (one_per_cu) {
       steps_rowwise = std::min<int64_t>(256 / TY, tiles / 256);
@@ -874,7 +908,8 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       steps = (int)std::max<int64_t>(1, std::min<int64_t>(steps, max_rows / TY));
     }
     if (!tile_rows(s2.R, steps, g)) return BCAST_ERR_LAUNCH_FAILED;
-    plan.grid = dim3((unsigned)(g.n_ct * g.n_rt), 1, 1);
+    if (g.n_ct * g.n_rt > 0x7fffffffLL / s2.O) return BCAST_ERR_LAUNCH_FAILED;
+    plan.grid = dim3((unsigned)(s2.O * g.n_ct * g.n_rt), 1, 1);
     const int rows_pb = TY * g.steps;
 
     // split the gradients over launches so that each launch's LDS accumulators fit
@@ -891,7 +926,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.nt_store = (o.nontemporal_stores >> 1) & 1;
       p.reverse = o.reverse_tiles;
       p.interleave = o.interleave_rows;
-      p.xcd_remap = o.xcd_order != 0 && (g.n_ct * g.n_rt) % 8 == 0;
+      p.xcd_remap = o.xcd_order != 0 && (s2.O * g.n_ct * g.n_rt) % 8 == 0;
       p.col_chunks = chunks;
       p.uniform_stride = uniform_stride;
       p.ragged = ragged;
@@ -899,7 +934,10 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.n_ct = g.n_ct;
       p.n_rt = g.n_rt;
       p.row_stride = bwd_sr;
-      for (int i = 0; i < M; ++i) p.adj[i] = tview(c, i, v[i].p);
+      p.O = s2.O;
+      p.tiles_per_slice = g.n_ct * g.n_rt;
+      p.outer_stride = bwd_so;
+      for (int i = 0; i < M; ++i) p.adj[i] = sview(c, i, v[i].p);
     };
     auto lds_need = [&](const BwdTiledParams &p, size_t &row_off, size_t &col_off, size_t &all_off) {
       size_t o = 0;
@@ -933,28 +971,54 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         reset(cur);
       }
       BwdEntry &en = cur.e[cur.n_entries++];
-      for (int i = 0; i < M; ++i) en.P[i] = tview(c, M + i * ND + j, v[M + i * ND + j].p);
+      for (int i = 0; i < M; ++i) en.P[i] = sview(c, M + i * ND + j, v[M + i * ND + j].p);
       en.g = tview(c, g0 + j, v[g0 + j].p);
       en.cls = cls[j];
       en.ws_off = 0;
       en.direct = 1;
+      en.outer_sum = outer_sum[j];
+      // the second pass's view of this gradient's partial sums (layouts: see Pass2Job); a gradient that
+      // keeps the outer dim has O times the outputs, one summed over it O times the partials per output
+      const int64_t O = s2.O, tiles_ps = g.n_ct * g.n_rt;
+      const bool kept = O > 1 && !outer_sum[j];
       Pass2Job job{};
       job.g = en.g.p;
+      job.g_outer_stride = en.g.so;
+      job.n_outer = kept ? O : 1;
       if (cls[j] == kGradRowSum) {
         en.slot = cur.n_row_slots++;
-        en.direct = g.n_ct == 1;
-        job = Pass2Job{en.g.p, en.g.sr, s2.R, g.n_ct, 1, g.n_ct, 0, 0, 0, g.n_ct <= 256 ? 0 : 1, 0};
-        job.n_blocks = job.kind == 0 ? ceil_div(s2.R, kBlock / 64) : s2.R;
+        en.direct = g.n_ct == 1 && !outer_sum[j];
+        job.g_stride = en.g.sr;
+        job.outer_major = 0;  // output (r, o) = r * O + o
+        job.n_out = kept ? s2.R * O : s2.R;
+        job.n_part = kept ? g.n_ct : g.n_ct * O;
+        job.part_stride = 1;
+        job.out_stride = job.n_part;
+        job.kind = job.n_part <= 256 ? 0 : 1;
+        job.n_blocks = job.kind == 0 ? ceil_div(job.n_out, kBlock / 64) : job.n_out;
       } else if (cls[j] == kGradColSum) {
         en.slot = cur.n_col_slots++;
-        en.direct = g.n_rt == 1;
+        en.direct = g.n_rt == 1 && !outer_sum[j];
+        job.g_stride = en.g.sc;
+        job.outer_major = 1;  // output (o, c) = o * C + c
+        job.n_out = kept ? O * s2.C : s2.C;
+        job.n_part = kept ? g.n_rt : g.n_rt * O;
+        job.part_stride = kept ? O * s2.C : s2.C;
+        job.out_stride = 1;
         // many partials per output: 16 outputs per block, each summed by 16 groups of lanes
-        job = g.n_rt <= 32 ? Pass2Job{en.g.p, en.g.sc, s2.C, g.n_rt, s2.C, 1, 0, 0, ceil_div(s2.C, 64), 2, 0}
-                           : Pass2Job{en.g.p, en.g.sc, s2.C, g.n_rt, s2.C, 1, 0, 0, ceil_div(s2.C, 16), 3, 0};
+        job.kind = job.n_part <= 32 ? 2 : 3;
+        job.n_blocks = ceil_div(job.n_out, job.kind == 2 ? 64 : 16);
       } else if (cls[j] == kGradAllSum) {
         en.slot = cur.n_all_slots++;
-        en.direct = g.n_ct * g.n_rt == 1;
-        job = Pass2Job{en.g.p, 0, 1, g.n_ct * g.n_rt, 1, 0, 0, 0, 1, 1, 0};
+        en.direct = tiles_ps == 1 && !outer_sum[j];
+        job.g_stride = 0;
+        job.outer_major = 1;  // output o
+        job.n_out = kept ? O : 1;
+        job.n_part = kept ? tiles_ps : tiles_ps * O;
+        job.part_stride = kept ? O : 1;
+        job.out_stride = kept ? 1 : 0;
+        job.kind = 1;
+        job.n_blocks = job.n_out;
       }
       if (!en.direct) {
         en.ws_off = (int64_t)ws;
@@ -975,6 +1039,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
         const TView tv = tview(c, a0 + j, v[a0 + j].p);
         ra.arg_p[j] = tv.p;
         ra.arg_sr[j] = tv.sr;
+        ra.arg_so[j] = tv.so;
         if (tv.sr == 0) ra.row_invariant |= 1u << j;
         if (tv.sc == 0) ra.col_invariant |= 1u << j;
       }
@@ -992,7 +1057,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     plan.info.ty = TY;
     plan.info.rows_per_block = rows_pb;
     plan.info.grid_x = g.n_ct;
-    plan.info.grid_y = g.n_rt;
+    plan.info.grid_y = g.n_rt * s2.O;
     plan.info.n_launches = (int)plan.main.size() + (p2_blocks > 0 ? 1 : 0);
     plan.info.n_second_pass = plan.p2.n_jobs;
     // the class-specialised kernels exist for the widest vector only

@@ -18,10 +18,20 @@ constexpr int kBlock = 256;  // threads per block of every tiled kernel (4 wavef
 // (row_stride of the parameter block): both parts are then computed once per row step and
 // serve every plane.  Otherwise (uniform_stride == 0: arguments or gradients that are slices
 // of wider buffers) a second instantiation of the kernels forms them per view from its own sr.
+// A problem of three merged dims is a batch of O such 2-D problems (slices): the block grid is
+// laid out O times, a block takes its slice from its index, and element (o, r, c) of a view lives
+// at p + o*so + r*sr + c*sc.  Views that vary along all dims normally share so as well as sr.
 struct TView {
   void *p;
   int64_t sr;
   int64_t sc;
+  int64_t so;
+};
+// A view the backward kernels stream with vector loads (an adjoint, a plane): its column stride is 1.
+struct SView {
+  void *p;
+  int64_t sr;
+  int64_t so;
 };
 
 struct FwdTiledParams {
@@ -31,8 +41,11 @@ struct FwdTiledParams {
   int32_t nt_store;    // non-temporal stores
   int32_t has_partials;
   int32_t xcd_remap;   // 1: consecutive tiles go to one XCD (block b of a grid of 8 n serves tile (b % 8) n + b / 8)
-  int64_t n_ct;        // column tiles; block b serves column tile b % n_ct of row tile b / n_ct
+  int64_t n_ct;        // column tiles; block b of a slice serves column tile b % n_ct of row tile b / n_ct
   int64_t row_stride;  // elements between rows of every full-shape view (0 when R == 1)
+  int64_t O;           // slices (extent of the outer dim of a 3-D problem; 1 otherwise)
+  int64_t tiles_per_slice;  // blocks per slice; block B of the grid serves block B % tiles_per_slice of slice B / tiles_per_slice
+  int64_t outer_stride;     // elements between slices of every full-shape view (0 when O == 1)
   uint32_t row_invariant;  // bit j: argument j does not vary along the rows
   uint32_t col_invariant;  // bit j: argument j does not vary along the columns
   // pointers are kept apart from the rarely used strides so that a few wide scalar loads
@@ -51,6 +64,12 @@ struct FwdTiledParams {
   int32_t ragged;
   int64_t out_sr[BCAST_MAX_OUTS];
   int64_t part_sr[BCAST_MAX_PLANES];
+  // outer strides (3-D problems): of every argument, always used; of outputs, planes and branch ids, used
+  // like the row strides above when the views do not share one
+  int64_t arg_so[BCAST_MAX_ARGS];
+  int64_t out_so[BCAST_MAX_OUTS];
+  int64_t part_so[BCAST_MAX_PLANES];
+  int64_t branch_so;
 };
 
 // A strided view of up to BCAST_MAX_DIMS merged dims for the generic kernels.
@@ -80,13 +99,13 @@ enum GradClass : int32_t {
 };
 
 struct BwdEntry {
-  TView P[BCAST_MAX_OUTS];  // planes d Y_i / d X_j for this j; p == nullptr: zeros
+  SView P[BCAST_MAX_OUTS];  // planes d Y_i / d X_j for this j; p == nullptr: zeros
   TView g;                  // gradient view (sr/sc are 0 on reduced dims)
   int32_t cls;
   int32_t slot;             // index among the entries of the same class in this launch
   int64_t ws_off;           // byte offset of this entry's partial sums in the workspace
   int32_t direct;           // 1: this launch writes the final gradient (no second pass)
-  int32_t pad;
+  int32_t outer_sum;        // 1: the gradient is also summed over the slices of a 3-D problem (always through the second pass)
 };
 
 struct BwdTiledParams {
@@ -101,10 +120,11 @@ struct BwdTiledParams {
   int32_t ragged;      // as in FwdTiledParams (the run-time-table and recompute kernels only)
   int32_t n_row_slots, n_col_slots, n_all_slots;
   uint32_t lds_row_off, lds_col_off, lds_all_off;  // byte offsets into dynamic LDS
-  int64_t n_ct, n_rt;  // column tiles, row tiles; block b = rt * n_ct + ct
+  int64_t n_ct, n_rt;  // column tiles, row tiles of one slice; block b of a slice = rt * n_ct + ct
   int64_t row_stride;  // elements between rows of every full-shape view (0 when R == 1)
+  int64_t O, tiles_per_slice, outer_stride;  // as in FwdTiledParams
   unsigned char *ws;
-  TView adj[BCAST_MAX_OUTS];
+  SView adj[BCAST_MAX_OUTS];
   BwdEntry e[BCAST_MAX_ARGS];
 };
 
@@ -114,14 +134,23 @@ struct RecomputeArgs {
   uint32_t row_invariant, col_invariant;   // as in FwdTiledParams
   const void *arg_p[BCAST_MAX_ARGS];
   int64_t arg_sr[BCAST_MAX_ARGS];
+  int64_t arg_so[BCAST_MAX_ARGS];
   int8_t entry_of[BCAST_MAX_ARGS];         // differentiable argument jd -> row of the gradient table, -1: skipped
 };
 
 // second pass: one job per gradient that needs it
+// Workspace layouts of the main pass (accumulator elements; O slices, o the block's slice):
+//   row sums  [(r * O + o) * n_ct + ct]      column sums  [(rt * O + o) * C + c]      full sums  [b * O + o]
+// (b: block within its slice).  A gradient that keeps the outer dim has O times the outputs, one that sums over
+// it O times the partials per output; with O = 1 these are the layouts of a 2-D problem.
 struct Pass2Job {
   void *g;              // final gradient
-  int64_t g_stride;     // elements between consecutive outputs
-  int64_t n_out;        // outputs of this job
+  int64_t g_stride;     // elements between consecutive outputs of one slice
+  int64_t g_outer_stride;  // elements between slices (outputs that keep the outer dim)
+  int64_t n_outer;      // 1, or O when the outputs keep the outer dim: output index = (inner, slice) ...
+  int32_t outer_major;  // ... as slice * n_inner + inner (1) or inner * n_outer + slice (0)
+  int32_t pad0;
+  int64_t n_out;        // outputs of this job (over all slices)
   int64_t n_part;       // partial sums per output
   int64_t part_stride;  // in accumulator elements: between partials of one output
   int64_t out_stride;   // in accumulator elements: between outputs

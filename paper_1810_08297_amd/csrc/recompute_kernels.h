@@ -10,6 +10,9 @@ namespace bd {
 
 template <class T> struct type_tag { using type = T; };
 
+// a launch's arguments are limited to 4 KiB
+static_assert(sizeof(BwdTiledParams) + sizeof(RecomputeArgs) <= 4096, "the recompute kernel's two parameter blocks exceed the kernel argument limit");
+
 // PATTERN: 0 = the class of every gradient is read from the table at run time; otherwise 3 bits
 // per differentiable argument (class + 1), and if no class sums over rows the block handles one
 // row step without a loop.
@@ -79,9 +82,9 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
       constexpr int form = arg_form<Op, PATTERN>(j);
       avec[j] = LV(T(0));
       if constexpr (form == kFormFull)
-        avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
+        avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j], ra.arg_so[j]), voff(ra.arg_sr[j])));
       else if constexpr (form == kFormRowVector)
-        avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(at<const T>(ra.arg_p[j], col_off));
+        avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(at<const T>(static_cast<const T *>(ra.arg_p[j]) + g.slice * ra.arg_so[j], col_off));
       else if constexpr (form == kFormRuntime) {
         const bool colinv = (ra.col_invariant >> j) & 1u;
         if constexpr (PATTERN != 0) {
@@ -89,13 +92,13 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
           // form does not apply the lane reads the first adjoint's vector instead (valid
           // memory that is loaded anyway) and the result is replaced by zero bits
           const bool rowinv = (ra.row_invariant >> j) & 1u;
-          const LV x = load_lane_vec<T, VEC, false, RAGGED>(colinv   ? at<const T>(rs.base(p.adj[0].p, p.adj[0].sr), voff(p.adj[0].sr))
-                                             : rowinv ? at<const T>(ra.arg_p[j], col_off)
-                                                      : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
+          const LV x = load_lane_vec<T, VEC, false, RAGGED>(colinv   ? at<const T>(rs.base(p.adj[0]), voff(p.adj[0].sr))
+                                             : rowinv ? at<const T>(static_cast<const T *>(ra.arg_p[j]) + g.slice * ra.arg_so[j], col_off)
+                                                      : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j], ra.arg_so[j]), voff(ra.arg_sr[j])));
           avec[j] = colinv ? LV(T(0)) : x;
         } else if (!colinv) {
-          avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(((ra.row_invariant >> j) & 1u) ? at<const T>(ra.arg_p[j], col_off)
-                                                                                           : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j]), voff(ra.arg_sr[j])));
+          avec[j] = load_lane_vec<T, VEC, kRecArgNt, RAGGED>(((ra.row_invariant >> j) & 1u) ? at<const T>(static_cast<const T *>(ra.arg_p[j]) + g.slice * ra.arg_so[j], col_off)
+                                                                                           : at<const T>(rs.base(ra.arg_p[j], ra.arg_sr[j], ra.arg_so[j]), voff(ra.arg_sr[j])));
         }
       }
     });
@@ -104,22 +107,22 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
       constexpr int form = arg_form<Op, PATTERN>(j);
       asc[j] = T(0);
       if constexpr (form == kFormColVector)
-        asc[j] = static_cast<const T *>(ra.arg_p[j])[r_ld * ra.arg_sr[j]];
+        asc[j] = static_cast<const T *>(ra.arg_p[j])[g.slice * ra.arg_so[j] + r_ld * ra.arg_sr[j]];
       else if constexpr (form == kFormScalar)
-        asc[j] = static_cast<const T *>(ra.arg_p[j])[0];
+        asc[j] = static_cast<const T *>(ra.arg_p[j])[g.slice * ra.arg_so[j]];
       else if constexpr (form == kFormRuntime) {
         const bool colinv = (colinv_again >> j) & 1u;
         if constexpr (PATTERN != 0) {  // element 0 exists for every argument
-          const T x = static_cast<const T *>(ra.arg_p[j])[(colinv && !((ra.row_invariant >> j) & 1u)) ? r_ld * ra.arg_sr[j] : 0];
+          const T x = static_cast<const T *>(ra.arg_p[j])[g.slice * ra.arg_so[j] + ((colinv && !((ra.row_invariant >> j) & 1u)) ? r_ld * ra.arg_sr[j] : 0)];
           asc[j] = colinv ? x : T(0);
         } else if (colinv) {
-          asc[j] = static_cast<const T *>(ra.arg_p[j])[((ra.row_invariant >> j) & 1u) ? 0 : r_ld * ra.arg_sr[j]];
+          asc[j] = static_cast<const T *>(ra.arg_p[j])[g.slice * ra.arg_so[j] + (((ra.row_invariant >> j) & 1u) ? 0 : r_ld * ra.arg_sr[j])];
         }
       }
     });
     T adj[M][VEC];
 #pragma unroll
-    for (int i = 0; i < M; ++i) load_plane<T, VEC, true, RAGGED>(rs.base(p.adj[i].p, p.adj[i].sr), rs.lane(p.adj[i].sr), valid, adj[i], g.shift);
+    for (int i = 0; i < M; ++i) load_plane<T, VEC, true, RAGGED>(rs.base(p.adj[i]), rs.lane(p.adj[i].sr), valid, adj[i], g.shift);
 #pragma unroll
     for (int j = 0; j < N; ++j)  // the opaque point after the last load
       if (arg_form<Op, PATTERN>(j) == kFormRuntime) {
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
         constexpr int fixed = (int)((PATTERN >> (3 * jd)) & 7u);
         const int cls = fixed ? fixed - 1 : en.cls;
         if (cls == kGradFull)
-          apply_full<T, VEC, M, true, RAGGED>(rs.base(en.g.p, en.g.sr), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
+          apply_full<T, VEC, M, true, RAGGED>(rs.base(en.g), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
         else if (cls == kGradRowSum)
           apply_rowsum<T, VEC, M>(p, g, en, adj, P, r, ri);
         else if (cls == kGradColSum)

@@ -426,11 +426,11 @@ def test_lean_plane_layout_gives_identical_results(dtype):
 
 
 def test_recompute_refuses_what_it_cannot_do_and_skips_null_gradients():
-    # rank 3 that does not merge to two dims: only the plane-reading path has generic kernels
+    # four dims of which no two merge: only the plane-reading path has generic kernels
     rng = np.random.default_rng(4)
-    x = to_dev(rng.standard_normal((3, 1, 5)).astype(np.float32))
-    t = to_dev(rng.standard_normal((1, 4, 1)).astype(np.float32))
-    adj = to_dev(rng.standard_normal((3, 4, 5)).astype(np.float32))
+    x = to_dev(rng.standard_normal((3, 1, 5, 1)).astype(np.float32))
+    t = to_dev(rng.standard_normal((1, 4, 1, 6)).astype(np.float32))
+    adj = to_dev(rng.standard_normal((3, 4, 5, 6)).astype(np.float32))
     op = P.bcast_op_lookup("scale_xt")
     with pytest.raises(P.BcastError) as e:
         P.bcast_dual_backward_recompute(op, [x, t], [adj], [torch.empty_like(x), torch.empty_like(t)])
@@ -1573,8 +1573,10 @@ def test_tall_thin_and_long_flat_problems(shape):
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
 def test_rank3_problem_takes_vectors_along_the_innermost_dim(dtype):
     """An argument broadcast along the middle dim only keeps the problem at rank 3 (no two dims
-    merge): the generic kernels serve it, with 16-byte accesses along the contiguous innermost dim
-    where every view allows them and element by element where one does not."""
+    merge).  The tiled kernels take it as a batch of two-dim slices; the generic kernels (forced
+    here) serve it with 16-byte accesses along the contiguous innermost dim where every view
+    allows them and element by element where one does not."""
+    generic = P.Options(force_generic=1)
     rng = np.random.default_rng(314)
     T_, B_, H_ = 6, 10, 64
     A = rng.standard_normal((T_, B_, H_)).astype(dtype)
@@ -1586,15 +1588,19 @@ def test_rank3_problem_takes_vectors_along_the_innermost_dim(dtype):
     dev = [to_dev(x) for x in (A, Bm, r, s, t)]
     fb = P.alloc_forward("branchy5", dev, want_branch=True)
     info = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials, fb.branch)
+    assert info["path"] == 1 and info["ndim"] == 3 and info["shape"] == [T_, B_, H_], info
+    info = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials, fb.branch, options=generic)
     assert info["path"] == 2 and info["ndim"] == 3 and info["vec"] == (4 if dtype == np.float32 else 2), info
-    check_op("branchy5", [A, Bm, r, s, t], adj, what="rank 3, vectors ")
+    check_op("branchy5", [A, Bm, r, s, t], adj, what="rank 3 as slices ", recompute="required")
+    check_op("branchy5", [A, Bm, r, s, t], adj, what="rank 3, generic, vectors ", options=generic)
     # an innermost extent that is not a multiple of the vector, and a view with padded rows whose
-    # stride is not one either: element by element
+    # stride is not one either: element by element on the generic kernels
     A2, B2, r2, adj2 = A[..., :63], Bm[..., :63], r[..., :63], [adj[0][..., :63]]
     dev2 = [to_dev(x) for x in (A2, B2, r2, s, t)]
     f2 = P.alloc_forward("branchy5", dev2)
-    assert P.bcast_dual_forward_plan(f2.op_id, dev2, f2.outs, f2.partials)["vec"] == 1
-    check_op("branchy5", [A2, B2, r2, s, t], adj2, what="rank 3, elements ")
+    assert P.bcast_dual_forward_plan(f2.op_id, dev2, f2.outs, f2.partials, options=generic)["vec"] == 1
+    check_op("branchy5", [A2, B2, r2, s, t], adj2, what="rank 3 as slices, rows of 63 ", recompute="required")
+    check_op("branchy5", [A2, B2, r2, s, t], adj2, what="rank 3, generic, elements ", options=generic)
 
     def padded(tn, k):  # rows padded by 3 elements: outer strides 67 and 670 keep no vector boundary
         if k != 0:
@@ -1603,15 +1609,18 @@ def test_rank3_problem_takes_vectors_along_the_innermost_dim(dtype):
         wide[..., :H_] = tn
         return wide[..., :H_]
 
-    check_op("branchy5", [A, Bm, r, s, t], adj, view=padded, what="rank 3, one padded view ")
+    check_op("branchy5", [A, Bm, r, s, t], adj, view=padded, what="rank 3 as slices, one padded view ")
+    check_op("branchy5", [A, Bm, r, s, t], adj, view=padded, what="rank 3, generic, one padded view ", options=generic)
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
 def test_rank3_reductions_of_many_chunks(dtype):
-    """Rank-3 problems large enough that the generic reductions cut their fibres into chunks
-    (partial sums in the workspace, final kernel), in both lane arrangements: fibres along the
-    contiguous dim (gradients [1 x B x 1], [T x 1 x 1], scalar) and gradients along it
-    ([T x 1 x H], [1 x 1 x H])."""
+    """Rank-3 problems with every kind of reduced gradient -- kept or summed along the outer dim,
+    along rows, along columns: [T x 1 x H], [1 x B x 1], [1 x 1 x H], [T x 1 x 1], scalar -- on the
+    tiled kernels (a batch of slices: one main launch and the second pass) and on the generic kernels,
+    large enough that those cut their fibres into chunks (partial sums in the workspace, final
+    kernel), in both lane arrangements."""
+    generic = P.Options(force_generic=1)
     rng = np.random.default_rng(2718)
     T_, B_, H_ = 24, 70, 1030
     full = (T_, B_, H_)
@@ -1626,9 +1635,23 @@ def test_rank3_reductions_of_many_chunks(dtype):
         grads = [torch.empty(sh, dtype=dev[0].dtype, device="cuda") for sh in shapes]
         adj_dev = [to_dev(adj[0])]
         info = P.bcast_dual_backward_plan(adj_dev, fb.partials, grads)
+        assert info["path"] == 1 and info["ndim"] == 3 and info["n_launches"] == 2 and info["n_second_pass"] == 3, info
+        info = P.bcast_dual_backward_plan(adj_dev, fb.partials, grads, options=generic)
         assert info["path"] == 2 and info["ndim"] == 3 and info["n_launches"] > 5  # some reductions need the final kernel
-        assert P.bcast_dual_backward_workspace(adj_dev, fb.partials, grads) > 0
-        check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what=f"r {rs} s {ss} t {ts} ")
+        assert P.bcast_dual_backward_workspace(adj_dev, fb.partials, grads, options=generic) > 0
+        check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what=f"slices: r {rs} s {ss} t {ts} ", recompute="required")
+        for steps in (1, 5):  # few and many partial sums per output for the second pass
+            check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what=f"slices, {steps} row steps per block: r {rs} s {ss} t {ts} ",
+                     options=P.Options(bwd_row_steps=steps), recompute=False)
+        check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what=f"generic: r {rs} s {ss} t {ts} ", options=generic)
+    # a gradient with the shape of a slice, summed over the slices only, stays with the generic kernels
+    r, s, t = (rng.standard_normal(sh).astype(dtype) for sh in ((1, B_, H_), (1, B_, 1), (T_, 1, 1)))
+    dev = [to_dev(x) for x in (A, Bm, r, s, t)]
+    fb = gpu_forward("branchy5", dev)
+    assert P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials)["path"] == 1
+    grads = [torch.empty(x.shape, dtype=dev[0].dtype, device="cuda") for x in (A, Bm, r, s, t)]
+    assert P.bcast_dual_backward_plan([to_dev(adj[0])], fb.partials, grads)["path"] == 2
+    check_op("branchy5", [A, Bm, r, s, t], adj, threads=16, what="r [1 x B x H] ")
 
 
 def _offset_by_one_element(t, k):

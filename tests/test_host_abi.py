@@ -646,10 +646,12 @@ def test_launching_wrappers_refuse_host_tensors():
         P.broadcast("tanh_xy_b", x, y, b)
 
 
-def test_generic_path_plans_chunked_reductions():
-    """A problem that stays at rank 3 runs on the generic kernels: vectors along the innermost dim
-    where the views allow it, and reductions over long fibres cut into chunks, which need
-    workspace for their partial sums and one more small launch each."""
+def test_rank3_problem_plans_as_slices_and_on_the_generic_kernels():
+    """A problem that stays at rank 3 (an argument broadcast along the middle dim only) is a batch of
+    two-dim slices for the tiled kernels: one block grid per slice, one main backward launch, reduced
+    gradients kept or summed along the outer dim through the second pass.  Forced onto the generic
+    kernels it takes vectors along the innermost dim where the views allow it, and reductions over long
+    fibres are cut into chunks, which need workspace for their partial sums and one more small launch each."""
     T_, B_, H_ = 64, 256, 1024
     base = [1 << 40]
 
@@ -662,24 +664,51 @@ def test_generic_path_plans_chunked_reductions():
         return B.raw_view(base[0], shape, tuple(reversed(strides)))
 
     full, rs, ss, ts = (T_, B_, H_), (T_, 1, H_), (1, B_, 1), (1, 1, 1)
-    op = P.bcast_op_lookup("branchy5")
     args = [view(full), view(full), view(rs), view(ss), view(ts)]
     outs, parts = [view(full)], [view(full) for _ in range(5)]
-    rc, d = _fwd_plan("branchy5", 0, args, outs, parts)
-    assert rc == 0 and d["path"] == 2 and d["ndim"] == 3 and d["vec"] == 4
     adj, grads = [view(full)], [view(full), view(full), view(rs), view(ss), view(ts)]
-    info = B.PlanInfo()
     L = B.lib()
+    info = B.PlanInfo()
+    # tiled: 64 slices of [256 x 1024]; one row per block step, 256 blocks per slice
+    rc, d = _fwd_plan("branchy5", 0, args, outs, parts)
+    assert rc == 0 and d["path"] == 1 and d["ndim"] == 3 and d["shape"] == [T_, B_, H_] and d["vec"] == 4
+    assert d["uniform_stride"] == 1 and d["grid_x"] == 1 and d["grid_y"] == T_ * B_
     rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
                                     ctypes.c_int32(5), B._views(grads), ctypes.byref(info), None)
-    # two elementwise launches, three reductions, each cut into chunks and followed by its final kernel
-    assert rc == 0 and info.path == 2 and info.n_launches == 2 + 3 + 3
+    # the kernel compiled for branchy5's mix (2 full, 1 row-sum, 1 col-sum, 1 all-sum per slice) + the second pass
+    assert rc == 0 and info.path == 1 and info.n_launches == 2 and info.specialized == 1 and info.n_second_pass == 3
     ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
                                          ctypes.c_int32(5), B._views(grads), None)
-    assert 0 < ws < (1 << 22)  # 65536 x 2 partial sums of 8 bytes for the [T x 1 x H] gradient, a few KiB for the others
+    assert 0 < ws < (1 << 24)
     rc = L.bcast_dual_backward(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts), ctypes.c_int32(5),
                                B._views(grads), None, ctypes.c_size_t(0), None, None)
     assert rc == -3  # the workspace is asked for before anything is launched
+    # the recompute entry point takes the slices too
+    op = P.bcast_op_lookup("branchy5")
+    rc = L.bcast_dual_backward_recompute_plan(ctypes.c_int32(op), ctypes.c_int(0), ctypes.c_int32(5), B._views(args), ctypes.c_int32(1),
+                                              B._views(adj), ctypes.c_int32(5), B._views(grads), ctypes.byref(info), None)
+    assert rc == 0 and info.path == 1 and info.ndim == 3
+    # a gradient shaped like one slice (summed over the outer dim only): generic kernels
+    g2 = [view(full), view(full), view((1, B_, H_)), view(ss), view(ts)]
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                    ctypes.c_int32(5), B._views(g2), ctypes.byref(info), None)
+    assert rc == 0 and info.path == 2
+    # forced onto the generic kernels
+    generic = P.Options(force_generic=1)
+    rc, d = _fwd_plan("branchy5", 0, args, outs, parts, generic)
+    assert rc == 0 and d["path"] == 2 and d["ndim"] == 3 and d["vec"] == 4
+    rc = L.bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                    ctypes.c_int32(5), B._views(grads), ctypes.byref(info), ctypes.byref(generic))
+    # two elementwise launches, three reductions, each cut into chunks and followed by its final kernel
+    assert rc == 0 and info.path == 2 and info.n_launches == 2 + 3 + 3
+    ws = L.bcast_dual_backward_workspace(ctypes.c_int(0), ctypes.c_int32(1), B._views(adj), B._views(parts),
+                                         ctypes.c_int32(5), B._views(grads), ctypes.byref(generic))
+    assert 0 < ws < (1 << 22)  # 65536 x 2 partial sums of 8 bytes for the [T x 1 x H] gradient, a few KiB for the others
+    # four dims that do not merge stay with the generic kernels
+    f4, r4 = (6, 5, 4, 64), (6, 1, 4, 1)
+    a4 = [view(f4), view(f4), view((1, 5, 1, 64)), view(r4), view((1, 1, 1, 1))]
+    rc, d = _fwd_plan("branchy5", 0, a4, [view(f4)], [view(f4) for _ in range(5)])
+    assert rc == 0 and d["path"] == 2 and d["ndim"] == 4
 
 
 def test_backward_and_recompute_plans_for_rows_the_vector_does_not_fit():
