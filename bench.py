@@ -383,7 +383,45 @@ def main():
     # unfused comparison: one library kernel per primitive, both branches + select, reverse mode
     unfused_extra = None
     if a.unfused_baseline:
-        from paper_1810_08297_amd.unfused_baseline import UnfusedStep
+        from paper_1810_08297_amd.unfused_baseline import UnfusedPrimitives, UnfusedStep
+        # the library's own per-primitive kernels (written from the math), then the same chain on torch's
+        prim = None
+        try:
+            up = UnfusedPrimitives(op, dev, adj_dev)
+        except (KeyError, ValueError):
+            up = None
+        if up is not None:
+            for _ in range(3):
+                n_k = up.run(sptr)[2]
+            torch.cuda.synchronize()
+            n_un = max(5, a.steps // 4)
+            t0 = time.perf_counter()
+            for _ in range(n_un):
+                up.run(sptr)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            prim = {"value": round(E * n_un / wall, 1), "unit": "elements/s", "steps": n_un, "ms_per_step": round(wall * 1e3 / n_un, 5),
+                    "kernels_per_step": n_k, "kind": "the library's per-primitive kernels, reverse mode rule by rule"}
+            g = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            with torch.cuda.stream(side):
+                up.run()
+            stream.wait_stream(side)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g):
+                up.run()
+            for _ in range(3):
+                g.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n_un):
+                g.replay()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            prim["graph_replay"] = {"value": round(E * n_un / wall, 1), "ms_per_step": round(wall * 1e3 / n_un, 5)}
+            del up, g
+            torch.cuda.empty_cache()
         ust = UnfusedStep(op, dev, adj_dev)
         for _ in range(max(3, a.warmup // 4)):
             ust.run()
@@ -419,6 +457,7 @@ def main():
             unfused_extra["graph_replay"] = {"value": round(E * n_un / wall, 1), "ms_per_step": round(wall * 1e3 / n_un, 5)}
         except Exception as e:  # capture of library kernels is best effort; the eager number stands
             unfused_extra["graph_replay"] = {"error": str(e)[:200]}
+        unfused_extra = {"per_primitive_hip_kernels": prim, "torch_elementwise_autograd": unfused_extra}
 
     cpu = None
     if not a.no_cpu_baseline:

@@ -281,6 +281,26 @@ int bcast_dual_backward_recompute_plan(int32_t op_id, bcast_dtype dt, int32_t n_
                                        int32_t n_out, const bcast_tensor *adjoints, int32_t n_grads,
                                        const bcast_tensor *grads, bcast_plan_info *info, const bcast_dual_options *opt);
 
+/* ---- unfused comparison: one kernel per primitive, reverse mode (Sec. 3.2.1, 3.2.2) -----------
+ * Not the method: the comparison system the paper measures it against, written from the math.  The op's
+ * scalar function becomes a chain of whole-array primitives (add, mul, sigmoid, tanh, exp, log1p, compare,
+ * select, ...), each a kernel launch with its result in a temporary; every branch is computed for every
+ * element and chosen by select; the reverse pass applies each primitive's own derivative rule, again one
+ * kernel per rule, and sums a broadcast argument's gradient over its expanded dims with a reduction kernel.
+ * For timing beside bcast_dual_forward + bcast_dual_backward; available for "hmlstm_update", "update_c",
+ * "tanh_xy_b" and "branchy5" (else BCAST_ERR_UNSUPPORTED).
+ * Every array is contiguous, row major, [rows x cols]; arg_kind[j] says what argument j is.  The gates,
+ * cell and hidden state of the two cell updates, and A and B of branchy5, must be full arrays.
+ * outs[n_out] (written), adjoints[n_out] (read): full arrays.  grads[n_grads = N_d] (written): each in its
+ * argument's shape.  workspace: at least bcast_unfused_workspace(...) bytes, 256-byte aligned.
+ * n_kernels (may be NULL) receives the number of kernels the call enqueued. */
+enum { BCAST_UNFUSED_FULL = 0, BCAST_UNFUSED_ROW_VECTOR = 1 /* [1 x cols] */, BCAST_UNFUSED_COL_VECTOR = 2 /* [rows x 1] */,
+       BCAST_UNFUSED_SCALAR = 3 };
+size_t bcast_unfused_workspace(int32_t op_id, bcast_dtype dt, int64_t rows, int64_t cols);
+int bcast_unfused_step(int32_t op_id, bcast_dtype dt, int64_t rows, int64_t cols, int32_t n_args, const void *const *args,
+                       const int32_t *arg_kind, int32_t n_out, void *const *outs, const void *const *adjoints, int32_t n_grads,
+                       void *const *grads, void *workspace, size_t workspace_bytes, void *stream, int32_t *n_kernels);
+
 /* ---- misc ---------------------------------------------------------------------- */
 const char *bcast_status_string(int status);
 

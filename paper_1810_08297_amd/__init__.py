@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     bcast_dual_forward, bcast_dual_forward_plan, bcast_dual_backward_workspace,
     bcast_dual_backward, bcast_dual_backward_plan, bcast_dual_backward_noalloc, NOALLOC_SCRATCH_BYTES, bcast_dual_stream_probe, bcast_dual_slab_layout, status_string, as_view, raw_view, PreparedForward, PreparedBackward, PreparedRecompute,
     bcast_dual_backward_recompute, bcast_dual_backward_recompute_workspace, bcast_dual_backward_recompute_plan,
+    bcast_unfused_workspace, bcast_unfused_step,
 )
 from .helpers import ForwardBuffers, BackwardBuffers, alloc_forward, alloc_backward, alloc_planes, to_slab, alloc_recompute, LaunchTimer  # noqa: F401
 from .autograd import broadcast  # noqa: F401

@@ -86,6 +86,7 @@ EXPORTS = ("bcast_op_lookup", "bcast_op_count", "bcast_op_name", "bcast_op_info"
            "bcast_dual_forward_plan", "bcast_dual_backward_workspace", "bcast_dual_backward",
            "bcast_dual_backward_plan", "bcast_dual_backward_noalloc", "bcast_status_string", "bcast_dual_options_default",
            "bcast_dual_stream_probe", "bcast_dual_slab_layout", "bcast_op_plane_alias",
+           "bcast_unfused_workspace", "bcast_unfused_step",
            "bcast_dual_backward_recompute", "bcast_dual_backward_recompute_workspace",
            "bcast_dual_backward_recompute_plan")
 
@@ -128,6 +129,9 @@ def lib():
             "bcast_dual_slab_layout": (sz, [sz, i32, ctypes.POINTER(sz)]),
             "bcast_dual_stream_probe": (cint, [i32, ctypes.POINTER(vp), ctypes.POINTER(i64), i32, ctypes.POINTER(vp),
                                                ctypes.POINTER(i64), i64, vp, O]),
+            "bcast_unfused_workspace": (sz, [i32, cint, i64, i64]),
+            "bcast_unfused_step": (cint, [i32, cint, i64, i64, i32, ctypes.POINTER(vp), ctypes.POINTER(i32), i32, ctypes.POINTER(vp),
+                                          ctypes.POINTER(vp), i32, ctypes.POINTER(vp), vp, sz, vp, ctypes.POINTER(i32)]),
         }
         assert set(proto) == set(EXPORTS)
         for name, (res, argt) in proto.items():
@@ -438,3 +442,45 @@ class PreparedRecompute:
         _check(self._fn(self._op, self._dt, self._na, self._a, self._no, self._o, self._ng, self._g, self._ws,
                         self._wsb, _stream_ptr(stream), self._opt if options is None else ctypes.byref(options)),
                "bcast_dual_backward_recompute")
+
+
+# ---- unfused comparison (one kernel per primitive, reverse mode) ------------------------------
+UNFUSED_FULL, UNFUSED_ROW_VECTOR, UNFUSED_COL_VECTOR, UNFUSED_SCALAR = 0, 1, 2, 3
+
+
+def _unfused_kind(t, rows, cols):
+    shape = tuple(t.shape)
+    if shape == (rows, cols):
+        return UNFUSED_FULL
+    if shape == (1, cols):
+        return UNFUSED_ROW_VECTOR
+    if shape == (rows, 1):
+        return UNFUSED_COL_VECTOR
+    if shape == (1, 1):
+        return UNFUSED_SCALAR
+    raise ValueError(f"bcast_unfused_step: an argument of shape {shape} in a problem of {rows} x {cols}")
+
+
+def bcast_unfused_workspace(op_id: int, dtype_like, rows: int, cols: int) -> int:
+    return int(lib().bcast_unfused_workspace(ctypes.c_int32(op_id), ctypes.c_int(_dtype_code(dtype_like)),
+                                             ctypes.c_int64(rows), ctypes.c_int64(cols)))
+
+
+def bcast_unfused_step(op_id: int, args, outs, adjoints, grads, workspace, stream=None) -> int:
+    """Enqueue the per-primitive forward + reverse-mode chain; returns the number of kernels launched.
+    All tensors contiguous 2-D device tensors; `outs`, `adjoints` full-shape, `grads` in their argument's shape."""
+    _on_device(args, outs, adjoints, grads, [workspace])
+    rows, cols = outs[0].shape
+    for t in list(args) + list(outs) + list(adjoints) + list(grads):
+        if not t.is_contiguous():
+            raise ValueError("bcast_unfused_step takes contiguous tensors")
+    def ptrs(ts):
+        return (ctypes.c_void_p * max(1, len(ts)))(*[t.data_ptr() for t in ts])
+    kinds = (ctypes.c_int32 * len(args))(*[_unfused_kind(t, rows, cols) for t in args])
+    n = ctypes.c_int32()
+    _check(lib().bcast_unfused_step(
+        ctypes.c_int32(op_id), ctypes.c_int(_dtype_code(outs[0])), ctypes.c_int64(rows), ctypes.c_int64(cols),
+        ctypes.c_int32(len(args)), ptrs(args), kinds, ctypes.c_int32(len(outs)), ptrs(outs), ptrs(adjoints),
+        ctypes.c_int32(len(grads)), ptrs(grads), ctypes.c_void_p(workspace.data_ptr()),
+        ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream_ptr(stream), ctypes.byref(n)), "bcast_unfused_step")
+    return n.value

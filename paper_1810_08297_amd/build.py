@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbcast_dual.so")
 
-SOURCES = ["host.cpp", "bwd_kernels.hip", "ops_core.hip", "ops_misc.hip",
+SOURCES = ["host.cpp", "bwd_kernels.hip", "unfused.hip", "ops_core.hip", "ops_misc.hip",
            "ops_arity_a.hip", "ops_arity_b.hip", "ops_arity_c.hip"]
 
 # packed-fp32 instructions are switched off for device code on purpose

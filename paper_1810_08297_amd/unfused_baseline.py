@@ -1,8 +1,10 @@
-"""Unfused reverse-mode comparison point (stands in for the paper's per-primitive graph
-baseline, Sec. 3.2.1 / 3.4): the same scalar functions written as one library kernel per
-primitive, every branch computed for every element and chosen with a select, differentiated by
-plain reverse mode (torch.autograd).  NOT part of the product path: `bench.py --unfused-baseline`
-times it next to the fused kernels, and one GPU test checks that it computes the same function.
+"""Unfused reverse-mode comparison points (they stand in for the paper's per-primitive graph
+baselines, Sec. 3.2.1 / 3.2.2 / 3.4): the same scalar functions as one kernel per primitive,
+every branch computed for every element and chosen with a select, differentiated by plain
+reverse mode.  Two forms: `UnfusedPrimitives` drives the library's own per-primitive HIP kernels
+(bcast_unfused_step); `UnfusedStep` is the same chain on PyTorch's elementwise kernels and
+torch.autograd.  NOT part of the product path: `bench.py --unfused-baseline` times both next to
+the fused kernels, and GPU tests check that they compute the same function.
 """
 from __future__ import annotations
 
@@ -53,3 +55,27 @@ class UnfusedStep:
         outs = self.fn(*self.args)
         grads = torch.autograd.grad(outs, self.leaves, self.adjoints, allow_unused=True)
         return outs, [g if g is not None else torch.zeros_like(a) for g, a in zip(grads, self.leaves)]
+
+
+class UnfusedPrimitives:
+    """One forward + reverse pass of `op` on the library's per-primitive kernels over fixed device
+    tensors (2-D, contiguous); `run()` enqueues it and returns (outputs, gradients, kernels launched)."""
+
+    def __init__(self, op, args, adjoints):
+        from . import binding as B
+        self.B = B
+        self.op_id = B.bcast_op_lookup(op)
+        self.args = [a.contiguous() for a in args]
+        self.adjoints = [a.contiguous() for a in adjoints]
+        rows, cols = self.adjoints[0].shape
+        n_out = B.bcast_op_info(self.op_id)[1]
+        self.outs = [torch.empty_like(self.adjoints[0]) for _ in range(n_out)]
+        self.grads = [torch.empty_like(self.args[j]) for j in B.diff_arg_indices(self.op_id)]
+        nbytes = B.bcast_unfused_workspace(self.op_id, self.adjoints[0], rows, cols)
+        if nbytes == 0:
+            raise KeyError(f"no unfused program for {op}")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.adjoints[0].device)
+
+    def run(self, stream=None):
+        n = self.B.bcast_unfused_step(self.op_id, self.args, self.outs, self.adjoints, self.grads, self.workspace, stream)
+        return self.outs, self.grads, n

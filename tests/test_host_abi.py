@@ -767,3 +767,33 @@ def test_noalloc_backward_refuses_what_exceeds_its_scratch_array():
     assert rc == -7
     header = open(os.path.join(ROOT, "include", "bcast_dual.h")).read()
     assert f"#define BCAST_NOALLOC_SCRATCH_BYTES ({P.NOALLOC_SCRATCH_BYTES >> 20}u << 20)" in header
+
+
+def test_unfused_step_argument_checks():
+    """bcast_unfused_step validates on the host before anything is launched (addresses never touched)."""
+    L = B.lib()
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    op = P.bcast_op_lookup("tanh_xy_b")
+    R, C = 64, 128
+    assert L.bcast_unfused_workspace(i32(op), ctypes.c_int(0), ctypes.c_int64(R), ctypes.c_int64(C)) >= 8 * R * C * 4
+    assert L.bcast_unfused_workspace(i32(P.bcast_op_lookup("cos_x")), ctypes.c_int(0), ctypes.c_int64(R), ctypes.c_int64(C)) == 0
+    ptr = lambda n: (vp * n)(*[4096 * (k + 1) for k in range(n)])
+    kinds = lambda *k: (i32 * len(k))(*k)
+    n = i32()
+
+    def call(op_id, dt, n_args, kind, n_out, n_grads, ws, ws_bytes):
+        return L.bcast_unfused_step(i32(op_id), ctypes.c_int(dt), ctypes.c_int64(R), ctypes.c_int64(C), i32(n_args), ptr(max(n_args, 1)),
+                                    kind, i32(n_out), ptr(1), ptr(1), i32(n_grads), ptr(max(n_grads, 1)), vp(ws), ctypes.c_size_t(ws_bytes),
+                                    None, ctypes.byref(n))
+    big = 1 << 40
+    assert call(op, 0, 3, kinds(0, 0, 2), 1, 3, 0, big) == -3           # no workspace
+    assert call(op, 0, 3, kinds(0, 0, 2), 1, 3, 4096, 1024) == -8        # workspace too small
+    assert call(op, 0, 3, kinds(0, 0, 2), 1, 3, 4096 + 8, big) == -11    # workspace not 256-byte aligned
+    assert call(op, 0, 2, kinds(0, 0), 1, 3, 4096, big) == -2            # argument count
+    assert call(op, 0, 3, kinds(0, 0, 2), 1, 2, 4096, big) == -2         # gradient count
+    assert call(op, 7, 3, kinds(0, 0, 2), 1, 3, 4096, big) == -7         # dtype
+    assert call(op, 0, 3, kinds(0, 0, 5), 1, 3, 4096, big) == -5         # unknown argument kind
+    assert call(P.bcast_op_lookup("cos_x"), 0, 1, kinds(0), 1, 1, 4096, big) == -12
+    assert call(10 ** 6, 0, 3, kinds(0, 0, 2), 1, 3, 4096, big) == -1
+    b5 = P.bcast_op_lookup("branchy5")
+    assert call(b5, 0, 5, kinds(0, 1, 1, 2, 3), 1, 5, 4096, big) == -12  # B must be a full array
