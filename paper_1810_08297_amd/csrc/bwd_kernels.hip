@@ -113,11 +113,16 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
 #pragma unroll
         for (int i = 0; i < M; ++i) AT::add_prod(allacc[e], adj[0][i][v], P[0][share_src(SHARE, NF + NR + NC + e)][i][v]);
   };
+  // A block that takes several row steps walks them last to first when the tiles are (p.reverse): the
+  // resident blocks all start together, so it is this walk, not the order of the blocks, that decides
+  // whether the rows the forward kernel wrote last -- the ones the memory-side cache may still hold --
+  // are read first.
   const int steps = LOOP ? p.steps : 1;
+  const int k0 = p.reverse ? steps - 1 : 0, dk = p.reverse ? -1 : 1;
   if (g.interior)
-    for (int k = 0; k < steps; ++k) row_step(std::false_type{}, k);
+    for (int n = 0, k = k0; n < steps; ++n, k += dk) row_step(std::false_type{}, k);
   else
-    for (int k = 0; k < steps; ++k) row_step(std::true_type{}, k);
+    for (int n = 0, k = k0; n < steps; ++n, k += dk) row_step(std::true_type{}, k);
   if constexpr (LOOP) {  // slots were handed out in table order within each class
 #pragma unroll
     for (int e = 0; e < NC; ++e)
@@ -145,7 +150,8 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
   const BwdGeom<T, VEC> g(p, smem);
   const int M = MCT > 0 ? MCT : p.M;
   const bool nt = p.nt_store != 0;
-  for (int k = 0; k < p.steps; ++k) {
+  for (int n = 0; n < p.steps; ++n) {
+    const int k = p.reverse ? p.steps - 1 - n : n;  // last to first with the tiles (see bwd_sig_kernel)
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;

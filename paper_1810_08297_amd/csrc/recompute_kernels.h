@@ -58,7 +58,9 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
   const uint32_t col_off = g.colvalid ? g.col_off : 0u;
   uint32_t colinv_again = ra.col_invariant;
   asm volatile("" : "+s"(colinv_again));
-  for (int k = 0; k < (LOOP ? p.steps : 1); ++k) {
+  const int n_steps = LOOP ? p.steps : 1;
+  for (int n = 0; n < n_steps; ++n) {
+    const int k = p.reverse ? n_steps - 1 - n : n;  // last to first with the tiles
     const int ri = k * g.TY + g.ty;
     const int64_t r = g.row(k);
     const bool valid = g.colvalid && r < p.R;
