@@ -471,9 +471,9 @@ using namespace bd;
   X(2, 6, 4, 0, 0, BD_HM_LEAN, BD_HM_SHARE, 0, 1)                         \
   X(2, 6, 0, 4, 0, 0ull, 0ull, 0, 0) /* HM-LSTM update stored [batch x hidden]: per-column biases */ \
   X(2, 6, 0, 4, 0, BD_HM_LEAN, BD_HM_SHARE, 0, 0)                         \
-  X(1, 2, 1, 0, 0, 0ull, 0ull, 1, 0) /* tanh(x*y + b) */                  \
-  X(1, 2, 1, 1, 1, 0ull, 0ull, 0, 0) /* branchy5 */                       \
-  X(1, 2, 1, 1, 1, 1ull << 4, 0ull, 0, 0) /* branchy5 without the always-zero plane of t */ \
+  X(1, 2, 1, 0, 0, 0ull, 0ull, 1, 1) /* tanh(x*y + b) */                  \
+  X(1, 2, 1, 1, 1, 0ull, 0ull, 0, 1) /* branchy5 */                       \
+  X(1, 2, 1, 1, 1, 1ull << 4, 0ull, 0, 1) /* branchy5 without the always-zero plane of t */ \
   X(1, 4, 0, 0, 0, 0ull, 0ull, 0, 0) /* six-argument cell update */       \
   X(1, 1, 0, 0, 0, 0ull, 0ull, 0, 0) X(1, 2, 0, 0, 0, 0ull, 0ull, 0, 0) X(1, 3, 0, 0, 0, 0ull, 0ull, 0, 0) \
   X(1, 5, 0, 0, 0, 0ull, 0ull, 0, 0) X(1, 8, 0, 0, 0, 0ull, 0ull, 0, 0)
