@@ -1579,7 +1579,7 @@ def test_row_expanded_planes_and_second_adjoint():
         assert planes[k].stride() == (0, 1)
         bb = P.alloc_backward(adj_dev, planes, shapes)
         plan = P.bcast_dual_backward_plan(adj_dev, planes, bb.grads)
-        assert plan["path"] == 2 or (plan["specialized"] == 0 and plan["uniform_stride"] == 0), plan
+        assert plan["path"] == 2 or plan["uniform_stride"] == 0, plan
         bb.run(adj_dev, planes)
         torch.cuda.synchronize()
         want = oracle.backward(adj, [p.contiguous().cpu().numpy() for p in planes], shapes, threads=8)
