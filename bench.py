@@ -10,7 +10,7 @@ a "configs" object with every benchmark configuration timed the same way in the 
 
 Workloads: cfg0 cfg1 cfg2 cfg3 (p via --p-index 0|1|2) cfg4 cfg4_f64, paper_n512 /
 paper_n1024 / paper_n2048 (the paper's own experiment shape, Sec. 3.4), hmlstm_<H>x<B>,
-linear12_<H>x<B>.
+linear12_<H>x<B>, branchy5_3d_<O>x<R>x<C>, branchy5_3dm_<O>x<R>x<C>.
 """
 from __future__ import annotations
 
@@ -79,6 +79,13 @@ def build_workload(name, p_index, uniform_run=0):
         args, adj = inputs.hmlstm_inputs(H, Bt, seed=inputs.BASE_SEED + 300 + H + Bt, dtype=dtype, z_per_element=True,
                                          p=inputs.P_SWEEP[p_index])
         op, desc = "linear12", f"linear12 (HM-LSTM traffic, no transcendental) hidden={H} batch={Bt}"
+    elif base.startswith("branchy5_3d"):  # branchy5_3d_<O>x<R>x<C>: r broadcast along the middle dim only; branchy5_3dm_...: shapes that merge to two dims
+        merging = base.startswith("branchy5_3dm_")
+        O, R, C = (int(x) for x in base.split("_")[-1].split("x"))
+        args, adj = inputs.branchy5_3d_inputs(O, R, C, seed=inputs.BASE_SEED + 500 + O + R + C, dtype=dtype, merging=merging)
+        op = "branchy5"
+        desc = (f"branchy5 over [{O} x {R} x {C}], " + (f"r [1 x 1 x {C}], s [{O} x {R} x 1] (merges to two dims)" if merging else
+                                                     f"r [{O} x 1 x {C}], s [1 x {R} x 1] (stays three dims)"))
     elif base.startswith("paper_n"):
         n = int(base[len("paper_n"):])
         args, adj = inputs.update_c_inputs(n, seed=inputs.BASE_SEED + 100 + n, dtype=dtype, uniform_run=uniform_run)
@@ -219,7 +226,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3",
-                    help="cfg0..cfg4, cfg4_f64, paper_n<N>, hmlstm_<hidden>x<batch>")
+                    help="cfg0..cfg4, cfg4_f64, paper_n<N>, hmlstm_<hidden>x<batch>, linear12_<hidden>x<batch>, "
+                         "branchy5_3d_<O>x<R>x<C>, branchy5_3dm_<O>x<R>x<C>")
     ap.add_argument("--p-index", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=16)

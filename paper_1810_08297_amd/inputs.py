@@ -79,6 +79,22 @@ def branchy5_inputs(rows, cols, *, seed, dtype=np.float32):
     return [A, B, r, s, t], adj
 
 
+def branchy5_3d_inputs(outer, rows, cols, *, seed, dtype=np.float32, merging=False):
+    """branchy5 over [outer x rows x cols] with an argument broadcast along the middle dim only:
+    r [outer x 1 x cols], s [1 x rows x 1], t scalar -- a problem that keeps three dims.
+    ``merging`` gives the same elements shapes that merge to two dims instead
+    (r [1 x 1 x cols], s [outer x rows x 1])."""
+    rng = np.random.default_rng(seed)
+    full = (outer, rows, cols)
+    A = _normal(rng, full, dtype)
+    B = np.ascontiguousarray(rng.uniform(0.1, 2.0, full).astype(dtype))
+    r = _normal(rng, (1, 1, cols) if merging else (outer, 1, cols), dtype)
+    s = _normal(rng, (outer, rows, 1) if merging else (1, rows, 1), dtype)
+    t = _normal(rng, (1, 1, 1), dtype)
+    adj = [_normal(rng, full, dtype)]
+    return [A, B, r, s, t], adj
+
+
 def update_c_inputs(n, *, seed, dtype=np.float32, uniform_run=0):
     """The paper's own experiment (Sec. 3.4): c,f,i,g n x n random, z1,z2
     n-element random control vectors varying along the contiguous dim.

@@ -1659,6 +1659,18 @@ def test_rank3_problem_takes_vectors_along_the_innermost_dim(dtype):
     check_op("branchy5", [A, Bm, r, s, t], adj, view=padded, what="rank 3, generic, one padded view ", options=generic)
 
 
+def test_three_dim_benchmark_shape_at_full_size():
+    """The three-dim workload bench.py times (`branchy5_3d_64x256x1024`: r broadcast along the middle dim only),
+    every element of the values, planes, branch ids and gradients against the oracle, planes stored and recomputed."""
+    args, adj = inputs.branchy5_3d_inputs(64, 256, 1024, seed=inputs.BASE_SEED + 500 + 64 + 256 + 1024)
+    dev = [to_dev(a) for a in args]
+    fb = P.alloc_forward("branchy5", dev)
+    info = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials)
+    assert info["path"] == 1 and info["ndim"] == 3, info
+    del fb, dev
+    check_op("branchy5", args, adj, threads=16, what="three dims at full size ", recompute="required")
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
 def test_rank3_reductions_of_many_chunks(dtype):
     """Rank-3 problems with every kind of reduced gradient -- kept or summed along the outer dim,

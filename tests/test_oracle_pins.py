@@ -500,6 +500,28 @@ def test_rank3_and_rank1_shapes():
     assert outs[0].shape == (11,)
 
 
+def test_middle_dim_broadcast_equals_the_same_problem_with_materialised_arguments():
+    """The three-dim benchmark shape (r broadcast along the middle dim only, s along the two others, Sec. 2.1.1):
+    the oracle's values and planes equal those of the same call with r and s expanded to the full shape by
+    numpy, and the reduced gradients are the sums of the expanded call's gradients over the broadcast dims."""
+    from paper_1810_08297_amd import inputs
+    args, adj = inputs.branchy5_3d_inputs(3, 5, 7, seed=11, dtype=np.float64)
+    assert [a.shape for a in args] == [(3, 5, 7), (3, 5, 7), (3, 1, 7), (1, 5, 1), (1, 1, 1)] and adj[0].shape == (3, 5, 7)
+    margs, _ = inputs.branchy5_3d_inputs(3, 5, 7, seed=11, dtype=np.float64, merging=True)
+    assert [a.shape for a in margs] == [(3, 5, 7), (3, 5, 7), (1, 1, 7), (3, 5, 1), (1, 1, 1)]
+    full = [np.ascontiguousarray(np.broadcast_to(a, (3, 5, 7))) for a in args]
+    outs, P, br = oracle.forward("branchy5", args)
+    outs_f, P_f, br_f = oracle.forward("branchy5", full)
+    assert np.array_equal(outs[0], outs_f[0]) and np.array_equal(br, br_f)
+    assert all(np.array_equal(a, b) for a, b in zip(P, P_f))
+    g = oracle.backward(adj, P, [a.shape for a in args])
+    g_f = oracle.backward(adj, P_f, [a.shape for a in full])
+    assert np.array_equal(g[0], g_f[0]) and np.array_equal(g[1], g_f[1])
+    assert_close(g[2], g_f[2].sum(axis=1, keepdims=True), 1e-14, 1e-15)
+    assert_close(g[3], g_f[3].sum(axis=(0, 2), keepdims=True), 1e-14, 1e-15)
+    assert_close(g[4], g_f[4].sum(keepdims=True), 1e-14, 1e-15)
+
+
 def test_fp32_outputs_are_correctly_rounded_from_wide_evaluation():
     args = random_args("tanh_xy_b", 6, 6, np.float32)
     o32, P32, _ = oracle.forward("tanh_xy_b", args)
