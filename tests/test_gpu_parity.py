@@ -1115,10 +1115,11 @@ def test_two_streams_run_independent_problems():
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
 def test_planes_interleaved_by_row(dtype):
     """Outputs and planes interleaved by row in one slab (and the arguments, adjoints and gradients likewise,
-    each group in a slab of its own): the groups have different row strides, the HM-LSTM mixes still get their
+    each group in a slab of its own): the groups have different row strides, the benchmark ops' mixes still get their
     compiled-per-mix backward kernel (built for views with strides of their own), and every result has the
     bits of the default layout."""
-    for op, R, C, lean in (("hmlstm_update", 300, 1024, False), ("hmlstm_update", 130, 2052, True), ("branchy5", 260, 1100, False)):
+    for op, R, C, lean in (("hmlstm_update", 300, 1024, False), ("hmlstm_update", 130, 2052, True), ("branchy5", 260, 1100, False),
+                           ("branchy5", 520, 2048, True), ("tanh_xy_b", 200, 4096, False), ("tanh_xy_b", 70, 1028, False)):
         args, adj = small_args(op, R, C, dtype, seed=R + C)
         dev, adj_dev = [to_dev(a) for a in args], [to_dev(a) for a in adj]
         shapes = [args[j].shape for j in oracle.diff_arg_indices(op, len(args))]
@@ -1134,8 +1135,8 @@ def test_planes_interleaved_by_row(dtype):
         bb = P.alloc_backward(adj_i, fb.partials, shapes, layout="interleaved")
         bplan = P.bcast_dual_backward_plan(adj_i, fb.partials, bb.grads)
         assert bplan["path"] == 1 and bplan["uniform_stride"] == 0
-        if op == "hmlstm_update" and C % (16 // np.dtype(dtype).itemsize) == 0:
-            assert bplan["specialized"] == 1, bplan
+        if C % (16 // np.dtype(dtype).itemsize) == 0:  # the benchmark ops' mixes are also built for strides per view
+            assert bplan["specialized"] == 1, (op, bplan)
         bb.run(adj_i, fb.partials)
         torch.cuda.synchronize()
         assert torch.equal(fb.branch, ref.branch)
