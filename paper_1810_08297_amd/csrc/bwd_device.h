@@ -152,6 +152,12 @@ struct BwdGeom {
   A *lds_row, *lds_col, *lds_all;
 
   BD_DEV BwdGeom(const BwdTiledParams &p, unsigned char *smem) {
+    // the scalars at the head of the argument block and the grid size, fetched together (see arrived)
+    const uint32_t grid = gridDim.x;
+    arrived(low_word(p.R) ^ low_word(p.C) ^ low_word(p.log2_tx) ^ low_word(p.steps) ^ low_word(p.nt_store) ^ low_word(p.reverse) ^
+            low_word(p.xcd_remap) ^ low_word(p.col_chunks) ^ low_word(p.interleave) ^ low_word(p.ragged) ^ low_word(p.n_col_slots) ^
+            low_word(p.n_all_slots) ^ p.lds_row_off ^ p.lds_col_off ^ p.lds_all_off ^ low_word(p.n_ct) ^ low_word(p.n_rt) ^
+            low_word(p.row_stride) ^ low_word(p.O) ^ low_word(p.tiles_per_slice) ^ low_word(p.outer_stride) ^ low_word(p.ws) ^ grid);
     tid = threadIdx.x;
     ltx = p.log2_tx;
     TX = 1 << ltx;
@@ -164,14 +170,14 @@ struct BwdGeom {
     // In reverse mode the grid is walked from the last tile to the first: the planes that
     // the forward kernel wrote last are the ones still held by the memory-side cache.
     bid = blockIdx.x;
-    if (p.xcd_remap) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);
+    if (p.xcd_remap) bid = (bid & 7u) * (grid >> 3) + (bid >> 3);
     if (p.reverse == 1) {
-      bid = gridDim.x - 1 - bid;
+      bid = grid - 1 - bid;
     } else if (p.reverse == 2) {
       // last to first in groups of eight, each block keeping its place within its group: the
       // hardware deals consecutive blocks round-robin to the 8 XCDs, so a tile then stays on the
       // XCD (its L2, its address-translation cache) whose forward block wrote it
-      const uint32_t full = gridDim.x & ~7u;
+      const uint32_t full = grid & ~7u;
       if (bid < full) bid = full - 8u - (bid & ~7u) + (bid & 7u);
     }
     slice = 0;

@@ -251,6 +251,10 @@ __global__ __launch_bounds__(kBlock) void bwd_pass2_kernel(const Pass2Params p) 
   for (int q = 1; q < p.n_jobs; ++q)
     if ((int64_t)blockIdx.x >= p.job[q].first_block) j = q;
   const Pass2Job &job = p.job[j];
+  // the job's fields, fetched together (see arrived)
+  arrived(low_word(job.g) ^ low_word(job.g_stride) ^ low_word(job.g_outer_stride) ^ low_word(job.n_outer) ^ low_word(job.outer_major) ^
+          low_word(job.n_out) ^ low_word(job.n_part) ^ low_word(job.part_stride) ^ low_word(job.out_stride) ^ low_word(job.ws_off) ^
+          low_word(job.first_block) ^ low_word(job.kind) ^ low_word(p.ws));
   const int64_t b = (int64_t)blockIdx.x - job.first_block;
   const A *ws = reinterpret_cast<const A *>(p.ws + job.ws_off);
   T *g = static_cast<T *>(job.g);

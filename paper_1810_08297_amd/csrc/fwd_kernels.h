@@ -113,6 +113,18 @@ BD_DEV void store_ragged(T *p, const T (&x)[VEC], bool nt, int shift) {
 
 // base + byte offset; with a uniform base and a 32-bit lane offset this is the
 // scalar-base + vector-offset addressing mode: no per-plane address arithmetic
+// Kernel arguments are read with scalar loads, and the compiler issues each where it is first
+// needed: behind uniform branches that means one load, one wait, one use, again and again -- some
+// thirty round trips to the scalar cache in a block that lives a few microseconds.  Folding the
+// values a block will need into one word and handing that word to an empty asm makes all their
+// loads issue together and complete at that point; the values themselves stay what they were
+// (pointers keep their address space, so accesses keep the scalar-base form).
+BD_DEV uint32_t low_word(const void *x) { return (uint32_t)reinterpret_cast<uintptr_t>(x); }
+BD_DEV uint32_t low_word(int64_t x) { return (uint32_t)x; }
+BD_DEV uint32_t low_word(int32_t x) { return (uint32_t)x; }
+BD_DEV uint32_t low_word(uint32_t x) { return x; }
+BD_DEV void arrived(uint32_t folded) { asm volatile("" ::"s"(folded)); }
+
 template <class T>
 BD_DEV T *at(const void *base, uint32_t byte_off) {
   // The empty asm pins the zero-extension of the offset to the basic block of the access;
@@ -183,6 +195,20 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   using Y = Dual<T, (!PARTIALS ? 0u : ND >= 32 ? 0xffffffffu : ((1u << ND) - 1u))>;
   constexpr bool ARG_NT = PARTIALS && kFwdArgNt;
   constexpr bool ROW_VECTORS_APART = ARG_NT;  // the streaming hint is not for row vectors, see below
+  // Up front, together: the geometry, the argument pointers and (for arguments read as one value per
+  // row) their row strides.  Ops with more arguments than scalar registers allow keep the lazy reads.
+  constexpr bool TOGETHER = N + M + (PARTIALS ? M * ND : 0) <= 36;
+  const void *ap[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) ap[j] = p.arg_p[j];
+  if constexpr (TOGETHER) {
+    uint32_t f = low_word(p.R) ^ low_word(p.C) ^ low_word(p.log2_tx) ^ low_word(p.nt_store) ^ low_word(p.xcd_remap) ^ low_word(p.n_ct) ^
+                 low_word(p.row_stride) ^ low_word(p.O) ^ low_word(p.tiles_per_slice) ^ low_word(p.outer_stride) ^ p.row_invariant ^
+                 p.col_invariant;
+#pragma unroll
+    for (int j = 0; j < N; ++j) f ^= low_word(ap[j]) ^ low_word(p.arg_sr[j]);
+    arrived(f);
+  }
   const int ltx = p.log2_tx;
   const int tx = threadIdx.x & ((1 << ltx) - 1);
   const int ty = threadIdx.x >> ltx;
@@ -208,6 +234,13 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   const int shift = RAGGED && c0 + VEC > p.C ? (int)(c0 + VEC - p.C) : 0;
   const int64_t cl = c0 - shift;
   const uint32_t col_off = (uint32_t)cl * (uint32_t)sizeof(T);
+  int64_t aoff[N];  // where the block's slice starts in each argument, in elements
+#pragma unroll
+  for (int j = 0; j < N; ++j) aoff[j] = 0;
+  if (p.O > 1) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) aoff[j] = slice * p.arg_so[j];
+  }
   const RowStep<T, US> rs{r0, slice, (slice * p.outer_stride + r0 * p.row_stride) * (int64_t)sizeof(T),
                           ((uint32_t)ty * (uint32_t)p.row_stride + (uint32_t)cl) * (uint32_t)sizeof(T), (uint32_t)ty, col_off};
 
@@ -227,11 +260,11 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int v = 0; v < VEC; ++v) avec[j][v] = T(0);
     if constexpr (ROW_VECTORS_APART) {
       if (!(((p.col_invariant | p.row_invariant) >> j) & 1u))  // from this row
-        load_vec<T, VEC, ARG_NT, RAGGED>(at<const T>(rs.base(p.arg_p[j], p.arg_sr[j], p.arg_so[j]), rs.lane(p.arg_sr[j])), avec[j]);
+        load_vec<T, VEC, ARG_NT, RAGGED>(at<const T>(rs.base(ap[j], p.arg_sr[j], p.arg_so[j]), rs.lane(p.arg_sr[j])), avec[j]);
     } else {
       if (!((p.col_invariant >> j) & 1u))  // from this row, or (row vectors) from the only row
-        load_vec<T, VEC, ARG_NT, RAGGED>(((p.row_invariant >> j) & 1u) ? at<const T>(static_cast<const T *>(p.arg_p[j]) + slice * p.arg_so[j], col_off)
-                                                                         : at<const T>(rs.base(p.arg_p[j], p.arg_sr[j], p.arg_so[j]), rs.lane(p.arg_sr[j])), avec[j]);
+        load_vec<T, VEC, ARG_NT, RAGGED>(((p.row_invariant >> j) & 1u) ? at<const T>(static_cast<const T *>(ap[j]) + aoff[j], col_off)
+                                                                         : at<const T>(rs.base(ap[j], p.arg_sr[j], p.arg_so[j]), rs.lane(p.arg_sr[j])), avec[j]);
     }
   }
   // Row vectors, in the kernels that stream their arguments, are a third form with registers of
@@ -250,14 +283,33 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int j = 0; j < N; ++j) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) arow[j][v] = T(0);
-      if ((rowvec >> j) & 1u) load_vec<T, VEC, false, RAGGED>(at<const T>(static_cast<const T *>(p.arg_p[j]) + slice * p.arg_so[j], col_off), arow[j]);
+      if ((rowvec >> j) & 1u) load_vec<T, VEC, false, RAGGED>(at<const T>(static_cast<const T *>(ap[j]) + aoff[j], col_off), arow[j]);
     }
   }
 #pragma unroll
   for (int j = 0; j < N; ++j) {
     asc[j] = T(0);
     if ((colinv_again >> j) & 1u)  // one value for the row (column vectors) or for everything (scalars)
-      asc[j] = static_cast<const T *>(p.arg_p[j])[slice * p.arg_so[j] + (((p.row_invariant >> j) & 1u) ? 0 : r * p.arg_sr[j])];
+      asc[j] = static_cast<const T *>(ap[j])[aoff[j] + (((p.row_invariant >> j) & 1u) ? 0 : r * p.arg_sr[j])];
+  }
+  // the pointers of everything the block writes, fetched together while its loads are in flight
+  void *op_[M];
+  void *pp[PARTIALS ? M * ND : 1];
+#pragma unroll
+  for (int i = 0; i < M; ++i) op_[i] = p.out_p[i];
+  if constexpr (PARTIALS) {
+#pragma unroll
+    for (int k = 0; k < M * ND; ++k) pp[k] = p.part_p[k];
+  }
+  if constexpr (TOGETHER) {
+    uint32_t f = low_word(p.branch_p);
+#pragma unroll
+    for (int i = 0; i < M; ++i) f ^= low_word(op_[i]);
+    if constexpr (PARTIALS) {
+#pragma unroll
+      for (int k = 0; k < M * ND; ++k) f ^= low_word(pp[k]);
+    }
+    arrived(f);
   }
   // the merge below must not sink into the conditional loads above (each load would then be
   // waited for on its own): the broadcast values pass through an opaque point after all loads
@@ -290,14 +342,14 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      put(at<T>(rs.base(p.out_p[i], p.out_sr[i], p.out_so[i]), rs.lane(p.out_sr[i])), o);
+      put(at<T>(rs.base(op_[i], p.out_sr[i], p.out_so[i]), rs.lane(p.out_sr[i])), o);
     }
     if constexpr (PARTIALS) {
 #pragma unroll
       for (int i = 0; i < M; ++i) {
         static_for<0, ND>([&](auto JD) {
           constexpr int jd = decltype(JD)::value;
-          void *pl = p.part_p[i * ND + jd];
+          void *pl = pp[i * ND + jd];
           if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
