@@ -93,6 +93,11 @@ typedef struct {
   int32_t uniform_stride; /* tiled path: 1 if every view the kernels stream row by row has the same row
                           stride (one address offset per lane then serves them all), 0 if each is addressed
                           with its own (slices of wider buffers, views that repeat one row) */
+  int64_t nontemporal_tiles; /* forward, tiled path: how many tiles, counted from the start of the kernel's walk,
+                          are written with the nontemporal hint (0: none; grid_x * grid_y: all; see
+                          bcast_dual_options.fwd_keep_mib).  backward: the blocks of the main pass that write
+                          full-shape gradients with the hint (0 or all; only the kernels compiled for a mix,
+                          with one common row stride and one column chunk per block, have that form) */
 } bcast_plan_info;
 
 /* Per-call options.  Every entry point that plans or launches takes a `const bcast_dual_options *`
@@ -106,8 +111,9 @@ typedef struct {
 typedef struct {
   uint32_t struct_size;     /* sizeof(bcast_dual_options) as the caller compiled it; any other value is refused */
   int32_t bwd_row_steps;    /* row steps per block of the tiled backward kernels: 0 (default) = automatic, else 1..256 */
-  int32_t nontemporal_stores; /* bit 0: the forward kernel's outputs and planes, bit 1: the backward kernels'
-                               gradients (default 3 = both; measured: no difference) */
+  int32_t nontemporal_stores; /* bit 0: the forward kernel may write outputs and planes with the nontemporal hint
+                               (see fwd_keep_mib), bit 1: the backward kernels may write full-shape gradients with it
+                               (see bwd_nt_min_mib); default 3 = both */
   int32_t force_generic;    /* 1 = the generic strided kernels even where the tiled ones apply (testing); default 0 */
   int32_t max_vector_bytes; /* widest vector access per lane: 16 (default), 8 or 4 */
   int32_t runtime_table;    /* 1 = never a backward / recompute kernel compiled for the call's mix of gradient
@@ -141,6 +147,14 @@ typedef struct {
                                of every row taken singly; 0 = the widest aligned access that fits (8 or 4 bytes) */
   int32_t probe_nt_loads;   /* bcast_dual_stream_probe: 1 (default) = nontemporal loads, 0 = plain */
   int32_t probe_lds_kib;    /* bcast_dual_stream_probe: unused dynamic LDS per block, as fwd_lds_kib (default 0) */
+  int32_t fwd_keep_mib;     /* MiB of outputs and planes, counted from the end of what the forward kernel writes, that
+                               it writes plainly so that they stay cached for a reverse pass that starts with them;
+                               everything before is written with the nontemporal hint (streamed past the caches).
+                               -1 (default) = automatic (a launch that writes up to 1 GiB: all of it; a larger one:
+                               128); 0..1048576; a launch that writes no more than this is written plainly throughout */
+  int32_t bwd_nt_min_mib;   /* MiB of full-shape gradients written by one backward call from which on they are written
+                               with the nontemporal hint (bit 1 of nontemporal_stores permitting): -1 (default) =
+                               automatic (256), 0 = always; 0..1048576 */
   /* Timing of one launch by the runtime itself: two hipEvent_t the caller created with timing enabled, both
    * or neither.  The main-pass kernel of the call (the forward kernel, the main backward or recompute kernel
    * -- the first one if the gradients need several launches, never the second reduction pass -- or the probe

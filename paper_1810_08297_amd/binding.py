@@ -31,7 +31,7 @@ class PlanInfo(ctypes.Structure):
                 ("shape", ctypes.c_int64 * MAX_DIMS), ("tx", ctypes.c_int32), ("ty", ctypes.c_int32),
                 ("rows_per_block", ctypes.c_int32), ("grid_x", ctypes.c_int64), ("grid_y", ctypes.c_int64),
                 ("n_launches", ctypes.c_int32), ("n_second_pass", ctypes.c_int32), ("specialized", ctypes.c_int32),
-                ("ragged", ctypes.c_int32), ("uniform_stride", ctypes.c_int32)]
+                ("ragged", ctypes.c_int32), ("uniform_stride", ctypes.c_int32), ("nontemporal_tiles", ctypes.c_int64)]
 
     def as_dict(self):
         d = {k: getattr(self, k) for k, _ in self._fields_ if k != "shape"}
@@ -48,8 +48,8 @@ class Options(ctypes.Structure):
                 ("reverse_tiles", ctypes.c_int32), ("interleave_rows", ctypes.c_int32),
                 ("xcd_order", ctypes.c_int32), ("col_chunks", ctypes.c_int32), ("fwd_lds_kib", ctypes.c_int32),
                 ("bwd_lds_kib", ctypes.c_int32), ("narrow_tiles", ctypes.c_int32), ("ragged_rows", ctypes.c_int32),
-                ("probe_nt_loads", ctypes.c_int32), ("probe_lds_kib", ctypes.c_int32),
-                ("start_event", ctypes.c_void_p), ("stop_event", ctypes.c_void_p)]
+                ("probe_nt_loads", ctypes.c_int32), ("probe_lds_kib", ctypes.c_int32), ("fwd_keep_mib", ctypes.c_int32),
+                ("bwd_nt_min_mib", ctypes.c_int32), ("start_event", ctypes.c_void_p), ("stop_event", ctypes.c_void_p)]
 
     def __init__(self, **fields):
         super().__init__()

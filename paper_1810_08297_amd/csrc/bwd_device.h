@@ -154,7 +154,7 @@ struct BwdGeom {
   BD_DEV BwdGeom(const BwdTiledParams &p, unsigned char *smem) {
     // the scalars at the head of the argument block and the grid size, fetched together (see arrived)
     const uint32_t grid = gridDim.x;
-    arrived(low_word(p.R) ^ low_word(p.C) ^ low_word(p.log2_tx) ^ low_word(p.steps) ^ low_word(p.nt_store) ^ low_word(p.reverse) ^
+    arrived(low_word(p.R) ^ low_word(p.C) ^ low_word(p.log2_tx) ^ low_word(p.steps) ^ low_word(p.reverse) ^
             low_word(p.xcd_remap) ^ low_word(p.col_chunks) ^ low_word(p.interleave) ^ low_word(p.ragged) ^ low_word(p.n_col_slots) ^
             low_word(p.n_all_slots) ^ p.lds_row_off ^ p.lds_col_off ^ p.lds_all_off ^ low_word(p.n_ct) ^ low_word(p.n_rt) ^
             low_word(p.row_stride) ^ low_word(p.O) ^ low_word(p.tiles_per_slice) ^ low_word(p.outer_stride) ^ low_word(p.ws) ^ grid);
@@ -258,15 +258,16 @@ BD_DEV void load_plane(const void *base, uint32_t off, bool valid, T (&x)[VEC], 
 // the per-class treatment of one gradient at one row step
 // `gbase`: the gradient's own view at the row step's first row; `off`: the lane's byte offset from there
 // (RAGGED: `off` is where the lane's loads go, `shift` columns left of its own first column)
-template <class T, int VEC, int MAXM, bool EDGE, bool RAGGED = false>
+// NTS: the gradient is written with the nontemporal hint
+template <class T, int VEC, int MAXM, bool EDGE, bool RAGGED = false, bool NTS = false>
 BD_DEV void apply_full(const void *gbase, const T (&adj)[MAXM][VEC], const T (&P)[MAXM][VEC], uint32_t off,
-                       bool valid, bool nt, int shift = 0) {
+                       bool valid, int shift = 0) {
   T o[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, MAXM, VEC>(adj, P, v);
   if (!EDGE || valid) {
-    if constexpr (RAGGED && EDGE) store_ragged<T, VEC>(at<T>(gbase, off), o, nt, shift);
-    else store_vec<T, VEC, RAGGED>(at<T>(gbase, off), o, nt);
+    if constexpr (RAGGED && EDGE) store_ragged<T, VEC>(at<T>(gbase, off), o, shift);
+    else store_vec<T, VEC, RAGGED, NTS>(at<T>(gbase, off), o);
   }
 }
 // row sums in two halves: a lane's own columns first (over as many column chunks as the kernel

@@ -30,7 +30,8 @@ constexpr int share_src(uint64_t share, int e) {
 // US: every streamed view shares one row stride (the usual case); the kernels for the HM-LSTM mixes are
 // also built with US = false, where each adjoint, plane and gradient is addressed with its own -- planes
 // interleaved by row in one slab, gradients written into slices of a wider buffer.
-template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, int CU, bool US = true>
+// NTS: full-shape gradients are written with the nontemporal hint (built for the common-stride, one-chunk form only).
+template <class T, int VEC, int M, int NF, int NR, int NC, int NA, uint64_t ABSENT, uint64_t SHARE, int CU, bool US = true, bool NTS = false>
 __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p) {
   using AT = acc_traits<T>;
   using A = typename AT::type;
@@ -43,7 +44,6 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
   static_assert(!LOOP || CU == 1, "several column chunks only in the kernels without a row loop");
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
-  const bool nt = p.nt_store != 0;
   // sums over rows accumulate in registers during the walk and are parked in LDS afterwards
   A colacc[NC > 0 ? NC : 1][VEC], allacc[NA > 0 ? NA : 1];
 #pragma unroll
@@ -91,8 +91,8 @@ __global__ __launch_bounds__(kBlock) void bwd_sig_kernel(const BwdTiledParams p)
     for (int q = 0; q < CU; ++q)
 #pragma unroll
       for (int e = 0; e < NF; ++e)
-        apply_full<T, VEC, M, EDGE, true>(rs.base(p.e[e].g), adj[q], P[q][share_src(SHARE, e)], off(p.e[e].g.sr, q), valid[q], nt,
-                                          shift[q]);
+        apply_full<T, VEC, M, EDGE, true, NTS>(rs.base(p.e[e].g), adj[q], P[q][share_src(SHARE, e)], off(p.e[e].g.sr, q), valid[q],
+                                               shift[q]);
 #pragma unroll
     for (int e = NF; e < NF + NR; ++e) {
       A rs = AT::zero();
@@ -149,7 +149,6 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
   const int M = MCT > 0 ? MCT : p.M;
-  const bool nt = p.nt_store != 0;
   for (int n = 0; n < p.steps; ++n) {
     const int k = p.reverse ? p.steps - 1 - n : n;  // last to first with the tiles (see bwd_sig_kernel)
     const int ri = k * g.TY + g.ty;
@@ -192,7 +191,7 @@ __global__ __launch_bounds__(kBlock) void bwd_tiled_kernel(const BwdTiledParams 
 #pragma unroll
           for (int i = 0; i < MAXM; ++i) unshift<T, VEC>(P[i], g.shift);
         if (en.cls == kGradFull)
-          apply_full<T, VEC, MAXM, true, RAGGED>(rs.base(en.g), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
+          apply_full<T, VEC, MAXM, true, RAGGED>(rs.base(en.g), adj, P, rs.lane(en.g.sr), valid, g.shift);
         else if (en.cls == kGradRowSum)
           apply_rowsum<T, VEC, MAXM>(p, g, en, adj, P, r, ri);
         else if (en.cls == kGradColSum)
@@ -337,7 +336,7 @@ __global__ __launch_bounds__(kBlock) void bwd_generic_full_kernel(const BwdGener
   T o[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) o[v] = wide_dot<T, BCAST_MAX_OUTS, VEC>(a, P, v);
-  store_vec<T, VEC>(static_cast<T *>(p.g.p) + off(p.g), o, false);
+  store_vec<T, VEC>(static_cast<T *>(p.g.p) + off(p.g), o);
 }
 
 // Reduced gradients on the generic path: see BwdGenericParams for the two lane arrangements and
@@ -500,6 +499,7 @@ static void launch_sig(int chunks, const BwdTiledParams &p, dim3 grid, size_t ld
     if (chunks == 4) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 4>), grid, dim3(kBlock), lds, s, p);
     if (chunks == 2) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 2>), grid, dim3(kBlock), lds, s, p);
   }
+  if (p.nt_store) return launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 1, true, true>), grid, dim3(kBlock), lds, s, p);
   launch((bwd_sig_kernel<T, VEC, M, NF, NR, NC, NA, ABSENT, SHARE, 1>), grid, dim3(kBlock), lds, s, p);
 }
 

@@ -66,16 +66,19 @@ BD_DEV T lane_elem(const typename lane_vec<T, VEC>::type &x, int k) {
   if constexpr (VEC == 1) return x; else return x[k];
 }
 
-template <class T, int VEC, bool UNALIGNED = false>
-BD_DEV void store_vec(T *p, const T (&x)[VEC], bool nt) {
+// NTS: with the nontemporal hint, fixed at compile time.  (A run-time choice written as a plain
+// if / else does not survive: the compiler merges the two stores, which differ in nothing but the
+// hint, into one without it.  store_at below is the form that does.)
+template <class T, int VEC, bool UNALIGNED = false, bool NTS = false>
+BD_DEV void store_vec(T *p, const T (&x)[VEC]) {
   if constexpr (VEC == 1) {
-    if (nt) __builtin_nontemporal_store(x[0], p); else *p = x[0];
+    if constexpr (NTS) __builtin_nontemporal_store(x[0], p); else *p = x[0];
   } else {
     using V = std::conditional_t<UNALIGNED, typename vec_of<T, VEC>::unaligned, typename vec_of<T, VEC>::type>;
     typename vec_of<T, VEC>::type v;
 #pragma unroll
     for (int k = 0; k < VEC; ++k) v[k] = x[k];
-    if (nt) __builtin_nontemporal_store(v, reinterpret_cast<V *>(p)); else *reinterpret_cast<V *>(p) = v;
+    if constexpr (NTS) __builtin_nontemporal_store(v, reinterpret_cast<V *>(p)); else *reinterpret_cast<V *>(p) = v;
   }
 }
 
@@ -101,9 +104,9 @@ BD_DEV void unshift(T (&x)[VEC], int shift) {
 // `p`: where the lane's loads go (its first column less `shift`).  A whole vector is stored as
 // one; the row's last lane stores its VEC - shift columns one by one.
 template <class T, int VEC>
-BD_DEV void store_ragged(T *p, const T (&x)[VEC], bool nt, int shift) {
+BD_DEV void store_ragged(T *p, const T (&x)[VEC], int shift) {
   if (shift == 0) {
-    store_vec<T, VEC, true>(p, x, nt);
+    store_vec<T, VEC, true>(p, x);
   } else {
 #pragma unroll
     for (int v = 0; v < VEC; ++v)
@@ -132,6 +135,30 @@ BD_DEV T *at(const void *base, uint32_t byte_off) {
   // both there (accesses sit behind uniform null-pointer and bounds branches).
   asm("" : "+v"(byte_off));
   return reinterpret_cast<T *>(const_cast<char *>(static_cast<const char *>(base)) + byte_off);
+}
+
+// One vector to base + byte offset, with or without the nontemporal hint, chosen at run time by a
+// value that is the same for the whole block.  The two empty asm statements keep the two stores
+// from being merged into one without the hint, and forming the address inside each branch keeps
+// the scalar-base + lane-offset form for both.  (In a kernel that loops over row steps the branch
+// costs: the backward kernels take the hint as a template parameter instead.)
+template <class T, int VEC, bool UNALIGNED = false>
+BD_DEV void store_at(const void *base, uint32_t byte_off, const T (&x)[VEC], bool nt) {
+  using V = std::conditional_t<VEC == 1, T, std::conditional_t<UNALIGNED, typename lane_vec_unaligned<T, VEC>::type, typename lane_vec<T, VEC>::type>>;
+  typename lane_vec<T, VEC>::type v;
+  if constexpr (VEC == 1) {
+    v = x[0];
+  } else {
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) v[k] = x[k];
+  }
+  if (nt) {
+    asm volatile("" ::: "memory");
+    __builtin_nontemporal_store(v, reinterpret_cast<V *>(at<T>(base, byte_off)));
+    asm volatile("" ::: "memory");
+  } else {
+    *reinterpret_cast<V *>(at<T>(base, byte_off)) = v;
+  }
 }
 
 // Where the lanes of one row step find their vectors in a view whose rows are `sr` elements
@@ -202,7 +229,7 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
 #pragma unroll
   for (int j = 0; j < N; ++j) ap[j] = p.arg_p[j];
   if constexpr (TOGETHER) {
-    uint32_t f = low_word(p.R) ^ low_word(p.C) ^ low_word(p.log2_tx) ^ low_word(p.nt_store) ^ low_word(p.xcd_remap) ^ low_word(p.n_ct) ^
+    uint32_t f = low_word(p.R) ^ low_word(p.C) ^ low_word(p.log2_tx) ^ p.nt_tiles ^ low_word(p.xcd_remap) ^ low_word(p.n_ct) ^
                  low_word(p.row_stride) ^ low_word(p.O) ^ low_word(p.tiles_per_slice) ^ low_word(p.outer_stride) ^ p.row_invariant ^
                  p.col_invariant;
 #pragma unroll
@@ -216,6 +243,7 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   const uint32_t nct = (uint32_t)p.n_ct;
   uint32_t bid = blockIdx.x;
   if (p.xcd_remap) bid = (bid & 7u) * (gridDim.x >> 3) + (bid >> 3);  // the host sets this only for grids of 8 n blocks
+  const uint32_t walk = bid;  // the tile's place in the order in which the launch writes
   uint32_t slice32 = 0;
   if (p.O > 1) {  // a 3-D problem: the grid holds the blocks of slice 0, then those of slice 1, ...
     slice32 = bid / (uint32_t)p.tiles_per_slice;
@@ -228,7 +256,9 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
   const int64_t r0 = (int64_t)rt * TY;  // the block's first row, the same for all its lanes
   const int64_t r = r0 + ty;
   if (r >= p.R) return;
-  const bool nt = p.nt_store != 0;
+  // blocks write with the nontemporal hint up to tile nt_tiles of the walk and plainly from there on:
+  // what the launch writes last is what a reverse pass reads first and may still find cached
+  const bool nt = walk < p.nt_tiles;
   // the row's last lane reads the vector that ends with the row (the host sees that C >= VEC)
   const bool last_tile = ct + 1 == nct;  // uniform: only these blocks hold a row's end
   const int shift = RAGGED && c0 + VEC > p.C ? (int)(c0 + VEC - p.C) : 0;
@@ -327,9 +357,9 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int v = 0; v < VEC; ++v) a[j][v] = or_bits(avec[j][v], asc[j]);
   }
   // stores: whole vectors, or (RAGGED, in the blocks that hold a row's end) the row's last columns one by one
-  auto put = [&](T *dst, const T (&o)[VEC]) {
-    if (RAGGED && last_tile) store_ragged<T, VEC>(dst, o, nt, shift);
-    else store_vec<T, VEC, RAGGED>(dst, o, nt);
+  auto put = [&](const void *base, uint32_t off, const T (&o)[VEC]) {
+    if (RAGGED && last_tile) store_ragged<T, VEC>(at<T>(base, off), o, shift);
+    else store_at<T, VEC, RAGGED>(base, off, o, nt);
   };
   {
     Y y[VEC][M];
@@ -342,7 +372,7 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
     for (int i = 0; i < M; ++i) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-      put(at<T>(rs.base(op_[i], p.out_sr[i], p.out_so[i]), rs.lane(p.out_sr[i])), o);
+      put(rs.base(op_[i], p.out_sr[i], p.out_so[i]), rs.lane(p.out_sr[i]), o);
     }
     if constexpr (PARTIALS) {
 #pragma unroll
@@ -353,7 +383,7 @@ __global__ __launch_bounds__(kBlock) void fwd_tiled_kernel(const FwdTiledParams 
           if (pl != nullptr) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-            put(at<T>(rs.base(pl, p.part_sr[i * ND + jd], p.part_so[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd])), o);
+            put(rs.base(pl, p.part_sr[i * ND + jd], p.part_so[i * ND + jd]), rs.lane(p.part_sr[i * ND + jd]), o);
           }
         });
       }
@@ -442,14 +472,14 @@ __global__ __launch_bounds__(kBlock) void fwd_generic_kernel(const FwdGenericPar
   for (int i = 0; i < M; ++i) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) o[v] = y[v][i].v;
-    store_vec<T, VEC>(static_cast<T *>(p.out[i].p) + off(p.out[i]), o, false);
+    store_vec<T, VEC>(static_cast<T *>(p.out[i].p) + off(p.out[i]), o);
     static_for<0, ND>([&](auto JD) {
       constexpr int jd = decltype(JD)::value;
       const GView &pl = p.part[i * ND + jd];
       if (pl.p != nullptr) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) o[v] = y[v][i].template partial<jd>();
-        store_vec<T, VEC>(static_cast<T *>(pl.p) + off(pl), o, false);
+        store_vec<T, VEC>(static_cast<T *>(pl.p) + off(pl), o);
       }
     });
   }

@@ -102,6 +102,12 @@ constexpr int kNumOps = (int)(sizeof(kOps) / sizeof(kOps[0]));
 
 // ---- per-call options ------------------------------------------------------------------------
 using Opt = bcast_dual_options;
+// what a forward launch of more than 1 GiB of output writes plainly at the end of its walk when fwd_keep_mib is automatic
+constexpr int kFwdKeepMiB = 256;
+// full-shape gradient bytes of one backward call from which on they are written with the nontemporal hint
+constexpr int64_t kNtGradientBytes = (int64_t)256 << 20;
+// plane bytes (written by a forward launch, read by a backward one) up to which the whole step fits the memory-side cache
+constexpr int64_t kSmallStepBytes = (int64_t)128 << 20;
 
 void default_options(Opt &o) {
   std::memset(&o, 0, sizeof o);
@@ -115,6 +121,8 @@ void default_options(Opt &o) {
   o.narrow_tiles = 1;
   o.ragged_rows = 1;
   o.probe_nt_loads = 1;
+  o.fwd_keep_mib = -1;
+  o.bwd_nt_min_mib = -1;
 }
 
 // NULL: the defaults; otherwise a checked copy
@@ -131,7 +139,8 @@ int resolve_options(const bcast_dual_options *in, Opt &o) {
                   in_range(o.reverse_tiles, 0, 2) && in_range(o.interleave_rows, 0, 1) && in_range(o.xcd_order, 0, 1) &&
                   in_range(o.col_chunks, 0, 1) && in_range(o.fwd_lds_kib, -1, 64) && in_range(o.bwd_lds_kib, 0, 64) &&
                   in_range(o.narrow_tiles, 0, 1) && in_range(o.ragged_rows, 0, 1) && in_range(o.probe_nt_loads, 0, 1) &&
-                  in_range(o.probe_lds_kib, 0, 64) && ((o.start_event == nullptr) == (o.stop_event == nullptr));
+                  in_range(o.probe_lds_kib, 0, 64) && in_range(o.fwd_keep_mib, -1, 1 << 20) && in_range(o.bwd_nt_min_mib, -1, 1 << 20) &&
+                  ((o.start_event == nullptr) == (o.stop_event == nullptr));
   return ok ? BCAST_OK : BCAST_ERR_BAD_OPTION;
 }
 
@@ -554,7 +563,6 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     p.tiles_per_slice = g.n_ct * g.n_rt;
     p.n_ct = g.n_ct;
     p.log2_tx = g.log2_tx;
-    p.nt_store = o.nontemporal_stores & 1;
     p.xcd_remap = o.xcd_order != 0 && (s2.O * g.n_ct * g.n_rt) % 8 == 0;
     p.has_partials = n_planes > 0;
     for (int j = 0; j < N; ++j) {
@@ -589,6 +597,25 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     // fp64 runs best with four blocks (cfg 4 in fp64: 722 against 750 us with three, 770 with no limit).
     const int lds_kib = o.fwd_lds_kib >= 0 ? o.fwd_lds_kib : (es == 8 ? 40 : 48);
     p.lds_bytes = planes_read >= 2 && 2 * planes_written >= 5 * planes_read ? lds_kib * 1024 : 0;
+    // Nontemporal stores for everything but the tail of what the launch writes (see fwd_keep_mib): the
+    // tail, kept in the caches, is what a reverse pass walking last to first reads first.
+    {
+      const int64_t n_tiles = s2.O * g.n_ct * g.n_rt;
+      const int64_t tile_bytes = (int64_t)planes_written * (kBlock >> g.log2_tx) * ((int64_t)g.vec << g.log2_tx) * (int64_t)es;
+      // Automatic, by how what is written compares with the caches (32 MB of L2, 256 MB memory-side):
+      //  - up to 128 MiB (a whole forward + reverse step then fits the memory-side cache): hint everywhere; the data
+      //    reaches that cache either way, and plain stores leave it to the end of the kernel to write the L2 back
+      //    (HM-LSTM 2048 x 256, 46 MB written: 27.0 -> 23.7 us per step with the reverse pass doing the same);
+      //  - up to 1 GiB: plain everywhere; the memory-side cache absorbs the writes faster than memory takes them
+      //    and the reverse pass finds most of them there (4096 x 1024, 369 MB: 74 us plain, 94 us with the hint);
+      //  - beyond: hint, except for the last 256 MiB, which the reverse pass reads first (8192 x 8192 branchy5,
+      //    1.6 GB: forward 363 -> 340 us).
+      const int64_t total = n_tiles * tile_bytes;
+      const int64_t auto_keep = total <= kSmallStepBytes ? 0 : total <= ((int64_t)1 << 30) ? total : (int64_t)kFwdKeepMiB << 20;
+      const int64_t keep_bytes = o.fwd_keep_mib >= 0 ? (int64_t)o.fwd_keep_mib << 20 : auto_keep;
+      const int64_t keep_tiles = (keep_bytes + tile_bytes - 1) / tile_bytes;
+      p.nt_tiles = (o.nontemporal_stores & 1) && keep_tiles < n_tiles ? (uint32_t)(n_tiles - keep_tiles) : 0u;
+    }
     if (want_branch) {
       const TView tv = tview(c, v.size(), const_cast<uint8_t *>(branch_id));
       p.branch_p = static_cast<uint8_t *>(tv.p);
@@ -601,6 +628,7 @@ int plan_forward(int32_t op_id, int dt, int32_t n_args, const bcast_tensor *args
     plan.info.vec = g.vec;
     plan.info.ragged = p.ragged;
     plan.info.uniform_stride = p.uniform_stride;
+    plan.info.nontemporal_tiles = p.nt_tiles;
     plan.info.tx = 1 << g.log2_tx;
     plan.info.ty = kBlock >> g.log2_tx;
     plan.info.rows_per_block = plan.info.ty * g.steps;
@@ -912,6 +940,17 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     plan.grid = dim3((unsigned)(s2.O * g.n_ct * g.n_rt), 1, 1);
     const int rows_pb = TY * g.steps;
 
+    // Full-shape gradients are written with the nontemporal hint when there are so many bytes of them that
+    // keeping them in the caches only displaces what the launch still has to read (256 MiB and more), or when
+    // the planes the call reads are so few that the whole step lives in the memory-side cache anyway (see the
+    // forward launch); in between plain stores measured faster.
+    int n_fullgrads = 0, n_planes_read = M;
+    for (int j = 0; j < ND; ++j) n_fullgrads += (cls[j] == kGradFull);
+    for (int k = 0; k < M * ND; ++k) n_planes_read += (v[M + k].p != nullptr);
+    const int64_t plane_bytes = s2.O * s2.R * s2.C * (int64_t)es;
+    const bool nt_wanted = o.bwd_nt_min_mib >= 0 ? n_fullgrads * plane_bytes >= ((int64_t)o.bwd_nt_min_mib << 20)
+                                                 : n_fullgrads * plane_bytes >= kNtGradientBytes || n_planes_read * plane_bytes <= kSmallStepBytes;
+    const int32_t nt_gradients = ((o.nontemporal_stores >> 1) & 1) && n_fullgrads > 0 && nt_wanted;
     // split the gradients over launches so that each launch's LDS accumulators fit
     size_t ws = 0;
     plan.p2.n_jobs = 0;
@@ -923,7 +962,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
       p.C = s2.C;
       p.log2_tx = g.log2_tx;
       p.steps = g.steps;
-      p.nt_store = (o.nontemporal_stores >> 1) & 1;
+      p.nt_store = nt_gradients;
       p.reverse = o.reverse_tiles;
       p.interleave = o.interleave_rows;
       p.xcd_remap = o.xcd_order != 0 && (s2.O * g.n_ct * g.n_rt) % 8 == 0;
@@ -1064,6 +1103,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     plan.info.specialized = plan.signature && ((dt == BCAST_F32 && g.vec == 4) || (dt == BCAST_F64 && g.vec == 2));
     plan.info.ragged = ragged;
     plan.info.uniform_stride = uniform_stride;
+    plan.info.nontemporal_tiles = nt_gradients && plan.info.specialized && uniform_stride && chunks == 1 ? g.n_ct * g.n_rt * s2.O : 0;
   } else {
     size_t gen_ws = 0;  // partial sums of the reductions that are cut into chunks
     for (int j = 0; j < ND; ++j) {

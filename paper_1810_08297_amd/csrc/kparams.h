@@ -38,7 +38,7 @@ struct FwdTiledParams {
   int64_t R, C;        // rows, columns of the merged 2-D problem
   int32_t log2_tx;     // lanes along the columns = 1 << log2_tx; rows per step = 256 >> log2_tx
   int32_t lds_bytes;   // dynamic LDS requested at launch; the kernel does not touch it, it limits the blocks per CU
-  int32_t nt_store;    // non-temporal stores
+  uint32_t nt_tiles;   // tiles [0, nt_tiles) of the walk are written with the nontemporal hint, the rest plainly
   int32_t has_partials;
   int32_t xcd_remap;   // 1: consecutive tiles go to one XCD (block b of a grid of 8 n serves tile (b % 8) n + b / 8)
   int64_t n_ct;        // column tiles; block b of a slice serves column tile b % n_ct of row tile b / n_ct

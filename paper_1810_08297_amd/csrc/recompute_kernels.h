@@ -54,7 +54,6 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
   using Y = Dual<T, (ND >= 32 ? 0xffffffffu : ((1u << ND) - 1u))>;
   extern __shared__ __align__(16) unsigned char smem[];
   const BwdGeom<T, VEC> g(p, smem);
-  const bool nt = p.nt_store != 0;
   const uint32_t col_off = g.colvalid ? g.col_off : 0u;
   uint32_t colinv_again = ra.col_invariant;
   asm volatile("" : "+s"(colinv_again));
@@ -167,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void bwdr_tiled_kernel(const BwdTiledParams
         constexpr int fixed = (int)((PATTERN >> (3 * jd)) & 7u);
         const int cls = fixed ? fixed - 1 : en.cls;
         if (cls == kGradFull)
-          apply_full<T, VEC, M, true, RAGGED>(rs.base(en.g), adj, P, rs.lane(en.g.sr), valid, nt, g.shift);
+          apply_full<T, VEC, M, true, RAGGED>(rs.base(en.g), adj, P, rs.lane(en.g.sr), valid, g.shift);
         else if (cls == kGradRowSum)
           apply_rowsum<T, VEC, M>(p, g, en, adj, P, r, ri);
         else if (cls == kGradColSum)

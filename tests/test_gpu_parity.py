@@ -1165,6 +1165,35 @@ def test_planes_interleaved_by_row(dtype):
             check_close(g.cpu().numpy(), w, f"{op} gradient {k} against the oracle")
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "f64"])
+def test_store_forms_give_identical_bits(dtype):
+    """Plain stores, stores with the nontemporal hint, and a forward launch that changes from one to the other
+    part way through its walk write the same bits: outputs, planes, branch ids and gradients of every class,
+    on the kernels compiled per mix and on the one that reads the gradient table."""
+    for op, R, C in (("hmlstm_update", 300, 1024), ("branchy5", 520, 2048), ("tanh_xy_b", 200, 1024), ("hmlstm_update", 70, 1028)):
+        args, adj = small_args(op, R, C, dtype, seed=R + C)
+        dev, adj_dev = [to_dev(a) for a in args], [to_dev(a) for a in adj]
+        shapes = [args[j].shape for j in oracle.diff_arg_indices(op, len(args))]
+        results = []
+        for opt in (P.Options(nontemporal_stores=0), P.Options(nontemporal_stores=3, fwd_keep_mib=0, bwd_nt_min_mib=0),
+                    P.Options(nontemporal_stores=3, fwd_keep_mib=1, bwd_nt_min_mib=0), P.Options(runtime_table=1, fwd_keep_mib=2)):
+            fb = P.alloc_forward(op, dev, want_branch=True, options=opt)
+            plan = P.bcast_dual_forward_plan(fb.op_id, dev, fb.outs, fb.partials, fb.branch, options=opt)
+            fb.run(dev)
+            bb = P.alloc_backward(adj_dev, fb.partials, shapes, options=opt).run(adj_dev, fb.partials)
+            torch.cuda.synchronize()
+            results.append((plan["nontemporal_tiles"], fb.outs + fb.partials + [fb.branch] + bb.grads))
+        tiles = [r[0] for r in results]
+        assert tiles[0] == 0 and tiles[1] > tiles[2] > 0, tiles  # none, all, all but the last MiB
+        for k in range(1, 3):
+            for a, b in zip(results[0][1], results[k][1]):
+                assert torch.equal(a, b), f"{op} [{R} x {C}] option set {k}"
+        for a, b in zip(results[0][1][: -len(shapes)], results[3][1][: -len(shapes)]):
+            assert torch.equal(a, b)
+        for a, b in zip(results[0][1][-len(shapes):], results[3][1][-len(shapes):]):  # another kernel's sums may round differently
+            check_close(a.cpu().numpy(), b.cpu().numpy(), f"{op} gradient, run-time table")
+
+
 def test_two_host_threads_with_different_options():
     """The library holds no state between calls: two host threads, each launching its own problem on its own
     stream with options of its own (one forces the generic kernels and plain stores, the other the run-time

@@ -348,6 +348,46 @@ def test_expanded_read_views_break_the_common_row_stride():
     assert d["uniform_stride"] == 0, d
 
 
+def test_nontemporal_store_policy_by_size():
+    """Which stores carry the nontemporal hint follows from how the bytes written compare with the caches: a
+    forward launch that writes up to 128 MiB hints everything, up to 1 GiB nothing, beyond that all but the last
+    256 MiB of its walk; a backward call hints its full-shape gradients when it reads at most 128 MiB of planes or
+    writes at least 256 MiB of gradients.  Options move or switch off each rule."""
+    # tanh_xy_b writes 1 + 3 planes and has 2 full-shape gradients
+    def plans(R, C, **opt):
+        slot = 1 << 36
+        view = lambda k, shape: B.raw_view(4096 + k * slot, shape, (shape[1], 1))
+        x, y, b = view(0, (R, C)), view(1, (R, C)), view(2, (R, 1))
+        outs, parts = [view(3, (R, C))], [view(4 + k, (R, C)) for k in range(3)]
+        grads = [view(8, (R, C)), view(9, (R, C)), view(10, (R, 1))]
+        o = P.Options(**opt) if opt else None
+        rc, f = _fwd_plan("tanh_xy_b", 0, [x, y, b], outs, parts, o)
+        assert rc == 0
+        info = B.PlanInfo()
+        rc = B.lib().bcast_dual_backward_plan(ctypes.c_int(0), ctypes.c_int32(1), B._views(outs), B._views(parts), ctypes.c_int32(3),
+                                              B._views(grads), ctypes.byref(info), None if o is None else ctypes.byref(o))
+        assert rc == 0
+        return f, info.as_dict()
+
+    f, r = plans(1024, 1024)      # 16 MiB written, 16 MiB of planes read
+    assert f["nontemporal_tiles"] == f["grid_x"] * f["grid_y"] and r["nontemporal_tiles"] == r["grid_x"] * r["grid_y"] > 0
+    f, r = plans(4096, 4096)      # 256 MiB written; 256 MiB of planes, 128 MiB of gradients
+    assert f["nontemporal_tiles"] == 0 and r["nontemporal_tiles"] == 0
+    f, r = plans(8192, 16384)     # 2 GiB written; 1 GiB of gradients
+    tiles = f["grid_x"] * f["grid_y"]
+    tile_bytes = 4 * f["ty"] * f["tx"] * f["vec"] * 4
+    assert f["nontemporal_tiles"] == tiles - (256 << 20) // tile_bytes and r["nontemporal_tiles"] > 0
+    f, r = plans(8192, 16384, nontemporal_stores=0)
+    assert f["nontemporal_tiles"] == 0 and r["nontemporal_tiles"] == 0
+    f, r = plans(8192, 16384, fwd_keep_mib=0, bwd_nt_min_mib=2048)
+    assert f["nontemporal_tiles"] == tiles and r["nontemporal_tiles"] == 0
+    f, r = plans(4096, 4096, fwd_keep_mib=64, bwd_nt_min_mib=0, col_chunks=0)  # (the kernels that take a row's four column chunks have no such form)
+    assert f["nontemporal_tiles"] == f["grid_x"] * f["grid_y"] - (64 << 20) // (4 * f["ty"] * f["tx"] * f["vec"] * 4) and r["nontemporal_tiles"] > 0
+    # the backward kernels that read the gradient table at run time have no such form
+    f, r = plans(8192, 16384, runtime_table=1)
+    assert r["specialized"] == 0 and r["nontemporal_tiles"] == 0
+
+
 def test_options_defaults_ranges_and_struct_size():
     """NULL options and a default-filled struct plan alike; a field outside its range, a struct of another
     size or half an event pair are refused with BCAST_ERR_BAD_OPTION before anything else is looked at."""
@@ -355,14 +395,14 @@ def test_options_defaults_ranges_and_struct_size():
     assert o.struct_size == ctypes.sizeof(P.Options) and (o.nontemporal_stores, o.reverse_tiles, o.fwd_lds_kib) == (3, 2, -1)
     assert (o.max_vector_bytes, o.interleave_rows, o.col_chunks, o.narrow_tiles, o.ragged_rows, o.probe_nt_loads) == (16, 1, 1, 1, 1, 1)
     assert (o.bwd_row_steps, o.force_generic, o.runtime_table, o.xcd_order, o.bwd_lds_kib, o.probe_lds_kib) == (0,) * 6
-    assert o.start_event is None and o.stop_event is None
+    assert o.start_event is None and o.stop_event is None and (o.fwd_keep_mib, o.bwd_nt_min_mib) == (-1, -1)
     x, y, b = _t(64, 2048), _t(64, 2048), _t(64, 1)
     outs, parts = [_t(64, 2048)], [_t(64, 2048) for _ in range(3)]
     op = P.bcast_op_lookup("tanh_xy_b")
     assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts) == P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=o)
     assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=P.Options(force_generic=1))["path"] == 2
     bad = [P.Options(bwd_row_steps=257), P.Options(bwd_row_steps=-1), P.Options(nontemporal_stores=4), P.Options(max_vector_bytes=12),
-           P.Options(fwd_lds_kib=65), P.Options(fwd_lds_kib=-2), P.Options(reverse_tiles=3), P.Options(force_generic=2), P.Options(struct_size=ctypes.sizeof(P.Options) - 8),
+           P.Options(fwd_lds_kib=65), P.Options(fwd_lds_kib=-2), P.Options(fwd_keep_mib=-2), P.Options(bwd_nt_min_mib=(1 << 20) + 1), P.Options(reverse_tiles=3), P.Options(force_generic=2), P.Options(struct_size=ctypes.sizeof(P.Options) - 8),
            P.Options(start_event=4096), P.Options(stop_event=4096)]
     for opt in bad:
         with pytest.raises(P.BcastError) as e:
