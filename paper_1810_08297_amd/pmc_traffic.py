@@ -46,9 +46,11 @@ def source_hash() -> str:
 
 
 def counter_means(directory, counter):
-    """kernel name -> (mean counter value per dispatch, dispatches) over every CSV under `directory`."""
+    """kernel name -> (mean counter value per dispatch, dispatches) from the newest CSV under `directory`
+    (a directory that several runs wrote into holds one file per run)."""
     agg = collections.defaultdict(list)
-    for f in glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True):
+    files = sorted(glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True), key=os.path.getmtime)
+    for f in files[-1:]:
         with open(f, newline="") as fh:
             for r in csv.DictReader(fh):
                 if r["Counter_Name"] == counter:
