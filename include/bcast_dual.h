@@ -110,7 +110,7 @@ typedef struct {
  * A workspace query, a plan query and the call itself must be given the same options. */
 typedef struct {
   uint32_t struct_size;     /* sizeof(bcast_dual_options) as the caller compiled it; any other value is refused */
-  int32_t bwd_row_steps;    /* row steps per block of the tiled backward kernels: 0 (default) = automatic, else 1..256 */
+  int32_t bwd_row_steps;    /* row steps per block of the tiled backward kernels: 0 (default) = automatic, else 1..512 */
   int32_t nontemporal_stores; /* bit 0: the forward kernel may write outputs and planes with the nontemporal hint
                                (see fwd_keep_mib), bit 1: the backward kernels may write full-shape gradients with it
                                (see bwd_nt_min_mib); default 3 = both */

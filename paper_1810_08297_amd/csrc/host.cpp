@@ -134,7 +134,7 @@ int resolve_options(const bcast_dual_options *in, Opt &o) {
   if (in->struct_size != sizeof(Opt)) return BCAST_ERR_BAD_OPTION;
   o = *in;
   auto in_range = [](int32_t v, int32_t lo, int32_t hi) { return v >= lo && v <= hi; };
-  const bool ok = in_range(o.bwd_row_steps, 0, 256) && in_range(o.nontemporal_stores, 0, 3) && in_range(o.force_generic, 0, 1) &&
+  const bool ok = in_range(o.bwd_row_steps, 0, 512) && in_range(o.nontemporal_stores, 0, 3) && in_range(o.force_generic, 0, 1) &&
                   (o.max_vector_bytes == 4 || o.max_vector_bytes == 8 || o.max_vector_bytes == 16) && in_range(o.runtime_table, 0, 1) &&
                   in_range(o.reverse_tiles, 0, 2) && in_range(o.interleave_rows, 0, 1) && in_range(o.xcd_order, 0, 1) &&
                   in_range(o.col_chunks, 0, 1) && in_range(o.fwd_lds_kib, -1, 64) && in_range(o.bwd_lds_kib, 0, 64) &&
@@ -890,7 +890,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     const int64_t tiles = ceil_div(s2.R, TY) * g.n_ct * s2.O;  // row steps x column chunks of the whole problem
     int64_t steps_rowwise;
     if (one_per_cu) {
-      steps_rowwise = std::min<int64_t>(256 / TY, tiles / 256);
+      steps_rowwise = std::min<int64_t>(512 / TY, tiles / 256);  // (fp64 8192 x 8192 branchy5: 512 steps, one block per CU, 700 us; 256 steps, two per CU, 747 us)
     } else {
       steps_rowwise = tiles / 512;
       if (steps_rowwise < 8) steps_rowwise = std::min<int64_t>(8, tiles / 256);
@@ -932,7 +932,7 @@ int plan_backward(int dt, int32_t n_out, const bcast_tensor *adjoints, const bca
     // rows wider than a wavefront park one accumulator per wavefront and row in LDS
     const int wpr = g.log2_tx > 6 ? (1 << (g.log2_tx - 6)) : 1;
     if (g.log2_tx > 6 && n_rowsum > 0) {
-      const int64_t max_rows = (int64_t)(kLdsBudget / 2) / ((int64_t)n_rowsum * wpr * as);
+      const int64_t max_rows = (int64_t)(kLdsBudget * 2 / 3) / ((int64_t)n_rowsum * wpr * as);
       steps = (int)std::max<int64_t>(1, std::min<int64_t>(steps, max_rows / TY));
     }
     if (!tile_rows(s2.R, steps, g)) return BCAST_ERR_LAUNCH_FAILED;

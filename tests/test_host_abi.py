@@ -401,7 +401,7 @@ def test_options_defaults_ranges_and_struct_size():
     op = P.bcast_op_lookup("tanh_xy_b")
     assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts) == P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=o)
     assert P.bcast_dual_forward_plan(op, [x, y, b], outs, parts, options=P.Options(force_generic=1))["path"] == 2
-    bad = [P.Options(bwd_row_steps=257), P.Options(bwd_row_steps=-1), P.Options(nontemporal_stores=4), P.Options(max_vector_bytes=12),
+    bad = [P.Options(bwd_row_steps=513), P.Options(bwd_row_steps=-1), P.Options(nontemporal_stores=4), P.Options(max_vector_bytes=12),
            P.Options(fwd_lds_kib=65), P.Options(fwd_lds_kib=-2), P.Options(fwd_keep_mib=-2), P.Options(bwd_nt_min_mib=(1 << 20) + 1), P.Options(reverse_tiles=3), P.Options(force_generic=2), P.Options(struct_size=ctypes.sizeof(P.Options) - 8),
            P.Options(start_event=4096), P.Options(stop_event=4096)]
     for opt in bad:
